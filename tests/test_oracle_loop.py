@@ -1,0 +1,196 @@
+"""Pins for the oracle's speculative loop: the invariants the paper fixes.
+
+I1  every policy emits exactly the target's greedy text (abstract; Sec. 3 last sentence; Sec. 4).
+I2  static-SL text == DISCO text == oracle-SL text (corollary).
+I3  the iteration structure of every policy follows from the per-position match vector of the
+    labelling run of App. D.1 (draft predicts one token from prompt + target prefix).
+I4  oracle SL == the maximum number of accepted draft tokens over all static lookaheads, and the
+    smallest lookahead that reaches it (Sec. 3, "optimal (maximum)"), by brute force.
+I5  under i.i.d. acceptance alpha, mean tokens per iteration -> (1 - alpha^(g+1)) / (1 - alpha)
+    (numerator of Eq. 1)."""
+import math
+
+import pytest
+import torch
+
+from oracle import disco_oracle as O
+from workloads import synth as W
+
+
+def _cfg0(n_new=64):
+    tw = W.make_weights(W.CFG0_TARGET, seed=0, dtype="f32")
+    target = O.Model(W.CFG0_TARGET, tw)
+    draft = O.Model(W.CFG0_DRAFT, W.early_exit_draft(tw, 1))
+    clf = W.make_classifier(100)
+    prompt = W.make_prompt(1, 32, W.CFG0_TARGET.vocab).tolist()
+    return target, draft, clf, prompt
+
+
+@pytest.fixture(scope="module")
+def cfg0():
+    target, draft, clf, prompt = _cfg0()
+    ref, margins = O.greedy_target(target, prompt, 64)
+    return target, draft, clf, prompt, ref
+
+
+def test_i1_i2_all_policies_emit_greedy_text(cfg0):
+    target, draft, clf, prompt, ref = cfg0
+    policies = [{"mode": "static", "gamma": g} for g in (0, 1, 5, 8)]
+    policies += [{"mode": "disco", "tau": t, "sl_max": 8, "pos_mode": pm}
+                 for t in (0.0, 0.5, 0.55, 0.6, 0.9, 1.1) for pm in ("absolute", "block")]
+    policies += [{"mode": "oracle", "reference": ref}]
+    hists = []
+    for pol in policies:
+        r = O.spec_decode(target, draft, clf, prompt, 64, pol)
+        assert r["tokens"] == ref, pol
+        assert sum(len(it["emit"]) for it in r["iterations"]) == 64
+        assert r["n_target_forwards"] == r["n_iterations"]
+        hists.append(r["sl_hist"])
+    # gamma = 0 is plain decoding: one token per target forward, no draft forwards
+    r0 = O.spec_decode(target, draft, clf, prompt, 64, policies[0])
+    assert r0["n_iterations"] == 64 and r0["n_draft_forwards"] == 0
+    # tau above 1 halts after every first token; tau = 0 never halts before the cap
+    r_hi = O.spec_decode(target, draft, clf, prompt, 64, {"mode": "disco", "tau": 1.1, "sl_max": 8})
+    assert set(r_hi["sl_hist"]) <= {0, 1}
+    r_lo = O.spec_decode(target, draft, clf, prompt, 64, {"mode": "disco", "tau": 0.0, "sl_max": 8})
+    r_st = O.spec_decode(target, draft, clf, prompt, 64, {"mode": "static", "gamma": 8})
+    assert r_lo["sl_hist"] == r_st["sl_hist"]
+    assert r_lo["n_draft_forwards"] == r_st["n_draft_forwards"]
+
+
+def _labelling_run(target, draft, clf, prompt, ref):
+    """App. D.1: for every generated position p the draft predicts ONE token from
+    prompt + target tokens < p.  Returns match vector m_p and the classifier score at p with the
+    absolute position feature (p + 1)."""
+    kv = draft.new_cache(len(prompt) + len(ref) + 1)
+    draft.prefill(prompt[:-1], kv)
+    seq = list(prompt) + list(ref)
+    m, score = [], []
+    for p in range(len(ref)):
+        logits = draft.forward([seq[len(prompt) - 1 + p]], kv)[0]
+        ft = O.features(logits, p + 1)
+        m.append(ft["token"] == ref[p])
+        score.append(O.classifier(ft["feats"], clf))
+    return m, score
+
+
+def _simulate(m, score, max_new, mode, gamma=None, tau=None, sl_max=None):
+    """Iteration structure from the match vector alone: [(start index, n accepted, SL or None)]."""
+    out, e = [], 0
+    while e < max_new:
+        remaining = max_new - e
+        run = 0
+        while e + run < max_new and m[e + run]:
+            run += 1
+        if mode == "static":
+            sl = min(gamma, remaining - 1)
+            n = min(sl, run)
+        elif mode == "oracle":
+            sl = min(run, remaining - 1)
+            n = sl
+        else:
+            cap = min(sl_max, remaining - 1)
+            sl, n = None, min(run, cap)
+            # halting is decided by labelling-run scores only up to the first mismatching token
+            for j in range(1, min(run + 1, cap) + 1):
+                if score[e + j - 1] < tau:
+                    sl, n = j, min(j, run)
+                    break
+        out.append((e, n, sl))
+        e += min(n + 1, remaining)
+    return out
+
+
+def _small_pair():
+    """Small vocabulary and large weights: the early-exit draft agrees with the target often."""
+    shape = W.ModelShape("A", 2, 32, 2, 16, 2, 64, 24, max_pos=128)
+    tw = W.make_weights(shape, seed=21, dtype="f32", sigma=0.5)
+    target = O.Model(shape, tw)
+    draft = O.Model(W.scaled_shape(shape, n_layers=1), W.early_exit_draft(tw, 1))
+    prompt = W.make_prompt(5, 6, shape.vocab).tolist()
+    ref, _ = O.greedy_target(target, prompt, 64)
+    return target, draft, W.make_classifier(100), prompt, ref
+
+
+@pytest.mark.parametrize("setup", ["cfg0", "small"])
+def test_i3_schedule_follows_from_match_vector(cfg0, setup):
+    target, draft, clf, prompt, ref = cfg0 if setup == "cfg0" else _small_pair()
+    m, score = _labelling_run(target, draft, clf, prompt, ref)
+    assert 0 < sum(m) < len(m)            # the early-exit draft agrees sometimes, not always
+    if setup == "small":
+        assert sum(m) >= 16
+    taus = sorted(score)[len(score) // 4::len(score) // 4][:3]   # thresholds that do halt
+    for pol in ([{"mode": "static", "gamma": g} for g in (1, 3, 8)]
+                + [{"mode": "disco", "tau": t, "sl_max": 8, "pos_mode": "absolute"}
+                   for t in [0.5] + taus]
+                + [{"mode": "oracle", "reference": ref}]):
+        r = O.spec_decode(target, draft, clf, prompt, 64, pol)
+        sim = _simulate(m, score, 64, pol["mode"], pol.get("gamma"), pol.get("tau"), pol.get("sl_max"))
+        assert len(sim) == r["n_iterations"], pol
+        e = 0
+        for (s_e, s_n, s_sl), it in zip(sim, r["iterations"]):
+            assert s_e == e and s_n == it["n"], pol
+            if s_sl is not None:
+                assert s_sl == it["sl"], pol
+            e += len(it["emit"])
+        if pol["mode"] == "static":
+            assert r["n_draft_forwards"] == sum(s[2] for s in sim)
+        if pol["mode"] == "oracle":
+            # one draft forward per accepted token plus the mismatching one (absent when the
+            # block ran into the end of the text)
+            hit_end = sum(1 for (s_e, s_n, s_sl) in sim if s_sl == 64 - s_e - 1)
+            assert r["n_draft_forwards"] == sum(s[2] for s in sim) + len(sim) - hit_end
+
+
+def test_i4_oracle_sl_is_brute_force_optimum():
+    shape = W.ModelShape("A", 2, 32, 2, 16, 2, 64, 24, max_pos=64)
+    tw = W.make_weights(shape, seed=21, dtype="f32", sigma=0.5)
+    target = O.Model(shape, tw)
+    draft = O.Model(W.scaled_shape(shape, n_layers=1), W.early_exit_draft(tw, 1))
+    prompt = W.make_prompt(5, 6, shape.vocab).tolist()
+    ref, _ = O.greedy_target(target, prompt, 24)
+    orc = O.spec_decode(target, draft, None, prompt, 24, {"mode": "oracle", "reference": ref})
+    assert orc["tokens"] == ref
+    seen_positive = False
+    e = 0
+    for it in orc["iterations"]:
+        cap = 24 - e - 1
+        sub_prompt = prompt + ref[:e]
+        n_acc = []
+        for g in range(0, cap + 1):
+            r = O.spec_decode(target, draft, None, sub_prompt, 24 - e, {"mode": "static", "gamma": g})
+            n_acc.append(r["iterations"][0]["n"])
+        best = max(n_acc) if n_acc else 0
+        assert it["sl"] == best == it["n"]
+        assert it["sl"] == (n_acc.index(best) if n_acc else 0)   # smallest lookahead reaching it
+        seen_positive |= best > 0
+        e += len(it["emit"])
+    assert seen_positive and e == 24
+
+
+def test_i5_eq1_expected_tokens_per_iteration():
+    shape = W.ModelShape("B", 1, 32, 2, 16, 2, 64, 512)
+    target = O.Model(shape, W.make_weights(shape, seed=31, dtype="f32", sigma=0.3))
+    draft = O.Model(shape, W.make_weights(shape, seed=32, dtype="f32", sigma=0.3))
+    alpha, n_new = 0.6, 300
+    for gamma in (1, 3, 5):
+        emitted = iters = accepted = drafted = 0
+        for pi in range(4):
+            prompt = W.make_prompt(40 + pi, 8, shape.vocab).tolist()
+            ref, _ = O.greedy_target(target, prompt, n_new)
+            force = {"mask": W.make_force_mask(50 + pi, n_new, alpha), "tokens": ref}
+            r = O.spec_decode(target, draft, None, prompt, n_new,
+                              {"mode": "static", "gamma": gamma}, force=force)
+            assert r["tokens"] == ref
+            full = [it for it in r["iterations"] if it["sl"] == gamma]   # drop the truncated tail
+            iters += len(full)
+            emitted += sum(it["n"] + 1 for it in full)
+        a = alpha + (1 - alpha) / shape.vocab           # unforced positions agree by chance 1/V
+        want = (1 - a ** (gamma + 1)) / (1 - a)
+        got = emitted / iters
+        # per-iteration std < 1.7 tokens; >= 200 iterations -> 4 sigma < 0.5; observed far tighter
+        assert abs(got - want) < 4 * 1.7 / math.sqrt(iters), (gamma, got, want, iters)
+    # Eq. 1 itself at the values it is quoted with: c -> 0 gives the numerator, gamma = 0 gives 1
+    assert O.improvement_factor(0.6, 5, 0.0) == pytest.approx((1 - 0.6 ** 6) / 0.4)
+    assert O.improvement_factor(0.6, 0, 0.3) == pytest.approx(1.0)
+    assert O.improvement_factor(0.0, 5, 0.1) == pytest.approx(1 / 1.5)
