@@ -1,0 +1,221 @@
+/*
+ * disco.h -- C boundary of the MI355X (gfx950) hot path of one DISCO speculative-decoding iteration
+ * (arXiv 2405.04304, "Dynamic Speculation Lookahead Accelerates Speculative Decoding of LLMs").
+ *
+ * One iteration (paper Sec. 2 and Fig. 1; Sec. 3 "Dynamic Speculation Lookahead Optimization"):
+ *   the draft model decodes tokens one at a time (disco_draft_step); after every draft token a
+ *   small classifier over [top-10 draft probabilities, entropy, position] decides whether to draft
+ *   another token (disco_classify, Eq. 2); the target model then checks the whole block of
+ *   SL + 1 tokens in one forward against its KV cache (disco_verify); the longest draft prefix that
+ *   equals the target's arg-max tokens is accepted (disco_accept; rejection sampling at temperature
+ *   0) and the rejected suffix is dropped from both KV caches (disco_kv_rollback).
+ *
+ * Conventions
+ *   - "dev" pointers are DEVICE memory, "host" pointers are HOST memory.  The caller owns every
+ *     device buffer (weights, KV pages, workspace, logits, outputs); the library allocates no
+ *     device memory and keeps borrowed pointers only.  Handles are small host objects.
+ *   - Every call validates its arguments on the host BEFORE any launch and returns 0 on success or
+ *     a negative DISCO_E* code; it never aborts, throws or prints.  disco_last_error() gives the
+ *     message of the calling thread's last failure.
+ *   - All launches are asynchronous on the caller's HIP stream (disco_stream is a hipStream_t).
+ *     KV lengths are host-side metadata updated at enqueue time.
+ *   - Weight matrices are bf16.  A "packed" matrix W[N x K] (N % 16 == 0, K % 32 == 0) is stored
+ *     as 1 KiB tiles of 16 rows x 32 columns, tile (rt, kt) at element offset (rt * K/32 + kt) * 512,
+ *     and inside a tile the element of row r, column c at  ((c / 8) * 16 + r) * 8 + c % 8  -- the
+ *     operand order of the 16x16x32 bf16 matrix instruction, so a wavefront streams a tile with one
+ *     fully coalesced 128-bit load per lane.  disco_pack_weight converts from row-major.
+ *   - At most DISCO_MAX_BLOCK tokens are fed per forward.
+ */
+#ifndef DISCO_H
+#define DISCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DISCO_MAX_BLOCK 16
+#define DISCO_TOPK 10          /* k of Eq. 2 (the paper's footnote: k = 10 in all experiments) */
+#define DISCO_N_FEAT 12        /* top-10 probabilities, entropy, position                       */
+#define DISCO_CLF_HIDDEN_MAX 256
+
+enum {
+  DISCO_OK = 0,
+  DISCO_EINVAL = -1,  /* null / misaligned pointer, bad enum, shape the kernels do not support   */
+  DISCO_ECAP = -2,    /* block length or KV capacity exceeded                                    */
+  DISCO_ESTATE = -3,  /* rollback outside [0, len], handle mismatch                               */
+  DISCO_EHIP = -4     /* a HIP runtime call failed                                                */
+};
+
+enum { DISCO_FAMILY_A = 0,   /* pre-LN LayerNorm, exact-erf GELU MLP, learned position table     */
+       DISCO_FAMILY_B = 1 }; /* RMSNorm, rotary (pairs c, c + d_head/2), SwiGLU MLP               */
+
+typedef void* disco_stream;  /* a hipStream_t (0 = the null stream) */
+
+typedef struct disco_model_desc {
+  int32_t family, n_layers, d_model, n_heads, d_head, n_kv_heads, d_ff, vocab;
+  int32_t max_pos;           /* rows of the position table (family A), ignored for family B      */
+  float norm_eps;            /* LayerNorm / RMSNorm epsilon                                       */
+  float rope_base;           /* rotary base (family B)                                            */
+} disco_model_desc;
+
+/* Device pointers of one layer.  Vectors are fp32; matrices are packed bf16 (see above).
+ * w_in: family A = W1 [d_ff x d_model]; family B = gate and up matrices interleaved by 16-row
+ * tiles (disco_pack_gate_up), [2 d_ff x d_model].  w_out: W2 / down [d_model x d_ff].
+ * wqkv: rows ordered [q heads | k heads | v heads], [(n_heads + 2 n_kv_heads) d_head x d_model]. */
+typedef struct disco_layer_weights {
+  const float* norm1_g; const float* norm1_b;   /* *_b NULL for family B */
+  const void* wqkv; const void* wo;
+  const float* norm2_g; const float* norm2_b;
+  const void* w_in; const void* w_out;
+} disco_layer_weights;
+
+typedef struct disco_model_weights {
+  const void* tok_emb;        /* bf16 row-major [vocab x tok_emb_stride], first d_model columns used */
+  int64_t tok_emb_stride;     /* elements between rows (>= d_model)                                 */
+  const void* pos_emb;        /* bf16 row-major [max_pos x d_model], family A; else NULL            */
+  const disco_layer_weights* layers;  /* HOST array of n_layers entries (copied by the library)    */
+  const float* normf_g; const float* normf_b;
+  const void* wlm;            /* packed [vocab x d_model]                                           */
+} disco_model_weights;
+
+typedef struct disco_model disco_model;  /* immutable: desc + borrowed device weight pointers       */
+typedef struct disco_kv disco_kv;        /* one sequence's paged KV cache: page order + length      */
+
+/* Halting classifier of Eq. 2: C = sigmoid(w2 . relu(W1 f + b1) + b2), f = 12 features.
+ * dev_params: fp32 [W1 (hidden x 12, row-major) | b1 (hidden) | w2 (hidden) | b2 (1)].             */
+typedef struct disco_clf {
+  const float* dev_params;
+  int32_t hidden;             /* 1 .. DISCO_CLF_HIDDEN_MAX */
+} disco_clf;
+
+/* Result of one disco_classify call (device memory, 16-byte aligned). */
+typedef struct disco_clf_out {
+  int32_t token;              /* arg-max of the draft logits, lowest id on ties                     */
+  float feats[DISCO_N_FEAT];  /* top-10 probabilities (descending), entropy (nats), position        */
+  float score;                /* C_i                                                                */
+  uint32_t halt;              /* 1: stop drafting after this token                                  */
+  uint32_t executed;          /* 1 if the call ran, 0 if it was gated off                            */
+} disco_clf_out;
+
+typedef struct disco_accept_out {
+  int32_t n;                        /* number of accepted draft tokens                              */
+  int32_t n_emit;                   /* n + 1                                                        */
+  int32_t emit[DISCO_MAX_BLOCK];    /* accepted draft tokens followed by the target's token         */
+} disco_accept_out;
+
+const char* disco_last_error(void);
+
+/* ---- layout helpers ------------------------------------------------------------------------- */
+
+/* Row-major bf16 [n x k] -> packed.  n % 16 == 0, k % 32 == 0; src and dst must not overlap.       */
+int disco_pack_weight(const void* dev_src, int64_t n, int64_t k, void* dev_dst, disco_stream s);
+/* Gate [d_ff x k] and up [d_ff x k] (row-major) -> one packed [2 d_ff x k] matrix whose 16-row
+ * tiles alternate gate tile i, up tile i, so the SwiGLU product is formed inside one workgroup.   */
+int disco_pack_gate_up(const void* dev_gate, const void* dev_up, int64_t d_ff, int64_t k,
+                       void* dev_dst, disco_stream s);
+
+/* ---- handles --------------------------------------------------------------------------------- */
+
+int disco_model_create(const disco_model_desc* desc, const disco_model_weights* w, disco_model** out);
+void disco_model_destroy(disco_model* m);
+
+/* Bytes of KV page storage for capacity_tokens positions (rounded up to whole pages).              */
+size_t disco_kv_bytes(const disco_model* m, int capacity_tokens, int page_tokens);
+/* dev_pages: caller's buffer of at least disco_kv_bytes(...), 256-byte aligned.  Logical page i of
+ * the sequence lives in physical page host_page_order[i] (a permutation of 0..n_pages-1), or in
+ * page i when host_page_order is NULL.  Page layout:
+ * [layer][physical page][K | V][kv head][token in page][d_head] bf16.                             */
+int disco_kv_create(const disco_model* m, void* dev_pages, size_t bytes, int capacity_tokens,
+                    int page_tokens, const int32_t* host_page_order, disco_kv** out);
+void disco_kv_destroy(disco_kv* kv);
+int disco_kv_len(const disco_kv* kv);
+int disco_kv_pages_in_use(const disco_kv* kv);
+/* Install given keys/values, bf16 [n_layers][2][ctx][n_kv_heads][d_head], as positions [0, ctx);
+ * sets len = ctx.  (Synthetic workloads pre-fill the cache this way.)                              */
+int disco_kv_fill(disco_kv* kv, const void* dev_src, int ctx, disco_stream s);
+
+/* Workspace bytes for forwards of up to max_block tokens against up to max_ctx cached positions.   */
+size_t disco_workspace_bytes(const disco_model* m, int max_block, int max_ctx);
+
+/* ---- the five calls of the iteration --------------------------------------------------------- */
+
+/* Draft decode step (Sec. 2: the draft model generates autoregressively).  Feeds n_in tokens
+ * (1, or 2 when the previous block was fully accepted and the draft has not yet seen its own last
+ * token) from dev_tokens_in at positions kv->len .., appends their keys/values, and writes the fp32
+ * logits [vocab] of the LAST fed token to dev_logits.  kv->len += n_in.
+ * dev_gate (may be NULL): if *dev_gate != 0 when the kernels run, the step does nothing on the
+ * device (the host still advances kv->len; roll it back with disco_kv_rollback).
+ * Errors: EINVAL (null/misaligned, n_in not in [1, DISCO_MAX_BLOCK]), ECAP (KV capacity).          */
+int disco_draft_step(const disco_model* draft, disco_kv* kv, const int32_t* dev_tokens_in, int n_in,
+                     float* dev_logits, void* dev_ws, size_t ws_bytes, const uint32_t* dev_gate,
+                     disco_stream s);
+
+/* Features and halting decision of Eq. 2 in one launch.  Reads logits [vocab]; computes the
+ * soft-max's top-10 probabilities (descending), its entropy in nats, the arg-max token; evaluates
+ * the classifier on [top-10, entropy, pos_feature]; halt = (score < tau) || force_halt.
+ * Writes *dev_out; if dev_token_next != NULL stores the token there (input of the next draft step);
+ * if dev_block_slot != NULL stores the token there too (slot of the draft block);
+ * if dev_gate != NULL: the call is skipped when *dev_gate != 0, and sets *dev_gate = 1 on halt;
+ * if dev_sl_count != NULL it is incremented when the call executes;
+ * if dev_force_token != NULL and *dev_force_token >= 0, the logit of that token is first raised to
+ * max + 4 (in dev_logits too): the synthetic-workload hook that makes the draft agree with a known
+ * target token at chosen positions.  clf may be NULL (score = NaN, halt = force_halt).             */
+int disco_classify(const disco_clf* clf, float* dev_logits, int vocab, float pos_feature, float tau,
+                   int force_halt, disco_clf_out* dev_out, int32_t* dev_token_next,
+                   int32_t* dev_block_slot, uint32_t* dev_gate, int32_t* dev_sl_count,
+                   const int32_t* dev_force_token, disco_stream s);
+
+/* Target verification forward (Fig. 1: the target validates all draft tokens in parallel).
+ * dev_block = [last emitted token, d_1 .. d_SL], n_block = SL + 1 in [1, DISCO_MAX_BLOCK]; token j
+ * sits at position kv->len + j and attends to positions <= its own (causal inside the block).
+ * Appends n_block KV entries (kv->len += n_block); writes the arg-max token of every row to
+ * dev_argmax[n_block] (lowest id on ties) and, if dev_logits != NULL, the fp32 logits
+ * [n_block x vocab].  Errors as disco_draft_step.                                                   */
+int disco_verify(const disco_model* target, disco_kv* kv, const int32_t* dev_block, int n_block,
+                 int32_t* dev_argmax, float* dev_logits, void* dev_ws, size_t ws_bytes,
+                 disco_stream s);
+
+/* Greedy acceptance (Sec. 3: rejection sampling at zero temperature; Fig. 1).
+ * n = the largest j <= n_block - 1 with block[i] == argmax[i-1] for all 1 <= i <= j;
+ * emit = block[1..n] followed by argmax[n].  Writes *dev_out and, if host_out != NULL (pinned,
+ * device-accessible host memory), the same record there.
+ * dev_n_block (may be NULL) overrides n_block with a device-resident value in [1, n_block].         */
+int disco_accept(const int32_t* dev_block, const int32_t* dev_argmax, int n_block,
+                 const int32_t* dev_n_block, disco_accept_out* dev_out, disco_accept_out* host_out,
+                 disco_stream s);
+
+/* KV rollback of the rejected suffix (implied by Fig. 1: rejected tokens leave no state).
+ * Sets len = new_len, 0 <= new_len <= len (else ESTATE); whole pages beyond it are released.  Host
+ * metadata only: entries >= new_len are dead and are overwritten by the next append; work already
+ * enqueued on any stream is unaffected.  new_len == len is a no-op.                                */
+int disco_kv_rollback(disco_kv* kv, int new_len);
+
+/* ---- fused draft loop (Sec. 3: draft, classify, repeat until halt or SL_max) ------------------ */
+
+typedef struct disco_loop_out {
+  int32_t sl;                         /* number of drafted tokens                                   */
+  int32_t block[DISCO_MAX_BLOCK];     /* block[0] = last emitted token, block[1..sl] = draft tokens */
+} disco_loop_out;
+
+/* Enqueues up to `cap` (draft step, classify) pairs with no host round trip: a device flag set by
+ * the first halting classify turns the remaining steps into no-ops.  dev_tokens_in/n_in as in
+ * disco_draft_step for the first step; pos_feature0 is the position feature of the first drafted
+ * token and grows by 1 per step; static_sl > 0 forces "halt exactly at step static_sl" (static
+ * lookahead) and ignores the classifier's verdict.  dev_force_tokens (may be NULL): cap entries,
+ * one per step, as dev_force_token of disco_classify.  dev_steps: cap records of disco_clf_out.
+ * On return the host's kv->len has advanced by n_in + cap - 1; after synchronising, the caller
+ * reads sl from host_out (pinned) or dev_out and calls disco_kv_rollback(kv, len0 + n_in + sl - 1).
+ * dev_logits: fp32 [vocab] scratch for the draft logits.  cap in [1, DISCO_MAX_BLOCK - 1].          */
+int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* clf,
+                     const int32_t* dev_tokens_in, int n_in, int cap, int static_sl,
+                     float pos_feature0, float tau, const int32_t* dev_force_tokens,
+                     float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out,
+                     disco_loop_out* host_out, void* dev_ws, size_t ws_bytes, disco_stream s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DISCO_H */

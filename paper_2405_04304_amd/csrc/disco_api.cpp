@@ -1,0 +1,392 @@
+// C boundary of the DISCO hot path: handles, host-side validation, workspace carving and the launch
+// sequences of a draft step, a verification forward and the fused draft loop.  Every check runs on
+// the host before the first launch, so argument errors are reported without touching the GPU.
+#include "../../include/disco.h"
+#include "disco_internal.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace disco;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int hip_fail(hipError_t e, const char* what) {
+  return fail(DISCO_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+struct disco_model {
+  disco_model_desc d;
+  disco_model_weights w;
+  std::vector<disco_layer_weights> layers;
+  int d_q, d_kv, d_qkv;
+};
+
+struct disco_kv {
+  const disco_model* model;
+  bf16_t* pages;
+  int32_t* dev_page_table;   // inside the caller's buffer, or nullptr for the identity order
+  int page_tokens, n_pages, capacity, len;
+  size_t layer_stride;       // elements between layers
+};
+
+namespace {
+
+struct Ws {
+  float* h; float* q; bf16_t* xn; bf16_t* xattn; bf16_t* xact; float* part; float* logits;
+  uint32_t* gate; int32_t* sl_count; int32_t* tok_next;
+  size_t total;
+};
+
+// Carve the workspace; with base == nullptr only the total is meaningful.
+Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
+  (void)max_block;  // buffers are sized for DISCO_MAX_BLOCK tokens
+  const disco_model_desc& d = m->d;
+  char* p = static_cast<char*>(base);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { void* r = p ? p + off : nullptr; off += round_up(bytes, 256); return r; };
+  Ws w;
+  w.h = static_cast<float*>(take(sizeof(float) * 16 * d.d_model));
+  w.q = static_cast<float*>(take(sizeof(float) * 16 * m->d_q));
+  w.xn = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * 16 * d.d_model));
+  w.xattn = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * 16 * m->d_q));
+  w.xact = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * 16 * d.d_ff));
+  const int n_splits = (max_ctx + DISCO_MAX_BLOCK + ATTN_SPLIT_LEN - 1) / ATTN_SPLIT_LEN;
+  w.part = static_cast<float*>(take(sizeof(float) * (size_t)d.n_heads * n_splits * 16 * (d.d_head + 2)));
+  w.logits = static_cast<float*>(take(sizeof(float) * 16 * (size_t)d.vocab));
+  w.gate = static_cast<uint32_t*>(take(256));
+  w.sl_count = reinterpret_cast<int32_t*>(w.gate ? w.gate + 16 : nullptr);
+  w.tok_next = reinterpret_cast<int32_t*>(w.gate ? w.gate + 32 : nullptr);
+  w.total = off;
+  return w;
+}
+
+int check_forward_args(const disco_model* m, const disco_kv* kv, const int32_t* tokens, int n,
+                       const void* ws, size_t ws_bytes) {
+  if (!m || !kv || !tokens || !ws) return fail(DISCO_EINVAL, "null argument");
+  if (kv->model != m) return fail(DISCO_ESTATE, "KV cache belongs to another model");
+  if (n < 1 || n > DISCO_MAX_BLOCK) return fail(DISCO_ECAP, "block of %d tokens outside [1, %d]", n, DISCO_MAX_BLOCK);
+  if (kv->len + n > kv->capacity) return fail(DISCO_ECAP, "KV capacity %d exceeded (len %d + %d)", kv->capacity, kv->len, n);
+  if (m->d.family == DISCO_FAMILY_A && kv->len + n > m->d.max_pos)
+    return fail(DISCO_ECAP, "position table of %d rows exceeded", m->d.max_pos);
+  if (!aligned(tokens, 4) || !aligned(ws, 256)) return fail(DISCO_EINVAL, "misaligned pointer");
+  const size_t need = carve(m, n, kv->len + n, nullptr).total;
+  if (ws_bytes < need) return fail(DISCO_EINVAL, "workspace of %zu bytes, %zu needed", ws_bytes, need);
+  return DISCO_OK;
+}
+
+#define HIP_TRY(expr, what) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return hip_fail(e__, what); } while (0)
+
+// One forward of n tokens at positions kv->len ..: the shared body of draft step and verification.
+// logits_out: [vocab] of the last token (only_last) or [n x vocab].
+int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens, int n, float* logits_out,
+                  bool only_last, const Ws& ws, const uint32_t* gate, hipStream_t s) {
+  const disco_model_desc& d = m->d;
+  const int pos0 = kv->len;
+  const bool fam_a = d.family == DISCO_FAMILY_A;
+
+  NormArgs na{};
+  na.h = ws.h; na.d = d.d_model; na.M = n; na.layernorm = fam_a; na.eps = d.norm_eps;
+  na.Xout = ws.xn; na.gate = gate; na.pos0 = pos0; na.vocab = d.vocab; na.max_pos = d.max_pos;
+
+  for (int l = 0; l <= d.n_layers; ++l) {
+    // norm feeding layer l (or the LM head when l == n_layers); the first one also embeds
+    NormArgs n1 = na;
+    if (l < d.n_layers) { n1.g = m->layers[l].norm1_g; n1.b = m->layers[l].norm1_b; }
+    else { n1.g = m->w.normf_g; n1.b = m->w.normf_b; }
+    if (l == 0) {
+      n1.tokens = dev_tokens; n1.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb);
+      n1.tok_stride = m->w.tok_emb_stride; n1.pos_emb = static_cast<const bf16_t*>(m->w.pos_emb);
+    }
+    HIP_TRY(launch_norm(n1, s), "norm launch");
+    if (l == d.n_layers) break;
+    const disco_layer_weights& L = m->layers[l];
+
+    GemmArgs g{};
+    g.M = n; g.gate = gate;
+    // QKV projection, rotary, KV append
+    g.W = static_cast<const bf16_t*>(L.wqkv); g.X = ws.xn; g.KT = d.d_model / 32; g.n_rows = m->d_qkv;
+    g.grp = d.d_head / 32; g.q = ws.q; g.ldq = m->d_q; g.nq = d.n_heads; g.nkv = d.n_kv_heads; g.dh = d.d_head;
+    g.pos0 = pos0; g.rope = fam_a ? 0 : 1; g.rope_base = d.rope_base;
+    g.kv_layer = kv->pages + (size_t)l * kv->layer_stride; g.page_table = kv->dev_page_table;
+    g.page_tokens = kv->page_tokens;
+    HIP_TRY(launch_gemm(g, EPI_QKV, s), "qkv launch");
+
+    AttnArgs at{};
+    at.q = ws.q; at.ldq = m->d_q; at.kv_layer = g.kv_layer; at.page_table = kv->dev_page_table;
+    at.page_tokens = kv->page_tokens; at.nq = d.n_heads; at.nkv = d.n_kv_heads; at.dh = d.d_head; at.M = n;
+    at.pos0 = pos0; at.scale = 1.0f / sqrtf((float)d.d_head); at.part = ws.part;
+    at.split_len = ATTN_SPLIT_LEN; at.n_splits = (pos0 + n + ATTN_SPLIT_LEN - 1) / ATTN_SPLIT_LEN;
+    at.Xout = ws.xattn; at.gate = gate;
+    HIP_TRY(launch_attn(at, s), "attention launch");
+
+    GemmArgs o{};
+    o.M = n; o.gate = gate; o.W = static_cast<const bf16_t*>(L.wo); o.X = ws.xattn; o.KT = m->d_q / 32;
+    o.n_rows = d.d_model; o.out = ws.h; o.ld_out = d.d_model; o.only_row = -1;
+    HIP_TRY(launch_gemm(o, EPI_RESID, s), "o-proj launch");
+
+    NormArgs n2 = na;
+    n2.g = L.norm2_g; n2.b = L.norm2_b;
+    HIP_TRY(launch_norm(n2, s), "norm launch");
+
+    GemmArgs u{};
+    u.M = n; u.gate = gate; u.W = static_cast<const bf16_t*>(L.w_in); u.X = ws.xn; u.KT = d.d_model / 32;
+    u.n_rows = fam_a ? d.d_ff : 2 * d.d_ff; u.grp = 1; u.Xout = ws.xact; u.KT_out = d.d_ff / 32;
+    HIP_TRY(launch_gemm(u, fam_a ? EPI_GELU : EPI_SWIGLU, s), "mlp-in launch");
+
+    GemmArgs dn{};
+    dn.M = n; dn.gate = gate; dn.W = static_cast<const bf16_t*>(L.w_out); dn.X = ws.xact; dn.KT = d.d_ff / 32;
+    dn.n_rows = d.d_model; dn.out = ws.h; dn.ld_out = d.d_model; dn.only_row = -1;
+    HIP_TRY(launch_gemm(dn, EPI_RESID, s), "mlp-out launch");
+  }
+  GemmArgs lm{};
+  lm.M = n; lm.gate = gate; lm.W = static_cast<const bf16_t*>(m->w.wlm); lm.X = ws.xn; lm.KT = d.d_model / 32;
+  lm.n_rows = d.vocab; lm.out = logits_out; lm.ld_out = d.vocab; lm.only_row = only_last ? n - 1 : -1;
+  HIP_TRY(launch_gemm(lm, EPI_STORE, s), "lm-head launch");
+  kv->len = pos0 + n;
+  return DISCO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* disco_last_error(void) { return g_err; }
+
+int disco_pack_weight(const void* dev_src, int64_t n, int64_t k, void* dev_dst, disco_stream s) {
+  if (!dev_src || !dev_dst) return fail(DISCO_EINVAL, "null pointer");
+  if (n <= 0 || k <= 0 || n % 16 || k % 32) return fail(DISCO_EINVAL, "matrix %lld x %lld: rows %% 16 and columns %% 32 must be 0", (long long)n, (long long)k);
+  if (!aligned(dev_src, 16) || !aligned(dev_dst, 16)) return fail(DISCO_EINVAL, "misaligned pointer");
+  HIP_TRY(launch_pack(static_cast<const bf16_t*>(dev_src), n, k, static_cast<bf16_t*>(dev_dst), 1, 0, static_cast<hipStream_t>(s)), "pack launch");
+  return DISCO_OK;
+}
+
+int disco_pack_gate_up(const void* dev_gate, const void* dev_up, int64_t d_ff, int64_t k, void* dev_dst, disco_stream s) {
+  if (!dev_gate || !dev_up || !dev_dst) return fail(DISCO_EINVAL, "null pointer");
+  if (d_ff <= 0 || k <= 0 || d_ff % 16 || k % 32) return fail(DISCO_EINVAL, "matrix %lld x %lld: rows %% 16 and columns %% 32 must be 0", (long long)d_ff, (long long)k);
+  if (!aligned(dev_gate, 16) || !aligned(dev_up, 16) || !aligned(dev_dst, 16)) return fail(DISCO_EINVAL, "misaligned pointer");
+  hipStream_t st = static_cast<hipStream_t>(s);
+  HIP_TRY(launch_pack(static_cast<const bf16_t*>(dev_gate), d_ff, k, static_cast<bf16_t*>(dev_dst), 2, 0, st), "pack launch");
+  HIP_TRY(launch_pack(static_cast<const bf16_t*>(dev_up), d_ff, k, static_cast<bf16_t*>(dev_dst), 2, 1, st), "pack launch");
+  return DISCO_OK;
+}
+
+int disco_model_create(const disco_model_desc* desc, const disco_model_weights* w, disco_model** out) {
+  if (!desc || !w || !out) return fail(DISCO_EINVAL, "null argument");
+  const disco_model_desc& d = *desc;
+  if (d.family != DISCO_FAMILY_A && d.family != DISCO_FAMILY_B) return fail(DISCO_EINVAL, "unknown family %d", d.family);
+  if (d.n_layers < 1 || d.d_model < 32 || d.d_model % 32 || d.d_ff < 32 || d.d_ff % 32 || d.vocab < 16 || d.vocab % 16)
+    return fail(DISCO_EINVAL, "d_model and d_ff must be multiples of 32, vocab of 16");
+  if (d.d_head != 64 && d.d_head != 128) return fail(DISCO_EINVAL, "d_head %d unsupported (64 or 128)", d.d_head);
+  if (d.n_heads < 1 || d.n_kv_heads < 1 || d.n_heads % d.n_kv_heads) return fail(DISCO_EINVAL, "n_heads must be a multiple of n_kv_heads");
+  if (d.family == DISCO_FAMILY_A && (d.max_pos < 1 || !w->pos_emb)) return fail(DISCO_EINVAL, "family A needs a position table");
+  if (!(d.norm_eps > 0.f)) return fail(DISCO_EINVAL, "norm_eps must be positive");
+  if (!w->tok_emb || !w->layers || !w->normf_g || !w->wlm) return fail(DISCO_EINVAL, "null weight pointer");
+  if (w->tok_emb_stride < d.d_model || w->tok_emb_stride % 4) return fail(DISCO_EINVAL, "bad embedding stride");
+  if (d.family == DISCO_FAMILY_A && !w->normf_b) return fail(DISCO_EINVAL, "family A needs norm biases");
+  if (!aligned(w->tok_emb, 16) || !aligned(w->wlm, 16) || !aligned(w->normf_g, 16) || !aligned(w->normf_b, 16) || !aligned(w->pos_emb, 16))
+    return fail(DISCO_EINVAL, "misaligned weight pointer");
+  for (int l = 0; l < d.n_layers; ++l) {
+    const disco_layer_weights& L = w->layers[l];
+    if (!L.norm1_g || !L.norm2_g || !L.wqkv || !L.wo || !L.w_in || !L.w_out) return fail(DISCO_EINVAL, "null weight pointer in layer %d", l);
+    if (d.family == DISCO_FAMILY_A && (!L.norm1_b || !L.norm2_b)) return fail(DISCO_EINVAL, "family A needs norm biases (layer %d)", l);
+    const void* ps[] = {L.norm1_g, L.norm1_b, L.norm2_g, L.norm2_b, L.wqkv, L.wo, L.w_in, L.w_out};
+    for (const void* p : ps) if (!aligned(p, 16)) return fail(DISCO_EINVAL, "misaligned weight pointer in layer %d", l);
+  }
+  disco_model* m = new (std::nothrow) disco_model();
+  if (!m) return fail(DISCO_EINVAL, "out of host memory");
+  m->d = d; m->w = *w;
+  m->layers.assign(w->layers, w->layers + d.n_layers);
+  m->w.layers = m->layers.data();
+  if (d.family == DISCO_FAMILY_B) { m->w.pos_emb = nullptr; m->w.normf_b = nullptr; for (auto& L : m->layers) { L.norm1_b = nullptr; L.norm2_b = nullptr; } }
+  m->d_q = d.n_heads * d.d_head; m->d_kv = d.n_kv_heads * d.d_head; m->d_qkv = m->d_q + 2 * m->d_kv;
+  *out = m;
+  return DISCO_OK;
+}
+
+void disco_model_destroy(disco_model* m) { delete m; }
+
+static size_t kv_table_bytes(int n_pages) { return round_up(sizeof(int32_t) * (size_t)n_pages, 256); }
+
+size_t disco_kv_bytes(const disco_model* m, int capacity_tokens, int page_tokens) {
+  if (!m || capacity_tokens < 1 || page_tokens < 1) return 0;
+  const int n_pages = (capacity_tokens + page_tokens - 1) / page_tokens;
+  const size_t page_elems = (size_t)2 * m->d.n_kv_heads * page_tokens * m->d.d_head;
+  return kv_table_bytes(n_pages) + sizeof(bf16_t) * page_elems * n_pages * m->d.n_layers;
+}
+
+int disco_kv_create(const disco_model* m, void* dev_pages, size_t bytes, int capacity_tokens, int page_tokens,
+                    const int32_t* host_page_order, disco_kv** out) {
+  if (!m || !dev_pages || !out) return fail(DISCO_EINVAL, "null argument");
+  if (capacity_tokens < 1 || page_tokens < 1) return fail(DISCO_EINVAL, "capacity and page size must be positive");
+  if (!aligned(dev_pages, 256)) return fail(DISCO_EINVAL, "KV buffer must be 256-byte aligned");
+  const size_t need = disco_kv_bytes(m, capacity_tokens, page_tokens);
+  if (bytes < need) return fail(DISCO_ECAP, "KV buffer of %zu bytes, %zu needed", bytes, need);
+  const int n_pages = (capacity_tokens + page_tokens - 1) / page_tokens;
+  if (host_page_order) {
+    std::vector<char> seen(n_pages, 0);
+    for (int i = 0; i < n_pages; ++i) {
+      const int p = host_page_order[i];
+      if (p < 0 || p >= n_pages || seen[p]) return fail(DISCO_EINVAL, "page order is not a permutation");
+      seen[p] = 1;
+    }
+  }
+  disco_kv* kv = new (std::nothrow) disco_kv();
+  if (!kv) return fail(DISCO_EINVAL, "out of host memory");
+  kv->model = m; kv->page_tokens = page_tokens; kv->n_pages = n_pages;
+  kv->capacity = n_pages * page_tokens; kv->len = 0;
+  kv->pages = reinterpret_cast<bf16_t*>(static_cast<char*>(dev_pages) + kv_table_bytes(n_pages));
+  kv->layer_stride = (size_t)2 * m->d.n_kv_heads * page_tokens * m->d.d_head * n_pages;
+  kv->dev_page_table = nullptr;
+  if (host_page_order) {
+    kv->dev_page_table = static_cast<int32_t*>(dev_pages);
+    hipError_t e = hipMemcpy(kv->dev_page_table, host_page_order, sizeof(int32_t) * n_pages, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { delete kv; return hip_fail(e, "page table upload"); }
+  }
+  *out = kv;
+  return DISCO_OK;
+}
+
+void disco_kv_destroy(disco_kv* kv) { delete kv; }
+int disco_kv_len(const disco_kv* kv) { return kv ? kv->len : DISCO_EINVAL; }
+int disco_kv_pages_in_use(const disco_kv* kv) {
+  return kv ? (kv->len + kv->page_tokens - 1) / kv->page_tokens : DISCO_EINVAL;
+}
+
+int disco_kv_fill(disco_kv* kv, const void* dev_src, int ctx, disco_stream s) {
+  if (!kv || !dev_src) return fail(DISCO_EINVAL, "null argument");
+  if (ctx < 0 || ctx > kv->capacity) return fail(DISCO_ECAP, "fill of %d positions exceeds capacity %d", ctx, kv->capacity);
+  if (!aligned(dev_src, 16)) return fail(DISCO_EINVAL, "misaligned pointer");
+  if (ctx > 0) {
+    const disco_model_desc& d = kv->model->d;
+    HIP_TRY(launch_kv_fill(static_cast<const bf16_t*>(dev_src), kv->pages, kv->dev_page_table, d.n_layers, kv->n_pages,
+                           kv->page_tokens, d.n_kv_heads, d.d_head, ctx, static_cast<hipStream_t>(s)), "kv fill launch");
+  }
+  kv->len = ctx;
+  return DISCO_OK;
+}
+
+size_t disco_workspace_bytes(const disco_model* m, int max_block, int max_ctx) {
+  if (!m || max_block < 1 || max_block > DISCO_MAX_BLOCK || max_ctx < 0) return 0;
+  return carve(m, max_block, max_ctx, nullptr).total;
+}
+
+int disco_draft_step(const disco_model* draft, disco_kv* kv, const int32_t* dev_tokens_in, int n_in, float* dev_logits,
+                     void* dev_ws, size_t ws_bytes, const uint32_t* dev_gate, disco_stream s) {
+  int rc = check_forward_args(draft, kv, dev_tokens_in, n_in, dev_ws, ws_bytes);
+  if (rc) return rc;
+  if (!dev_logits || !aligned(dev_logits, 16)) return fail(DISCO_EINVAL, "logits pointer null or misaligned");
+  if (dev_gate && !aligned(dev_gate, 4)) return fail(DISCO_EINVAL, "misaligned gate pointer");
+  const Ws ws = carve(draft, n_in, kv->len + n_in, dev_ws);
+  return forward_block(draft, kv, dev_tokens_in, n_in, dev_logits, true, ws, dev_gate, static_cast<hipStream_t>(s));
+}
+
+int disco_classify(const disco_clf* clf, float* dev_logits, int vocab, float pos_feature, float tau, int force_halt,
+                   disco_clf_out* dev_out, int32_t* dev_token_next, int32_t* dev_block_slot, uint32_t* dev_gate,
+                   int32_t* dev_sl_count, const int32_t* dev_force_token, disco_stream s) {
+  if (!dev_logits || !dev_out) return fail(DISCO_EINVAL, "null argument");
+  if (vocab < 1) return fail(DISCO_EINVAL, "vocab must be positive");
+  if (!aligned(dev_logits, 4) || !aligned(dev_out, 4) || !aligned(dev_token_next, 4) || !aligned(dev_block_slot, 4) ||
+      !aligned(dev_gate, 4) || !aligned(dev_sl_count, 4) || !aligned(dev_force_token, 4))
+    return fail(DISCO_EINVAL, "misaligned pointer");
+  if (clf) {
+    if (!clf->dev_params || !aligned(clf->dev_params, 4)) return fail(DISCO_EINVAL, "classifier parameters null or misaligned");
+    if (clf->hidden < 1 || clf->hidden > DISCO_CLF_HIDDEN_MAX) return fail(DISCO_EINVAL, "classifier hidden size %d outside [1, %d]", clf->hidden, DISCO_CLF_HIDDEN_MAX);
+  }
+  ClassifyArgs a{};
+  a.logits = dev_logits; a.vocab = vocab; a.clf_params = clf ? clf->dev_params : nullptr; a.hidden = clf ? clf->hidden : 0;
+  a.pos_feature = pos_feature; a.tau = tau; a.force_halt = force_halt; a.out = dev_out; a.token_next = dev_token_next;
+  a.block_slot = dev_block_slot; a.gate = dev_gate; a.sl_count = dev_sl_count; a.force_token = dev_force_token;
+  HIP_TRY(launch_classify(a, static_cast<hipStream_t>(s)), "classify launch");
+  return DISCO_OK;
+}
+
+int disco_verify(const disco_model* target, disco_kv* kv, const int32_t* dev_block, int n_block, int32_t* dev_argmax,
+                 float* dev_logits, void* dev_ws, size_t ws_bytes, disco_stream s) {
+  int rc = check_forward_args(target, kv, dev_block, n_block, dev_ws, ws_bytes);
+  if (rc) return rc;
+  if (!dev_argmax || !aligned(dev_argmax, 4)) return fail(DISCO_EINVAL, "argmax pointer null or misaligned");
+  if (dev_logits && !aligned(dev_logits, 16)) return fail(DISCO_EINVAL, "misaligned logits pointer");
+  const Ws ws = carve(target, n_block, kv->len + n_block, dev_ws);
+  float* logits = dev_logits ? dev_logits : ws.logits;
+  hipStream_t st = static_cast<hipStream_t>(s);
+  rc = forward_block(target, kv, dev_block, n_block, logits, false, ws, nullptr, st);
+  if (rc) return rc;
+  HIP_TRY(launch_argmax_rows(logits, n_block, target->d.vocab, dev_argmax, st), "argmax launch");
+  return DISCO_OK;
+}
+
+int disco_accept(const int32_t* dev_block, const int32_t* dev_argmax, int n_block, const int32_t* dev_n_block,
+                 disco_accept_out* dev_out, disco_accept_out* host_out, disco_stream s) {
+  if (!dev_block || !dev_argmax || !dev_out) return fail(DISCO_EINVAL, "null argument");
+  if (n_block < 1 || n_block > DISCO_MAX_BLOCK) return fail(DISCO_ECAP, "block of %d tokens outside [1, %d]", n_block, DISCO_MAX_BLOCK);
+  if (!aligned(dev_block, 4) || !aligned(dev_argmax, 4) || !aligned(dev_out, 4) || !aligned(host_out, 4) || !aligned(dev_n_block, 4))
+    return fail(DISCO_EINVAL, "misaligned pointer");
+  HIP_TRY(launch_accept(dev_block, dev_argmax, n_block, dev_n_block, dev_out, host_out, static_cast<hipStream_t>(s)), "accept launch");
+  return DISCO_OK;
+}
+
+int disco_kv_rollback(disco_kv* kv, int new_len) {
+  if (!kv) return fail(DISCO_EINVAL, "null argument");
+  if (new_len < 0 || new_len > kv->len) return fail(DISCO_ESTATE, "rollback to %d outside [0, %d]", new_len, kv->len);
+  kv->len = new_len;
+  return DISCO_OK;
+}
+
+int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in, int n_in,
+                     int cap, int static_sl, float pos_feature0, float tau, const int32_t* dev_force_tokens,
+                     float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
+                     void* dev_ws, size_t ws_bytes, disco_stream s) {
+  if (cap < 1 || cap > DISCO_MAX_BLOCK - 1) return fail(DISCO_ECAP, "cap %d outside [1, %d]", cap, DISCO_MAX_BLOCK - 1);
+  if (static_sl < 0 || static_sl > cap) return fail(DISCO_EINVAL, "static_sl %d outside [0, cap]", static_sl);
+  if (n_in < 1 || n_in > 2) return fail(DISCO_EINVAL, "n_in must be 1 or 2");
+  int rc = check_forward_args(draft, kv, dev_tokens_in, n_in, dev_ws, ws_bytes);
+  if (rc) return rc;
+  if (kv->len + n_in + cap - 1 > kv->capacity) return fail(DISCO_ECAP, "KV capacity %d exceeded by the draft loop", kv->capacity);
+  if (draft->d.family == DISCO_FAMILY_A && kv->len + n_in + cap - 1 > draft->d.max_pos) return fail(DISCO_ECAP, "position table exceeded by the draft loop");
+  if (!dev_logits || !dev_steps || !dev_out) return fail(DISCO_EINVAL, "null argument");
+  if (!aligned(dev_logits, 16) || !aligned(dev_steps, 4) || !aligned(dev_out, 4) || !aligned(host_out, 4) || !aligned(dev_force_tokens, 4))
+    return fail(DISCO_EINVAL, "misaligned pointer");
+  if (clf) {
+    if (!clf->dev_params || clf->hidden < 1 || clf->hidden > DISCO_CLF_HIDDEN_MAX) return fail(DISCO_EINVAL, "bad classifier");
+  }
+  if (carve(draft, 2, kv->len + n_in + cap, nullptr).total > ws_bytes) return fail(DISCO_EINVAL, "workspace too small for the draft loop");
+  hipStream_t st = static_cast<hipStream_t>(s);
+  const Ws ws = carve(draft, 2, kv->len + n_in + cap, dev_ws);
+  HIP_TRY(launch_loop_init(ws.gate, ws.sl_count, dev_tokens_in, n_in, dev_out, st), "loop init launch");
+  const int steps = static_sl > 0 ? static_sl : cap;
+  for (int j = 1; j <= steps; ++j) {
+    rc = forward_block(draft, kv, j == 1 ? dev_tokens_in : ws.tok_next, j == 1 ? n_in : 1, dev_logits, true, ws, ws.gate, st);
+    if (rc) return rc;
+    ClassifyArgs a{};
+    a.logits = dev_logits; a.vocab = draft->d.vocab; a.clf_params = clf ? clf->dev_params : nullptr; a.hidden = clf ? clf->hidden : 0;
+    a.pos_feature = pos_feature0 + (float)(j - 1);
+    a.tau = static_sl > 0 ? -1.0e30f : tau;
+    a.force_halt = (j == steps) ? 1 : 0;
+    a.out = dev_steps + (j - 1); a.token_next = ws.tok_next; a.block_slot = dev_out->block + j; a.gate = ws.gate;
+    a.sl_count = ws.sl_count; a.force_token = dev_force_tokens ? dev_force_tokens + (j - 1) : nullptr;
+    HIP_TRY(launch_classify(a, st), "classify launch");
+  }
+  HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, st), "loop finish launch");
+  return DISCO_OK;
+}
+
+}  // extern "C"

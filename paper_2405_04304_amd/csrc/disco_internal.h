@@ -1,0 +1,84 @@
+// Internal launcher interface between the C boundary (disco_api.cpp) and the gfx950 kernels
+// (disco_kernels.hip).  Plain structs and pointers; nothing here is exported.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace disco {
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+
+// Epilogues of the skinny GEMM  Y[M x N] = X[M x K] . W[N x K]^T.
+enum Epi {
+  EPI_RESID = 0,   // out[m][n] += y           (O-projection, MLP down: residual stream update)
+  EPI_STORE = 1,   // out[m][n]  = y           (LM head logits)
+  EPI_QKV = 2,     // rotary (optional) + q store + paged K/V append
+  EPI_SWIGLU = 3,  // silu(gate) * up  -> packed activation panel
+  EPI_GELU = 4,    // gelu(y)          -> packed activation panel
+};
+
+struct GemmArgs {
+  const bf16_t* W;      // packed [N x K]
+  const bf16_t* X;      // activation panels (see xpack layout in disco_kernels.hip)
+  int KT;               // K / 32
+  int M;                // live tokens, 1..16
+  int n_rows;           // N
+  int grp;              // row-tile pairing distance for two-tile workgroups (1 = adjacent tiles)
+  const uint32_t* gate; // optional: skip when *gate != 0
+  float* out;           // RESID / STORE target, row stride ld_out
+  int64_t ld_out;
+  int only_row;         // STORE: write only this token's row to out[0..N) (-1: all rows)
+  // QKV epilogue
+  float* q; int ldq; int nq, nkv, dh; int pos0; int rope; float rope_base;
+  bf16_t* kv_layer; const int32_t* page_table; int page_tokens;
+  // packed-activation epilogues
+  bf16_t* Xout; int KT_out;
+};
+
+struct NormArgs {
+  float* h; int d; int M; int layernorm; float eps;
+  const float* g; const float* b;
+  bf16_t* Xout;                      // packed panels, K = d
+  // embedding mode (tokens != nullptr): h = tok_emb[token] (+ pos_emb[pos0 + m]) first
+  const int32_t* tokens; const bf16_t* tok_emb; int64_t tok_stride; const bf16_t* pos_emb;
+  int pos0; int vocab; int max_pos;
+  const uint32_t* gate;
+};
+
+struct AttnArgs {
+  const float* q; int ldq;
+  const bf16_t* kv_layer; const int32_t* page_table; int page_tokens;
+  int nq, nkv, dh, M, pos0; float scale;
+  float* part; int n_splits; int split_len;
+  bf16_t* Xout;                      // packed panels, K = nq * dh
+  const uint32_t* gate;
+};
+
+struct ClassifyArgs {
+  float* logits; int vocab; const float* clf_params; int hidden;
+  float pos_feature; float tau; int force_halt;
+  void* out;                         // disco_clf_out*
+  int32_t* token_next; int32_t* block_slot; uint32_t* gate; int32_t* sl_count;
+  const int32_t* force_token;
+};
+
+hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int64_t tile_mul,
+                       int64_t tile_add, hipStream_t s);
+hipError_t launch_gemm(const GemmArgs& a, int epi, hipStream_t s);
+hipError_t launch_norm(const NormArgs& a, hipStream_t s);
+hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
+hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s);
+hipError_t launch_argmax_rows(const float* logits, int M, int vocab, int32_t* out, hipStream_t s);
+hipError_t launch_accept(const int32_t* block, const int32_t* argmax, int n_block,
+                         const int32_t* dev_n_block, void* dev_out, void* host_out, hipStream_t s);
+hipError_t launch_kv_fill(const bf16_t* src, bf16_t* pages, const int32_t* page_table, int n_layers,
+                          int n_pages, int page_tokens, int nkv, int dh, int ctx, hipStream_t s);
+hipError_t launch_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in,
+                            void* dev_loop_out, hipStream_t s);
+hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void* host_loop_out,
+                              hipStream_t s);
+
+constexpr int ATTN_SPLIT_LEN = 128;  // cached positions per attention workgroup
+
+}  // namespace disco

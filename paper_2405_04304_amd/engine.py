@@ -1,0 +1,148 @@
+"""Host driver of the speculative-decoding loop over the C entry points.
+
+One iteration = disco_draft_loop (draft steps + Eq. 2 classifier, no host round trip between steps)
+-> disco_verify -> disco_accept -> disco_kv_rollback on both caches.  The host synchronises twice
+per iteration: once to learn SL (it sizes the verification block) and once to learn the accepted
+length.  This module moves token ids and lengths around; all arithmetic runs in the library."""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+class SpecEngine:
+    def __init__(self, target: B.DiscoModel, draft: Optional[B.DiscoModel], clf: Optional[B.DiscoClf],
+                 max_ctx: int, page_tokens: int = 16, page_order_target=None, page_order_draft=None):
+        self.target, self.draft, self.clf = target, draft, clf
+        self.dev = target.device
+        self.max_ctx = max_ctx
+        cap = max_ctx + B.MAX_BLOCK
+        self.kv_t = B.DiscoKV(target, cap, page_tokens, page_order_target)
+        self.ws_t = target.workspace(B.MAX_BLOCK, cap)
+        if draft is not None:
+            self.kv_d = B.DiscoKV(draft, cap, page_tokens, page_order_draft)
+            self.ws_d = draft.workspace(B.MAX_BLOCK, cap)
+            self.logits_d = torch.empty(draft.shape.vocab, dtype=torch.float32, device=self.dev)
+        self.steps = B.struct_tensor(B.ClfOut, B.MAX_BLOCK, self.dev)
+        self.loop_dev = B.struct_tensor(B.LoopOut, 1, self.dev)
+        self.loop_host = B.struct_tensor(B.LoopOut, 1, pinned=True)
+        self.acc_dev = B.struct_tensor(B.AcceptOut, 1, self.dev)
+        self.acc_host = B.struct_tensor(B.AcceptOut, 1, pinned=True)
+        self.argmax = torch.zeros(B.MAX_BLOCK, dtype=torch.int32, device=self.dev)
+        self.tok_in = torch.zeros(B.MAX_BLOCK, dtype=torch.int32, device=self.dev)
+        self.tok_stage = torch.zeros(B.MAX_BLOCK, dtype=torch.int32, pin_memory=True)
+
+    # -- helpers ---------------------------------------------------------------------------------
+    def _put_tokens(self, toks: Sequence[int]) -> None:
+        n = len(toks)
+        self.tok_stage[:n] = torch.as_tensor(list(toks), dtype=torch.int32)
+        self.tok_in[:n].copy_(self.tok_stage[:n], non_blocking=True)
+
+    def reset(self) -> None:
+        B.disco_kv_rollback(self.kv_t, 0)
+        if self.draft is not None:
+            B.disco_kv_rollback(self.kv_d, 0)
+
+    def prefill(self, tokens: Sequence[int]) -> None:
+        """Feed the prompt through both models in blocks of DISCO_MAX_BLOCK tokens."""
+        toks = torch.as_tensor(list(tokens), dtype=torch.int32).to(self.dev)
+        for model, kv, ws in ((self.target, self.kv_t, self.ws_t),) + (
+                ((self.draft, self.kv_d, self.ws_d),) if self.draft is not None else ()):
+            for i in range(0, len(tokens), B.MAX_BLOCK):
+                n = min(B.MAX_BLOCK, len(tokens) - i)
+                B.disco_verify(model, kv, toks.data_ptr() + 4 * i, n, self.argmax, None, ws)
+        torch.cuda.synchronize(self.dev)
+
+    def greedy(self, prompt: Sequence[int], max_new: int) -> List[int]:
+        """Plain greedy decoding of the target (verification blocks of one token)."""
+        self.reset()
+        self.prefill(prompt[:-1])
+        out, last = [], int(prompt[-1])
+        for _ in range(max_new):
+            self._put_tokens([last])
+            B.disco_verify(self.target, self.kv_t, self.tok_in, 1, self.argmax, None, self.ws_t)
+            last = int(self.argmax[0].item())
+            out.append(last)
+        return out
+
+    # -- the loop --------------------------------------------------------------------------------
+    def generate(self, prompt: Sequence[int], max_new: int, policy: Dict, force: Optional[Dict] = None,
+                 trace: bool = False, do_prefill: bool = True) -> Dict:
+        mode = policy["mode"]
+        assert mode in ("static", "disco")
+        pos_mode = policy.get("pos_mode", "absolute")
+        cap_policy = policy["gamma"] if mode == "static" else policy["sl_max"]
+        tau = float(policy.get("tau", 0.0))
+        if do_prefill:
+            self.reset()
+            self.prefill(prompt[:-1])
+        force_dev = None
+        if force is not None:
+            ft = torch.where(torch.as_tensor(force["mask"][:max_new]),
+                             torch.as_tensor(force["tokens"][:max_new], dtype=torch.int32),
+                             torch.full((max_new,), -1, dtype=torch.int32))
+            force_dev = torch.cat([ft.to(torch.int32), torch.full((B.MAX_BLOCK,), -1, dtype=torch.int32)]).to(self.dev)
+        seq = [int(t) for t in prompt]
+        n_prompt = len(seq)
+        iters: List[Dict] = []
+        n_draft_fwd = n_target_fwd = 0
+        loop_block_ptr = self.loop_dev.data_ptr() + 4
+        while len(seq) - n_prompt < max_new:
+            emitted = len(seq) - n_prompt
+            remaining = max_new - emitted
+            cap = min(cap_policy, remaining - 1)
+            ctx_t = self.kv_t.len
+            steps_rec = None
+            if cap >= 1:
+                len_d0 = self.kv_d.len
+                pending = seq[len_d0:]
+                assert 1 <= len(pending) <= 2
+                self._put_tokens(pending)
+                B.disco_draft_loop(self.draft, self.kv_d, self.clf, self.tok_in,
+                                   len(pending), cap, cap if mode == "static" else 0,
+                                   float(emitted + 1) if pos_mode == "absolute" else 1.0, tau,
+                                   (force_dev.data_ptr() + 4 * emitted) if force_dev is not None else None,
+                                   self.logits_d, self.steps, self.loop_dev, self.loop_host, self.ws_d)
+                torch.cuda.current_stream().synchronize()
+                lo = B.LoopOut.from_buffer_copy(self.loop_host.numpy().tobytes())
+                sl = lo.sl
+                block = list(lo.block[:sl + 1])
+                B.disco_kv_rollback(self.kv_d, len_d0 + len(pending) + sl - 1)
+                n_draft_fwd += sl
+                if trace:
+                    raw = self.steps.cpu().numpy().tobytes()
+                    sz = C.sizeof(B.ClfOut)
+                    steps_rec = [B.ClfOut.from_buffer_copy(raw[i * sz:(i + 1) * sz]) for i in range(sl)]
+            else:
+                sl, block = 0, [seq[-1]]
+                lo = B.LoopOut()
+                lo.sl = 0
+                lo.block[0] = seq[-1]
+                self.loop_dev.copy_(torch.frombuffer(bytearray(bytes(lo)), dtype=torch.uint8))
+            B.disco_verify(self.target, self.kv_t, loop_block_ptr, sl + 1, self.argmax, None, self.ws_t)
+            B.disco_accept(loop_block_ptr, self.argmax, sl + 1, self.acc_dev, self.acc_host)
+            torch.cuda.current_stream().synchronize()
+            n_target_fwd += 1
+            acc = B.AcceptOut.from_buffer_copy(self.acc_host.numpy().tobytes())
+            n = acc.n
+            emit = list(acc.emit[:n + 1])[:remaining]
+            seq.extend(emit)
+            B.disco_kv_rollback(self.kv_t, ctx_t + n + 1)
+            if self.draft is not None and self.kv_d.len > ctx_t + n + 1:
+                B.disco_kv_rollback(self.kv_d, ctx_t + n + 1)
+            it = {"sl": sl, "n": n, "block": block, "emit": emit, "ctx": ctx_t}
+            if trace:
+                it["target_argmax"] = self.argmax[:sl + 1].tolist()
+                it["steps"] = steps_rec
+            iters.append(it)
+        hist: Dict[int, int] = {}
+        for it in iters:
+            hist[it["sl"]] = hist.get(it["sl"], 0) + 1
+        return {"tokens": seq[n_prompt:], "iterations": iters, "n_iterations": len(iters),
+                "n_draft_forwards": n_draft_fwd, "n_target_forwards": n_target_fwd,
+                "sl_hist": dict(sorted(hist.items()))}

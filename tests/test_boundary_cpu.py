@@ -1,0 +1,130 @@
+"""The C boundary without a GPU: the library loads, exports every declared symbol, and rejects bad
+arguments on the host before any launch (fake device addresses are never dereferenced)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2405_04304_amd as D
+from paper_2405_04304_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000  # 256-byte aligned address that is never touched
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "disco.h")).read()
+    return sorted(set(re.findall(r"\b(disco_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.lib()
+    names = _declared()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def _model(family=1, **over):
+    d = dict(family=family, n_layers=2, d_model=64, n_heads=2, d_head=64, n_kv_heads=2, d_ff=128,
+             vocab=256, max_pos=64, norm_eps=1e-5, rope_base=10000.0)
+    d.update(over)
+    desc = B.ModelDesc(*[d[k] for k in ("family", "n_layers", "d_model", "n_heads", "d_head", "n_kv_heads",
+                                        "d_ff", "vocab", "max_pos", "norm_eps", "rope_base")])
+    layers = (B.LayerWeights * d["n_layers"])()
+    for L in layers:
+        for f, _ in B.LayerWeights._fields_:
+            setattr(L, f, FAKE)
+    mw = B.ModelWeights(FAKE, d["d_model"], FAKE, layers, FAKE, FAKE, FAKE)
+    h = C.c_void_p()
+    rc = B.lib().disco_model_create(C.byref(desc), C.byref(mw), C.byref(h))
+    return rc, h
+
+
+def test_model_create_validation():
+    rc, h = _model()
+    assert rc == 0 and h.value
+    B.lib().disco_model_destroy(h)
+    assert _model(family=7)[0] == B.EINVAL
+    assert _model(d_head=48)[0] == B.EINVAL
+    assert _model(d_model=65)[0] == B.EINVAL
+    assert _model(n_heads=3, n_kv_heads=2)[0] == B.EINVAL
+    assert _model(vocab=250)[0] == B.EINVAL
+    assert "vocab" in B.last_error() or "multiples" in B.last_error()
+
+
+def _kv(model, capacity=40, page=16):
+    nbytes = B.lib().disco_kv_bytes(model, capacity, page)
+    h = C.c_void_p()
+    rc = B.lib().disco_kv_create(model, FAKE, nbytes, capacity, page, None, C.byref(h))
+    return rc, h, nbytes
+
+
+def test_kv_and_rollback_host_logic():
+    rc, m = _model()
+    assert rc == 0
+    lib = B.lib()
+    rc, kv, nbytes = _kv(m)
+    assert rc == 0 and nbytes > 0
+    # capacity rounds up to whole pages: 40 -> 48
+    assert lib.disco_kv_len(kv) == 0 and lib.disco_kv_pages_in_use(kv) == 0
+    assert lib.disco_kv_rollback(kv, 0) == 0               # no-op on an empty cache
+    assert lib.disco_kv_rollback(kv, 1) == B.ESTATE
+    assert lib.disco_kv_rollback(kv, -1) == B.ESTATE
+    assert lib.disco_kv_rollback(None, 0) == B.EINVAL
+    h = C.c_void_p()
+    assert lib.disco_kv_create(m, FAKE, nbytes - 1, 40, 16, None, C.byref(h)) == B.ECAP
+    assert lib.disco_kv_create(m, FAKE + 8, nbytes, 40, 16, None, C.byref(h)) == B.EINVAL
+    bad = (C.c_int32 * 3)(0, 0, 2)
+    assert lib.disco_kv_create(m, FAKE, nbytes, 40, 16, bad, C.byref(h)) == B.EINVAL
+    lib.disco_kv_destroy(kv)
+    lib.disco_model_destroy(m)
+
+
+def test_forward_calls_reject_bad_arguments_before_any_launch():
+    rc, m = _model()
+    rc2, other = _model()
+    lib = B.lib()
+    rc, kv, _ = _kv(m)
+    ws = lib.disco_workspace_bytes(m, 16, 48)
+    assert ws > 0 and lib.disco_workspace_bytes(m, 17, 48) == 0
+    # null pointers
+    assert lib.disco_draft_step(m, kv, None, 1, FAKE, FAKE, ws, None, None) == B.EINVAL
+    assert lib.disco_draft_step(m, kv, FAKE, 1, None, FAKE, ws, None, None) == B.EINVAL
+    assert lib.disco_verify(m, kv, FAKE, 1, None, None, FAKE, ws, None) == B.EINVAL
+    # block length outside [1, 16]
+    assert lib.disco_verify(m, kv, FAKE, 0, FAKE, None, FAKE, ws, None) == B.ECAP
+    assert lib.disco_verify(m, kv, FAKE, 17, FAKE, None, FAKE, ws, None) == B.ECAP
+    assert lib.disco_draft_step(m, kv, FAKE, 0, FAKE, FAKE, ws, None, None) == B.ECAP
+    # workspace too small / misaligned
+    assert lib.disco_verify(m, kv, FAKE, 4, FAKE, None, FAKE, 1024, None) == B.EINVAL
+    assert lib.disco_verify(m, kv, FAKE, 4, FAKE, None, FAKE + 4, ws, None) == B.EINVAL
+    # KV handle of another model
+    assert lib.disco_verify(other, kv, FAKE, 4, FAKE, None, FAKE, ws, None) == B.ESTATE
+    # accept / classify / loop argument checks
+    assert lib.disco_accept(FAKE, FAKE, 0, None, FAKE, None, None) == B.ECAP
+    assert lib.disco_accept(None, FAKE, 4, None, FAKE, None, None) == B.EINVAL
+    assert lib.disco_classify(None, None, 256, 1.0, 0.5, 0, FAKE, None, None, None, None, None, None) == B.EINVAL
+    clf = B.Clf(FAKE, 300)
+    assert lib.disco_classify(C.byref(clf), FAKE, 256, 1.0, 0.5, 0, FAKE, None, None, None, None, None, None) == B.EINVAL
+    assert lib.disco_draft_loop(m, kv, None, FAKE, 1, 16, 0, 1.0, 0.5, None, FAKE, FAKE, FAKE, None, FAKE, ws, None) == B.ECAP
+    assert lib.disco_draft_loop(m, kv, None, FAKE, 3, 4, 0, 1.0, 0.5, None, FAKE, FAKE, FAKE, None, FAKE, ws, None) == B.EINVAL
+    assert lib.disco_pack_weight(FAKE, 17, 32, FAKE, None) == B.EINVAL
+    assert lib.disco_pack_weight(FAKE, 16, 40, FAKE, None) == B.EINVAL
+    assert lib.disco_kv_len(kv) == 0                         # nothing advanced the cache
+    lib.disco_kv_destroy(kv)
+    lib.disco_model_destroy(m)
+    lib.disco_model_destroy(other)
+
+
+def test_kv_capacity_is_enforced_on_the_host():
+    rc, m = _model(family=0)
+    lib = B.lib()
+    rc, kv, _ = _kv(m, capacity=16, page=16)
+    ws = lib.disco_workspace_bytes(m, 16, 64)
+    # a fill that would exceed the capacity is refused, as is a block that does not fit
+    assert lib.disco_kv_fill(kv, FAKE, 17, None) == B.ECAP
+    assert lib.disco_kv_len(kv) == 0
+    lib.disco_kv_destroy(kv)
+    lib.disco_model_destroy(m)

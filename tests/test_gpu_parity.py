@@ -1,0 +1,391 @@
+"""GPU parity: the HIP path, called through the C boundary, against the CPU oracle on the same
+seeded inputs.
+
+Tolerances.  Logits: the workload statement allows max |x_gpu - x_ref| <= 2e-2 * max |x_ref| per row
+(bf16 weights, fp32-vs-fp64 arithmetic); the kernels keep activations at fp32 grade (bf16 hi/lo
+split), so the tests also hold a much tighter bound, 2e-3, to catch regressions.  Token ids and halt
+bits must be identical except where the oracle flags a top-2 logit margin below 2e-2 or a classifier
+score within 1e-3 of the threshold.  Integer results (acceptance, rollback lengths) are bit-exact."""
+import ctypes as C
+import math
+
+import pytest
+import torch
+
+import paper_2405_04304_amd as D
+from paper_2405_04304_amd import binding as B
+from paper_2405_04304_amd.engine import SpecEngine
+from oracle import disco_oracle as O
+from workloads import synth as W
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 2e-2      # the stated bar
+REL_TIGHT = 2e-3    # what the fp32-grade path actually holds
+MARGIN = 2e-2
+
+
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch.device("cuda:0")
+
+
+def check_logits(got: torch.Tensor, ref: torch.Tensor, what=""):
+    got, ref = got.detach().cpu().double(), ref.double()
+    assert got.shape == ref.shape
+    assert torch.isfinite(got).all(), what
+    worst = 0.0
+    for r in range(ref.shape[0]):
+        err = float((got[r] - ref[r]).abs().max())
+        scale = float(ref[r].abs().max())
+        worst = max(worst, err / scale)
+        assert err <= REL_TOL * scale, (what, r, err, scale)
+        assert err <= REL_TIGHT * scale, (what, "tight", r, err, scale)
+    print(f"[parity] {what}: max rel err {worst:.3e} (bar {REL_TOL}, tight {REL_TIGHT})", flush=True)
+    return worst
+
+
+def check_argmax(got, ref_logits: torch.Tensor, what=""):
+    for r, g in enumerate(got):
+        want = O.argmax_lowest(ref_logits[r])
+        if int(g) != want:
+            assert O.top2_margin(ref_logits[r]) < MARGIN, (what, r, int(g), want)
+
+
+def setup_pair(shape, seed, kv_ctx=0, kv_seed=2, page_tokens=16, permute=False, capacity=None,
+               gain_jitter=0.0, sigma=0.02, weights=None):
+    """Oracle model + GPU model on the same bf16 weights, optionally with the same pre-filled KV."""
+    w = weights if weights is not None else W.make_weights(shape, seed, "bf16", sigma=sigma, gain_jitter=gain_jitter)
+    om = O.Model(shape, w, kv_bf16=True)
+    gm = B.DiscoModel(shape, w, dev())
+    capacity = capacity or (kv_ctx + 64)
+    okv = om.new_cache(capacity + 16)
+    order = None
+    if permute:
+        n_pages = (capacity + page_tokens - 1) // page_tokens
+        g = torch.Generator().manual_seed(77)
+        order = torch.randperm(n_pages, generator=g).tolist()
+    gkv = B.DiscoKV(gm, capacity, page_tokens, order)
+    if kv_ctx:
+        fill = W.make_kv_fill(shape, kv_ctx, kv_seed)
+        okv.fill(fill)
+        gkv.fill(fill.to(dev()))
+    ws = gm.workspace(16, capacity)
+    return om, gm, okv, gkv, ws
+
+
+# ---- Eq. 2 kernel --------------------------------------------------------------------------------
+
+def _run_classify(logits, clf_params, pos, tau, force=None, force_halt=0):
+    d = dev()
+    x = logits.to(torch.float32).to(d).contiguous()
+    clf = B.DiscoClf(clf_params, d) if clf_params is not None else None
+    out = B.struct_tensor(B.ClfOut, 1, d)
+    ft = torch.tensor([force if force is not None else -1], dtype=torch.int32, device=d)
+    B.disco_classify(clf, x, x.numel(), float(pos), float(tau), force_halt, out, force_token=ft)
+    torch.cuda.synchronize()
+    return B.read_struct(B.ClfOut, out), x.cpu()
+
+
+@pytest.mark.parametrize("V", [16, 1001, 4096, 32000, 49152])
+def test_classify_matches_oracle(V):
+    clf = W.make_classifier(100)
+    g = torch.Generator().manual_seed(V)
+    for trial in range(3):
+        x = (torch.randn(V, generator=g) * (0.5 + trial)).to(torch.float32)
+        pos = 1 + 7 * trial
+        r, _ = _run_classify(x, clf, pos, 0.5)
+        f = O.features(x.double(), pos)
+        assert r.executed == 1
+        assert r.token == f["token"]
+        got = torch.tensor(list(r.feats), dtype=torch.float64)
+        assert torch.allclose(got, f["feats"].double(), rtol=2e-5, atol=1e-6), (V, trial, got, f["feats"])
+        c = O.classifier(f["feats"], clf)
+        assert abs(r.score - c) < 1e-5
+        if abs(c - 0.5) > 1e-3:
+            assert r.halt == int(c < 0.5)
+
+
+def test_classify_closed_forms_ties_and_forcing():
+    clf = W.make_classifier(100)
+    V = 32000
+    # all-equal logits: p = 1/V, H = ln V, token 0; exercises the massive-tie path
+    r, _ = _run_classify(torch.full((V,), 1.5), clf, 3, 0.5)
+    assert r.token == 0
+    assert all(abs(p - 1.0 / V) < 1e-9 for p in list(r.feats)[:10])
+    assert abs(r.feats[10] - math.log(V)) < 1e-4
+    # single spike
+    x = torch.zeros(V)
+    x[12345] = 5.0
+    r, _ = _run_classify(x, clf, 3, 0.5)
+    z = math.exp(5.0) + V - 1
+    assert r.token == 12345 and abs(r.feats[0] - math.exp(5.0) / z) < 1e-6
+    assert abs(r.feats[1] - 1 / z) < 1e-9 and abs(r.feats[9] - 1 / z) < 1e-9
+    # forcing: the chosen logit becomes max + 4, in the features and in the logits buffer
+    g = torch.Generator().manual_seed(3)
+    x = torch.randn(V, generator=g)
+    r, xb = _run_classify(x, clf, 9, 0.5, force=777)
+    xo = x.double().clone()
+    xo[777] = xo.max() + 4.0
+    f = O.features(xo, 9)
+    assert r.token == 777 and abs(float(xb[777]) - float(xo[777])) < 1e-6
+    assert torch.allclose(torch.tensor(list(r.feats), dtype=torch.float64), f["feats"].double(), rtol=2e-5, atol=1e-6)
+    # no classifier: score NaN, halt only when forced
+    r, _ = _run_classify(x, None, 1, 0.5)
+    assert math.isnan(r.score) and r.halt == 0
+    r, _ = _run_classify(x, None, 1, 0.5, force_halt=1)
+    assert r.halt == 1
+    # tau above every score halts, tau = 0 never does
+    assert _run_classify(x, clf, 1, 1.1)[0].halt == 1 and _run_classify(x, clf, 1, 0.0)[0].halt == 0
+
+
+# ---- acceptance ------------------------------------------------------------------------------------
+
+def test_accept_bit_exact():
+    d = dev()
+    g = torch.Generator().manual_seed(11)
+    cases = [([100, 1, 2, 3, 4, 5], [1, 2, 3, 40, 50, 60])]          # Fig. 1: SL 5, three accepted
+    cases += [([9], [4]), ([9, 1, 2], [7, 2, 3]), ([9, 1, 2], [1, 2, 3]), ([9, 1, 2, 3], [1, 5, 3, 4])]
+    for _ in range(40):
+        nb = int(torch.randint(1, 17, (1,), generator=g))
+        a = torch.randint(0, 50, (nb,), generator=g).tolist()
+        n_true = int(torch.randint(0, nb, (1,), generator=g))
+        blk = [7] + a[:nb - 1]
+        if n_true < nb - 1:
+            blk[n_true + 1] = a[n_true] + 1                            # first mismatch after n_true
+        cases.append((blk, a))
+    out = B.struct_tensor(B.AcceptOut, 1, d)
+    host = B.struct_tensor(B.AcceptOut, 1, pinned=True)
+    for blk, a in cases:
+        tb = torch.tensor(blk + [0] * (16 - len(blk)), dtype=torch.int32, device=d)
+        ta = torch.tensor(a + [0] * (16 - len(a)), dtype=torch.int32, device=d)
+        B.disco_accept(tb, ta, len(blk), out, host)
+        torch.cuda.synchronize()
+        r = B.read_struct(B.AcceptOut, out)
+        rh = B.AcceptOut.from_buffer_copy(host.numpy().tobytes())
+        n, emit = O.accept(blk, a)
+        assert (r.n, list(r.emit[:r.n_emit])) == (n, emit) and r.n_emit == n + 1
+        assert (rh.n, list(rh.emit[:rh.n_emit])) == (n, emit)
+
+
+# ---- draft step -----------------------------------------------------------------------------------
+
+SMALL_B = W.ModelShape("B", 2, 128, 2, 64, 2, 256, 512)
+SMALL_B_GQA = W.ModelShape("B", 2, 256, 4, 64, 2, 288, 1008)
+SMALL_A = W.ModelShape("A", 2, 128, 2, 64, 2, 256, 512, max_pos=512)
+SMALL_A_MQA = W.ModelShape("A", 2, 256, 2, 128, 1, 512, 496, max_pos=512)
+
+
+@pytest.mark.parametrize("shape,ctx,page,permute", [
+    (SMALL_B, 0, 16, False), (SMALL_B, 37, 16, True), (SMALL_B_GQA, 300, 8, True),
+    (SMALL_A, 129, 16, True), (SMALL_A_MQA, 200, 32, True)])
+def test_draft_step_small_models(shape, ctx, page, permute):
+    om, gm, okv, gkv, ws = setup_pair(shape, 5, kv_ctx=ctx, page_tokens=page, permute=permute, gain_jitter=0.2,
+                                      sigma=0.05, capacity=ctx + 40)
+    d = dev()
+    logits = torch.empty(shape.vocab, dtype=torch.float32, device=d)
+    toks = W.make_tokens(3, 12, shape.vocab).tolist()
+    i = 0
+    for n_in in (1, 2, 1, 1, 2, 1):                      # single-token steps and 2-token catch-up steps
+        t = torch.tensor(toks[i:i + n_in], dtype=torch.int32, device=d)
+        B.disco_draft_step(gm, gkv, t, n_in, logits, ws)
+        torch.cuda.synchronize()
+        ref = om.forward(toks[i:i + n_in], okv)[-1:]
+        check_logits(logits[None], ref, f"draft_step {shape.family} ctx {okv.len} n_in {n_in}")
+        i += n_in
+        assert gkv.len == okv.len
+
+
+@pytest.mark.parametrize("ctx", [512, 2048])
+def test_draft_step_68m_shape(ctx):
+    shape = W.CFG1_DRAFT
+    om, gm, okv, gkv, ws = setup_pair(shape, 0, kv_ctx=ctx, capacity=ctx + 32)
+    d = dev()
+    logits = torch.empty(shape.vocab, dtype=torch.float32, device=d)
+    clf = W.make_classifier(100)
+    gclf = B.DiscoClf(clf, d)
+    out = B.struct_tensor(B.ClfOut, 1, d)
+    tok = int(W.make_tokens(3, 1, shape.vocab)[0])
+    for step in range(3):
+        t = torch.tensor([tok], dtype=torch.int32, device=d)
+        B.disco_draft_step(gm, gkv, t, 1, logits, ws)
+        B.disco_classify(gclf, logits, shape.vocab, float(step + 1), 0.5, 0, out)
+        torch.cuda.synchronize()
+        ref = om.forward([tok], okv)
+        check_logits(logits[None], ref, f"68M draft step ctx {ctx}+{step}")
+        r = B.read_struct(B.ClfOut, out)
+        f = O.features(ref[0], step + 1)
+        if f["margin"] >= MARGIN:
+            assert r.token == f["token"]
+        assert torch.allclose(torch.tensor(list(r.feats)), f["feats"], rtol=1e-3, atol=1e-6)
+        c = O.classifier(f["feats"], clf)
+        assert abs(r.score - c) < 1e-4
+        if abs(c - 0.5) > 1e-3:
+            assert r.halt == int(c < 0.5)
+        tok = f["token"]
+
+
+# ---- verification block -----------------------------------------------------------------------------
+
+def _verify_case(shape, seed, ctx, ms, page=16, permute=True, what="", weights=None, jitter=0.0):
+    om, gm, okv, gkv, ws = setup_pair(shape, seed, kv_ctx=ctx, page_tokens=page, permute=permute,
+                                      capacity=ctx + 24, gain_jitter=jitter, weights=weights)
+    d = dev()
+    for M in ms:
+        blk = W.make_tokens(30 + M, M, shape.vocab).tolist()
+        tb = torch.tensor(blk, dtype=torch.int32, device=d)
+        am = torch.zeros(16, dtype=torch.int32, device=d)
+        lg = torch.empty(M, shape.vocab, dtype=torch.float32, device=d)
+        B.disco_verify(gm, gkv, tb, M, am, lg, ws)
+        torch.cuda.synchronize()
+        assert gkv.len == ctx + M
+        ref = om.forward(blk, okv)
+        check_logits(lg, ref, f"verify {what} ctx {ctx} M {M}")
+        check_argmax(am[:M].tolist(), ref, what)
+        # arg-max without the optional logits output must be the same tokens
+        B.disco_kv_rollback(gkv, ctx)
+        am2 = torch.zeros(16, dtype=torch.int32, device=d)
+        B.disco_verify(gm, gkv, tb, M, am2, None, ws)
+        torch.cuda.synchronize()
+        assert am2[:M].tolist() == am[:M].tolist()
+        B.disco_kv_rollback(gkv, ctx)
+        okv.rollback(ctx)
+    return om, gm, okv, gkv, ws
+
+
+def test_verify_small_models_all_block_lengths():
+    _verify_case(SMALL_B, 6, 100, range(1, 17), page=8, what="B small", jitter=0.2)
+    _verify_case(SMALL_A_MQA, 7, 130, (1, 3, 8, 9, 16), page=16, what="A MQA small", jitter=0.2)
+    _verify_case(SMALL_B_GQA, 8, 0, (1, 5, 16), page=16, what="B GQA empty cache")
+
+
+def test_verify_13b_shape_two_layers():
+    shape = W.scaled_shape(W.CFG2_TARGET, n_layers=2)
+    _verify_case(shape, 0, 1024, (1, 2, 4, 8, 11), what="13B-shape x2 layers")
+    _verify_case(shape, 0, 1000, (11,), page=16, what="13B-shape ragged ctx")
+
+
+def test_verify_mqa_code_model_shape_two_layers():
+    shape = W.scaled_shape(W.CFG3_TARGET, n_layers=2, max_pos=2304)
+    _verify_case(shape, 0, 2048, (1, 11), what="15B-MQA-shape x2 layers")
+
+
+def test_verify_rollback_causality_and_m1_equals_draft_step():
+    shape = SMALL_B_GQA
+    om, gm, okv, gkv, ws = setup_pair(shape, 9, kv_ctx=50, page_tokens=8, permute=True, capacity=120)
+    d = dev()
+    a = torch.tensor([5, 6, 7, 8, 9, 10, 11, 12, 13], dtype=torch.int32, device=d)
+    b = torch.tensor([5, 6, 70, 80, 90, 1, 2, 3, 4], dtype=torch.int32, device=d)
+    am = torch.zeros(16, dtype=torch.int32, device=d)
+    la = torch.empty(9, shape.vocab, dtype=torch.float32, device=d)
+    lb = torch.empty_like(la)
+    lf = torch.empty_like(la)
+    B.disco_verify(gm, gkv, a, 9, am, la, ws)
+    B.disco_kv_rollback(gkv, 50)
+    B.disco_kv_rollback(gkv, 50)                          # idempotent
+    assert gkv.len == 50 and gkv.pages_in_use == 7
+    B.disco_verify(gm, gkv, b, 9, am, lb, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(la[:2], lb[:2])                    # rows that see equal prefixes: bitwise equal
+    assert not torch.equal(la[2], lb[2])
+    # fresh cache, block B only: the stale suffix left by block A must be dead
+    om2, gm2, okv2, gkv2, ws2 = setup_pair(shape, 9, kv_ctx=50, page_tokens=8, permute=True, capacity=120)
+    B.disco_verify(gm2, gkv2, b, 9, am, lf, ws2)
+    torch.cuda.synchronize()
+    assert torch.equal(lf, lb)
+    with pytest.raises(B.DiscoError) as e:
+        B.disco_kv_rollback(gkv, 60)
+    assert e.value.code == B.ESTATE
+    # a one-token verification block is the same computation as a draft step
+    B.disco_kv_rollback(gkv, 50)
+    l1 = torch.empty(1, shape.vocab, dtype=torch.float32, device=d)
+    B.disco_verify(gm, gkv, b, 1, am, l1, ws)
+    B.disco_kv_rollback(gkv, 50)
+    l2 = torch.empty(shape.vocab, dtype=torch.float32, device=d)
+    B.disco_draft_step(gm, gkv, b, 1, l2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(l1[0], l2)
+    # capacity errors come from the host and leave the length alone
+    B.disco_kv_rollback(gkv, 50)
+    with pytest.raises(B.DiscoError) as e:
+        big = B.DiscoKV(gm, 16, 16)
+        B.disco_verify(gm, big, a, 9, am, None, ws)
+        B.disco_verify(gm, big, a, 9, am, None, ws)
+    assert e.value.code == B.ECAP
+
+
+# ---- the loop ----------------------------------------------------------------------------------------
+
+def _compare_runs(gpu, orc, tau=None):
+    """Token streams and schedules must agree up to the first flagged position."""
+    diverged = False
+    for gi, oi in zip(gpu["iterations"], orc["iterations"]):
+        flagged = any(m < MARGIN for m in oi["target_margins"]) or any(
+            s["margin"] < MARGIN or (tau is not None and abs(s["score"] - tau) <= 1e-3) for s in oi["steps"])
+        if (gi["sl"], gi["n"], gi["block"], gi["emit"]) != (oi["sl"], oi["n"], oi["block"], oi["emit"]):
+            assert flagged, (gi, {k: oi[k] for k in ("sl", "n", "block", "emit")})
+            diverged = True
+            break
+        if "steps" in gi and gi["steps"] is not None:
+            for gs, os_ in zip(gi["steps"], oi["steps"]):
+                assert torch.allclose(torch.tensor(list(gs.feats)), os_["feats"], rtol=2e-3, atol=1e-5)
+                assert abs(gs.score - os_["score"]) < 1e-3
+    return diverged
+
+
+def test_loop_cfg0_matches_oracle_and_greedy():
+    shape_t, shape_d = W.CFG0_TARGET, W.CFG0_DRAFT
+    tw = W.make_weights(shape_t, 0, "bf16")
+    dw = W.early_exit_draft(tw, 1)
+    ot, od = O.Model(shape_t, tw, kv_bf16=True), O.Model(shape_d, dw, kv_bf16=True)
+    clf = W.make_classifier(100)
+    prompt = W.make_prompt(1, 32, shape_t.vocab).tolist()
+    ref, margins = O.greedy_target(ot, prompt, 64)
+    d = dev()
+    gt, gd = B.DiscoModel(shape_t, tw, d), B.DiscoModel(shape_d, dw, d)
+    eng = SpecEngine(gt, gd, B.DiscoClf(clf, d), max_ctx=112, page_tokens=16)
+    # GPU greedy == oracle greedy up to the first flagged position
+    gg = eng.greedy(prompt, 64)
+    for p, (a, b) in enumerate(zip(gg, ref)):
+        if a != b:
+            assert margins[p] < MARGIN, (p, a, b, margins[p])
+            break
+    n_div = 0
+    for pol in ([{"mode": "static", "gamma": g} for g in (0, 1, 5, 8)]
+                + [{"mode": "disco", "tau": t, "sl_max": 8, "pos_mode": pm}
+                   for t in (0.5, 0.55, 0.6, 0.9) for pm in ("absolute", "block")]):
+        orc = O.spec_decode(ot, od, clf, prompt, 64, pol)
+        gpu = eng.generate(prompt, 64, pol, trace=True)
+        assert len(gpu["tokens"]) == 64
+        n_div += _compare_runs(gpu, orc, pol.get("tau"))
+        # whatever the schedule, the GPU's speculative text equals the GPU's own greedy text
+        # unless a flagged position intervened
+        if gpu["tokens"] != gg:
+            p = next(i for i, (a, b) in enumerate(zip(gpu["tokens"], gg)) if a != b)
+            assert margins[p] < MARGIN
+    print(f"[parity] cfg0 loop: {n_div} of 12 policy runs diverged at a flagged position", flush=True)
+
+
+def test_loop_forced_acceptance_small_pair():
+    """Independent draft, 60 % forced agreement (the full-loop workload's recipe), small shapes."""
+    st = W.ModelShape("B", 2, 128, 2, 64, 2, 256, 512)
+    sd = W.ModelShape("B", 1, 128, 2, 64, 2, 256, 512)
+    tw, dw = W.make_weights(st, 0, "bf16", sigma=0.1), W.make_weights(sd, 10, "bf16", sigma=0.1)
+    ot, od = O.Model(st, tw, kv_bf16=True), O.Model(sd, dw, kv_bf16=True)
+    clf = W.make_classifier(100)
+    prompt = W.make_prompt(1, 40, st.vocab).tolist()
+    n_new = 96
+    ref, margins = O.greedy_target(ot, prompt, n_new)
+    force = {"mask": W.make_force_mask(5, n_new, 0.6), "tokens": ref}
+    d = dev()
+    eng = SpecEngine(B.DiscoModel(st, tw, d), B.DiscoModel(sd, dw, d), B.DiscoClf(clf, d), max_ctx=160, page_tokens=8)
+    for pol in ({"mode": "static", "gamma": 5}, {"mode": "disco", "tau": 0.7, "sl_max": 10, "pos_mode": "block"},
+                {"mode": "disco", "tau": 0.9, "sl_max": 10, "pos_mode": "absolute"}):
+        orc = O.spec_decode(ot, od, clf, prompt, n_new, pol, force=force)
+        assert orc["tokens"] == ref
+        gpu = eng.generate(prompt, n_new, pol, force=force, trace=True)
+        div = _compare_runs(gpu, orc, pol.get("tau"))
+        if not div:
+            assert gpu["tokens"] == ref and gpu["sl_hist"] == orc["sl_hist"]
+            assert gpu["n_draft_forwards"] == sum(it["sl"] for it in orc["iterations"])
+        assert sum(it["n"] for it in gpu["iterations"]) > n_new // 4      # forcing does produce acceptance
