@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the DISCO speculative-decoding hot path on one MI355X.
+
+Workload (full-loop configuration: 13B-class target, 68M-class draft, bf16, batch 1): a 512-token
+random prompt is prefilled, then speculative iterations run with DISCO halting (cap 10) and 60 %
+seed-forced draft/target agreement.  One "step" is one whole iteration: draft steps with the fused
+feature/classifier kernel, the target's verification forward, greedy acceptance, KV rollback.
+`value` counts the tokens emitted per second (accepted draft tokens plus the target's own token of
+every iteration), inputs resident in HBM.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(target_shape, draft_shape, tw_host, dw_host, clf, gamma, tokens_per_iter, ctx, layers_sampled):
+    """The oracle as it stands, timed on this host: gamma draft steps (full 68M-class draft) and one
+    verification block of gamma + 1 tokens through `layers_sampled` of the target's layers plus
+    embedding and LM head; the per-layer time is extrapolated to the full depth."""
+    from oracle import disco_oracle as O
+    from workloads import synth as W
+    t_all0 = time.time()
+    od = O.Model(draft_shape, dw_host, kv_bf16=True)
+    kv_d = od.new_cache(ctx + 32)
+    kv_d.fill(W.make_kv_fill(draft_shape, ctx, 2))
+    tok = 17
+    t0 = time.time()
+    for j in range(gamma):
+        logits = od.forward([tok], kv_d)[0]
+        f = O.features(logits, j + 1)
+        O.classifier(f["feats"], clf)
+        tok = f["token"]
+    t_draft = time.time() - t0
+    blk = W.make_tokens(3, gamma + 1, target_shape.vocab).tolist()
+    times = {}
+    for nl in (0, layers_sampled):
+        sh = W.scaled_shape(target_shape, n_layers=nl)
+        om = O.Model(sh, tw_host, kv_bf16=True, cache_upcast=False)
+        kv = om.new_cache(ctx + 32)
+        if nl:
+            kv.fill(W.make_kv_fill(sh, ctx, 2))
+        else:
+            kv.len = ctx
+        t0 = time.time()
+        lg = om.forward(blk, kv)
+        a = [O.argmax_lowest(lg[r]) for r in range(gamma + 1)]
+        O.accept(blk, a)
+        times[nl] = time.time() - t0
+    per_layer = (times[layers_sampled] - times[0]) / layers_sampled
+    t_verify = times[0] + per_layer * target_shape.n_layers
+    t_iter = t_draft + t_verify
+    return {
+        "value": tokens_per_iter / t_iter, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+        "sample": (f"one iteration at static lookahead {gamma}: {gamma} oracle draft steps (full draft, ctx {ctx}) "
+                   f"+ one oracle verification block of {gamma + 1} tokens through {layers_sampled} of "
+                   f"{target_shape.n_layers} target layers, embedding and LM head (per-layer time extrapolated "
+                   f"to {target_shape.n_layers}); tokens/iteration taken from the GPU run; "
+                   f"{time.time() - t_all0:.0f} s of CPU work"),
+        "draft_step_ms": 1e3 * t_draft / gamma, "verify_block_ms_extrapolated": 1e3 * t_verify,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--policy", default="disco", choices=["disco", "static"])
+    ap.add_argument("--gamma", type=int, default=5)
+    ap.add_argument("--tau", type=float, default=0.5)
+    ap.add_argument("--sl-max", type=int, default=10)
+    ap.add_argument("--alpha", type=float, default=0.6)
+    ap.add_argument("--prompt-len", type=int, default=512)
+    ap.add_argument("--layers", type=int, default=0, help="debug: truncate the target (invalidates the number)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one process, one sequence); --gpus must be 1. "
+              "The path shards by sequence across GPUs with no exchange; see DESIGN.md.", file=sys.stderr)
+        sys.exit(2)
+    assert torch.cuda.is_available(), "bench.py needs an MI355X"
+    dev = torch.device("cuda:0")
+
+    from paper_2405_04304_amd import binding as B
+    from paper_2405_04304_amd.engine import SpecEngine
+    from workloads import synth as W
+
+    target_shape = W.CFG2_TARGET if not args.layers else W.scaled_shape(W.CFG2_TARGET, n_layers=args.layers)
+    draft_shape = W.CFG1_DRAFT
+    t0 = time.time()
+    tw = W.make_weights(target_shape, 0, "bf16", device=dev)
+    dw = W.make_weights(draft_shape, 10, "bf16", device="cpu")
+    clf = W.make_classifier(100)
+    layers_sampled = min(16, target_shape.n_layers)
+    tw_host = None
+    if not args.no_cpu_baseline:
+        keep = lambda k: (not k.startswith("l")) or int(k[1:k.index(".")]) < layers_sampled
+        tw_host = {k: v.cpu() for k, v in tw.items() if keep(k)}
+    gt = B.DiscoModel(target_shape, tw, dev)
+    del tw
+    torch.cuda.empty_cache()
+    gd = B.DiscoModel(draft_shape, dw, dev)
+    log(f"[bench] weights ready in {time.time() - t0:.1f} s")
+
+    n_iter = args.warmup + args.steps
+    cap = args.gamma if args.policy == "static" else args.sl_max
+    max_new = n_iter * (cap + 1) + 2           # enough text for every iteration at full acceptance
+    prompt = W.make_prompt(1, args.prompt_len, target_shape.vocab).tolist()
+    eng = SpecEngine(gt, gd, B.DiscoClf(clf, dev), max_ctx=args.prompt_len + max_new + 16, page_tokens=16)
+
+    # untimed input shaping: the target's own greedy text decides which draft logits get forced
+    t0 = time.time()
+    n_greedy = min(max_new, int(n_iter * 3.2) + 32)
+    greedy = eng.greedy(prompt, n_greedy)
+    greedy += [0] * (max_new - n_greedy)
+    mask = W.make_force_mask(5, max_new, args.alpha)
+    mask[n_greedy:] = False
+    force = {"mask": mask, "tokens": greedy}
+    log(f"[bench] prefill + {n_greedy} greedy target tokens in {time.time() - t0:.1f} s")
+
+    policy = ({"mode": "static", "gamma": args.gamma} if args.policy == "static" else
+              {"mode": "disco", "tau": args.tau, "sl_max": args.sl_max, "pos_mode": "absolute"})
+
+    # the timed region: a hand-rolled loop over engine iterations so that exactly K are timed
+    probe_layer = target_shape.n_layers // 2
+    B.disco_probe_enable(probe_layer)
+    probe_ms, stamps = [], []
+
+    def on_iter(it):
+        torch.cuda.synchronize()
+        stamps.append(time.perf_counter())
+        probe_ms.append(B.disco_probe_read_ms())
+
+    eng.reset()
+    eng.prefill(prompt[:-1])
+    torch.cuda.synchronize()
+    stamps.append(time.perf_counter())
+    res = eng.generate(prompt, max_new, policy, force=force, do_prefill=False, on_iteration=on_iter,
+                       max_iterations=n_iter)
+    torch.cuda.synchronize()
+    B.disco_probe_enable(-1)
+    its = res["iterations"]
+    assert len(its) == n_iter, (len(its), n_iter)
+    t_timed = stamps[n_iter] - stamps[args.warmup]
+    timed = its[args.warmup:]
+    emitted = sum(len(it["emit"]) for it in timed)
+    drafted = sum(it["sl"] for it in timed)
+    accepted = sum(it["n"] for it in timed)
+    ms_per_step = 1e3 * t_timed / args.steps
+    value = emitted / t_timed
+
+    # algorithmic bytes (bf16 weights once per forward, live KV once per forward, fp32 logits)
+    def fwd_bytes(s, ctx, m):
+        w = sum(int(torch.tensor(sh).prod()) for n_, sh, kind in W.weight_specs(s)
+                if kind == "matrix" and n_ not in ("tok_emb", "pos_emb")) * 2
+        kv = s.n_layers * 2 * ctx * s.d_kv * 2
+        return w + kv + m * s.n_layers * 2 * s.d_kv * 2 + m * s.vocab * 4
+    ctx_mid = args.prompt_len + sum(len(it["emit"]) for it in its[:args.warmup]) + emitted // 2
+    iter_bytes = fwd_bytes(target_shape, ctx_mid, 1 + drafted / args.steps) + (drafted / args.steps) * fwd_bytes(draft_shape, ctx_mid, 1)
+    gemm_bytes = 2 * target_shape.d_ff * target_shape.d_model * 2          # gate + up matrices, bf16
+    pm = [p for p in probe_ms[args.warmup:] if p > 0]
+    gemm_ms = sum(pm) / len(pm)
+    achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "accepted tokens/s at 13B/68M bf16 (verify+draft achieved HBM GB/s in roofline)",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {
+            "workload": ("full DISCO loop, 13B-class target (40 layers, d 5120, 40x128 heads, SwiGLU 13824, vocab 32000) "
+                         "+ 68M-class draft (2 layers, d 768), bf16 weights and KV, batch 1, "
+                         f"{args.prompt_len}-token random prompt, greedy, forced acceptance {args.alpha}"),
+            "policy": policy, "target_layers": target_shape.n_layers,
+            "tokens_counted": "accepted draft tokens + the target's token of each iteration",
+        },
+        "iterations_per_s": args.steps / t_timed,
+        "tokens_per_iteration": emitted / args.steps,
+        "accepted_draft_tokens_per_iteration": accepted / args.steps,
+        "drafted_tokens_per_iteration": drafted / args.steps,
+        "sl_hist": res["sl_hist"],
+        "iteration_hbm_gbs": iter_bytes / (t_timed / args.steps) / 1e9,
+        "iteration_hbm_frac": iter_bytes / (t_timed / args.steps) / 1e9 / HBM_PEAK_GBS,
+        "roofline": {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "kernel": "k_gemm<*,2,EPI_SWIGLU> (target gate/up GEMM + SwiGLU)",
+            "bytes_per_launch": gemm_bytes, "avg_launch_ms": gemm_ms, "launches_timed": len(pm),
+            "timing": f"HIP events around the launch of layer {probe_layer} in every timed verification forward",
+        },
+    }
+    if not args.no_cpu_baseline:
+        g = max(1, round(drafted / args.steps))
+        out["cpu_baseline"] = cpu_baseline(target_shape, draft_shape, tw_host, dw, clf, g, emitted / args.steps,
+                                           args.prompt_len, layers_sampled)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -206,14 +206,25 @@ typedef struct disco_loop_out {
  * token and grows by 1 per step; static_sl > 0 forces "halt exactly at step static_sl" (static
  * lookahead) and ignores the classifier's verdict.  dev_force_tokens (may be NULL): cap entries,
  * one per step, as dev_force_token of disco_classify.  dev_steps: cap records of disco_clf_out.
- * On return the host's kv->len has advanced by n_in + cap - 1; after synchronising, the caller
- * reads sl from host_out (pinned) or dev_out and calls disco_kv_rollback(kv, len0 + n_in + sl - 1).
+ * On return the host's kv->len has advanced by n_in + steps - 1 (steps = static_sl if > 0, else
+ * cap); after synchronising, the caller reads sl from host_out (pinned) or dev_out and calls
+ * disco_kv_rollback(kv, len0 + n_in + sl - 1).
  * dev_logits: fp32 [vocab] scratch for the draft logits.  cap in [1, DISCO_MAX_BLOCK - 1].          */
 int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* clf,
                      const int32_t* dev_tokens_in, int n_in, int cap, int static_sl,
                      float pos_feature0, float tau, const int32_t* dev_force_tokens,
                      float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out,
                      disco_loop_out* host_out, void* dev_ws, size_t ws_bytes, disco_stream s);
+
+/* ---- measurement probe ------------------------------------------------------------------------- */
+
+/* Brackets, with two HIP events on the launch stream, the MLP-input GEMM (gate/up + SwiGLU, or
+ * W1 + GELU) of layer `layer` in every forward of a model that has more than `layer` layers
+ * (layer < 0 switches the probe off).  disco_probe_read_ms returns the elapsed time of the most
+ * recent bracket (the caller has synchronised the stream) or a negative value if none was taken.
+ * Process-wide state, for benchmarks; not thread-safe.                                             */
+int disco_probe_enable(int layer);
+float disco_probe_read_ms(void);
 
 #ifdef __cplusplus
 }

@@ -85,6 +85,8 @@ _SIGNATURES = {
     "disco_draft_loop": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(Clf), C.c_void_p, C.c_int, C.c_int,
                                    C.c_int, C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "disco_probe_enable": (C.c_int, [C.c_int]),
+    "disco_probe_read_ms": (C.c_float, []),
 }
 EXPORTS = sorted(_SIGNATURES)
 
@@ -172,6 +174,14 @@ def disco_draft_loop(model, kv, clf, tokens_in, n_in, cap, static_sl, pos_featur
                                   _ptr(force_tokens), _ptr(logits), _ptr(steps), _ptr(out),
                                   _ptr(host_out), _ptr(ws.buf), ws.nbytes,
                                   _stream() if stream is None else stream))
+
+
+def disco_probe_enable(layer: int) -> None:
+    _check(lib().disco_probe_enable(layer))
+
+
+def disco_probe_read_ms() -> float:
+    return float(lib().disco_probe_read_ms())
 
 
 # ---- holders of device memory ------------------------------------------------------------------

@@ -16,6 +16,11 @@ namespace {
 
 thread_local char g_err[512] = "";
 
+// measurement probe (see disco_probe_enable)
+int g_probe_layer = -1;
+bool g_probe_taken = false;
+hipEvent_t g_probe_ev[2] = {nullptr, nullptr};
+
 int fail(int code, const char* fmt, ...) {
   va_list ap;
   va_start(ap, fmt);
@@ -150,7 +155,10 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     GemmArgs u{};
     u.M = n; u.gate = gate; u.W = static_cast<const bf16_t*>(L.w_in); u.X = ws.xn; u.KT = d.d_model / 32;
     u.n_rows = fam_a ? d.d_ff : 2 * d.d_ff; u.grp = 1; u.Xout = ws.xact; u.KT_out = d.d_ff / 32;
+    const bool probe = (l == g_probe_layer) && g_probe_ev[0] != nullptr;
+    if (probe) HIP_TRY(hipEventRecord(g_probe_ev[0], s), "probe event");
     HIP_TRY(launch_gemm(u, fam_a ? EPI_GELU : EPI_SWIGLU, s), "mlp-in launch");
+    if (probe) { HIP_TRY(hipEventRecord(g_probe_ev[1], s), "probe event"); g_probe_taken = true; }
 
     GemmArgs dn{};
     dn.M = n; dn.gate = gate; dn.W = static_cast<const bf16_t*>(L.w_out); dn.X = ws.xact; dn.KT = d.d_ff / 32;
@@ -387,6 +395,22 @@ int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* cl
   }
   HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, st), "loop finish launch");
   return DISCO_OK;
+}
+
+int disco_probe_enable(int layer) {
+  g_probe_taken = false;
+  if (layer < 0) { g_probe_layer = -1; return DISCO_OK; }
+  for (int i = 0; i < 2; ++i)
+    if (!g_probe_ev[i]) HIP_TRY(hipEventCreate(&g_probe_ev[i]), "probe event create");
+  g_probe_layer = layer;
+  return DISCO_OK;
+}
+
+float disco_probe_read_ms(void) {
+  if (!g_probe_taken) return -1.0f;
+  float ms = -1.0f;
+  if (hipEventElapsedTime(&ms, g_probe_ev[0], g_probe_ev[1]) != hipSuccess) return -1.0f;
+  return ms;
 }
 
 }  // extern "C"

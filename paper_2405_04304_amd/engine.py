@@ -72,7 +72,8 @@ class SpecEngine:
 
     # -- the loop --------------------------------------------------------------------------------
     def generate(self, prompt: Sequence[int], max_new: int, policy: Dict, force: Optional[Dict] = None,
-                 trace: bool = False, do_prefill: bool = True) -> Dict:
+                 trace: bool = False, do_prefill: bool = True, on_iteration=None,
+                 max_iterations: Optional[int] = None) -> Dict:
         mode = policy["mode"]
         assert mode in ("static", "disco")
         pos_mode = policy.get("pos_mode", "absolute")
@@ -93,6 +94,8 @@ class SpecEngine:
         n_draft_fwd = n_target_fwd = 0
         loop_block_ptr = self.loop_dev.data_ptr() + 4
         while len(seq) - n_prompt < max_new:
+            if max_iterations is not None and len(iters) >= max_iterations:
+                break
             emitted = len(seq) - n_prompt
             remaining = max_new - emitted
             cap = min(cap_policy, remaining - 1)
@@ -140,6 +143,8 @@ class SpecEngine:
                 it["target_argmax"] = self.argmax[:sl + 1].tolist()
                 it["steps"] = steps_rec
             iters.append(it)
+            if on_iteration is not None:
+                on_iteration(it)
         hist: Dict[int, int] = {}
         for it in iters:
             hist[it["sl"]] = hist.get(it["sl"], 0) + 1
