@@ -56,7 +56,7 @@ struct disco_kv {
 namespace {
 
 struct Ws {
-  float* h; float* q; bf16_t* xn; bf16_t* xattn; bf16_t* xact; float* part; float* logits;
+  float* h; float* q; bf16_t* xn; bf16_t* xattn; bf16_t* xact; float* part; float* gpart; float* logits;
   uint32_t* gate; int32_t* sl_count; int32_t* tok_next;
   size_t total;
 };
@@ -76,6 +76,7 @@ Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
   w.xact = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * 16 * d.d_ff));
   const int n_splits = (max_ctx + DISCO_MAX_BLOCK + ATTN_SPLIT_LEN - 1) / ATTN_SPLIT_LEN;
   w.part = static_cast<float*>(take(sizeof(float) * (size_t)d.n_heads * n_splits * 16 * (d.d_head + 2)));
+  w.gpart = static_cast<float*>(take(sizeof(float) * GEMM_MAX_SPLIT * 16 * (size_t)d.d_model));
   w.logits = static_cast<float*>(take(sizeof(float) * 16 * (size_t)d.vocab));
   w.gate = static_cast<uint32_t*>(take(256));
   w.sl_count = reinterpret_cast<int32_t*>(w.gate ? w.gate + 16 : nullptr);
@@ -111,12 +112,15 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   NormArgs na{};
   na.h = ws.h; na.d = d.d_model; na.M = n; na.layernorm = fam_a; na.eps = d.norm_eps;
   na.Xout = ws.xn; na.gate = gate; na.pos0 = pos0; na.vocab = d.vocab; na.max_pos = d.max_pos;
+  na.part = ws.gpart; na.part_stride = (int64_t)16 * d.d_model;
+  const int split_o = gemm_split_for(d.d_model, m->d_q / 32), split_dn = gemm_split_for(d.d_model, d.d_ff / 32);
 
   for (int l = 0; l <= d.n_layers; ++l) {
     // norm feeding layer l (or the LM head when l == n_layers); the first one also embeds
     NormArgs n1 = na;
     if (l < d.n_layers) { n1.g = m->layers[l].norm1_g; n1.b = m->layers[l].norm1_b; }
     else { n1.g = m->w.normf_g; n1.b = m->w.normf_b; }
+    n1.n_part = (l == 0) ? 0 : split_dn;      // adds the previous layer's MLP output to the stream
     if (l == 0) {
       n1.tokens = dev_tokens; n1.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb);
       n1.tok_stride = m->w.tok_emb_stride; n1.pos_emb = static_cast<const bf16_t*>(m->w.pos_emb);
@@ -145,11 +149,12 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
 
     GemmArgs o{};
     o.M = n; o.gate = gate; o.W = static_cast<const bf16_t*>(L.wo); o.X = ws.xattn; o.KT = m->d_q / 32;
-    o.n_rows = d.d_model; o.out = ws.h; o.ld_out = d.d_model; o.only_row = -1;
-    HIP_TRY(launch_gemm(o, EPI_RESID, s), "o-proj launch");
+    o.n_rows = d.d_model; o.out = ws.gpart; o.ld_out = d.d_model; o.only_row = -1;
+    o.n_split = split_o; o.part_stride = na.part_stride;
+    HIP_TRY(launch_gemm(o, EPI_PARTIAL, s), "o-proj launch");
 
     NormArgs n2 = na;
-    n2.g = L.norm2_g; n2.b = L.norm2_b;
+    n2.g = L.norm2_g; n2.b = L.norm2_b; n2.n_part = split_o;   // adds the attention output to the stream
     HIP_TRY(launch_norm(n2, s), "norm launch");
 
     GemmArgs u{};
@@ -162,8 +167,9 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
 
     GemmArgs dn{};
     dn.M = n; dn.gate = gate; dn.W = static_cast<const bf16_t*>(L.w_out); dn.X = ws.xact; dn.KT = d.d_ff / 32;
-    dn.n_rows = d.d_model; dn.out = ws.h; dn.ld_out = d.d_model; dn.only_row = -1;
-    HIP_TRY(launch_gemm(dn, EPI_RESID, s), "mlp-out launch");
+    dn.n_rows = d.d_model; dn.out = ws.gpart; dn.ld_out = d.d_model; dn.only_row = -1;
+    dn.n_split = split_dn; dn.part_stride = na.part_stride;
+    HIP_TRY(launch_gemm(dn, EPI_PARTIAL, s), "mlp-out launch");
   }
   GemmArgs lm{};
   lm.M = n; lm.gate = gate; lm.W = static_cast<const bf16_t*>(m->w.wlm); lm.X = ws.xn; lm.KT = d.d_model / 32;
@@ -203,6 +209,7 @@ int disco_model_create(const disco_model_desc* desc, const disco_model_weights* 
   if (d.family != DISCO_FAMILY_A && d.family != DISCO_FAMILY_B) return fail(DISCO_EINVAL, "unknown family %d", d.family);
   if (d.n_layers < 1 || d.d_model < 32 || d.d_model % 32 || d.d_ff < 32 || d.d_ff % 32 || d.vocab < 16 || d.vocab % 16)
     return fail(DISCO_EINVAL, "d_model and d_ff must be multiples of 32, vocab of 16");
+  if (d.d_model > 8192) return fail(DISCO_EINVAL, "d_model %d above 8192 unsupported", d.d_model);
   if (d.d_head != 64 && d.d_head != 128) return fail(DISCO_EINVAL, "d_head %d unsupported (64 or 128)", d.d_head);
   if (d.n_heads < 1 || d.n_kv_heads < 1 || d.n_heads % d.n_kv_heads) return fail(DISCO_EINVAL, "n_heads must be a multiple of n_kv_heads");
   if (d.family == DISCO_FAMILY_A && (d.max_pos < 1 || !w->pos_emb)) return fail(DISCO_EINVAL, "family A needs a position table");
@@ -311,8 +318,8 @@ int disco_classify(const disco_clf* clf, float* dev_logits, int vocab, float pos
                    disco_clf_out* dev_out, int32_t* dev_token_next, int32_t* dev_block_slot, uint32_t* dev_gate,
                    int32_t* dev_sl_count, const int32_t* dev_force_token, disco_stream s) {
   if (!dev_logits || !dev_out) return fail(DISCO_EINVAL, "null argument");
-  if (vocab < 1) return fail(DISCO_EINVAL, "vocab must be positive");
-  if (!aligned(dev_logits, 4) || !aligned(dev_out, 4) || !aligned(dev_token_next, 4) || !aligned(dev_block_slot, 4) ||
+  if (vocab < 1 || vocab > 65536) return fail(DISCO_EINVAL, "vocab %d outside [1, 65536]", vocab);
+  if (!aligned(dev_logits, 16) || !aligned(dev_out, 4) || !aligned(dev_token_next, 4) || !aligned(dev_block_slot, 4) ||
       !aligned(dev_gate, 4) || !aligned(dev_sl_count, 4) || !aligned(dev_force_token, 4))
     return fail(DISCO_EINVAL, "misaligned pointer");
   if (clf) {

@@ -11,11 +11,12 @@ typedef uint16_t bf16_t;  // raw bfloat16 bits
 
 // Epilogues of the skinny GEMM  Y[M x N] = X[M x K] . W[N x K]^T.
 enum Epi {
-  EPI_RESID = 0,   // out[m][n] += y           (O-projection, MLP down: residual stream update)
   EPI_STORE = 1,   // out[m][n]  = y           (LM head logits)
   EPI_QKV = 2,     // rotary (optional) + q store + paged K/V append
   EPI_SWIGLU = 3,  // silu(gate) * up  -> packed activation panel
   EPI_GELU = 4,    // gelu(y)          -> packed activation panel
+  EPI_PARTIAL = 5, // out[split][m][n] = y     (O-projection, MLP down: split-K partial sums that the
+                   //                           next norm kernel adds to the residual stream)
 };
 
 struct GemmArgs {
@@ -26,7 +27,9 @@ struct GemmArgs {
   int n_rows;           // N
   int grp;              // row-tile pairing distance for two-tile workgroups (1 = adjacent tiles)
   const uint32_t* gate; // optional: skip when *gate != 0
-  float* out;           // RESID / STORE target, row stride ld_out
+  int n_split;          // K ranges (grid.y); > 1 only with EPI_PARTIAL
+  int64_t part_stride;  // elements between the partial-sum planes of EPI_PARTIAL
+  float* out;           // RESID / STORE / PARTIAL target, row stride ld_out
   int64_t ld_out;
   int only_row;         // STORE: write only this token's row to out[0..N) (-1: all rows)
   // QKV epilogue
@@ -40,6 +43,7 @@ struct NormArgs {
   float* h; int d; int M; int layernorm; float eps;
   const float* g; const float* b;
   bf16_t* Xout;                      // packed panels, K = d
+  const float* part; int n_part; int64_t part_stride;  // split-K partial sums to add to h first
   // embedding mode (tokens != nullptr): h = tok_emb[token] (+ pos_emb[pos0 + m]) first
   const int32_t* tokens; const bf16_t* tok_emb; int64_t tok_stride; const bf16_t* pos_emb;
   int pos0; int vocab; int max_pos;
@@ -66,6 +70,7 @@ struct ClassifyArgs {
 hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int64_t tile_mul,
                        int64_t tile_add, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, int epi, hipStream_t s);
+int gemm_split_for(int n_rows, int KT);   // K ranges the PARTIAL epilogue should be launched with
 hipError_t launch_norm(const NormArgs& a, hipStream_t s);
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s);
@@ -79,6 +84,7 @@ hipError_t launch_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* to
 hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void* host_loop_out,
                               hipStream_t s);
 
+constexpr int GEMM_MAX_SPLIT = 8;
 constexpr int ATTN_SPLIT_LEN = 128;  // cached positions per attention workgroup
 
 }  // namespace disco

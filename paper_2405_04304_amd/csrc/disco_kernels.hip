@@ -57,15 +57,42 @@ __device__ __forceinline__ void xpack_store4(bf16_t* X, int KT, int M, int m, in
   *reinterpret_cast<uint2*>(X + off_lo) = make_uint2(lo[0], lo[1]);
 }
 
+// Wavefront reductions on the DPP cross-lane network (no LDS traffic): xor-1, xor-2 inside quads,
+// half-row mirror, row mirror, then row broadcasts 15 and 31; lane 63 ends up with the result, which
+// is broadcast through a scalar register.  The combination order is fixed, so sums are reproducible.
+#define DPP_QUAD_XOR1 0xB1
+#define DPP_QUAD_XOR2 0x4E
+#define DPP_ROW_HALF_MIRROR 0x141
+#define DPP_ROW_MIRROR 0x140
+#define DPP_ROW_BCAST15 0x142
+#define DPP_ROW_BCAST31 0x143
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f(float old, float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_i(int old, int v) {
+  return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xF, false);
+}
+
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-  return v;
+  v += dpp_f<DPP_QUAD_XOR1, 0xF>(0.f, v);
+  v += dpp_f<DPP_QUAD_XOR2, 0xF>(0.f, v);
+  v += dpp_f<DPP_ROW_HALF_MIRROR, 0xF>(0.f, v);
+  v += dpp_f<DPP_ROW_MIRROR, 0xF>(0.f, v);
+  v += dpp_f<DPP_ROW_BCAST15, 0xA>(0.f, v);
+  v += dpp_f<DPP_ROW_BCAST31, 0xC>(0.f, v);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-  return v;
+  v = fmaxf(v, dpp_f<DPP_QUAD_XOR1, 0xF>(v, v));
+  v = fmaxf(v, dpp_f<DPP_QUAD_XOR2, 0xF>(v, v));
+  v = fmaxf(v, dpp_f<DPP_ROW_HALF_MIRROR, 0xF>(v, v));
+  v = fmaxf(v, dpp_f<DPP_ROW_MIRROR, 0xF>(v, v));
+  v = fmaxf(v, dpp_f<DPP_ROW_BCAST15, 0xA>(v, v));
+  v = fmaxf(v, dpp_f<DPP_ROW_BCAST31, 0xC>(v, v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
 // Block-wide sum in a fixed order (deterministic); every thread gets the result.
@@ -86,13 +113,22 @@ struct VI { float v; int i; };
 __device__ __forceinline__ VI vi_best(VI a, VI b) {
   return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
 }
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ VI vi_step(VI x) {
+  VI y; y.v = dpp_f<CTRL, ROW_MASK>(x.v, x.v); y.i = dpp_i<CTRL, ROW_MASK>(x.i, x.i);
+  return vi_best(x, y);
+}
 __device__ __forceinline__ VI wave_argmax(VI x) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    VI y; y.v = __shfl_xor(x.v, o); y.i = __shfl_xor(x.i, o);
-    x = vi_best(x, y);
-  }
-  return x;
+  x = vi_step<DPP_QUAD_XOR1, 0xF>(x);
+  x = vi_step<DPP_QUAD_XOR2, 0xF>(x);
+  x = vi_step<DPP_ROW_HALF_MIRROR, 0xF>(x);
+  x = vi_step<DPP_ROW_MIRROR, 0xF>(x);
+  x = vi_step<DPP_ROW_BCAST15, 0xA>(x);
+  x = vi_step<DPP_ROW_BCAST31, 0xC>(x);
+  VI r;
+  r.v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x.v), 63));
+  r.i = __builtin_amdgcn_readlane(x.i, 63);
+  return r;
 }
 template <int NT>
 __device__ __forceinline__ VI block_argmax(VI x, float* sv, int* si) {
@@ -138,22 +174,40 @@ hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int
 // ---------------------------------------------------------------------------------------------
 // skinny GEMM: weights streamed once from HBM, M <= 16 tokens on the matrix unit's column side
 // ---------------------------------------------------------------------------------------------
-
-constexpr int GEMM_NW = 8;  // wavefronts per workgroup; they split K and reduce through LDS
-constexpr int GEMM_U = 4;   // k-tiles in flight per wavefront
+//
+// Workgroup (blockIdx.x, blockIdx.y) owns RT 16-row tiles and the blockIdx.y-th of n_split equal
+// K ranges.  Its NW wavefronts interleave over the k-tiles of that range, each keeping U k-tiles of
+// loads in flight, and reduce through LDS in a fixed order.  With n_split > 1 the workgroup stores
+// its partial sums and the consumer (k_norm) adds the partials in a fixed order: no float atomics,
+// bitwise reproducible results.
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
   union { u32x4 u; bf16x8 b; } c; c.u = v; return c.b;
 }
 
-template <int P, int RT, int EPI>
-__global__ __launch_bounds__(GEMM_NW * 64) void k_gemm(GemmArgs a) {
+template <int EPI> struct EpiTraits { static constexpr bool pair = (EPI == EPI_QKV || EPI == EPI_SWIGLU); };
+
+template <int P, int RT, int EPI, int NW, int U>
+__global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
   if (gated(a.gate)) return;
+  constexpr bool PAIR = EpiTraits<EPI>::pair;
+  constexpr int UNITS = PAIR ? RT / 2 : RT;       // output units handled by one wavefront each
+  static_assert(!PAIR || RT % 2 == 0, "pair epilogues need an even tile count");
+  static_assert(UNITS <= NW, "one epilogue wavefront per unit");
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int b = blockIdx.x;
+  const int b = blockIdx.x, split = blockIdx.y;
   int rt[RT];
-  if (RT == 1) { rt[0] = b; }
-  else { rt[0] = (b / a.grp) * (2 * a.grp) + (b % a.grp); rt[RT - 1] = rt[0] + a.grp; }
+  if (PAIR) {
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) {
+      const int bp = b * UNITS + u;
+      rt[2 * u] = (bp / a.grp) * (2 * a.grp) + (bp % a.grp);
+      rt[2 * u + 1] = rt[2 * u] + a.grp;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < RT; ++r) rt[r] = b * RT + r;
+  }
 
   f32x4 acc[RT][P];
 #pragma unroll
@@ -162,24 +216,25 @@ __global__ __launch_bounds__(GEMM_NW * 64) void k_gemm(GemmArgs a) {
     for (int p = 0; p < P; ++p) acc[r][p] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   const int KT = a.KT;
+  const int kt_begin = (int)((int64_t)KT * split / a.n_split), kt_end = (int)((int64_t)KT * (split + 1) / a.n_split);
   const u32x4* Wp[RT];
 #pragma unroll
   for (int r = 0; r < RT; ++r) Wp[r] = reinterpret_cast<const u32x4*>(a.W) + (size_t)rt[r] * KT * 64 + lane;
   const u32x4* Xp = reinterpret_cast<const u32x4*>(a.X) + lane;
 
-  int kt = w;
-  for (; kt + (GEMM_U - 1) * GEMM_NW < KT; kt += GEMM_U * GEMM_NW) {
-    u32x4 A[GEMM_U][RT], B[GEMM_U][P];
+  int kt = kt_begin + w;
+  for (; kt + (U - 1) * NW < kt_end; kt += U * NW) {
+    u32x4 A[U][RT], B[U][P];
 #pragma unroll
-    for (int u = 0; u < GEMM_U; ++u) {
-      const size_t t = (size_t)(kt + u * GEMM_NW) * 64;
+    for (int u = 0; u < U; ++u) {
+      const size_t t = (size_t)(kt + u * NW) * 64;
 #pragma unroll
       for (int r = 0; r < RT; ++r) A[u][r] = __builtin_nontemporal_load(Wp[r] + t);
 #pragma unroll
       for (int p = 0; p < P; ++p) B[u][p] = Xp[(size_t)p * KT * 64 + t];
     }
 #pragma unroll
-    for (int u = 0; u < GEMM_U; ++u)
+    for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int r = 0; r < RT; ++r)
 #pragma unroll
@@ -187,7 +242,7 @@ __global__ __launch_bounds__(GEMM_NW * 64) void k_gemm(GemmArgs a) {
           acc[r][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[u][r]), as_bf16x8(B[u][p]),
                                                               acc[r][p], 0, 0, 0);
   }
-  for (; kt < KT; kt += GEMM_NW) {
+  for (; kt < kt_end; kt += NW) {
     const size_t t = (size_t)kt * 64;
     u32x4 A[RT], B[P];
 #pragma unroll
@@ -202,7 +257,7 @@ __global__ __launch_bounds__(GEMM_NW * 64) void k_gemm(GemmArgs a) {
   }
 
   // hi + lo: same panel, columns n and n + 8 (P == 1), or two panels (P == 2)
-  __shared__ f32x4 red[GEMM_NW][RT][64];
+  __shared__ f32x4 red[NW][RT][64];
 #pragma unroll
   for (int r = 0; r < RT; ++r) {
     f32x4 y;
@@ -215,38 +270,38 @@ __global__ __launch_bounds__(GEMM_NW * 64) void k_gemm(GemmArgs a) {
     red[w][r][lane] = y;
   }
   __syncthreads();
-  if (w != 0) return;
-  f32x4 y[RT];
+  if (w >= UNITS) return;
+  constexpr int TPU = PAIR ? 2 : 1;               // tiles per unit
+  f32x4 y[TPU];
+  int urt[TPU];
 #pragma unroll
-  for (int r = 0; r < RT; ++r) {
-    y[r] = red[0][r][lane];
+  for (int i = 0; i < TPU; ++i) {
+    const int r = w * TPU + i;
+    // (runtime index into rt[] would spill it: select with a compile-time loop)
+    urt[i] = 0;
 #pragma unroll
-    for (int ww = 1; ww < GEMM_NW; ++ww) y[r] += red[ww][r][lane];   // fixed order: deterministic
+    for (int rr = 0; rr < RT; ++rr) if (rr == r) urt[i] = rt[rr];
+    y[i] = red[0][r][lane];
+#pragma unroll
+    for (int ww = 1; ww < NW; ++ww) y[i] += red[ww][r][lane];   // fixed order: deterministic
   }
   const int m = lane & 15, g = lane >> 4;   // token column, 4-row group of the 16x16 result
   if (m >= a.M) return;
 
-  if (EPI == EPI_RESID) {
-#pragma unroll
-    for (int r = 0; r < RT; ++r) {
-      float4* p = reinterpret_cast<float4*>(a.out + (size_t)m * a.ld_out + rt[r] * 16 + 4 * g);
-      float4 h = *p;
-      h.x += y[r][0]; h.y += y[r][1]; h.z += y[r][2]; h.w += y[r][3];
-      *p = h;
-    }
+  if (EPI == EPI_PARTIAL) {
+    float* dst = a.out + (size_t)split * a.part_stride + (size_t)m * a.ld_out + urt[0] * 16 + 4 * g;
+    *reinterpret_cast<float4*>(dst) = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
   } else if (EPI == EPI_STORE) {
     if (a.only_row >= 0 && m != a.only_row) return;
     const size_t row_off = a.only_row >= 0 ? 0 : (size_t)m * a.ld_out;
-#pragma unroll
-    for (int r = 0; r < RT; ++r)
-      *reinterpret_cast<float4*>(a.out + row_off + rt[r] * 16 + 4 * g) = make_float4(y[r][0], y[r][1], y[r][2], y[r][3]);
+    *reinterpret_cast<float4*>(a.out + row_off + urt[0] * 16 + 4 * g) = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
   } else if (EPI == EPI_QKV) {
     // two tiles: features c .. c+3 and their rotary partners c + dh/2 .. of one head
-    const int n0 = rt[0] * 16 + 4 * g;
+    const int n0 = urt[0] * 16 + 4 * g;
     const int head = n0 / a.dh, c = n0 % a.dh, half = a.dh >> 1;
     float lo4[4], hi4[4];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) { lo4[v] = y[0][v]; hi4[v] = y[RT - 1][v]; }
+    for (int v = 0; v < 4; ++v) { lo4[v] = y[0][v]; hi4[v] = y[TPU - 1][v]; }
     const int pos = a.pos0 + m;
     const bool is_v = head >= a.nq + a.nkv;
     if (a.rope && !is_v) {
@@ -280,113 +335,168 @@ __global__ __launch_bounds__(GEMM_NW * 64) void k_gemm(GemmArgs a) {
     }
   } else if (EPI == EPI_SWIGLU) {
     // tile 0 = gate rows, tile 1 = the matching up rows
-    const int f = (rt[0] >> 1) * 16 + 4 * g;
+    const int f = (urt[0] >> 1) * 16 + 4 * g;
     float act[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
       const float gt = y[0][v];
-      act[v] = gt / (1.0f + expf(-gt)) * y[RT - 1][v];
+      act[v] = gt / (1.0f + expf(-gt)) * y[TPU - 1][v];
     }
     xpack_store4(a.Xout, a.KT_out, a.M, m, f, act);
   } else if (EPI == EPI_GELU) {
+    float act[4];
 #pragma unroll
-    for (int r = 0; r < RT; ++r) {
-      float act[4];
-#pragma unroll
-      for (int v = 0; v < 4; ++v) act[v] = 0.5f * y[r][v] * (1.0f + erff(y[r][v] * 0.70710678118654752f));
-      xpack_store4(a.Xout, a.KT_out, a.M, m, rt[r] * 16 + 4 * g, act);
+    for (int v = 0; v < 4; ++v) act[v] = 0.5f * y[0][v] * (1.0f + erff(y[0][v] * 0.70710678118654752f));
+    xpack_store4(a.Xout, a.KT_out, a.M, m, urt[0] * 16 + 4 * g, act);
+  }
+}
+
+template <int P, int RT, int EPI, int NW, int U>
+static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t s) {
+  constexpr int rows = RT * 16;
+  if (a.n_rows % rows) return hipErrorInvalidValue;
+  hipLaunchKernelGGL((k_gemm<P, RT, EPI, NW, U>), dim3(a.n_rows / rows, a.n_split), dim3(NW * 64), 0, s, a);
+  return hipGetLastError();
+}
+
+#ifndef DISCO_GEMM_NO_DISPATCH
+// Launch shapes, from measurements on MI355X at the 13B-class sizes: weight streaming needs >= ~500
+// workgroups in flight, and the activation panels (re-read from L2 by every workgroup) cost as much
+// bandwidth as the weights unless a workgroup covers 32-64 rows.  Wide outputs therefore take 4 row
+// tiles per workgroup; narrow outputs (d_model rows) take 2 and split K across workgroups.
+int gemm_split_for(int n_rows, int KT) {
+  (void)n_rows;
+  int s = KT / 40;
+  return s < 1 ? 1 : (s > 8 ? 8 : s);
+}
+
+template <int P, int EPI>
+static hipError_t launch_gemm_p(const GemmArgs& a, hipStream_t s) {
+  constexpr bool PAIR = EpiTraits<EPI>::pair;
+  const int n = a.n_rows;
+  if constexpr (EPI == EPI_PARTIAL) {
+    const int64_t wg4 = (int64_t)(n / 64) * a.n_split, wg2 = (int64_t)(n / 32) * a.n_split;
+    if (n % 64 == 0 && wg4 >= 1024) return launch_gemm_cfg<P, 4, EPI, 8, 2>(a, s);
+    if (n % 32 == 0 && wg2 >= 480) {
+      if (a.KT / a.n_split <= 40) return launch_gemm_cfg<P, 2, EPI, 4, 4>(a, s);
+      return launch_gemm_cfg<P, 2, EPI, 8, 4>(a, s);
+    }
+    return launch_gemm_cfg<P, 1, EPI, 8, 4>(a, s);
+  } else {
+    if (n % 64 == 0 && n / 64 >= 400) return launch_gemm_cfg<P, 4, EPI, 8, 2>(a, s);
+    if constexpr (PAIR) {
+      return launch_gemm_cfg<P, 2, EPI, 8, 4>(a, s);
+    } else {
+      if (n % 32 == 0 && n / 32 >= 200) return launch_gemm_cfg<P, 2, EPI, 8, 4>(a, s);
+      return launch_gemm_cfg<P, 1, EPI, 8, 4>(a, s);
     }
   }
 }
 
-template <int P, int RT>
-static hipError_t launch_gemm_epi(const GemmArgs& a, int epi, int grid, hipStream_t s) {
-  const dim3 g(grid), b(GEMM_NW * 64);
+hipError_t launch_gemm(const GemmArgs& a0, int epi, hipStream_t s) {
+  if (a0.M < 1 || a0.M > 16 || a0.KT < 1 || (a0.n_rows & 15)) return hipErrorInvalidValue;
+  GemmArgs a = a0;
+  if (a.n_split < 1) a.n_split = 1;
+  if (epi != EPI_PARTIAL && a.n_split != 1) return hipErrorInvalidValue;
+  if (a.n_split > a.KT) return hipErrorInvalidValue;
+  if (epi != EPI_QKV) a.grp = 1;
+  if ((epi == EPI_QKV || epi == EPI_SWIGLU) && (a.n_rows % 32)) return hipErrorInvalidValue;
+  const bool p1 = a.M <= 8;
   switch (epi) {
-    case EPI_RESID: hipLaunchKernelGGL((k_gemm<P, RT, EPI_RESID>), g, b, 0, s, a); break;
-    case EPI_STORE: hipLaunchKernelGGL((k_gemm<P, RT, EPI_STORE>), g, b, 0, s, a); break;
-    case EPI_GELU: hipLaunchKernelGGL((k_gemm<P, RT, EPI_GELU>), g, b, 0, s, a); break;
-    case EPI_QKV:
-      if (RT == 2) hipLaunchKernelGGL((k_gemm<P, 2, EPI_QKV>), g, b, 0, s, a); else return hipErrorInvalidValue;
-      break;
-    case EPI_SWIGLU:
-      if (RT == 2) hipLaunchKernelGGL((k_gemm<P, 2, EPI_SWIGLU>), g, b, 0, s, a); else return hipErrorInvalidValue;
-      break;
+    case EPI_PARTIAL: return p1 ? launch_gemm_p<1, EPI_PARTIAL>(a, s) : launch_gemm_p<2, EPI_PARTIAL>(a, s);
+    case EPI_STORE: return p1 ? launch_gemm_p<1, EPI_STORE>(a, s) : launch_gemm_p<2, EPI_STORE>(a, s);
+    case EPI_GELU: return p1 ? launch_gemm_p<1, EPI_GELU>(a, s) : launch_gemm_p<2, EPI_GELU>(a, s);
+    case EPI_QKV: return p1 ? launch_gemm_p<1, EPI_QKV>(a, s) : launch_gemm_p<2, EPI_QKV>(a, s);
+    case EPI_SWIGLU: return p1 ? launch_gemm_p<1, EPI_SWIGLU>(a, s) : launch_gemm_p<2, EPI_SWIGLU>(a, s);
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
 }
-
-hipError_t launch_gemm(const GemmArgs& a, int epi, hipStream_t s) {
-  if (a.M < 1 || a.M > 16 || a.KT < 1 || (a.n_rows & 15)) return hipErrorInvalidValue;
-  const bool pair = (epi == EPI_QKV || epi == EPI_SWIGLU);
-  // two row tiles per workgroup halve the activation re-reads; keep >= ~2 workgroups per CU
-  const bool two = pair || ((a.n_rows % 32 == 0) && (a.n_rows / 32 >= 480));
-  if (pair && (a.n_rows % 32)) return hipErrorInvalidValue;
-  GemmArgs b = a;
-  if (!pair) b.grp = 1;
-  const int grid = two ? a.n_rows / 32 : a.n_rows / 16;
-  if (a.M <= 8) return two ? launch_gemm_epi<1, 2>(b, epi, grid, s) : launch_gemm_epi<1, 1>(b, epi, grid, s);
-  return two ? launch_gemm_epi<2, 2>(b, epi, grid, s) : launch_gemm_epi<2, 1>(b, epi, grid, s);
-}
+#endif
 
 // ---------------------------------------------------------------------------------------------
 // (embedding +) LayerNorm / RMSNorm -> packed activation panels
 // ---------------------------------------------------------------------------------------------
 
-__global__ __launch_bounds__(256) void k_norm(NormArgs a) {
+// One workgroup per token row.  The row lives in registers: embedding gather or residual stream,
+// plus the split-K partial sums of the preceding GEMM added in a fixed order (the updated row is
+// written back), then the statistics, then the normalised row as packed bf16 hi/lo panels.
+template <int NT>
+__global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
   if (gated(a.gate)) return;
-  __shared__ float red[8];
+  constexpr int VPT = 2;                       // float4 per thread: d <= NT * 8
+  __shared__ float red[NT / 64 + 1];
   const int m = blockIdx.x, t = threadIdx.x, d = a.d;
   float* h = a.h + (size_t)m * d;
+  float4 v[VPT];
+  const bf16_t* e = nullptr; const bf16_t* pe = nullptr;
   if (a.tokens) {
     int tok = a.tokens[m];
     tok = tok < 0 ? 0 : (tok >= a.vocab ? a.vocab - 1 : tok);
     int pos = a.pos0 + m;
     if (pos >= a.max_pos) pos = a.max_pos - 1;
-    const bf16_t* e = a.tok_emb + (size_t)tok * a.tok_stride;
-    const bf16_t* pe = a.pos_emb ? a.pos_emb + (size_t)pos * d : nullptr;
-    for (int k = t * 4; k < d; k += 1024) {
-      const uint2 u = *reinterpret_cast<const uint2*>(e + k);
-      float4 v = make_float4(bf16_to_f32(u.x & 0xFFFF), bf16_to_f32(u.x >> 16), bf16_to_f32(u.y & 0xFFFF), bf16_to_f32(u.y >> 16));
-      if (pe) {
-        const uint2 p = *reinterpret_cast<const uint2*>(pe + k);
-        v.x += bf16_to_f32(p.x & 0xFFFF); v.y += bf16_to_f32(p.x >> 16);
-        v.z += bf16_to_f32(p.y & 0xFFFF); v.w += bf16_to_f32(p.y >> 16);
+    e = a.tok_emb + (size_t)tok * a.tok_stride;
+    pe = a.pos_emb ? a.pos_emb + (size_t)pos * d : nullptr;
+  }
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int k = (i * NT + t) * 4;
+    v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k < d) {
+      if (e) {
+        const uint2 u = *reinterpret_cast<const uint2*>(e + k);
+        v[i] = make_float4(bf16_to_f32(u.x & 0xFFFF), bf16_to_f32(u.x >> 16), bf16_to_f32(u.y & 0xFFFF), bf16_to_f32(u.y >> 16));
+        if (pe) {
+          const uint2 p = *reinterpret_cast<const uint2*>(pe + k);
+          v[i].x += bf16_to_f32(p.x & 0xFFFF); v[i].y += bf16_to_f32(p.x >> 16);
+          v[i].z += bf16_to_f32(p.y & 0xFFFF); v[i].w += bf16_to_f32(p.y >> 16);
+        }
+      } else {
+        v[i] = *reinterpret_cast<const float4*>(h + k);
       }
-      *reinterpret_cast<float4*>(h + k) = v;   // each thread re-reads only what it wrote
+      for (int sp = 0; sp < a.n_part; ++sp) {
+        const float4 p = *reinterpret_cast<const float4*>(a.part + (size_t)sp * a.part_stride + (size_t)m * d + k);
+        v[i].x += p.x; v[i].y += p.y; v[i].z += p.z; v[i].w += p.w;
+      }
+      if (e || a.n_part > 0) *reinterpret_cast<float4*>(h + k) = v[i];
     }
   }
   float mean = 0.f;
   if (a.layernorm) {
     float s = 0.f;
-    for (int k = t * 4; k < d; k += 1024) { const float4 v = *reinterpret_cast<const float4*>(h + k); s += (v.x + v.y) + (v.z + v.w); }
-    mean = block_sum<256>(s, red) / (float)d;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);   // zero beyond d
+    mean = block_sum<NT>(s, red) / (float)d;
   }
   float ss = 0.f;
-  for (int k = t * 4; k < d; k += 1024) {
-    const float4 v = *reinterpret_cast<const float4*>(h + k);
-    const float x0 = v.x - mean, x1 = v.y - mean, x2 = v.z - mean, x3 = v.w - mean;
-    ss += (x0 * x0 + x1 * x1) + (x2 * x2 + x3 * x3);
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    if ((i * NT + t) * 4 < d) {
+      const float x0 = v[i].x - mean, x1 = v[i].y - mean, x2 = v[i].z - mean, x3 = v[i].w - mean;
+      ss += (x0 * x0 + x1 * x1) + (x2 * x2 + x3 * x3);
+    }
   }
-  const float var = block_sum<256>(ss, red) / (float)d;
+  const float var = block_sum<NT>(ss, red) / (float)d;
   const float rstd = 1.0f / sqrtf(var + a.eps);
   const int KT = d >> 5;
-  for (int k = t * 4; k < d; k += 1024) {
-    const float4 v = *reinterpret_cast<const float4*>(h + k);
-    const float4 g = *reinterpret_cast<const float4*>(a.g + k);
-    float o[4] = {(v.x - mean) * rstd * g.x, (v.y - mean) * rstd * g.y, (v.z - mean) * rstd * g.z, (v.w - mean) * rstd * g.w};
-    if (a.b) {
-      const float4 bb = *reinterpret_cast<const float4*>(a.b + k);
-      o[0] += bb.x; o[1] += bb.y; o[2] += bb.z; o[3] += bb.w;
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    const int k = (i * NT + t) * 4;
+    if (k < d) {
+      const float4 g = *reinterpret_cast<const float4*>(a.g + k);
+      float o[4] = {(v[i].x - mean) * rstd * g.x, (v[i].y - mean) * rstd * g.y, (v[i].z - mean) * rstd * g.z, (v[i].w - mean) * rstd * g.w};
+      if (a.b) {
+        const float4 bb = *reinterpret_cast<const float4*>(a.b + k);
+        o[0] += bb.x; o[1] += bb.y; o[2] += bb.z; o[3] += bb.w;
+      }
+      xpack_store4(a.Xout, KT, a.M, m, k, o);
     }
-    xpack_store4(a.Xout, KT, a.M, m, k, o);
   }
 }
 
 hipError_t launch_norm(const NormArgs& a, hipStream_t s) {
-  if (a.M < 1 || a.M > 16 || (a.d & 31)) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(k_norm, dim3(a.M), dim3(256), 0, s, a);
+  if (a.M < 1 || a.M > 16 || (a.d & 31) || a.d > 8192 || a.n_part < 0) return hipErrorInvalidValue;
+  if (a.d <= 2048) hipLaunchKernelGGL(k_norm<256>, dim3(a.M), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(k_norm<1024>, dim3(a.M), dim3(1024), 0, s, a);
   return hipGetLastError();
 }
 
@@ -549,6 +659,13 @@ struct ClfOut {  // mirrors disco_clf_out
 constexpr int FEAT_NT = 1024;
 constexpr int FEAT_CAND = 1024;
 
+// One workgroup, the whole logit vector in registers (V4 float4 per thread, one round of 128-bit
+// loads).  Arg-max, soft-max sums and entropy are DPP wave reductions merged across the 16
+// wavefronts in a fixed order.  Top-10: every wavefront takes the 10th largest of its lanes' maxima
+// (ten DPP arg-max rounds, no rescans); the largest of those 16 values is a lower bound of the 10th
+// largest logit, the few logits at or above it are collected in LDS, and one wavefront picks the ten
+// largest of them.
+template <int V4>
 __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
   ClfOut* out = reinterpret_cast<ClfOut*>(a.out);
   if (a.gate != nullptr && *a.gate != 0u) {
@@ -561,75 +678,132 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
   __shared__ int n_cand;
   __shared__ float top_s[10];
   __shared__ float feat_s[12];
-  const int t = threadIdx.x, V = a.vocab;
+  const int t = threadIdx.x, V = a.vocab, lane = t & 63, wv = t >> 6;
   const float* x = a.logits;
 
-  // pass 1: maximum and arg-max (lowest index on ties); also each thread's own maximum
+  float4 r[V4];
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    const int idx = (i * FEAT_NT + t) * 4;
+    if (idx + 3 < V) {
+      r[i] = *reinterpret_cast<const float4*>(x + idx);
+    } else {
+      r[i].x = idx < V ? x[idx] : -INFINITY;
+      r[i].y = idx + 1 < V ? x[idx + 1] : -INFINITY;
+      r[i].z = idx + 2 < V ? x[idx + 2] : -INFINITY;
+      r[i].w = -INFINITY;
+    }
+  }
+  if (t == 0) n_cand = 0;
+
+  // maximum and arg-max (lowest index on ties); `mine` is this thread's own maximum
   VI mine; mine.v = -INFINITY; mine.i = 0x7fffffff;
-  for (int i = t; i < V; i += FEAT_NT) { VI y; y.v = x[i]; y.i = i; mine = vi_best(mine, y); }
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    const int idx = (i * FEAT_NT + t) * 4;
+    VI y;
+    y.v = r[i].x; y.i = idx; mine = vi_best(mine, y);
+    y.v = r[i].y; y.i = idx + 1; mine = vi_best(mine, y);
+    y.v = r[i].z; y.i = idx + 2; mine = vi_best(mine, y);
+    y.v = r[i].w; y.i = idx + 3; mine = vi_best(mine, y);
+  }
   VI best = block_argmax<FEAT_NT>(mine, sv, si);
   int force = -1;
   if (a.force_token) { force = *a.force_token; if (force >= V) force = -1; }
-  float forced_val = 0.f;
   if (force >= 0) {
-    forced_val = best.v + 4.0f;
+    const float forced_val = best.v + 4.0f;
     best.v = forced_val; best.i = force;
-    if (t == (force % FEAT_NT)) { mine.v = forced_val; mine.i = force; }
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+      const int idx = (i * FEAT_NT + t) * 4;
+      if (force == idx) r[i].x = forced_val;
+      if (force == idx + 1) r[i].y = forced_val;
+      if (force == idx + 2) r[i].z = forced_val;
+      if (force == idx + 3) r[i].w = forced_val;
+    }
+    if ((force >> 2) % FEAT_NT == t) { mine.v = forced_val; mine.i = force; a.logits[force] = forced_val; }
   }
   const float mx = best.v;
 
-  // pass 2: S = sum e^(x - max), T = sum e^(x - max) (x - max)
+  // S = sum e^(x - max), T = sum e^(x - max) (x - max)
   float S = 0.f, T = 0.f;
-  for (int i = t; i < V; i += FEAT_NT) {
-    const float d = ((i == force) ? forced_val : x[i]) - mx;
-    const float e = expf(d);
-    S += e; T += e * d;
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    const float d0 = r[i].x - mx, d1 = r[i].y - mx, d2 = r[i].z - mx, d3 = r[i].w - mx;
+    const float e0 = expf(d0), e1 = expf(d1), e2 = expf(d2), e3 = expf(d3);
+    S += (e0 + e1) + (e2 + e3);
+    // e^(-inf) * (-inf) would be NaN: padded slots contribute nothing
+    T += (e0 > 0.f ? e0 * d0 : 0.f) + (e1 > 0.f ? e1 * d1 : 0.f) + (e2 > 0.f ? e2 * d2 : 0.f) + (e3 > 0.f ? e3 * d3 : 0.f);
   }
   S = block_sum<FEAT_NT>(S, sv);
   T = block_sum<FEAT_NT>(T, sv);
 
-  // top-10 values.  The 10th largest of the per-thread maxima bounds the 10th largest element from
-  // below, so only elements >= that bound can be in the top 10.
-  if (t == 0) n_cand = 0;
-  float bound = 0.f;
+  // lower bound of the 10th largest logit
   {
-    VI cur = mine; cur.i = t;
-    for (int r = 0; r < 10; ++r) {
-      const VI b = block_argmax<FEAT_NT>(cur, sv, si);
-      bound = b.v;
-      if (b.i == t) cur.v = -INFINITY;
+    VI cur; cur.v = mine.v; cur.i = lane;
+    float bound_w = -INFINITY;
+#pragma unroll 1
+    for (int rnd = 0; rnd < 10; ++rnd) {
+      const VI b = wave_argmax(cur);
+      bound_w = b.v;
+      if (b.i == lane) cur.v = -INFINITY;
     }
+    __syncthreads();
+    if (lane == 0) sv[wv] = bound_w;
+    __syncthreads();
   }
-  __syncthreads();
-  for (int i = t; i < V; i += FEAT_NT) {
-    const float v = (i == force) ? forced_val : x[i];
-    if (v >= bound) {
-      const int slot = atomicAdd(&n_cand, 1);
-      if (slot < FEAT_CAND) cand[slot] = v;
+  float bound = sv[0];
+#pragma unroll
+  for (int i = 1; i < FEAT_NT / 64; ++i) bound = fmaxf(bound, sv[i]);
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    const float vals[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (vals[e] >= bound && vals[e] > -INFINITY) {
+        const int slot = atomicAdd(&n_cand, 1);
+        if (slot < FEAT_CAND) cand[slot] = vals[e];
+      }
     }
   }
   __syncthreads();
   const int nc = n_cand;
-  if (nc <= FEAT_CAND) {
+  if (nc <= 64) {
+    if (wv == 0) {
+      VI cur; cur.v = (lane < nc) ? cand[lane] : -INFINITY; cur.i = lane;
+#pragma unroll 1
+      for (int rnd = 0; rnd < 10; ++rnd) {
+        const VI b = wave_argmax(cur);
+        if (lane == 0) top_s[rnd] = b.v;
+        if (b.i == lane) cur.v = -INFINITY;
+      }
+    }
+  } else if (nc <= FEAT_CAND) {
     VI cur; cur.v = (t < nc) ? cand[t] : -INFINITY; cur.i = t;
-    for (int r = 0; r < 10; ++r) {
+    for (int rnd = 0; rnd < 10; ++rnd) {
       const VI b = block_argmax<FEAT_NT>(cur, sv, si);
-      if (t == 0) top_s[r] = b.v;
+      if (t == 0) top_s[rnd] = b.v;
       if (b.i == t) cur.v = -INFINITY;
     }
   } else {
     // more candidates than the list holds (massive ties): ten full selection rounds, each taking
     // the largest element that comes after the previous pick in (value desc, index asc) order
     VI prev; prev.v = INFINITY; prev.i = -1;
-    for (int r = 0; r < 10; ++r) {
+    for (int rnd = 0; rnd < 10; ++rnd) {
       VI c; c.v = -INFINITY; c.i = 0x7fffffff;
-      for (int i = t; i < V; i += FEAT_NT) {
-        const float v = (i == force) ? forced_val : x[i];
-        const bool after = (v < prev.v) || (v == prev.v && i > prev.i);
-        if (after) { VI y; y.v = v; y.i = i; c = vi_best(c, y); }
+#pragma unroll
+      for (int i = 0; i < V4; ++i) {
+        const int idx = (i * FEAT_NT + t) * 4;
+        const float vals[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float v = vals[e];
+          const bool after = (v < prev.v) || (v == prev.v && idx + e > prev.i);
+          if (after && idx + e < V) { VI y; y.v = v; y.i = idx + e; c = vi_best(c, y); }
+        }
       }
       prev = block_argmax<FEAT_NT>(c, sv, si);
-      if (t == 0) top_s[r] = prev.v;
+      if (t == 0) top_s[rnd] = prev.v;
     }
   }
   __syncthreads();
@@ -659,7 +833,6 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
 #pragma unroll
     for (int i = 0; i < 12; ++i) out->feats[i] = feat_s[i];
     out->score = score; out->halt = halt; out->executed = 1u;
-    if (force >= 0) a.logits[force] = forced_val;
     if (a.token_next) *a.token_next = best.i;
     if (a.block_slot) *a.block_slot = best.i;
     if (a.sl_count) *a.sl_count += 1;
@@ -668,7 +841,10 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
 }
 
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(k_classify, dim3(1), dim3(FEAT_NT), 0, s, a);
+  if (a.vocab < 1 || a.vocab > 65536) return hipErrorInvalidValue;
+  if (a.vocab <= 8192) hipLaunchKernelGGL(k_classify<2>, dim3(1), dim3(FEAT_NT), 0, s, a);
+  else if (a.vocab <= 32768) hipLaunchKernelGGL(k_classify<8>, dim3(1), dim3(FEAT_NT), 0, s, a);
+  else hipLaunchKernelGGL(k_classify<16>, dim3(1), dim3(FEAT_NT), 0, s, a);
   return hipGetLastError();
 }
 
