@@ -126,8 +126,9 @@ void disco_model_destroy(disco_model* m);
 size_t disco_kv_bytes(const disco_model* m, int capacity_tokens, int page_tokens);
 /* dev_pages: caller's buffer of at least disco_kv_bytes(...), 256-byte aligned.  Logical page i of
  * the sequence lives in physical page host_page_order[i] (a permutation of 0..n_pages-1), or in
- * page i when host_page_order is NULL.  Page layout:
- * [layer][physical page][K | V][kv head][token in page][d_head] bf16.                             */
+ * page i when host_page_order is NULL.  page_tokens must be a multiple of 4.  Page layout:
+ * [layer][physical page][K | V][kv head] blocks of page_tokens x d_head bf16; K blocks are
+ * [token][d_head], V blocks are stored transposed, [d_head][token].                               */
 int disco_kv_create(const disco_model* m, void* dev_pages, size_t bytes, int capacity_tokens,
                     int page_tokens, const int32_t* host_page_order, disco_kv** out);
 void disco_kv_destroy(disco_kv* kv);

@@ -251,7 +251,7 @@ size_t disco_kv_bytes(const disco_model* m, int capacity_tokens, int page_tokens
 int disco_kv_create(const disco_model* m, void* dev_pages, size_t bytes, int capacity_tokens, int page_tokens,
                     const int32_t* host_page_order, disco_kv** out) {
   if (!m || !dev_pages || !out) return fail(DISCO_EINVAL, "null argument");
-  if (capacity_tokens < 1 || page_tokens < 1) return fail(DISCO_EINVAL, "capacity and page size must be positive");
+  if (capacity_tokens < 1 || page_tokens < 4 || page_tokens % 4) return fail(DISCO_EINVAL, "capacity must be positive and the page size a positive multiple of 4");
   if (!aligned(dev_pages, 256)) return fail(DISCO_EINVAL, "KV buffer must be 256-byte aligned");
   const size_t need = disco_kv_bytes(m, capacity_tokens, page_tokens);
   if (bytes < need) return fail(DISCO_ECAP, "KV buffer of %zu bytes, %zu needed", bytes, need);

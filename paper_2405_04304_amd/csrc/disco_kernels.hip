@@ -11,7 +11,8 @@
 //     columns 0..7 and lo in columns 8..15 (one MFMA per weight tile); for M <= 16 two panels
 //     (hi, lo).  Panel element (column n, k) lives at ((kt * 64) + (k % 32 / 8) * 16 + n) * 8 + k % 8,
 //     kt = k / 32, panels K * 16 elements apart.
-//   * paged KV: [layer][physical page][K | V][kv head][token in page][d_head] bf16.
+//   * paged KV: [layer][physical page][K | V][kv head] blocks of page_tokens x d_head bf16; a K block
+//     is [token][d_head], a V block is transposed, [d_head][token] (see the attention kernel).
 #include "disco_internal.h"
 
 namespace disco {
@@ -324,14 +325,23 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
       const int kvh = head - a.nq - sel * a.nkv;
       const int lp = pos / a.page_tokens, off = pos % a.page_tokens;
       const int pp = a.page_table ? a.page_table[lp] : lp;
-      bf16_t* dst = a.kv_layer + ((((size_t)pp * 2 + sel) * a.nkv + kvh) * a.page_tokens + off) * a.dh + c;
-      uint2 u0, u1;
-      u0.x = (uint32_t)f32_to_bf16(lo4[0]) | ((uint32_t)f32_to_bf16(lo4[1]) << 16);
-      u0.y = (uint32_t)f32_to_bf16(lo4[2]) | ((uint32_t)f32_to_bf16(lo4[3]) << 16);
-      u1.x = (uint32_t)f32_to_bf16(hi4[0]) | ((uint32_t)f32_to_bf16(hi4[1]) << 16);
-      u1.y = (uint32_t)f32_to_bf16(hi4[2]) | ((uint32_t)f32_to_bf16(hi4[3]) << 16);
-      *reinterpret_cast<uint2*>(dst) = u0;
-      *reinterpret_cast<uint2*>(dst + half) = u1;
+      bf16_t* blk = a.kv_layer + (((size_t)pp * 2 + sel) * a.nkv + kvh) * a.page_tokens * a.dh;
+      if (!is_v) {                 // K: [token][d_head]
+        bf16_t* dst = blk + (size_t)off * a.dh + c;
+        uint2 u0, u1;
+        u0.x = (uint32_t)f32_to_bf16(lo4[0]) | ((uint32_t)f32_to_bf16(lo4[1]) << 16);
+        u0.y = (uint32_t)f32_to_bf16(lo4[2]) | ((uint32_t)f32_to_bf16(lo4[3]) << 16);
+        u1.x = (uint32_t)f32_to_bf16(hi4[0]) | ((uint32_t)f32_to_bf16(hi4[1]) << 16);
+        u1.y = (uint32_t)f32_to_bf16(hi4[2]) | ((uint32_t)f32_to_bf16(hi4[3]) << 16);
+        *reinterpret_cast<uint2*>(dst) = u0;
+        *reinterpret_cast<uint2*>(dst + half) = u1;
+      } else {                     // V: transposed, [d_head][token]
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          blk[(size_t)(c + v) * a.page_tokens + off] = f32_to_bf16(lo4[v]);
+          blk[(size_t)(c + half + v) * a.page_tokens + off] = f32_to_bf16(hi4[v]);
+        }
+      }
     }
   } else if (EPI == EPI_SWIGLU) {
     // tile 0 = gate rows, tile 1 = the matching up rows
@@ -453,10 +463,14 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
       } else {
         v[i] = *reinterpret_cast<const float4*>(h + k);
       }
-      for (int sp = 0; sp < a.n_part; ++sp) {
-        const float4 p = *reinterpret_cast<const float4*>(a.part + (size_t)sp * a.part_stride + (size_t)m * d + k);
-        v[i].x += p.x; v[i].y += p.y; v[i].z += p.z; v[i].w += p.w;
-      }
+      // all partial planes are fetched before the (fixed-order) additions: one memory round trip
+      float4 pp[GEMM_MAX_SPLIT];
+#pragma unroll
+      for (int sp = 0; sp < GEMM_MAX_SPLIT; ++sp)
+        if (sp < a.n_part) pp[sp] = *reinterpret_cast<const float4*>(a.part + (size_t)sp * a.part_stride + (size_t)m * d + k);
+#pragma unroll
+      for (int sp = 0; sp < GEMM_MAX_SPLIT; ++sp)
+        if (sp < a.n_part) { v[i].x += pp[sp].x; v[i].y += pp[sp].y; v[i].z += pp[sp].z; v[i].w += pp[sp].w; }
       if (e || a.n_part > 0) *reinterpret_cast<float4*>(h + k) = v[i];
     }
   }
@@ -494,7 +508,7 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
 }
 
 hipError_t launch_norm(const NormArgs& a, hipStream_t s) {
-  if (a.M < 1 || a.M > 16 || (a.d & 31) || a.d > 8192 || a.n_part < 0) return hipErrorInvalidValue;
+  if (a.M < 1 || a.M > 16 || (a.d & 31) || a.d > 8192 || a.n_part < 0 || a.n_part > GEMM_MAX_SPLIT) return hipErrorInvalidValue;
   if (a.d <= 2048) hipLaunchKernelGGL(k_norm<256>, dim3(a.M), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(k_norm<1024>, dim3(a.M), dim3(1024), 0, s, a);
   return hipGetLastError();
@@ -504,110 +518,156 @@ hipError_t launch_norm(const NormArgs& a, hipStream_t s) {
 // paged attention: M <= 16 queries of one head against cached positions, causal inside the block
 // ---------------------------------------------------------------------------------------------
 
-constexpr int ATTN_CH = 64;  // positions staged in LDS per step
+// Workgroup = (query head, range of split_len cached positions), 4 wavefronts; a wavefront takes 32
+// positions per step straight from the paged cache into matrix-unit operands:
+//   S^T[key][query]  = K[16 keys x d_head] . Q^T      (16x16x32 bf16; K rows are 128-bit loads;
+//                                                     q is fp32 split into bf16 hi + lo)
+//   O^T[chan][query] = V^T[16 chan x 16 keys] . P^T   (16x16x16 bf16; the S accumulator layout is
+//                                                     exactly this instruction's P operand layout,
+//                                                     so probabilities never leave registers)
+// which is why V is cached transposed ([d_head][token] inside a page).  Soft-max statistics run
+// per query across the four 16-lane rows; P is fed as bf16 hi + lo.  The four wavefronts merge
+// their (max, sum, O) through LDS and write one partial record per (head, range, query).
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+__device__ __forceinline__ float row4_max(float v) {   // across lanes l, l^16, l^32, l^48
+  v = fmaxf(v, __shfl_xor(v, 16));
+  return fmaxf(v, __shfl_xor(v, 32));
+}
+__device__ __forceinline__ float row4_sum(float v) {
+  v += __shfl_xor(v, 16);
+  return v + __shfl_xor(v, 32);
+}
 
 template <int DH>
 __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
   if (gated(a.gate)) return;
-  constexpr int LDK = DH + 8;                 // padded row (elements) against LDS bank conflicts
-  constexpr int G = 256 / DH;                 // query groups in the P.V phase
-  constexpr int MAXQ = (16 + G - 1) / G;
-  __shared__ float q_s[16][DH];
-  __shared__ __attribute__((aligned(16))) bf16_t k_s[ATTN_CH][LDK];
-  __shared__ __attribute__((aligned(16))) bf16_t v_s[ATTN_CH][LDK];
-  __shared__ float p_s[16][ATTN_CH];
-  __shared__ float m_s[16], l_s[16], al_s[16];
-
-  const int head = blockIdx.x, split = blockIdx.y, t = threadIdx.x;
+  constexpr int KS = DH / 32, CT = DH / 16, NWV = 4, WKEYS = 32;
+  __shared__ f32x4 o_s[NWV][CT][64];
+  __shared__ float m_s[NWV][16], l_s[NWV][16];
+  const int head = blockIdx.x, split = blockIdx.y;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int j = lane & 15, g = lane >> 4;
   const int kvh = head / (a.nq / a.nkv);
-  const int total = a.pos0 + a.M;
-  const int s0 = split * a.split_len;
-  const int s1 = min(s0 + a.split_len, total);
+  const int total = a.pos0 + a.M, pt = a.page_tokens;
+  const int s0 = split * a.split_len, s1 = min(s0 + a.split_len, total);
+  const size_t kv_head_elems = (size_t)pt * DH;                  // one head's K (or V) block in a page
+  const size_t page_elems = 2 * (size_t)a.nkv * kv_head_elems;
 
-  for (int i = t; i < a.M * DH; i += 256) q_s[i / DH][i % DH] = a.q[(size_t)(i / DH) * a.ldq + head * DH + (i % DH)];
-  if (t < 16) { m_s[t] = NEG_BIG; l_s[t] = 0.f; al_s[t] = 1.f; }
-  float o[MAXQ];
-#pragma unroll
-  for (int i = 0; i < MAXQ; ++i) o[i] = 0.f;
-  __syncthreads();
-
-  for (int t0 = s0; t0 < s1; t0 += ATTN_CH) {
-    const int n_tok = min(ATTN_CH, s1 - t0);
-    // stage K and V rows of this chunk
-    constexpr int VPR = DH / 8;               // 16-byte vectors per row
-    for (int rr = t / VPR; rr < n_tok; rr += 256 / VPR) {
-      const int pos = t0 + rr, lp = pos / a.page_tokens, off = pos % a.page_tokens;
-      const int pp = a.page_table ? a.page_table[lp] : lp;
-      const bf16_t* kp = a.kv_layer + ((((size_t)pp * 2 + 0) * a.nkv + kvh) * a.page_tokens + off) * DH + (t % VPR) * 8;
-      const bf16_t* vp = kp + (size_t)a.nkv * a.page_tokens * DH;
-      *reinterpret_cast<uint4*>(&k_s[rr][(t % VPR) * 8]) = *reinterpret_cast<const uint4*>(kp);
-      *reinterpret_cast<uint4*>(&v_s[rr][(t % VPR) * 8]) = *reinterpret_cast<const uint4*>(vp);
-    }
-    __syncthreads();
-    // scores: thread = (position j, query group)
-    {
-      const int j = t & 63;
-      for (int m = t >> 6; m < a.M; m += 4) {
-        float sc = NEG_BIG;
-        if (j < n_tok && t0 + j <= a.pos0 + m) {
-          float acc = 0.f;
-#pragma unroll
-          for (int c = 0; c < DH; c += 8) {
-            const uint4 kk = *reinterpret_cast<const uint4*>(&k_s[j][c]);
-            const float* qq = &q_s[m][c];
-            acc += qq[0] * bf16_to_f32(kk.x & 0xFFFF) + qq[1] * bf16_to_f32(kk.x >> 16)
-                 + qq[2] * bf16_to_f32(kk.y & 0xFFFF) + qq[3] * bf16_to_f32(kk.y >> 16)
-                 + qq[4] * bf16_to_f32(kk.z & 0xFFFF) + qq[5] * bf16_to_f32(kk.z >> 16)
-                 + qq[6] * bf16_to_f32(kk.w & 0xFFFF) + qq[7] * bf16_to_f32(kk.w >> 16);
-          }
-          sc = acc * a.scale;
-        }
-        p_s[m][j] = sc;
-      }
-    }
-    __syncthreads();
-    // running soft-max per query: wavefront w owns queries w, w + 4, ..
-    {
-      const int lane = t & 63;
-      for (int m = t >> 6; m < a.M; m += 4) {
-        const float sc = p_s[m][lane];
-        const float m_old = m_s[m];
-        const float m_new = fmaxf(m_old, wave_max(sc));
-        const float e = (sc > 0.5f * NEG_BIG) ? expf(sc - m_new) : 0.f;
-        const float sum = wave_sum(e);
-        const float alpha = expf(m_old - m_new);
-        p_s[m][lane] = e;
-        if (lane == 0) { m_s[m] = m_new; l_s[m] = l_s[m] * alpha + sum; al_s[m] = alpha; }
-      }
-    }
-    __syncthreads();
-    // o = o * alpha + P . V : thread = (channel c, query group)
-    {
-      const int c = t % DH, mg = t / DH;
-#pragma unroll
-      for (int i = 0; i < MAXQ; ++i) {
-        const int m = mg + i * G;
-        if (m < a.M) {
-          float acc = o[i] * al_s[m];
-          for (int j = 0; j < n_tok; ++j) acc += p_s[m][j] * bf16_to_f32(v_s[j][c]);
-          o[i] = acc;
-        }
-      }
-    }
-    __syncthreads();
-  }
-  // partial record per (head, split, query): o[DH], running max, running sum
+  // query operand: column j holds query min(j, M-1) (surplus columns are never stored)
+  bf16x8 qh[KS], ql[KS];
   {
-    const int c = t % DH, mg = t / DH;
+    const float* qp = a.q + (size_t)min(j, a.M - 1) * a.ldq + head * DH + 8 * g;
 #pragma unroll
-    for (int i = 0; i < MAXQ; ++i) {
-      const int m = mg + i * G;
-      if (m < a.M) {
-        float* rec = a.part + (((size_t)head * a.n_splits + split) * 16 + m) * (DH + 2);
-        rec[c] = o[i];
-        if (c == 0) { rec[DH] = m_s[m]; rec[DH + 1] = l_s[m]; }
+    for (int ks = 0; ks < KS; ++ks) {
+      const float4 x0 = *reinterpret_cast<const float4*>(qp + ks * 32), x1 = *reinterpret_cast<const float4*>(qp + ks * 32 + 4);
+      const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+      union { bf16_t u[8]; bf16x8 v; } h, l;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { h.u[i] = f32_to_bf16(xv[i]); l.u[i] = f32_to_bf16(xv[i] - bf16_to_f32(h.u[i])); }
+      qh[ks] = h.v; ql[ks] = l.v;
+    }
+  }
+  f32x4 O[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) O[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = NEG_BIG, l_run = 0.f;
+  const int qpos = a.pos0 + j;                                    // last position query j may see
+
+  for (int base = s0 + w * WKEYS; base < s1; base += NWV * WKEYS) {
+    f32x4 S[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int kb = base + 16 * t;
+      S[t] = f32x4{NEG_BIG, NEG_BIG, NEG_BIG, NEG_BIG};
+      if (kb < s1) {
+        const int p = min(kb + j, total - 1), lp = p / pt, off = p - lp * pt;
+        const int pp = a.page_table ? a.page_table[lp] : lp;
+        const bf16_t* kp = a.kv_layer + (size_t)pp * page_elems + (size_t)kvh * kv_head_elems + (size_t)off * DH + 8 * g;
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const bf16x8 kk = as_bf16x8(*reinterpret_cast<const u32x4*>(kp + ks * 32));
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[ks], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[ks], acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int pos = kb + 4 * g + v;
+          if (pos < s1 && pos <= qpos) S[t][v] = acc[v] * a.scale;
+        }
       }
     }
+    float mx = fmaxf(fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3])), fmaxf(fmaxf(S[1][0], S[1][1]), fmaxf(S[1][2], S[1][3])));
+    mx = row4_max(mx);
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = expf(m_run - m_new);
+    float sum = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const float e = (S[t][v] > 0.5f * NEG_BIG) ? expf(S[t][v] - m_new) : 0.f;
+        S[t][v] = e;
+        sum += e;
+      }
+    sum = row4_sum(sum);
+    l_run = l_run * alpha + sum;
+    m_run = m_new;
+#pragma unroll
+    for (int c = 0; c < CT; ++c) O[c] *= alpha;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int kb = base + 16 * t;
+      if (kb < s1) {
+        union { bf16_t u[4]; s16x4 v; } ph, pl;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) { ph.u[v] = f32_to_bf16(S[t][v]); pl.u[v] = f32_to_bf16(S[t][v] - bf16_to_f32(ph.u[v])); }
+        // V^T operand: channel row = lane % 16 of each 16-channel tile, 4 consecutive positions
+        const int p0 = kb + 4 * g;
+        const int pc = min(p0, (total - 1) & ~3), lp = pc / pt, off = pc - lp * pt;
+        const int pp = a.page_table ? a.page_table[lp] : lp;
+        const bf16_t* vp = a.kv_layer + (size_t)pp * page_elems + (size_t)(a.nkv + kvh) * kv_head_elems + (size_t)j * pt + off;
+        // positions at or beyond `total` hold stale bytes: zero them (0 * NaN would poison the sum)
+        uint2 keep;
+        keep.x = (p0 < total ? 0x0000FFFFu : 0u) | (p0 + 1 < total ? 0xFFFF0000u : 0u);
+        keep.y = (p0 + 2 < total ? 0x0000FFFFu : 0u) | (p0 + 3 < total ? 0xFFFF0000u : 0u);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+          uint2 raw = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * pt);
+          raw.x &= keep.x; raw.y &= keep.y;
+          union { uint2 u; s16x4 v; } vv; vv.u = raw;
+          O[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vv.v, ph.v, O[c], 0, 0, 0);
+          O[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vv.v, pl.v, O[c], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  // merge the four wavefronts (fixed order), then one record per query: o[DH], max, sum
+#pragma unroll
+  for (int c = 0; c < CT; ++c) o_s[w][c][lane] = O[c];
+  if (g == 0) { m_s[w][j] = m_run; l_s[w][j] = l_run; }
+  __syncthreads();
+  float mm = m_s[0][j];
+#pragma unroll
+  for (int ww = 1; ww < NWV; ++ww) mm = fmaxf(mm, m_s[ww][j]);
+  float f[NWV], ll = 0.f;
+#pragma unroll
+  for (int ww = 0; ww < NWV; ++ww) { f[ww] = expf(m_s[ww][j] - mm); ll += l_s[ww][j] * f[ww]; }
+  if (j < a.M) {
+    float* rec = a.part + (((size_t)head * a.n_splits + split) * 16 + j) * (DH + 2);
+#pragma unroll
+    for (int ci = 0; ci < CT / NWV; ++ci) {
+      const int c = w * (CT / NWV) + ci;
+      f32x4 o = o_s[0][c][lane] * f[0];
+#pragma unroll
+      for (int ww = 1; ww < NWV; ++ww) o += o_s[ww][c][lane] * f[ww];
+      *reinterpret_cast<float2*>(rec + c * 16 + 4 * g) = make_float2(o[0], o[1]);
+      *reinterpret_cast<float2*>(rec + c * 16 + 4 * g + 2) = make_float2(o[2], o[3]);
+    }
+    if (w == 0 && g == 0) { rec[DH] = mm; rec[DH + 1] = ll; }
   }
 }
 
@@ -905,8 +965,16 @@ __global__ __launch_bounds__(256) void k_kv_fill(const bf16_t* __restrict__ src,
     const int layer = (int)r;
     const int lp = pos / pt, off = pos % pt;
     const int pp = page_table ? page_table[lp] : lp;
-    const size_t dst = (((((size_t)layer * n_pages + pp) * 2 + sel) * nkv + kvh) * pt + off) * dh + cv * 8;
-    *reinterpret_cast<uint4*>(pages + dst) = *reinterpret_cast<const uint4*>(src + i * 8);
+    const size_t blk = ((((size_t)layer * n_pages + pp) * 2 + sel) * nkv + kvh) * pt * dh;
+    const uint4 val = *reinterpret_cast<const uint4*>(src + i * 8);
+    if (sel == 0) {                                   // K: [token][d_head]
+      *reinterpret_cast<uint4*>(pages + blk + (size_t)off * dh + cv * 8) = val;
+    } else {                                          // V: transposed, [d_head][token]
+      const uint32_t wv[4] = {val.x, val.y, val.z, val.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        pages[blk + (size_t)(cv * 8 + e) * pt + off] = (bf16_t)(wv[e >> 1] >> ((e & 1) * 16));
+    }
   }
 }
 
