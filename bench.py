@@ -24,6 +24,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE counters
+# (profiles/gemm_gateup_13b_hbm_traffic.txt; counters cannot be read from inside this process)
+GATEUP_TRAFFIC_BYTES = 279972 * 1024
 
 
 def log(*a):
@@ -90,6 +93,8 @@ def main():
     ap.add_argument("--prompt-len", type=int, default=512)
     ap.add_argument("--layers", type=int, default=0, help="debug: truncate the target (invalidates the number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run plain device copies of known size and exit (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process, one sequence); --gpus must be 1. "
@@ -97,6 +102,16 @@ def main():
         sys.exit(2)
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     dev = torch.device("cuda:0")
+
+    if args.calibrate_copy:
+        # 256 MiB read + 256 MiB written per launch: the counter reading of this kernel is the scale
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": True, "bytes_read_per_launch": 256 << 20, "bytes_written_per_launch": 256 << 20}))
+        return
 
     from paper_2405_04304_amd import binding as B
     from paper_2405_04304_amd.engine import SpecEngine
@@ -128,7 +143,7 @@ def main():
     # untimed input shaping: the target's own greedy text decides which draft logits get forced
     t0 = time.time()
     n_greedy = min(max_new, int(n_iter * 3.2) + 32)
-    greedy = eng.greedy(prompt, n_greedy)
+    greedy = eng.greedy(prompt, n_greedy, progress=lambda i: log(f"[bench] greedy target token {i}/{n_greedy}"))
     greedy += [0] * (max_new - n_greedy)
     mask = W.make_force_mask(5, max_new, args.alpha)
     mask[n_greedy:] = False
@@ -147,6 +162,8 @@ def main():
         torch.cuda.synchronize()
         stamps.append(time.perf_counter())
         probe_ms.append(B.disco_probe_read_ms())
+        if len(stamps) % 10 == 1:
+            log(f"[bench] iteration {len(stamps) - 1}/{n_iter}")
 
     eng.reset()
     eng.prefill(prompt[:-1])
@@ -200,7 +217,7 @@ def main():
         "iteration_hbm_frac": iter_bytes / (t_timed / args.steps) / 1e9 / HBM_PEAK_GBS,
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": GATEUP_TRAFFIC_BYTES if not args.layers else None,
             "kernel": "k_gemm<*,2,EPI_SWIGLU> (target gate/up GEMM + SwiGLU)",
             "bytes_per_launch": gemm_bytes, "avg_launch_ms": gemm_ms, "launches_timed": len(pm),
             "timing": f"HIP events around the launch of layer {probe_layer} in every timed verification forward",

@@ -58,12 +58,14 @@ class SpecEngine:
                 B.disco_verify(model, kv, toks.data_ptr() + 4 * i, n, self.argmax, None, ws)
         torch.cuda.synchronize(self.dev)
 
-    def greedy(self, prompt: Sequence[int], max_new: int) -> List[int]:
+    def greedy(self, prompt: Sequence[int], max_new: int, progress=None) -> List[int]:
         """Plain greedy decoding of the target (verification blocks of one token)."""
         self.reset()
         self.prefill(prompt[:-1])
         out, last = [], int(prompt[-1])
-        for _ in range(max_new):
+        for i in range(max_new):
+            if progress is not None and i % 32 == 0:
+                progress(i)
             self._put_tokens([last])
             B.disco_verify(self.target, self.kv_t, self.tok_in, 1, self.argmax, None, self.ws_t)
             last = int(self.argmax[0].item())
