@@ -140,6 +140,12 @@ int disco_kv_fill(disco_kv* kv, const void* dev_src, int ctx, disco_stream s);
 
 /* Workspace bytes for forwards of up to max_block tokens against up to max_ctx cached positions.   */
 size_t disco_workspace_bytes(const disco_model* m, int max_block, int max_ctx);
+/* Must run once on a fresh workspace before its first use (and again if a launch that used it was
+ * aborted): zeroes the small ticket counters with which the workgroups of a split reduction find
+ * out which of them finishes last.  Kernels leave the counters at zero.  A workspace serves one
+ * stream at a time.                                                                               */
+int disco_workspace_init(const disco_model* m, void* dev_ws, size_t ws_bytes, int max_block, int max_ctx,
+                         disco_stream s);
 
 /* ---- the five calls of the iteration --------------------------------------------------------- */
 

@@ -72,6 +72,7 @@ _SIGNATURES = {
     "disco_kv_pages_in_use": (C.c_int, [C.c_void_p]),
     "disco_kv_fill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
     "disco_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int, C.c_int]),
+    "disco_workspace_init": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p]),
     "disco_draft_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
                                    C.c_size_t, C.c_void_p, C.c_void_p]),
     "disco_classify": (C.c_int, [C.POINTER(Clf), C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_int,
@@ -254,7 +255,9 @@ class DiscoModel:
         n = lib().disco_workspace_bytes(self.handle, max_block, max_ctx)
         if n == 0:
             raise DiscoError(EINVAL, "bad workspace request")
-        return Workspace(n, self.device)
+        ws = Workspace(n, self.device)
+        _check(lib().disco_workspace_init(self.handle, ws.buf.data_ptr(), n, max_block, max_ctx, _stream()))
+        return ws
 
     def close(self):
         if self.handle:

@@ -57,6 +57,7 @@ namespace {
 
 struct Ws {
   float* h; float* q; bf16_t* xn; bf16_t* xattn; bf16_t* xact; float* part; float* gpart; float* logits;
+  float* ssq; int* gemm_counters; int* attn_counters; int n_counters;
   uint32_t* gate; int32_t* sl_count; int32_t* tok_next;
   size_t total;
 };
@@ -74,13 +75,19 @@ Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
   w.xn = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * 16 * d.d_model));
   w.xattn = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * 16 * m->d_q));
   w.xact = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * 16 * d.d_ff));
-  const int n_splits = (max_ctx + DISCO_MAX_BLOCK + ATTN_SPLIT_LEN - 1) / ATTN_SPLIT_LEN;
-  w.part = static_cast<float*>(take(sizeof(float) * (size_t)d.n_heads * n_splits * 16 * (d.d_head + 2)));
   w.gpart = static_cast<float*>(take(sizeof(float) * GEMM_MAX_SPLIT * 16 * (size_t)d.d_model));
   w.logits = static_cast<float*>(take(sizeof(float) * 16 * (size_t)d.vocab));
+  w.ssq = static_cast<float*>(take(sizeof(float) * 16 * (size_t)(d.d_model / 16)));
+  w.n_counters = d.d_model / 16 + d.n_heads;
+  w.gemm_counters = static_cast<int*>(take(sizeof(int) * (size_t)w.n_counters));
+  w.attn_counters = w.gemm_counters ? w.gemm_counters + d.d_model / 16 : nullptr;
   w.gate = static_cast<uint32_t*>(take(256));
   w.sl_count = reinterpret_cast<int32_t*>(w.gate ? w.gate + 16 : nullptr);
   w.tok_next = reinterpret_cast<int32_t*>(w.gate ? w.gate + 32 : nullptr);
+  // the only buffer whose size depends on max_ctx goes last, so that every other offset (the ticket
+  // counters above all) is the same for every call on this workspace
+  const int n_splits = (max_ctx + DISCO_MAX_BLOCK + ATTN_SPLIT_LEN - 1) / ATTN_SPLIT_LEN;
+  w.part = static_cast<float*>(take(sizeof(float) * (size_t)d.n_heads * n_splits * 16 * (d.d_head + 2)));
   w.total = off;
   return w;
 }
@@ -109,30 +116,44 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   const int pos0 = kv->len;
   const bool fam_a = d.family == DISCO_FAMILY_A;
 
+  const int n_tiles = d.d_model / 16;            // one sum-of-squares slot per 16 columns of h
+  const int split_o = gemm_split_for(d.d_model, m->d_q / 32), split_dn = gemm_split_for(d.d_model, d.d_ff / 32);
+
   NormArgs na{};
   na.h = ws.h; na.d = d.d_model; na.M = n; na.layernorm = fam_a; na.eps = d.norm_eps;
   na.Xout = ws.xn; na.gate = gate; na.pos0 = pos0; na.vocab = d.vocab; na.max_pos = d.max_pos;
-  na.part = ws.gpart; na.part_stride = (int64_t)16 * d.d_model;
-  const int split_o = gemm_split_for(d.d_model, m->d_q / 32), split_dn = gemm_split_for(d.d_model, d.d_ff / 32);
+  if (!fam_a) { na.ssq_out = ws.ssq; na.n_ssq_out = n_tiles; }   // RMSNorm is deferred to the consumer GEMM
 
-  for (int l = 0; l <= d.n_layers; ++l) {
-    // norm feeding layer l (or the LM head when l == n_layers); the first one also embeds
-    NormArgs n1 = na;
-    if (l < d.n_layers) { n1.g = m->layers[l].norm1_g; n1.b = m->layers[l].norm1_b; }
-    else { n1.g = m->w.normf_g; n1.b = m->w.normf_b; }
-    n1.n_part = (l == 0) ? 0 : split_dn;      // adds the previous layer's MLP output to the stream
-    if (l == 0) {
-      n1.tokens = dev_tokens; n1.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb);
-      n1.tok_stride = m->w.tok_emb_stride; n1.pos_emb = static_cast<const bf16_t*>(m->w.pos_emb);
-    }
-    HIP_TRY(launch_norm(n1, s), "norm launch");
-    if (l == d.n_layers) break;
+  // Family B: every GEMM that reads a normalised row reads gain * h panels and rescales by 1 / rms
+  // in its epilogue; the residual-update GEMMs write those panels.  Family A keeps LayerNorm kernels.
+  auto normed_input = [&](GemmArgs& g) {
+    g.X = ws.xn; g.KT = d.d_model / 32;
+    if (!fam_a) { g.ssq = ws.ssq; g.n_ssq = n_tiles; g.d_in = d.d_model; g.eps = d.norm_eps; }
+  };
+  auto residual_update = [&](GemmArgs& g, const void* w, const bf16_t* x, int k, int split, const float* next_gain) {
+    g.M = n; g.gate = gate; g.W = static_cast<const bf16_t*>(w); g.X = x; g.KT = k / 32;
+    g.n_rows = d.d_model; g.h = ws.h; g.out = ws.gpart; g.ld_out = d.d_model; g.only_row = -1;
+    g.n_split = split; g.part_stride = (int64_t)16 * d.d_model; g.counters = ws.gemm_counters;
+    if (!fam_a) { g.Xout = ws.xn; g.KT_out = d.d_model / 32; g.gain = next_gain; g.ssq_out = ws.ssq; g.n_ssq_out = n_tiles; }
+  };
+
+  {
+    NormArgs n0 = na;
+    n0.g = m->layers[0].norm1_g; n0.b = m->layers[0].norm1_b;
+    n0.tokens = dev_tokens; n0.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb);
+    n0.tok_stride = m->w.tok_emb_stride; n0.pos_emb = static_cast<const bf16_t*>(m->w.pos_emb);
+    HIP_TRY(launch_norm(n0, s), "embedding launch");
+  }
+  for (int l = 0; l < d.n_layers; ++l) {
     const disco_layer_weights& L = m->layers[l];
+    const bool last = (l + 1 == d.n_layers);
+    const float* next_g = last ? m->w.normf_g : m->layers[l + 1].norm1_g;
+    const float* next_b = last ? m->w.normf_b : m->layers[l + 1].norm1_b;
 
     GemmArgs g{};
     g.M = n; g.gate = gate;
     // QKV projection, rotary, KV append
-    g.W = static_cast<const bf16_t*>(L.wqkv); g.X = ws.xn; g.KT = d.d_model / 32; g.n_rows = m->d_qkv;
+    g.W = static_cast<const bf16_t*>(L.wqkv); normed_input(g); g.n_rows = m->d_qkv;
     g.grp = d.d_head / 32; g.q = ws.q; g.ldq = m->d_q; g.nq = d.n_heads; g.nkv = d.n_kv_heads; g.dh = d.d_head;
     g.pos0 = pos0; g.rope = fam_a ? 0 : 1; g.rope_base = d.rope_base;
     g.kv_layer = kv->pages + (size_t)l * kv->layer_stride; g.page_table = kv->dev_page_table;
@@ -144,21 +165,21 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     at.page_tokens = kv->page_tokens; at.nq = d.n_heads; at.nkv = d.n_kv_heads; at.dh = d.d_head; at.M = n;
     at.pos0 = pos0; at.scale = 1.0f / sqrtf((float)d.d_head); at.part = ws.part;
     at.split_len = ATTN_SPLIT_LEN; at.n_splits = (pos0 + n + ATTN_SPLIT_LEN - 1) / ATTN_SPLIT_LEN;
-    at.Xout = ws.xattn; at.gate = gate;
+    at.Xout = ws.xattn; at.counters = ws.attn_counters; at.gate = gate;
     HIP_TRY(launch_attn(at, s), "attention launch");
 
     GemmArgs o{};
-    o.M = n; o.gate = gate; o.W = static_cast<const bf16_t*>(L.wo); o.X = ws.xattn; o.KT = m->d_q / 32;
-    o.n_rows = d.d_model; o.out = ws.gpart; o.ld_out = d.d_model; o.only_row = -1;
-    o.n_split = split_o; o.part_stride = na.part_stride;
+    residual_update(o, L.wo, ws.xattn, m->d_q, split_o, L.norm2_g);
     HIP_TRY(launch_gemm(o, EPI_PARTIAL, s), "o-proj launch");
 
-    NormArgs n2 = na;
-    n2.g = L.norm2_g; n2.b = L.norm2_b; n2.n_part = split_o;   // adds the attention output to the stream
-    HIP_TRY(launch_norm(n2, s), "norm launch");
+    if (fam_a) {
+      NormArgs n2 = na;
+      n2.g = L.norm2_g; n2.b = L.norm2_b;
+      HIP_TRY(launch_norm(n2, s), "norm launch");
+    }
 
     GemmArgs u{};
-    u.M = n; u.gate = gate; u.W = static_cast<const bf16_t*>(L.w_in); u.X = ws.xn; u.KT = d.d_model / 32;
+    u.M = n; u.gate = gate; u.W = static_cast<const bf16_t*>(L.w_in); normed_input(u);
     u.n_rows = fam_a ? d.d_ff : 2 * d.d_ff; u.grp = 1; u.Xout = ws.xact; u.KT_out = d.d_ff / 32;
     const bool probe = (l == g_probe_layer) && g_probe_ev[0] != nullptr;
     if (probe) HIP_TRY(hipEventRecord(g_probe_ev[0], s), "probe event");
@@ -166,13 +187,17 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     if (probe) { HIP_TRY(hipEventRecord(g_probe_ev[1], s), "probe event"); g_probe_taken = true; }
 
     GemmArgs dn{};
-    dn.M = n; dn.gate = gate; dn.W = static_cast<const bf16_t*>(L.w_out); dn.X = ws.xact; dn.KT = d.d_ff / 32;
-    dn.n_rows = d.d_model; dn.out = ws.gpart; dn.ld_out = d.d_model; dn.only_row = -1;
-    dn.n_split = split_dn; dn.part_stride = na.part_stride;
+    residual_update(dn, L.w_out, ws.xact, d.d_ff, split_dn, next_g);
     HIP_TRY(launch_gemm(dn, EPI_PARTIAL, s), "mlp-out launch");
+
+    if (fam_a) {
+      NormArgs n3 = na;
+      n3.g = next_g; n3.b = next_b;
+      HIP_TRY(launch_norm(n3, s), "norm launch");
+    }
   }
   GemmArgs lm{};
-  lm.M = n; lm.gate = gate; lm.W = static_cast<const bf16_t*>(m->w.wlm); lm.X = ws.xn; lm.KT = d.d_model / 32;
+  lm.M = n; lm.gate = gate; lm.W = static_cast<const bf16_t*>(m->w.wlm); normed_input(lm);
   lm.n_rows = d.vocab; lm.out = logits_out; lm.ld_out = d.vocab; lm.only_row = only_last ? n - 1 : -1;
   HIP_TRY(launch_gemm(lm, EPI_STORE, s), "lm-head launch");
   kv->len = pos0 + n;
@@ -209,6 +234,7 @@ int disco_model_create(const disco_model_desc* desc, const disco_model_weights* 
   if (d.family != DISCO_FAMILY_A && d.family != DISCO_FAMILY_B) return fail(DISCO_EINVAL, "unknown family %d", d.family);
   if (d.n_layers < 1 || d.d_model < 32 || d.d_model % 32 || d.d_ff < 32 || d.d_ff % 32 || d.vocab < 16 || d.vocab % 16)
     return fail(DISCO_EINVAL, "d_model and d_ff must be multiples of 32, vocab of 16");
+  if (d.d_model % 64) return fail(DISCO_EINVAL, "d_model must be a multiple of 64");
   if (d.d_model > 8192) return fail(DISCO_EINVAL, "d_model %d above 8192 unsupported", d.d_model);
   if (d.d_head != 64 && d.d_head != 128) return fail(DISCO_EINVAL, "d_head %d unsupported (64 or 128)", d.d_head);
   if (d.n_heads < 1 || d.n_kv_heads < 1 || d.n_heads % d.n_kv_heads) return fail(DISCO_EINVAL, "n_heads must be a multiple of n_kv_heads");
@@ -302,6 +328,16 @@ int disco_kv_fill(disco_kv* kv, const void* dev_src, int ctx, disco_stream s) {
 size_t disco_workspace_bytes(const disco_model* m, int max_block, int max_ctx) {
   if (!m || max_block < 1 || max_block > DISCO_MAX_BLOCK || max_ctx < 0) return 0;
   return carve(m, max_block, max_ctx, nullptr).total;
+}
+
+int disco_workspace_init(const disco_model* m, void* dev_ws, size_t ws_bytes, int max_block, int max_ctx, disco_stream s) {
+  if (!m || !dev_ws) return fail(DISCO_EINVAL, "null argument");
+  if (!aligned(dev_ws, 256)) return fail(DISCO_EINVAL, "misaligned workspace");
+  const size_t need = disco_workspace_bytes(m, max_block, max_ctx);
+  if (need == 0 || ws_bytes < need) return fail(DISCO_EINVAL, "workspace of %zu bytes, %zu needed", ws_bytes, need);
+  const Ws ws = carve(m, max_block, max_ctx, dev_ws);
+  HIP_TRY(launch_zero(ws.gemm_counters, ws.n_counters, static_cast<hipStream_t>(s)), "workspace init launch");
+  return DISCO_OK;
 }
 
 int disco_draft_step(const disco_model* draft, disco_kv* kv, const int32_t* dev_tokens_in, int n_in, float* dev_logits,

@@ -15,8 +15,8 @@ enum Epi {
   EPI_QKV = 2,     // rotary (optional) + q store + paged K/V append
   EPI_SWIGLU = 3,  // silu(gate) * up  -> packed activation panel
   EPI_GELU = 4,    // gelu(y)          -> packed activation panel
-  EPI_PARTIAL = 5, // out[split][m][n] = y     (O-projection, MLP down: split-K partial sums that the
-                   //                           next norm kernel adds to the residual stream)
+  EPI_PARTIAL = 5, // h[m][n] += y             (O-projection, MLP down; K may be split over workgroups,
+                   //                           partial planes in `out`, last workgroup adds them up)
 };
 
 struct GemmArgs {
@@ -29,7 +29,11 @@ struct GemmArgs {
   const uint32_t* gate; // optional: skip when *gate != 0
   int n_split;          // K ranges (grid.y); > 1 only with EPI_PARTIAL
   int64_t part_stride;  // elements between the partial-sum planes of EPI_PARTIAL
-  float* out;           // RESID / STORE / PARTIAL target, row stride ld_out
+  const float* ssq; int n_ssq; int d_in; float eps;   // deferred RMSNorm of the input (ssq == nullptr: none)
+  int* counters;        // PARTIAL with n_split > 1: one zeroed ticket counter per workgroup column
+  float* h;             // PARTIAL: residual stream updated in place, row stride ld_out
+  const float* gain; float* ssq_out; int n_ssq_out;   // PARTIAL with Xout: next norm's gain, sums of squares
+  float* out;           // STORE target / PARTIAL planes, row stride ld_out
   int64_t ld_out;
   int only_row;         // STORE: write only this token's row to out[0..N) (-1: all rows)
   // QKV epilogue
@@ -43,7 +47,7 @@ struct NormArgs {
   float* h; int d; int M; int layernorm; float eps;
   const float* g; const float* b;
   bf16_t* Xout;                      // packed panels, K = d
-  const float* part; int n_part; int64_t part_stride;  // split-K partial sums to add to h first
+  float* ssq_out; int n_ssq_out;     // deferred RMSNorm: write gain * h panels and the row's sum of squares
   // embedding mode (tokens != nullptr): h = tok_emb[token] (+ pos_emb[pos0 + m]) first
   const int32_t* tokens; const bf16_t* tok_emb; int64_t tok_stride; const bf16_t* pos_emb;
   int pos0; int vocab; int max_pos;
@@ -56,6 +60,7 @@ struct AttnArgs {
   int nq, nkv, dh, M, pos0; float scale;
   float* part; int n_splits; int split_len;
   bf16_t* Xout;                      // packed panels, K = nq * dh
+  int* counters;                     // one zeroed ticket counter per query head
   const uint32_t* gate;
 };
 
@@ -79,6 +84,7 @@ hipError_t launch_accept(const int32_t* block, const int32_t* argmax, int n_bloc
                          const int32_t* dev_n_block, void* dev_out, void* host_out, hipStream_t s);
 hipError_t launch_kv_fill(const bf16_t* src, bf16_t* pages, const int32_t* page_table, int n_layers,
                           int n_pages, int page_tokens, int nkv, int dh, int ctx, hipStream_t s);
+hipError_t launch_zero(int* p, int n, hipStream_t s);
 hipError_t launch_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in,
                             void* dev_loop_out, hipStream_t s);
 hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void* host_loop_out,

@@ -96,6 +96,42 @@ __device__ __forceinline__ float wave_max(float v) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 
+// Hand-off between workgroups of one launch (split reductions).  Data written by one workgroup and
+// read by another inside the same kernel moves with agent-scope relaxed atomic stores / loads: on
+// gfx950 these are write-through / L2-bypassing accesses (sc1), coherent across the eight XCDs'
+// separate L2s without the L2-wide write-back and invalidate that an agent-scope fence costs.  The
+// writers drain their stores (s_waitcnt 0) before the workgroup barrier that precedes the ticket.
+__device__ __forceinline__ void st_agent2(float* p, float a, float b) {
+  const unsigned long long v = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 ld_agent2(const float* p) {
+  const unsigned long long v = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
+}
+// Ticket of a split reduction: true in every thread of the workgroup that arrives last.
+__device__ __forceinline__ bool last_arrival(int* counter, int n, int* s_flag) {
+  __builtin_amdgcn_s_waitcnt(0);                 // this wavefront's hand-off stores have completed
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int t = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_flag = (t == n - 1) ? 1 : 0;
+    if (t == n - 1) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+  }
+  __syncthreads();
+  return *s_flag != 0;
+}
+
+// Across the four 16-lane rows of a wavefront (lanes l, l^16, l^32, l^48), every lane gets the result.
+__device__ __forceinline__ float row4_max(float v) {
+  v = fmaxf(v, __shfl_xor(v, 16));
+  return fmaxf(v, __shfl_xor(v, 32));
+}
+__device__ __forceinline__ float row4_sum(float v) {
+  v += __shfl_xor(v, 16);
+  return v + __shfl_xor(v, 32);
+}
+
 // Block-wide sum in a fixed order (deterministic); every thread gets the result.
 template <int NT>
 __device__ __forceinline__ float block_sum(float v, float* smem /* NT/64 + 1 floats */) {
@@ -178,9 +214,9 @@ hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int
 //
 // Workgroup (blockIdx.x, blockIdx.y) owns RT 16-row tiles and the blockIdx.y-th of n_split equal
 // K ranges.  Its NW wavefronts interleave over the k-tiles of that range, each keeping U k-tiles of
-// loads in flight, and reduce through LDS in a fixed order.  With n_split > 1 the workgroup stores
-// its partial sums and the consumer (k_norm) adds the partials in a fixed order: no float atomics,
-// bitwise reproducible results.
+// loads in flight, and reduce through LDS in a fixed order.  With n_split > 1 (residual-update
+// epilogue) each workgroup stores a partial plane and the last one to finish adds the planes in
+// range order: no float atomics, no waiting, bitwise reproducible results.
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
   union { u32x4 u; bf16x8 b; } c; c.u = v; return c.b;
@@ -215,6 +251,22 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
   for (int r = 0; r < RT; ++r)
 #pragma unroll
     for (int p = 0; p < P; ++p) acc[r][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // deferred RMSNorm: the panels hold g * h (not normalised).  The producer left one sum of squares
+  // per token and 16-column tile; every lane fetches a few of them now (lane = token lane % 16,
+  // slots (lane / 16) * NW + w + 4 NW k), the loads complete behind the weight stream, and the
+  // epilogue adds them up in a fixed order to get 1 / rms.
+  constexpr bool NORMED = (EPI != EPI_PARTIAL);
+  constexpr int MAXS = NORMED ? 128 / NW : 1;
+  float sv[MAXS];
+  if (NORMED) {
+#pragma unroll
+    for (int k = 0; k < MAXS; ++k) {
+      const int idx = (lane >> 4) * NW + w + 4 * NW * k;
+      sv[k] = (a.ssq != nullptr && idx < a.n_ssq) ? a.ssq[idx * 16 + (lane & 15)] : 0.f;   // [slot][token]
+    }
+    asm volatile("" ::: "memory");     // keep these loads ahead of the weight stream
+  }
 
   const int KT = a.KT;
   const int kt_begin = (int)((int64_t)KT * split / a.n_split), kt_end = (int)((int64_t)KT * (split + 1) / a.n_split);
@@ -259,6 +311,7 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
 
   // hi + lo: same panel, columns n and n + 8 (P == 1), or two panels (P == 2)
   __shared__ f32x4 red[NW][RT][64];
+  __shared__ float red_ssq[NORMED ? NW : 1][64];
 #pragma unroll
   for (int r = 0; r < RT; ++r) {
     f32x4 y;
@@ -270,14 +323,24 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
     }
     red[w][r][lane] = y;
   }
+  if (NORMED) {
+    float part = 0.f;
+#pragma unroll
+    for (int k = 0; k < MAXS; ++k) {
+      asm volatile("" : "+v"(sv[k]));  // first use of the early loads is here, after the stream
+      part += sv[k];
+    }
+    red_ssq[w][lane] = part;
+  }
   __syncthreads();
-  if (w >= UNITS) return;
   constexpr int TPU = PAIR ? 2 : 1;               // tiles per unit
+  const bool ep = w < UNITS;                      // this wavefront finishes one output unit
+  const int m = lane & 15, g = lane >> 4;         // token column, 4-row group of the 16x16 result
   f32x4 y[TPU];
   int urt[TPU];
 #pragma unroll
   for (int i = 0; i < TPU; ++i) {
-    const int r = w * TPU + i;
+    const int r = (ep ? w : 0) * TPU + i;
     // (runtime index into rt[] would spill it: select with a compile-time loop)
     urt[i] = 0;
 #pragma unroll
@@ -286,13 +349,63 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
 #pragma unroll
     for (int ww = 1; ww < NW; ++ww) y[i] += red[ww][r][lane];   // fixed order: deterministic
   }
-  const int m = lane & 15, g = lane >> 4;   // token column, 4-row group of the 16x16 result
-  if (m >= a.M) return;
+  if (NORMED && a.ssq != nullptr) {
+    float ss = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < NW; ++ww)
+#pragma unroll
+      for (int gg = 0; gg < 4; ++gg) ss += red_ssq[ww][gg * 16 + m];
+    const float rstd = 1.0f / sqrtf(ss / (float)a.d_in + a.eps);
+#pragma unroll
+    for (int i = 0; i < TPU; ++i) y[i] *= rstd;
+  }
 
   if (EPI == EPI_PARTIAL) {
-    float* dst = a.out + (size_t)split * a.part_stride + (size_t)m * a.ld_out + urt[0] * 16 + 4 * g;
-    *reinterpret_cast<float4*>(dst) = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
-  } else if (EPI == EPI_STORE) {
+    // residual-stream update h += X.W^T.  With several K ranges every workgroup stores its partial
+    // plane and takes a ticket; the last one to arrive adds the planes in range order (so the sum
+    // does not depend on arrival order) and finishes the row group.  Nobody waits for anybody.
+    __shared__ int s_last;
+    const int col = urt[0] * 16 + 4 * g;
+    const bool live = ep && m < a.M;
+    if (a.n_split > 1) {
+      if (live) {
+        float* dst = a.out + (size_t)split * a.part_stride + (size_t)m * a.ld_out + col;
+        st_agent2(dst, y[0][0], y[0][1]);
+        st_agent2(dst + 2, y[0][2], y[0][3]);
+      }
+      if (!last_arrival(a.counters + b, a.n_split, &s_last)) return;
+    }
+    if (!live) return;
+    float4 sum = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
+    if (a.n_split > 1) {
+      float2 pa[GEMM_MAX_SPLIT], pb[GEMM_MAX_SPLIT];
+#pragma unroll
+      for (int sp = 0; sp < GEMM_MAX_SPLIT; ++sp)
+        if (sp < a.n_split) {
+          const float* src = a.out + (size_t)sp * a.part_stride + (size_t)m * a.ld_out + col;
+          pa[sp] = ld_agent2(src); pb[sp] = ld_agent2(src + 2);
+        }
+      sum = make_float4(pa[0].x, pa[0].y, pb[0].x, pb[0].y);
+#pragma unroll
+      for (int sp = 1; sp < GEMM_MAX_SPLIT; ++sp)
+        if (sp < a.n_split) { sum.x += pa[sp].x; sum.y += pa[sp].y; sum.z += pb[sp].x; sum.w += pb[sp].y; }
+    }
+    float4* hp = reinterpret_cast<float4*>(a.h + (size_t)m * a.ld_out + col);
+    float4 h = *hp;
+    h.x += sum.x; h.y += sum.y; h.z += sum.z; h.w += sum.w;
+    *hp = h;
+    if (a.Xout != nullptr) {
+      // feed the next RMSNorm'ed GEMM: panels of gain * h and this tile's sum of squares
+      const float4 gn = *reinterpret_cast<const float4*>(a.gain + col);
+      const float o[4] = {h.x * gn.x, h.y * gn.y, h.z * gn.z, h.w * gn.w};
+      xpack_store4(a.Xout, a.KT_out, a.M, m, col, o);
+      const float sq = row4_sum((h.x * h.x + h.y * h.y) + (h.z * h.z + h.w * h.w));
+      if (g == 0) a.ssq_out[urt[0] * 16 + m] = sq;                          // [slot][token]
+    }
+    return;
+  }
+  if (!ep || m >= a.M) return;
+  if (EPI == EPI_STORE) {
     if (a.only_row >= 0 && m != a.only_row) return;
     const size_t row_off = a.only_row >= 0 ? 0 : (size_t)m * a.ld_out;
     *reinterpret_cast<float4*>(a.out + row_off + urt[0] * 16 + 4 * g) = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
@@ -408,6 +521,8 @@ hipError_t launch_gemm(const GemmArgs& a0, int epi, hipStream_t s) {
   GemmArgs a = a0;
   if (a.n_split < 1) a.n_split = 1;
   if (epi != EPI_PARTIAL && a.n_split != 1) return hipErrorInvalidValue;
+  if (epi == EPI_PARTIAL && (a.h == nullptr || a.n_split > GEMM_MAX_SPLIT || (a.n_split > 1 && a.counters == nullptr))) return hipErrorInvalidValue;
+  if (a.ssq != nullptr && (a.n_ssq < 1 || a.n_ssq > 512)) return hipErrorInvalidValue;
   if (a.n_split > a.KT) return hipErrorInvalidValue;
   if (epi != EPI_QKV) a.grp = 1;
   if ((epi == EPI_QKV || epi == EPI_SWIGLU) && (a.n_rows % 32)) return hipErrorInvalidValue;
@@ -427,9 +542,9 @@ hipError_t launch_gemm(const GemmArgs& a0, int epi, hipStream_t s) {
 // (embedding +) LayerNorm / RMSNorm -> packed activation panels
 // ---------------------------------------------------------------------------------------------
 
-// One workgroup per token row.  The row lives in registers: embedding gather or residual stream,
-// plus the split-K partial sums of the preceding GEMM added in a fixed order (the updated row is
-// written back), then the statistics, then the normalised row as packed bf16 hi/lo panels.
+// One workgroup per token row.  The row lives in registers: embedding gather (written to the
+// residual stream) or the residual stream itself, then the statistics, then the normalised row as
+// packed bf16 hi/lo panels -- or, for a deferred RMSNorm, gain * h panels plus the sum of squares.
 template <int NT>
 __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
   if (gated(a.gate)) return;
@@ -463,16 +578,27 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
       } else {
         v[i] = *reinterpret_cast<const float4*>(h + k);
       }
-      // all partial planes are fetched before the (fixed-order) additions: one memory round trip
-      float4 pp[GEMM_MAX_SPLIT];
-#pragma unroll
-      for (int sp = 0; sp < GEMM_MAX_SPLIT; ++sp)
-        if (sp < a.n_part) pp[sp] = *reinterpret_cast<const float4*>(a.part + (size_t)sp * a.part_stride + (size_t)m * d + k);
-#pragma unroll
-      for (int sp = 0; sp < GEMM_MAX_SPLIT; ++sp)
-        if (sp < a.n_part) { v[i].x += pp[sp].x; v[i].y += pp[sp].y; v[i].z += pp[sp].z; v[i].w += pp[sp].w; }
-      if (e || a.n_part > 0) *reinterpret_cast<float4*>(h + k) = v[i];
+      if (e) *reinterpret_cast<float4*>(h + k) = v[i];
     }
+  }
+  if (a.ssq_out != nullptr) {
+    // deferred RMSNorm: panels of gain * h, and the row's sum of squares in slot 0 of its ssq row
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) ss += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
+    ss = block_sum<NT>(ss, red);
+    for (int i = t; i < a.n_ssq_out; i += NT) a.ssq_out[i * 16 + m] = (i == 0) ? ss : 0.f;   // [slot][token]
+    const int KT = d >> 5;
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const int k = (i * NT + t) * 4;
+      if (k < d) {
+        const float4 g = *reinterpret_cast<const float4*>(a.g + k);
+        const float o[4] = {v[i].x * g.x, v[i].y * g.y, v[i].z * g.z, v[i].w * g.w};
+        xpack_store4(a.Xout, KT, a.M, m, k, o);
+      }
+    }
+    return;
   }
   float mean = 0.f;
   if (a.layernorm) {
@@ -508,7 +634,7 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
 }
 
 hipError_t launch_norm(const NormArgs& a, hipStream_t s) {
-  if (a.M < 1 || a.M > 16 || (a.d & 31) || a.d > 8192 || a.n_part < 0 || a.n_part > GEMM_MAX_SPLIT) return hipErrorInvalidValue;
+  if (a.M < 1 || a.M > 16 || (a.d & 31) || a.d > 8192) return hipErrorInvalidValue;
   if (a.d <= 2048) hipLaunchKernelGGL(k_norm<256>, dim3(a.M), dim3(256), 0, s, a);
   else hipLaunchKernelGGL(k_norm<1024>, dim3(a.M), dim3(1024), 0, s, a);
   return hipGetLastError();
@@ -531,14 +657,6 @@ hipError_t launch_norm(const NormArgs& a, hipStream_t s) {
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-__device__ __forceinline__ float row4_max(float v) {   // across lanes l, l^16, l^32, l^48
-  v = fmaxf(v, __shfl_xor(v, 16));
-  return fmaxf(v, __shfl_xor(v, 32));
-}
-__device__ __forceinline__ float row4_sum(float v) {
-  v += __shfl_xor(v, 16);
-  return v + __shfl_xor(v, 32);
-}
 
 template <int DH>
 __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
@@ -664,47 +782,44 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
       f32x4 o = o_s[0][c][lane] * f[0];
 #pragma unroll
       for (int ww = 1; ww < NWV; ++ww) o += o_s[ww][c][lane] * f[ww];
-      *reinterpret_cast<float2*>(rec + c * 16 + 4 * g) = make_float2(o[0], o[1]);
-      *reinterpret_cast<float2*>(rec + c * 16 + 4 * g + 2) = make_float2(o[2], o[3]);
+      st_agent2(rec + c * 16 + 4 * g, o[0], o[1]);
+      st_agent2(rec + c * 16 + 4 * g + 2, o[2], o[3]);
     }
-    if (w == 0 && g == 0) { rec[DH] = mm; rec[DH + 1] = ll; }
+    if (w == 0 && g == 0) st_agent2(rec + DH, mm, ll);
   }
-}
-
-template <int DH>
-__global__ __launch_bounds__(DH / 4) void k_attn_merge(AttnArgs a) {
-  if (gated(a.gate)) return;
-  const int head = blockIdx.x, m = blockIdx.y, t = threadIdx.x;
-  const float* base = a.part + (((size_t)head * a.n_splits) * 16 + m) * (DH + 2);
-  const size_t stride = (size_t)16 * (DH + 2);
-  float mx = NEG_BIG;
-  for (int s = 0; s < a.n_splits; ++s) mx = fmaxf(mx, base[s * stride + DH]);
-  float L = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < a.n_splits; ++s) {
-    const float* rec = base + s * stride;
-    const float wgt = expf(rec[DH] - mx);
-    L += rec[DH + 1] * wgt;
-    const float4 v = *reinterpret_cast<const float4*>(rec + 4 * t);
-    o[0] += v.x * wgt; o[1] += v.y * wgt; o[2] += v.z * wgt; o[3] += v.w * wgt;
-  }
-  const float inv = 1.0f / L;
+  // the last range of this head to finish merges all ranges (in range order) into the panels that
+  // feed the O-projection
+  __shared__ int s_last;
+  if (!last_arrival(a.counters + head, a.n_splits, &s_last)) return;
+  constexpr int TPQ = DH / 4;                                    // threads per query, 4 channels each
+  const int tq = threadIdx.x % TPQ;
+  for (int qm = threadIdx.x / TPQ; qm < a.M; qm += 256 / TPQ) {
+    const float* base = a.part + (((size_t)head * a.n_splits) * 16 + qm) * (DH + 2);
+    const size_t stride = (size_t)16 * (DH + 2);
+    float mx = NEG_BIG;
+    for (int sp = 0; sp < a.n_splits; ++sp) mx = fmaxf(mx, ld_agent2(base + sp * stride + DH).x);
+    float L = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int sp = 0; sp < a.n_splits; ++sp) {
+      const float* rc = base + sp * stride;
+      const float2 ml = ld_agent2(rc + DH);
+      const float wgt = expf(ml.x - mx);
+      L += ml.y * wgt;
+      const float2 v0 = ld_agent2(rc + 4 * tq), v1 = ld_agent2(rc + 4 * tq + 2);
+      o[0] += v0.x * wgt; o[1] += v0.y * wgt; o[2] += v1.x * wgt; o[3] += v1.y * wgt;
+    }
+    const float inv = 1.0f / L;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) o[i] *= inv;
-  xpack_store4(a.Xout, (a.nq * DH) >> 5, a.M, m, head * DH + 4 * t, o);
+    for (int i = 0; i < 4; ++i) o[i] *= inv;
+    xpack_store4(a.Xout, (a.nq * DH) >> 5, a.M, qm, head * DH + 4 * tq, o);
+  }
 }
 
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s) {
-  if (a.M < 1 || a.M > 16 || a.n_splits < 1) return hipErrorInvalidValue;
-  const dim3 g1(a.nq, a.n_splits), g2(a.nq, a.M);
-  if (a.dh == 128) {
-    hipLaunchKernelGGL(k_attn_partial<128>, g1, dim3(256), 0, s, a);
-    hipLaunchKernelGGL(k_attn_merge<128>, g2, dim3(32), 0, s, a);
-  } else if (a.dh == 64) {
-    hipLaunchKernelGGL(k_attn_partial<64>, g1, dim3(256), 0, s, a);
-    hipLaunchKernelGGL(k_attn_merge<64>, g2, dim3(16), 0, s, a);
-  } else {
-    return hipErrorInvalidValue;
-  }
+  if (a.M < 1 || a.M > 16 || a.n_splits < 1 || a.counters == nullptr) return hipErrorInvalidValue;
+  const dim3 g1(a.nq, a.n_splits);
+  if (a.dh == 128) hipLaunchKernelGGL(k_attn_partial<128>, g1, dim3(256), 0, s, a);
+  else if (a.dh == 64) hipLaunchKernelGGL(k_attn_partial<64>, g1, dim3(256), 0, s, a);
+  else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
@@ -1003,6 +1118,15 @@ __global__ void k_loop_finish(const int32_t* sl_count, LoopOut* out, LoopOut* ho
   if (threadIdx.x != 0) return;
   out->sl = *sl_count;
   if (host_out) { *host_out = *out; __threadfence_system(); }
+}
+
+__global__ __launch_bounds__(256) void k_zero(int* p, int n) {
+  for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) p[i] = 0;
+}
+
+hipError_t launch_zero(int* p, int n, hipStream_t s) {
+  hipLaunchKernelGGL(k_zero, dim3(n > 4096 ? 16 : 1), dim3(256), 0, s, p, n);
+  return hipGetLastError();
 }
 
 hipError_t launch_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in, void* dev_loop_out,
