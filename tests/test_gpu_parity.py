@@ -389,3 +389,104 @@ def test_loop_forced_acceptance_small_pair():
             assert gpu["tokens"] == ref and gpu["sl_hist"] == orc["sl_hist"]
             assert gpu["n_draft_forwards"] == sum(it["sl"] for it in orc["iterations"])
         assert sum(it["n"] for it in gpu["iterations"]) > n_new // 4      # forcing does produce acceptance
+
+
+# ---- full-size verification block, fused draft loop, reproducibility -----------------------------------
+
+def test_verify_13b_full_depth_block_of_11():
+    """The verification forward exactly as bench.py launches it: 40 layers of the 13B shape, block of
+    11 tokens, ctx 512, weights drawn on the device; the oracle gets the same bytes."""
+    shape = W.CFG2_TARGET
+    d = dev()
+    w = W.make_weights(shape, 0, "bf16", device=d)
+    gm = B.DiscoModel(shape, w, d)
+    w_host = {k: v.cpu() for k, v in w.items()}
+    del w
+    torch.cuda.empty_cache()
+    print("[parity] 13B full depth: weights on host", flush=True)
+    ctx, M = 512, 11
+    fill = W.make_kv_fill(shape, ctx, 2)
+    gkv = B.DiscoKV(gm, ctx + 32, 16)
+    gkv.fill(fill.to(d))
+    ws = gm.workspace(16, ctx + 32)
+    blk = W.make_tokens(41, M, shape.vocab).tolist()
+    tb = torch.tensor(blk, dtype=torch.int32, device=d)
+    am = torch.zeros(16, dtype=torch.int32, device=d)
+    lg = torch.empty(M, shape.vocab, dtype=torch.float32, device=d)
+    B.disco_verify(gm, gkv, tb, M, am, lg, ws)
+    torch.cuda.synchronize()
+    lg2 = torch.empty_like(lg)
+    B.disco_kv_rollback(gkv, ctx)
+    B.disco_verify(gm, gkv, tb, M, am, lg2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(lg, lg2)                      # split reductions add in a fixed order
+    om = O.Model(shape, w_host, kv_bf16=True, cache_upcast=False)
+    okv = om.new_cache(ctx + 32)
+    okv.fill(fill)
+    ref = om.forward(blk, okv)
+    check_logits(lg, ref, "verify 13B x40 layers ctx 512 M 11")
+    check_argmax(am[:M].tolist(), ref, "13B full depth")
+    n_flag = sum(1 for r in range(M) if O.top2_margin(ref[r]) < MARGIN)
+    print(f"[parity] 13B full depth: {n_flag} of {M} rows flagged by the top-2 margin", flush=True)
+
+
+def test_draft_loop_equals_step_by_step_and_gates_after_halt():
+    shape = W.scaled_shape(W.CFG1_DRAFT, vocab=4096)
+    d = dev()
+    w = W.make_weights(shape, 3, "bf16")
+    clf_p = W.make_classifier(100)
+    gm = B.DiscoModel(shape, w, d)
+    clf = B.DiscoClf(clf_p, d)
+    ctx, cap = 200, 7
+    fill = W.make_kv_fill(shape, ctx, 2).to(d)
+    ws = gm.workspace(16, ctx + 32)
+    logits = torch.empty(shape.vocab, dtype=torch.float32, device=d)
+    tok0 = torch.tensor([11, 12], dtype=torch.int32, device=d)
+
+    # reference: one call per step with a host decision in between
+    kv = B.DiscoKV(gm, ctx + 32, 16)
+    kv.fill(fill)
+    out = B.struct_tensor(B.ClfOut, 1, d)
+    nxt = torch.zeros(1, dtype=torch.int32, device=d)
+    scores = []
+    # scores grow with the block position under the seeded classifier: take tau between step 3 and 4
+    B.disco_draft_step(gm, kv, tok0, 2, logits, ws)
+    recs = []
+    for j in range(1, cap + 1):
+        B.disco_classify(clf, logits, shape.vocab, float(j), 0.0, 0, out, token_next=nxt)
+        torch.cuda.synchronize()
+        recs.append(B.read_struct(B.ClfOut, out))
+        if j < cap:
+            B.disco_draft_step(gm, kv, nxt, 1, logits, ws)
+    ref_scores = [r.score for r in recs]
+    assert all(b > a for a, b in zip(ref_scores, ref_scores[1:]))
+    for tau, want_sl in ((0.0, cap), (2.0, 1)):
+        kv2 = B.DiscoKV(gm, ctx + 32, 16)
+        kv2.fill(fill)
+        steps = B.struct_tensor(B.ClfOut, 16, d)
+        lo_d = B.struct_tensor(B.LoopOut, 1, d)
+        lo_h = B.struct_tensor(B.LoopOut, 1, pinned=True)
+        B.disco_draft_loop(gm, kv2, clf, tok0, 2, cap, 0, 1.0, tau, None, logits, steps, lo_d, lo_h, ws)
+        torch.cuda.synchronize()
+        lo = B.LoopOut.from_buffer_copy(lo_h.numpy().tobytes())
+        assert lo.sl == want_sl and lo.block[0] == 12
+        assert kv2.len == ctx + 2 + cap - 1            # host length advanced for every enqueued step
+        B.disco_kv_rollback(kv2, ctx + 2 + lo.sl - 1)
+        got = [B.read_struct(B.ClfOut, steps, i) for i in range(cap)]
+        for j in range(cap):
+            if j < want_sl:
+                assert got[j].executed == 1 and got[j].token == recs[j].token == lo.block[j + 1]
+                assert list(got[j].feats) == list(recs[j].feats) and got[j].score == recs[j].score
+                assert got[j].halt == (1 if j == want_sl - 1 else 0)
+            else:
+                assert got[j].executed == 0              # gated off on the device
+    # static lookahead: exactly gamma steps whatever the classifier says
+    kv3 = B.DiscoKV(gm, ctx + 32, 16)
+    kv3.fill(fill)
+    steps = B.struct_tensor(B.ClfOut, 16, d)
+    lo_d = B.struct_tensor(B.LoopOut, 1, d)
+    B.disco_draft_loop(gm, kv3, clf, tok0, 2, cap, 4, 1.0, 2.0, None, logits, steps, lo_d, None, ws)
+    torch.cuda.synchronize()
+    lo = B.read_struct(B.LoopOut, lo_d)
+    assert lo.sl == 4 and list(lo.block[1:5]) == [r.token for r in recs[:4]]
+    assert kv3.len == ctx + 2 + 4 - 1
