@@ -40,6 +40,7 @@ extern "C" {
 #define DISCO_TOPK 10          /* k of Eq. 2 (the paper's footnote: k = 10 in all experiments) */
 #define DISCO_N_FEAT 12        /* top-10 probabilities, entropy, position                       */
 #define DISCO_CLF_HIDDEN_MAX 256
+#define DISCO_CLASSIFY_SCRATCH_BYTES 4352   /* optional scratch of disco_classify */
 
 enum {
   DISCO_OK = 0,
@@ -169,11 +170,17 @@ int disco_draft_step(const disco_model* draft, disco_kv* kv, const int32_t* dev_
  * if dev_sl_count != NULL it is incremented when the call executes;
  * if dev_force_token != NULL and *dev_force_token >= 0, the logit of that token is first raised to
  * max + 4 (in dev_logits too): the synthetic-workload hook that makes the draft agree with a known
- * target token at chosen positions.  clf may be NULL (score = NaN, halt = force_halt).             */
+ * target token at chosen positions.  clf may be NULL (score = NaN, halt = force_halt).
+ * dev_scratch (may be NULL): DISCO_CLASSIFY_SCRATCH_BYTES of device memory, 256-byte aligned,
+ * prepared once by disco_classify_scratch_init and used by one stream at a time; with it the
+ * reduction over the vocabulary is spread over many workgroups, without it one workgroup does it
+ * all (same results up to fp32 summation order).  vocab <= 65536; dev_logits 16-byte aligned.       */
 int disco_classify(const disco_clf* clf, float* dev_logits, int vocab, float pos_feature, float tau,
                    int force_halt, disco_clf_out* dev_out, int32_t* dev_token_next,
                    int32_t* dev_block_slot, uint32_t* dev_gate, int32_t* dev_sl_count,
-                   const int32_t* dev_force_token, disco_stream s);
+                   const int32_t* dev_force_token, void* dev_scratch, disco_stream s);
+/* Zeroes the ticket word of a classify scratch buffer (kernels leave it at zero afterwards).        */
+int disco_classify_scratch_init(void* dev_scratch, disco_stream s);
 
 /* Target verification forward (Fig. 1: the target validates all draft tokens in parallel).
  * dev_block = [last emitted token, d_1 .. d_SL], n_block = SL + 1 in [1, DISCO_MAX_BLOCK]; token j

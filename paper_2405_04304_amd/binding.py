@@ -77,7 +77,8 @@ _SIGNATURES = {
                                    C.c_size_t, C.c_void_p, C.c_void_p]),
     "disco_classify": (C.c_int, [C.POINTER(Clf), C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_int,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
-                                 C.c_void_p]),
+                                 C.c_void_p, C.c_void_p]),
+    "disco_classify_scratch_init": (C.c_int, [C.c_void_p, C.c_void_p]),
     "disco_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
                                C.c_void_p, C.c_size_t, C.c_void_p]),
     "disco_accept": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -147,11 +148,21 @@ def disco_draft_step(model, kv, tokens_in, n_in, logits, ws, gate=None, stream=N
 
 
 def disco_classify(clf, logits, vocab, pos_feature, tau, force_halt, out, token_next=None,
-                   block_slot=None, gate=None, sl_count=None, force_token=None, stream=None):
+                   block_slot=None, gate=None, sl_count=None, force_token=None, scratch=None, stream=None):
     _check(lib().disco_classify(C.byref(clf.c) if clf is not None else None, _ptr(logits), vocab,
                                 pos_feature, tau, int(force_halt), _ptr(out), _ptr(token_next),
-                                _ptr(block_slot), _ptr(gate), _ptr(sl_count), _ptr(force_token),
+                                _ptr(block_slot), _ptr(gate), _ptr(sl_count), _ptr(force_token), _ptr(scratch),
                                 _stream() if stream is None else stream))
+
+
+CLASSIFY_SCRATCH_BYTES = 4352
+
+
+def classify_scratch(device="cuda") -> torch.Tensor:
+    """Device scratch for the many-workgroup form of disco_classify, ticket word zeroed."""
+    t = torch.empty(CLASSIFY_SCRATCH_BYTES, dtype=torch.uint8, device=device)
+    _check(lib().disco_classify_scratch_init(t.data_ptr(), _stream()))
+    return t
 
 
 def disco_verify(model, kv, block, n_block, argmax, logits, ws, stream=None):

@@ -57,7 +57,7 @@ namespace {
 
 struct Ws {
   float* h; float* q; bf16_t* xn; bf16_t* xattn; bf16_t* xact; float* part; float* gpart; float* logits;
-  float* ssq; int* gemm_counters; int* attn_counters; int n_counters;
+  float* ssq; int* gemm_counters; int* attn_counters; int n_counters; float* clf_scratch;
   uint32_t* gate; int32_t* sl_count; int32_t* tok_next;
   size_t total;
 };
@@ -81,6 +81,7 @@ Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
   w.n_counters = d.d_model / 16 + d.n_heads;
   w.gemm_counters = static_cast<int*>(take(sizeof(int) * (size_t)w.n_counters));
   w.attn_counters = w.gemm_counters ? w.gemm_counters + d.d_model / 16 : nullptr;
+  w.clf_scratch = static_cast<float*>(take(CLASSIFY_SCRATCH_BYTES));
   w.gate = static_cast<uint32_t*>(take(256));
   w.sl_count = reinterpret_cast<int32_t*>(w.gate ? w.gate + 16 : nullptr);
   w.tok_next = reinterpret_cast<int32_t*>(w.gate ? w.gate + 32 : nullptr);
@@ -337,6 +338,13 @@ int disco_workspace_init(const disco_model* m, void* dev_ws, size_t ws_bytes, in
   if (need == 0 || ws_bytes < need) return fail(DISCO_EINVAL, "workspace of %zu bytes, %zu needed", ws_bytes, need);
   const Ws ws = carve(m, max_block, max_ctx, dev_ws);
   HIP_TRY(launch_zero(ws.gemm_counters, ws.n_counters, static_cast<hipStream_t>(s)), "workspace init launch");
+  HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.clf_scratch), 64, static_cast<hipStream_t>(s)), "workspace init launch");
+  return DISCO_OK;
+}
+
+int disco_classify_scratch_init(void* dev_scratch, disco_stream s) {
+  if (!dev_scratch || !aligned(dev_scratch, 256)) return fail(DISCO_EINVAL, "scratch pointer null or not 256-byte aligned");
+  HIP_TRY(launch_zero(static_cast<int*>(dev_scratch), 64, static_cast<hipStream_t>(s)), "scratch init launch");
   return DISCO_OK;
 }
 
@@ -352,11 +360,11 @@ int disco_draft_step(const disco_model* draft, disco_kv* kv, const int32_t* dev_
 
 int disco_classify(const disco_clf* clf, float* dev_logits, int vocab, float pos_feature, float tau, int force_halt,
                    disco_clf_out* dev_out, int32_t* dev_token_next, int32_t* dev_block_slot, uint32_t* dev_gate,
-                   int32_t* dev_sl_count, const int32_t* dev_force_token, disco_stream s) {
+                   int32_t* dev_sl_count, const int32_t* dev_force_token, void* dev_scratch, disco_stream s) {
   if (!dev_logits || !dev_out) return fail(DISCO_EINVAL, "null argument");
   if (vocab < 1 || vocab > 65536) return fail(DISCO_EINVAL, "vocab %d outside [1, 65536]", vocab);
   if (!aligned(dev_logits, 16) || !aligned(dev_out, 4) || !aligned(dev_token_next, 4) || !aligned(dev_block_slot, 4) ||
-      !aligned(dev_gate, 4) || !aligned(dev_sl_count, 4) || !aligned(dev_force_token, 4))
+      !aligned(dev_gate, 4) || !aligned(dev_sl_count, 4) || !aligned(dev_force_token, 4) || !aligned(dev_scratch, 256))
     return fail(DISCO_EINVAL, "misaligned pointer");
   if (clf) {
     if (!clf->dev_params || !aligned(clf->dev_params, 4)) return fail(DISCO_EINVAL, "classifier parameters null or misaligned");
@@ -366,6 +374,7 @@ int disco_classify(const disco_clf* clf, float* dev_logits, int vocab, float pos
   a.logits = dev_logits; a.vocab = vocab; a.clf_params = clf ? clf->dev_params : nullptr; a.hidden = clf ? clf->hidden : 0;
   a.pos_feature = pos_feature; a.tau = tau; a.force_halt = force_halt; a.out = dev_out; a.token_next = dev_token_next;
   a.block_slot = dev_block_slot; a.gate = dev_gate; a.sl_count = dev_sl_count; a.force_token = dev_force_token;
+  a.scratch = static_cast<float*>(dev_scratch);
   HIP_TRY(launch_classify(a, static_cast<hipStream_t>(s)), "classify launch");
   return DISCO_OK;
 }
@@ -434,6 +443,7 @@ int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* cl
     a.force_halt = (j == steps) ? 1 : 0;
     a.out = dev_steps + (j - 1); a.token_next = ws.tok_next; a.block_slot = dev_out->block + j; a.gate = ws.gate;
     a.sl_count = ws.sl_count; a.force_token = dev_force_tokens ? dev_force_tokens + (j - 1) : nullptr;
+    a.scratch = ws.clf_scratch;
     HIP_TRY(launch_classify(a, st), "classify launch");
   }
   HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, st), "loop finish launch");

@@ -70,7 +70,9 @@ struct ClassifyArgs {
   void* out;                         // disco_clf_out*
   int32_t* token_next; int32_t* block_slot; uint32_t* gate; int32_t* sl_count;
   const int32_t* force_token;
+  float* scratch;                    // optional: >= CLASSIFY_SCRATCH_BYTES, first word zero (ticket counter)
 };
+constexpr size_t CLASSIFY_SCRATCH_BYTES = 256 + 64 * 16 * sizeof(float);
 
 hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int64_t tile_mul,
                        int64_t tile_add, hipStream_t s);

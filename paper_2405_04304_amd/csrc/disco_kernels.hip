@@ -367,6 +367,13 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
     __shared__ int s_last;
     const int col = urt[0] * 16 + 4 * g;
     const bool live = ep && m < a.M;
+    // operands of the finishing step that do not depend on other workgroups are fetched before the ticket
+    float4* hp = reinterpret_cast<float4*>(a.h + (size_t)m * a.ld_out + col);
+    float4 h = make_float4(0.f, 0.f, 0.f, 0.f), gn = h;
+    if (live) {
+      h = *hp;
+      if (a.Xout != nullptr) gn = *reinterpret_cast<const float4*>(a.gain + col);
+    }
     if (a.n_split > 1) {
       if (live) {
         float* dst = a.out + (size_t)split * a.part_stride + (size_t)m * a.ld_out + col;
@@ -390,13 +397,10 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
       for (int sp = 1; sp < GEMM_MAX_SPLIT; ++sp)
         if (sp < a.n_split) { sum.x += pa[sp].x; sum.y += pa[sp].y; sum.z += pb[sp].x; sum.w += pb[sp].y; }
     }
-    float4* hp = reinterpret_cast<float4*>(a.h + (size_t)m * a.ld_out + col);
-    float4 h = *hp;
     h.x += sum.x; h.y += sum.y; h.z += sum.z; h.w += sum.w;
     *hp = h;
     if (a.Xout != nullptr) {
       // feed the next RMSNorm'ed GEMM: panels of gain * h and this tile's sum of squares
-      const float4 gn = *reinterpret_cast<const float4*>(a.gain + col);
       const float o[4] = {h.x * gn.x, h.y * gn.y, h.z * gn.z, h.w * gn.w};
       xpack_store4(a.Xout, a.KT_out, a.M, m, col, o);
       const float sq = row4_sum((h.x * h.x + h.y * h.y) + (h.z * h.z + h.w * h.w));
@@ -695,18 +699,42 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
 
   for (int base = s0 + w * WKEYS; base < s1; base += NWV * WKEYS) {
     f32x4 S[2];
+    uint2 vraw[2][CT];
+    // issue every load of this step first: K rows of both 16-position tiles, then the V^T tiles
+    u32x4 kraw[2][KS];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int kb = base + 16 * t;
+      if (kb < s1) {
+        const int p = min(kb + j, total - 1), lp = p / pt, off = p - lp * pt;
+        const int pp = a.page_table ? a.page_table[lp] : lp;
+        const bf16_t* kp = a.kv_layer + (size_t)pp * page_elems + (size_t)kvh * kv_head_elems + (size_t)off * DH + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) kraw[t][ks] = *reinterpret_cast<const u32x4*>(kp + ks * 32);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int kb = base + 16 * t;
+      if (kb < s1) {
+        // V^T operand: channel row = lane % 16 of each 16-channel tile, 4 consecutive positions
+        const int p0 = kb + 4 * g;
+        const int pc = min(p0, (total - 1) & ~3), lp = pc / pt, off = pc - lp * pt;
+        const int pp = a.page_table ? a.page_table[lp] : lp;
+        const bf16_t* vp = a.kv_layer + (size_t)pp * page_elems + (size_t)(a.nkv + kvh) * kv_head_elems + (size_t)j * pt + off;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) vraw[t][c] = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * pt);
+      }
+    }
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int kb = base + 16 * t;
       S[t] = f32x4{NEG_BIG, NEG_BIG, NEG_BIG, NEG_BIG};
       if (kb < s1) {
-        const int p = min(kb + j, total - 1), lp = p / pt, off = p - lp * pt;
-        const int pp = a.page_table ? a.page_table[lp] : lp;
-        const bf16_t* kp = a.kv_layer + (size_t)pp * page_elems + (size_t)kvh * kv_head_elems + (size_t)off * DH + 8 * g;
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 kk = as_bf16x8(*reinterpret_cast<const u32x4*>(kp + ks * 32));
+          const bf16x8 kk = as_bf16x8(kraw[t][ks]);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[ks], acc, 0, 0, 0);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[ks], acc, 0, 0, 0);
         }
@@ -742,18 +770,14 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
         union { bf16_t u[4]; s16x4 v; } ph, pl;
 #pragma unroll
         for (int v = 0; v < 4; ++v) { ph.u[v] = f32_to_bf16(S[t][v]); pl.u[v] = f32_to_bf16(S[t][v] - bf16_to_f32(ph.u[v])); }
-        // V^T operand: channel row = lane % 16 of each 16-channel tile, 4 consecutive positions
-        const int p0 = kb + 4 * g;
-        const int pc = min(p0, (total - 1) & ~3), lp = pc / pt, off = pc - lp * pt;
-        const int pp = a.page_table ? a.page_table[lp] : lp;
-        const bf16_t* vp = a.kv_layer + (size_t)pp * page_elems + (size_t)(a.nkv + kvh) * kv_head_elems + (size_t)j * pt + off;
         // positions at or beyond `total` hold stale bytes: zero them (0 * NaN would poison the sum)
+        const int p0 = kb + 4 * g;
         uint2 keep;
         keep.x = (p0 < total ? 0x0000FFFFu : 0u) | (p0 + 1 < total ? 0xFFFF0000u : 0u);
         keep.y = (p0 + 2 < total ? 0x0000FFFFu : 0u) | (p0 + 3 < total ? 0xFFFF0000u : 0u);
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
-          uint2 raw = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * pt);
+          uint2 raw = vraw[t][c];
           raw.x &= keep.x; raw.y &= keep.y;
           union { uint2 u; s16x4 v; } vv; vv.u = raw;
           O[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vv.v, ph.v, O[c], 0, 0, 0);
@@ -1015,8 +1039,167 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
   }
 }
 
+// The same computation spread over ceil(V / 1024) workgroups (used when the caller gives scratch
+// memory).  Each workgroup reduces 1024 logits to a record {max, arg-max, S, T relative to its own
+// max, its ten largest values}; the last workgroup to finish (ticket, no waiting) merges the
+// records in index order: S = sum S_b e^(m_b - M), T = sum e^(m_b - M) (T_b + (m_b - M) S_b), the ten
+// largest of the <= 640 candidates, then features, classifier and halt decision.  Forcing a token
+// to max + 4 is applied to the merged sums in closed form.
+constexpr int CM_NT = 256;
+constexpr int CM_REC = 16;     // floats per record
+
+__global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
+  ClfOut* out = reinterpret_cast<ClfOut*>(a.out);
+  if (a.gate != nullptr && *a.gate != 0u) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) out->executed = 0u;
+    return;
+  }
+  __shared__ float sv[CM_NT / 64 + 1];
+  __shared__ int si[CM_NT / 64 + 1];
+  __shared__ float top_s[10];
+  __shared__ float feat_s[12];
+  __shared__ int s_last;
+  const int t = threadIdx.x, V = a.vocab, b = blockIdx.x, nb = gridDim.x;
+  const float* x = a.logits;
+  float* rec = a.scratch + 64 + (size_t)b * CM_REC;          // scratch[0] is the ticket counter
+  const int idx = (b * CM_NT + t) * 4;
+  float r4[4];
+  if (idx + 3 < V) {
+    const float4 v = *reinterpret_cast<const float4*>(x + idx);
+    r4[0] = v.x; r4[1] = v.y; r4[2] = v.z; r4[3] = v.w;
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r4[e] = idx + e < V ? x[idx + e] : -INFINITY;
+  }
+  VI mine; mine.v = -INFINITY; mine.i = 0x7fffffff;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { VI y; y.v = r4[e]; y.i = idx + e; mine = vi_best(mine, y); }
+  const VI best = block_argmax<CM_NT>(mine, sv, si);
+  float S = 0.f, T = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float d = r4[e] - best.v, ex = expf(d);
+    S += ex; T += ex > 0.f ? ex * d : 0.f;
+  }
+  S = block_sum<CM_NT>(S, sv);
+  T = block_sum<CM_NT>(T, sv);
+  // this workgroup's ten largest values: ten arg-max rounds, the winner drops the value it gave
+  {
+    float c4[4] = {r4[0], r4[1], r4[2], r4[3]};
+    for (int rnd = 0; rnd < 10; ++rnd) {
+      VI cur; cur.v = fmaxf(fmaxf(c4[0], c4[1]), fmaxf(c4[2], c4[3])); cur.i = t;
+      const VI w = block_argmax<CM_NT>(cur, sv, si);
+      if (t == 0) top_s[rnd] = w.v;
+      if (w.i == t) {
+        bool done = false;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) if (!done && c4[e] == w.v) { c4[e] = -INFINITY; done = true; }
+      }
+    }
+  }
+  __syncthreads();
+  if (t == 0) { st_agent2(rec, best.v, __int_as_float(best.i)); st_agent2(rec + 2, S, T); }
+  if (t >= 2 && t < 7) st_agent2(rec + 2 * t, top_s[2 * t - 4], top_s[2 * t - 3]);
+  if (!last_arrival(reinterpret_cast<int*>(a.scratch), nb, &s_last)) return;
+
+  // ---- merge (one workgroup) ----
+  VI bm; bm.v = -INFINITY; bm.i = 0x7fffffff;
+  float Sb = 0.f, Tb = 0.f, mb = 0.f;
+  if (t < nb) {
+    const float2 p0 = ld_agent2(a.scratch + 64 + (size_t)t * CM_REC), p1 = ld_agent2(a.scratch + 64 + (size_t)t * CM_REC + 2);
+    bm.v = p0.x; bm.i = __float_as_int(p0.y); mb = p0.x; Sb = p1.x; Tb = p1.y;
+  }
+  VI gbest = block_argmax<CM_NT>(bm, sv, si);
+  float Sg = 0.f, Tg = 0.f;
+  if (t < nb) {
+    const float d = mb - gbest.v, f = expf(d);
+    Sg = Sb * f; Tg = f > 0.f ? f * (Tb + d * Sb) : 0.f;
+  }
+  Sg = block_sum<CM_NT>(Sg, sv);
+  Tg = block_sum<CM_NT>(Tg, sv);
+  // ten largest of the nb * 10 candidates (up to 3 per thread)
+  float c3[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) {
+    const int ci = t + k * CM_NT;                              // candidate ci = record ci / 10, slot ci % 10
+    c3[k] = -INFINITY;
+    if (ci < nb * 10) {
+      const int rb = ci / 10, sl = ci % 10;
+      const float2 p = ld_agent2(a.scratch + 64 + (size_t)rb * CM_REC + 4 + (sl & ~1));
+      c3[k] = (sl & 1) ? p.y : p.x;
+    }
+  }
+  for (int rnd = 0; rnd < 10; ++rnd) {
+    VI cur; cur.v = fmaxf(fmaxf(c3[0], c3[1]), c3[2]); cur.i = t;
+    const VI w = block_argmax<CM_NT>(cur, sv, si);
+    if (t == 0) top_s[rnd] = w.v;
+    if (w.i == t) {
+      bool done = false;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) if (!done && c3[k] == w.v) { c3[k] = -INFINITY; done = true; }
+    }
+  }
+  __syncthreads();
+  int force = -1;
+  if (a.force_token) { force = *a.force_token; if (force >= V) force = -1; }
+  float mx = gbest.v;
+  if (force >= 0) {
+    // raise logit[force] from x_f to M + 4: shift every term to the new maximum, take the old
+    // contribution of x_f out and put the new one (e^0 = 1, with (x - max) = 0) in
+    const float xf = x[force], mnew = gbest.v + 4.0f;
+    const float sh = expf(-4.0f), ef = expf(xf - mnew);
+    Tg = sh * (Tg - 4.0f * Sg) - (ef > 0.f ? ef * (xf - mnew) : 0.f);
+    Sg = sh * Sg - ef + 1.0f;
+    if (t == 0) {
+      // new top ten: M + 4 first, then the old ones without one instance of x_f (or without the last)
+      float old[10];
+      for (int i = 0; i < 10; ++i) old[i] = top_s[i];
+      int drop = 9;
+      for (int i = 9; i >= 0; --i) if (old[i] == xf) drop = i;
+      top_s[0] = mnew;
+      for (int i = 0, o = 1; i < 10 && o < 10; ++i) if (i != drop) top_s[o++] = old[i];
+      a.logits[force] = mnew;
+    }
+    mx = mnew; gbest.v = mnew; gbest.i = force;
+    __syncthreads();
+  }
+  if (t < 10) feat_s[t] = (top_s[t] == -INFINITY) ? 0.f : expf(top_s[t] - mx) / Sg;
+  if (t == 10) feat_s[10] = logf(Sg) - Tg / Sg;
+  if (t == 11) feat_s[11] = a.pos_feature;
+  __syncthreads();
+  float contrib = 0.f;
+  if (a.clf_params && t < a.hidden) {
+    const float* W1 = a.clf_params + t * 12;
+    float acc = a.clf_params[a.hidden * 12 + t];
+#pragma unroll
+    for (int i = 0; i < 12; ++i) acc += W1[i] * feat_s[i];
+    contrib = fmaxf(acc, 0.f) * a.clf_params[a.hidden * 13 + t];
+  }
+  const float z = block_sum<CM_NT>(contrib, sv);
+  if (t == 0) {
+    float score = __builtin_nanf("");
+    uint32_t halt = a.force_halt ? 1u : 0u;
+    if (a.clf_params) {
+      score = 1.0f / (1.0f + expf(-(z + a.clf_params[a.hidden * 14])));
+      if (score < a.tau) halt = 1u;
+    }
+    out->token = gbest.i;
+#pragma unroll
+    for (int i = 0; i < 12; ++i) out->feats[i] = feat_s[i];
+    out->score = score; out->halt = halt; out->executed = 1u;
+    if (a.token_next) *a.token_next = gbest.i;
+    if (a.block_slot) *a.block_slot = gbest.i;
+    if (a.sl_count) *a.sl_count += 1;
+    if (a.gate && halt) *a.gate = 1u;
+  }
+}
+
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s) {
   if (a.vocab < 1 || a.vocab > 65536) return hipErrorInvalidValue;
+  if (a.scratch != nullptr && a.vocab >= 4096) {
+    hipLaunchKernelGGL(k_classify_multi, dim3((a.vocab + 1023) / 1024), dim3(CM_NT), 0, s, a);
+    return hipGetLastError();
+  }
   if (a.vocab <= 8192) hipLaunchKernelGGL(k_classify<2>, dim3(1), dim3(FEAT_NT), 0, s, a);
   else if (a.vocab <= 32768) hipLaunchKernelGGL(k_classify<8>, dim3(1), dim3(FEAT_NT), 0, s, a);
   else hipLaunchKernelGGL(k_classify<16>, dim3(1), dim3(FEAT_NT), 0, s, a);

@@ -76,15 +76,28 @@ def setup_pair(shape, seed, kv_ctx=0, kv_seed=2, page_tokens=16, permute=False, 
 
 # ---- Eq. 2 kernel --------------------------------------------------------------------------------
 
-def _run_classify(logits, clf_params, pos, tau, force=None, force_halt=0):
+def _run_classify(logits, clf_params, pos, tau, force=None, force_halt=0, multi=None):
+    """multi=None runs both forms of the kernel (one workgroup / many workgroups with scratch) and
+    checks that they agree before returning the first."""
+    if multi is None:
+        r1, x1 = _run_classify(logits, clf_params, pos, tau, force, force_halt, multi=False)
+        r2, x2 = _run_classify(logits, clf_params, pos, tau, force, force_halt, multi=True)
+        assert (r1.token, r1.halt, r1.executed) == (r2.token, r2.halt, r2.executed)
+        assert torch.allclose(torch.tensor(list(r1.feats)), torch.tensor(list(r2.feats)), rtol=1e-5, atol=1e-7)
+        assert (math.isnan(r1.score) and math.isnan(r2.score)) or abs(r1.score - r2.score) < 1e-6
+        assert torch.equal(x1, x2)
+        return r1, x1
     d = dev()
     x = logits.to(torch.float32).to(d).contiguous()
     clf = B.DiscoClf(clf_params, d) if clf_params is not None else None
     out = B.struct_tensor(B.ClfOut, 1, d)
     ft = torch.tensor([force if force is not None else -1], dtype=torch.int32, device=d)
-    B.disco_classify(clf, x, x.numel(), float(pos), float(tau), force_halt, out, force_token=ft)
-    torch.cuda.synchronize()
-    return B.read_struct(B.ClfOut, out), x.cpu()
+    scratch = B.classify_scratch(d) if multi else None
+    for _ in range(2 if multi else 1):       # a second call on the same scratch: the ticket word was left at zero
+        xc = x.clone()
+        B.disco_classify(clf, xc, xc.numel(), float(pos), float(tau), force_halt, out, force_token=ft, scratch=scratch)
+        torch.cuda.synchronize()
+    return B.read_struct(B.ClfOut, out), xc.cpu()
 
 
 @pytest.mark.parametrize("V", [16, 1001, 4096, 32000, 49152])
@@ -448,12 +461,12 @@ def test_draft_loop_equals_step_by_step_and_gates_after_halt():
     kv.fill(fill)
     out = B.struct_tensor(B.ClfOut, 1, d)
     nxt = torch.zeros(1, dtype=torch.int32, device=d)
-    scores = []
+    scratch = B.classify_scratch(d)            # the loop uses the many-workgroup classify: so does the reference
     # scores grow with the block position under the seeded classifier: take tau between step 3 and 4
     B.disco_draft_step(gm, kv, tok0, 2, logits, ws)
     recs = []
     for j in range(1, cap + 1):
-        B.disco_classify(clf, logits, shape.vocab, float(j), 0.0, 0, out, token_next=nxt)
+        B.disco_classify(clf, logits, shape.vocab, float(j), 0.0, 0, out, token_next=nxt, scratch=scratch)
         torch.cuda.synchronize()
         recs.append(B.read_struct(B.ClfOut, out))
         if j < cap:
