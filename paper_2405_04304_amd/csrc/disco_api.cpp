@@ -118,7 +118,7 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   const bool fam_a = d.family == DISCO_FAMILY_A;
 
   const int n_tiles = d.d_model / 16;            // one sum-of-squares slot per 16 columns of h
-  const int split_o = gemm_split_for(d.d_model, m->d_q / 32), split_dn = gemm_split_for(d.d_model, d.d_ff / 32);
+  const int split_o = gemm_split_for(d.d_model, m->d_q / 32, n), split_dn = gemm_split_for(d.d_model, d.d_ff / 32, n);
 
   NormArgs na{};
   na.h = ws.h; na.d = d.d_model; na.M = n; na.layernorm = fam_a; na.eps = d.norm_eps;

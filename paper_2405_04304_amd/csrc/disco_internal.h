@@ -77,7 +77,7 @@ constexpr size_t CLASSIFY_SCRATCH_BYTES = 256 + 64 * 16 * sizeof(float);
 hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int64_t tile_mul,
                        int64_t tile_add, hipStream_t s);
 hipError_t launch_gemm(const GemmArgs& a, int epi, hipStream_t s);
-int gemm_split_for(int n_rows, int KT);   // K ranges the PARTIAL epilogue should be launched with
+int gemm_split_for(int n_rows, int KT, int M);   // K ranges the PARTIAL epilogue should be launched with
 hipError_t launch_norm(const NormArgs& a, hipStream_t s);
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s);

@@ -491,10 +491,14 @@ static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t s) {
 // workgroups in flight, and the activation panels (re-read from L2 by every workgroup) cost as much
 // bandwidth as the weights unless a workgroup covers 32-64 rows.  Wide outputs therefore take 4 row
 // tiles per workgroup; narrow outputs (d_model rows) take 2 and split K across workgroups.
-int gemm_split_for(int n_rows, int KT) {
+int gemm_split_for(int n_rows, int KT, int M) {
   (void)n_rows;
-  int s = KT / 40;
-  return s < 1 ? 1 : (s > 8 ? 8 : s);
+  if (M > 8 && KT > 200) {               // two panels, long K: 64-row workgroups of 16 wavefronts
+    const int s = (KT + 36) / 72;
+    return s < 1 ? 1 : (s > GEMM_MAX_SPLIT ? GEMM_MAX_SPLIT : s);
+  }
+  const int s = KT / 40;
+  return s < 1 ? 1 : (s > GEMM_MAX_SPLIT ? GEMM_MAX_SPLIT : s);
 }
 
 template <int P, int EPI>
@@ -503,6 +507,7 @@ static hipError_t launch_gemm_p(const GemmArgs& a, hipStream_t s) {
   const int n = a.n_rows;
   if constexpr (EPI == EPI_PARTIAL) {
     const int64_t wg4 = (int64_t)(n / 64) * a.n_split, wg2 = (int64_t)(n / 32) * a.n_split;
+    if (P == 2 && a.KT > 200 && n % 64 == 0 && wg4 >= 400) return launch_gemm_cfg<P, 4, EPI, 16, 2>(a, s);
     if (n % 64 == 0 && wg4 >= 1024) return launch_gemm_cfg<P, 4, EPI, 8, 2>(a, s);
     if (n % 32 == 0 && wg2 >= 480) {
       if (a.KT / a.n_split <= 40) return launch_gemm_cfg<P, 2, EPI, 4, 4>(a, s);
@@ -511,6 +516,7 @@ static hipError_t launch_gemm_p(const GemmArgs& a, hipStream_t s) {
     return launch_gemm_cfg<P, 1, EPI, 8, 4>(a, s);
   } else {
     if (n % 64 == 0 && n / 64 >= 400) return launch_gemm_cfg<P, 4, EPI, 8, 2>(a, s);
+    if (P == 2 && n % 64 == 0 && n / 64 >= 200) return launch_gemm_cfg<P, 4, EPI, 16, 2>(a, s);
     if constexpr (PAIR) {
       return launch_gemm_cfg<P, 2, EPI, 8, 4>(a, s);
     } else {
