@@ -247,6 +247,7 @@ class DiscoModel:
         mw = ModelWeights()
         emb = tok_emb if tok_emb is not None else dev(weights["tok_emb"], torch.bfloat16)
         self._keep.append(emb)
+        self.tok_emb = emb                     # a draft may share this table (see tok_emb / tok_emb_stride)
         mw.tok_emb = emb.data_ptr()
         mw.tok_emb_stride = tok_emb_stride if tok_emb_stride is not None else emb.shape[1]
         mw.pos_emb = dev(weights["pos_emb"], torch.bfloat16).data_ptr() if fam_a else None

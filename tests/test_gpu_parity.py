@@ -503,3 +503,75 @@ def test_draft_loop_equals_step_by_step_and_gates_after_halt():
     lo = B.read_struct(B.LoopOut, lo_d)
     assert lo.sl == 4 and list(lo.block[1:5]) == [r.token for r in recs[:4]]
     assert kv3.len == ctx + 2 + 4 - 1
+
+
+# ---- more shapes and edges ----------------------------------------------------------------------------
+
+def test_loop_mqa_pair_with_shared_embedding_table():
+    """Multi-query LayerNorm/GELU pair (the code-model workload's structure, small): the draft reads
+    the first d_draft columns of the target's embedding table through tok_emb_stride."""
+    st = W.ModelShape("A", 2, 256, 2, 128, 1, 512, 496, max_pos=256)
+    sd = W.ModelShape("A", 1, 128, 2, 64, 1, 256, 496, max_pos=256)
+    tw = W.make_weights(st, 0, "bf16", sigma=0.08, gain_jitter=0.1)
+    dw = W.make_weights(sd, 10, "bf16", sigma=0.08, gain_jitter=0.1)
+    dw["tok_emb"] = tw["tok_emb"][:, :sd.d_model]              # oracle: a strided view of the same values
+    ot, od = O.Model(st, tw, kv_bf16=True), O.Model(sd, dw, kv_bf16=True)
+    clf = W.make_classifier(100)
+    prompt = W.make_prompt(1, 50, st.vocab).tolist()
+    n_new = 64
+    ref, margins = O.greedy_target(ot, prompt, n_new)
+    force = {"mask": W.make_force_mask(5, n_new, 0.6), "tokens": ref}
+    d = dev()
+    gt = B.DiscoModel(st, tw, d)
+    gd = B.DiscoModel(sd, dw, d, tok_emb=gt.tok_emb, tok_emb_stride=st.d_model)
+    eng = SpecEngine(gt, gd, B.DiscoClf(clf, d), max_ctx=140, page_tokens=8)
+    for pol in ({"mode": "static", "gamma": 4}, {"mode": "disco", "tau": 0.6, "sl_max": 10, "pos_mode": "block"}):
+        orc = O.spec_decode(ot, od, clf, prompt, n_new, pol, force=force)
+        assert orc["tokens"] == ref
+        gpu = eng.generate(prompt, n_new, pol, force=force, trace=True)
+        if not _compare_runs(gpu, orc, pol.get("tau")):
+            assert gpu["tokens"] == ref and gpu["sl_hist"] == orc["sl_hist"]
+
+
+@pytest.mark.parametrize("hidden", [1, 37, 256])
+def test_classifier_hidden_sizes(hidden):
+    shape = W.ClassifierShape(hidden=hidden)
+    clf = W.make_classifier(7, shape, sigma=0.5)
+    g = torch.Generator().manual_seed(hidden)
+    x = torch.randn(32000, generator=g) * 1.5
+    for pos in (1.0, 40.0):
+        r, _ = _run_classify(x, clf, pos, 0.5)
+        f = O.features(x.double(), pos)
+        c = O.classifier(f["feats"], clf)
+        assert abs(r.score - c) < 2e-5, (hidden, pos, r.score, c)
+        if abs(c - 0.5) > 1e-3:
+            assert r.halt == int(c < 0.5)
+
+
+def test_kv_capacity_and_page_edges():
+    shape = SMALL_B_GQA
+    om, gm, okv, gkv, ws = setup_pair(shape, 12, kv_ctx=40, page_tokens=8, permute=True, capacity=64)
+    d = dev()
+    am = torch.zeros(16, dtype=torch.int32, device=d)
+    toks = W.make_tokens(9, 40, shape.vocab).tolist()
+
+    def both(block, what):
+        tb = torch.tensor(block, dtype=torch.int32, device=d)
+        lg = torch.empty(len(block), shape.vocab, dtype=torch.float32, device=d)
+        B.disco_verify(gm, gkv, tb, len(block), am, lg, ws)
+        torch.cuda.synchronize()
+        check_logits(lg, om.forward(block, okv), what)
+
+    both(toks[:8], "fill to a page edge (48)")
+    assert gkv.len == 48 and gkv.pages_in_use == 6
+    both(toks[8:24], "fill to capacity (64)")
+    assert gkv.len == 64 and gkv.pages_in_use == 8
+    with pytest.raises(B.DiscoError) as e:                       # full: refused on the host, nothing launched
+        B.disco_verify(gm, gkv, torch.tensor([1], dtype=torch.int32, device=d), 1, am, None, ws)
+    assert e.value.code == B.ECAP and gkv.len == 64
+    for new_len in (49, 48, 47):                                 # one past, on, one before a page edge
+        B.disco_kv_rollback(gkv, new_len)
+        okv.rollback(new_len)
+        assert gkv.pages_in_use == (new_len + 7) // 8
+        both(toks[24:24 + 5], f"after rollback to {new_len}")
+        assert gkv.len == new_len + 5
