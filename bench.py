@@ -218,7 +218,7 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": GATEUP_TRAFFIC_BYTES if not args.layers else None,
-            "kernel": "k_gemm<2, 4, 3, 8, 2> (target gate/up GEMM + SwiGLU at M = 9..16)",
+            "kernel": "k_gemm<2, 8, 3, 8, 1> (target gate/up GEMM + SwiGLU at M = 9..16)",
             "bytes_per_launch": gemm_bytes, "avg_launch_ms": gemm_ms, "launches_timed": len(pm),
             "timing": f"HIP events around the launch of layer {probe_layer} in every timed verification forward",
         },

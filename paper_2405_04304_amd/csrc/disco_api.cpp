@@ -75,12 +75,18 @@ Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
   w.xn = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * 16 * d.d_model));
   w.xattn = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * 16 * m->d_q));
   w.xact = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * 16 * d.d_ff));
-  w.gpart = static_cast<float*>(take(sizeof(float) * GEMM_MAX_SPLIT * 16 * (size_t)d.d_model));
+  // partial tiles and ticket counters of split row groups: sized for the widest matrix of the model
+  int max_rows = d.vocab;
+  if (m->d_qkv > max_rows) max_rows = m->d_qkv;
+  if (2 * d.d_ff > max_rows) max_rows = 2 * d.d_ff;
+  if (d.d_model > max_rows) max_rows = d.d_model;
+  const int max_tiles = max_rows / 16;
+  w.gpart = static_cast<float*>(take(sizeof(float) * GEMM_MAX_SPLIT * 256 * (size_t)max_tiles));
   w.logits = static_cast<float*>(take(sizeof(float) * 16 * (size_t)d.vocab));
   w.ssq = static_cast<float*>(take(sizeof(float) * 16 * (size_t)(d.d_model / 16)));
-  w.n_counters = d.d_model / 16 + d.n_heads;
+  w.n_counters = max_tiles + d.n_heads;
   w.gemm_counters = static_cast<int*>(take(sizeof(int) * (size_t)w.n_counters));
-  w.attn_counters = w.gemm_counters ? w.gemm_counters + d.d_model / 16 : nullptr;
+  w.attn_counters = w.gemm_counters ? w.gemm_counters + max_tiles : nullptr;
   w.clf_scratch = static_cast<float*>(take(CLASSIFY_SCRATCH_BYTES));
   w.gate = static_cast<uint32_t*>(take(256));
   w.sl_count = reinterpret_cast<int32_t*>(w.gate ? w.gate + 16 : nullptr);
@@ -133,8 +139,8 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   };
   auto residual_update = [&](GemmArgs& g, const void* w, const bf16_t* x, int k, int split, const float* next_gain) {
     g.M = n; g.gate = gate; g.W = static_cast<const bf16_t*>(w); g.X = x; g.KT = k / 32;
-    g.n_rows = d.d_model; g.h = ws.h; g.out = ws.gpart; g.ld_out = d.d_model; g.only_row = -1;
-    g.n_split = split; g.part_stride = (int64_t)16 * d.d_model; g.counters = ws.gemm_counters;
+    g.n_rows = d.d_model; g.h = ws.h; g.ld_out = d.d_model; g.only_row = -1;
+    g.n_split = split; g.planes = ws.gpart; g.counters = ws.gemm_counters;
     if (!fam_a) { g.Xout = ws.xn; g.KT_out = d.d_model / 32; g.gain = next_gain; g.ssq_out = ws.ssq; g.n_ssq_out = n_tiles; }
   };
 
@@ -152,7 +158,7 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     const float* next_b = last ? m->w.normf_b : m->layers[l + 1].norm1_b;
 
     GemmArgs g{};
-    g.M = n; g.gate = gate;
+    g.M = n; g.gate = gate; g.planes = ws.gpart; g.counters = ws.gemm_counters;
     // QKV projection, rotary, KV append
     g.W = static_cast<const bf16_t*>(L.wqkv); normed_input(g); g.n_rows = m->d_qkv;
     g.grp = d.d_head / 32; g.q = ws.q; g.ldq = m->d_q; g.nq = d.n_heads; g.nkv = d.n_kv_heads; g.dh = d.d_head;
@@ -180,7 +186,8 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     }
 
     GemmArgs u{};
-    u.M = n; u.gate = gate; u.W = static_cast<const bf16_t*>(L.w_in); normed_input(u);
+    u.M = n; u.gate = gate; u.planes = ws.gpart; u.counters = ws.gemm_counters;
+    u.W = static_cast<const bf16_t*>(L.w_in); normed_input(u);
     u.n_rows = fam_a ? d.d_ff : 2 * d.d_ff; u.grp = 1; u.Xout = ws.xact; u.KT_out = d.d_ff / 32;
     const bool probe = (l == g_probe_layer) && g_probe_ev[0] != nullptr;
     if (probe) HIP_TRY(hipEventRecord(g_probe_ev[0], s), "probe event");
@@ -198,7 +205,8 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     }
   }
   GemmArgs lm{};
-  lm.M = n; lm.gate = gate; lm.W = static_cast<const bf16_t*>(m->w.wlm); normed_input(lm);
+  lm.M = n; lm.gate = gate; lm.planes = ws.gpart; lm.counters = ws.gemm_counters;
+  lm.W = static_cast<const bf16_t*>(m->w.wlm); normed_input(lm);
   lm.n_rows = d.vocab; lm.out = logits_out; lm.ld_out = d.vocab; lm.only_row = only_last ? n - 1 : -1;
   HIP_TRY(launch_gemm(lm, EPI_STORE, s), "lm-head launch");
   kv->len = pos0 + n;

@@ -27,13 +27,14 @@ struct GemmArgs {
   int n_rows;           // N
   int grp;              // row-tile pairing distance for two-tile workgroups (1 = adjacent tiles)
   const uint32_t* gate; // optional: skip when *gate != 0
-  int n_split;          // K ranges (grid.y); > 1 only with EPI_PARTIAL
-  int64_t part_stride;  // elements between the partial-sum planes of EPI_PARTIAL
+  int n_split;          // K ranges (grid.y) of the one-unit-per-workgroup launch
+  float* planes;        // partial tiles of row groups whose K range is shared by several workgroups:
+                        // [row group][GEMM_MAX_SPLIT][tile of the group][64 lanes][4] fp32
   const float* ssq; int n_ssq; int d_in; float eps;   // deferred RMSNorm of the input (ssq == nullptr: none)
-  int* counters;        // PARTIAL with n_split > 1: one zeroed ticket counter per workgroup column
+  int* counters;        // one zeroed ticket counter per row group (used when a K range is shared)
   float* h;             // PARTIAL: residual stream updated in place, row stride ld_out
   const float* gain; float* ssq_out; int n_ssq_out;   // PARTIAL with Xout: next norm's gain, sums of squares
-  float* out;           // STORE target / PARTIAL planes, row stride ld_out
+  float* out;           // STORE target, row stride ld_out
   int64_t ld_out;
   int only_row;         // STORE: write only this token's row to out[0..N) (-1: all rows)
   // QKV epilogue

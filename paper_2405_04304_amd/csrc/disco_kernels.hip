@@ -212,11 +212,14 @@ hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int
 // skinny GEMM: weights streamed once from HBM, M <= 16 tokens on the matrix unit's column side
 // ---------------------------------------------------------------------------------------------
 //
-// Workgroup (blockIdx.x, blockIdx.y) owns RT 16-row tiles and the blockIdx.y-th of n_split equal
-// K ranges.  Its NW wavefronts interleave over the k-tiles of that range, each keeping U k-tiles of
-// loads in flight, and reduce through LDS in a fixed order.  With n_split > 1 (residual-update
-// epilogue) each workgroup stores a partial plane and the last one to finish adds the planes in
-// range order: no float atomics, no waiting, bitwise reproducible results.
+// A work unit is (row group b of RT 16-row tiles, k-tile range [kt_begin, kt_end)).  The NW wavefronts
+// of the workgroup interleave over the k-tiles of the range, each keeping U k-tiles of loads in
+// flight, and reduce through LDS in a fixed order.  When a row group's K range is covered by n_seg > 1
+// units (of different workgroups), each stores its partial 16 x 16 tiles to a plane and takes a
+// ticket; the last one to arrive adds the planes in range order and runs the epilogue: no float
+// atomics, no waiting, bitwise reproducible results.
+//
+// k_gemm launches a grid of (row groups, K ranges): every workgroup owns one unit.
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
   union { u32x4 u; bf16x8 b; } c; c.u = v; return c.b;
@@ -225,14 +228,13 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
 template <int EPI> struct EpiTraits { static constexpr bool pair = (EPI == EPI_QKV || EPI == EPI_SWIGLU); };
 
 template <int P, int RT, int EPI, int NW, int U>
-__global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
-  if (gated(a.gate)) return;
+__device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const int kt_begin, const int kt_end,
+                                          const int seg, const int n_seg) {
   constexpr bool PAIR = EpiTraits<EPI>::pair;
   constexpr int UNITS = PAIR ? RT / 2 : RT;       // output units handled by one wavefront each
   static_assert(!PAIR || RT % 2 == 0, "pair epilogues need an even tile count");
   static_assert(UNITS <= NW, "one epilogue wavefront per unit");
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int b = blockIdx.x, split = blockIdx.y;
   int rt[RT];
   if (PAIR) {
 #pragma unroll
@@ -269,49 +271,58 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
   }
 
   const int KT = a.KT;
-  const int kt_begin = (int)((int64_t)KT * split / a.n_split), kt_end = (int)((int64_t)KT * (split + 1) / a.n_split);
   const u32x4* Wp[RT];
 #pragma unroll
   for (int r = 0; r < RT; ++r) Wp[r] = reinterpret_cast<const u32x4*>(a.W) + (size_t)rt[r] * KT * 64 + lane;
   const u32x4* Xp = reinterpret_cast<const u32x4*>(a.X) + lane;
 
-  int kt = kt_begin + w;
-  for (; kt + (U - 1) * NW < kt_end; kt += U * NW) {
-    u32x4 A[U][RT], B[U][P];
+  // Two register buffers: the loads of step i + 1 are issued before the matrix instructions of step
+  // i, so the memory pipe stays full while the matrix unit works.  A step is U k-tiles per wavefront;
+  // k-tiles past the end of the range are clamped to its last tile (loaded again, not used).
+  auto load_step = [&](u32x4 (&A)[U][RT], u32x4 (&B)[U][P], const int kt0) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const size_t t = (size_t)(kt + u * NW) * 64;
+      const int k = kt0 + u * NW;
+      const size_t t = (size_t)(k < kt_end ? k : kt_end - 1) * 64;
 #pragma unroll
       for (int r = 0; r < RT; ++r) A[u][r] = __builtin_nontemporal_load(Wp[r] + t);
 #pragma unroll
       for (int p = 0; p < P; ++p) B[u][p] = Xp[(size_t)p * KT * 64 + t];
     }
+  };
+  auto mma_step = [&](const u32x4 (&A)[U][RT], const u32x4 (&B)[U][P], const int kt0) {
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int u = 0; u < U; ++u) {
+      if (U == 1 || kt0 + u * NW < kt_end) {
 #pragma unroll
-      for (int r = 0; r < RT; ++r)
+        for (int r = 0; r < RT; ++r)
 #pragma unroll
-        for (int p = 0; p < P; ++p)
-          acc[r][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[u][r]), as_bf16x8(B[u][p]),
-                                                              acc[r][p], 0, 0, 0);
-  }
-  for (; kt < kt_end; kt += NW) {
-    const size_t t = (size_t)kt * 64;
-    u32x4 A[RT], B[P];
-#pragma unroll
-    for (int r = 0; r < RT; ++r) A[r] = __builtin_nontemporal_load(Wp[r] + t);
-#pragma unroll
-    for (int p = 0; p < P; ++p) B[p] = Xp[(size_t)p * KT * 64 + t];
-#pragma unroll
-    for (int r = 0; r < RT; ++r)
-#pragma unroll
-      for (int p = 0; p < P; ++p)
-        acc[r][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[r]), as_bf16x8(B[p]), acc[r][p], 0, 0, 0);
+          for (int p = 0; p < P; ++p)
+            acc[r][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[u][r]), as_bf16x8(B[u][p]), acc[r][p], 0, 0, 0);
+      }
+    }
+  };
+  {
+    constexpr int STEP = U * NW;
+    u32x4 A0[U][RT], B0[U][P], A1[U][RT], B1[U][P];
+    int kt = kt_begin + w;
+    if (kt < kt_end) load_step(A0, B0, kt);
+    while (kt < kt_end) {
+      if (kt + STEP < kt_end) load_step(A1, B1, kt + STEP);
+      mma_step(A0, B0, kt);
+      kt += STEP;
+      if (kt >= kt_end) break;
+      if (kt + STEP < kt_end) load_step(A0, B0, kt + STEP);
+      mma_step(A1, B1, kt);
+      kt += STEP;
+    }
   }
 
   // hi + lo: same panel, columns n and n + 8 (P == 1), or two panels (P == 2)
   __shared__ f32x4 red[NW][RT][64];
   __shared__ float red_ssq[NORMED ? NW : 1][64];
+  __shared__ int s_last;
+  __syncthreads();                                // a previous unit of this workgroup has left the buffers
 #pragma unroll
   for (int r = 0; r < RT; ++r) {
     f32x4 y;
@@ -349,6 +360,50 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
 #pragma unroll
     for (int ww = 1; ww < NW; ++ww) y[i] += red[ww][r][lane];   // fixed order: deterministic
   }
+
+  // operands of the residual update that do not depend on other workgroups are fetched before the ticket
+  float4 h = make_float4(0.f, 0.f, 0.f, 0.f), gn = h;
+  float4* hp = nullptr;
+  if (EPI == EPI_PARTIAL) {
+    const int col = urt[0] * 16 + 4 * g;
+    hp = reinterpret_cast<float4*>(a.h + (size_t)m * a.ld_out + col);
+    if (ep && m < a.M) {
+      h = *hp;
+      if (a.Xout != nullptr) gn = *reinterpret_cast<const float4*>(a.gain + col);
+    }
+  }
+
+  if (n_seg > 1) {
+    // this unit covers part of K: store the partial tiles, take a ticket; the last unit of the row
+    // group to arrive adds all partial tiles in range order (so the sum does not depend on arrival
+    // order) and finishes the row group.  Nobody waits for anybody.
+    float* plane = a.planes + ((size_t)b * GEMM_MAX_SPLIT * RT) * 256 + (size_t)lane * 4;
+    if (ep) {
+#pragma unroll
+      for (int i = 0; i < TPU; ++i) {
+        float* dst = plane + ((size_t)seg * RT + (w * TPU + i)) * 256;
+        st_agent2(dst, y[i][0], y[i][1]);
+        st_agent2(dst + 2, y[i][2], y[i][3]);
+      }
+    }
+    if (!last_arrival(a.counters + b, n_seg, &s_last)) return;
+    if (ep) {
+#pragma unroll
+      for (int i = 0; i < TPU; ++i) {
+        float2 pa[GEMM_MAX_SPLIT], pb[GEMM_MAX_SPLIT];
+#pragma unroll
+        for (int sp = 0; sp < GEMM_MAX_SPLIT; ++sp)
+          if (sp < n_seg) {
+            const float* src = plane + ((size_t)sp * RT + (w * TPU + i)) * 256;
+            pa[sp] = ld_agent2(src); pb[sp] = ld_agent2(src + 2);
+          }
+        y[i] = f32x4{pa[0].x, pa[0].y, pb[0].x, pb[0].y};
+#pragma unroll
+        for (int sp = 1; sp < GEMM_MAX_SPLIT; ++sp)
+          if (sp < n_seg) { y[i][0] += pa[sp].x; y[i][1] += pa[sp].y; y[i][2] += pb[sp].x; y[i][3] += pb[sp].y; }
+      }
+    }
+  }
   if (NORMED && a.ssq != nullptr) {
     float ss = 0.f;
 #pragma unroll
@@ -361,43 +416,10 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
   }
 
   if (EPI == EPI_PARTIAL) {
-    // residual-stream update h += X.W^T.  With several K ranges every workgroup stores its partial
-    // plane and takes a ticket; the last one to arrive adds the planes in range order (so the sum
-    // does not depend on arrival order) and finishes the row group.  Nobody waits for anybody.
-    __shared__ int s_last;
+    // residual-stream update h += X.W^T
+    if (!ep || m >= a.M) return;
     const int col = urt[0] * 16 + 4 * g;
-    const bool live = ep && m < a.M;
-    // operands of the finishing step that do not depend on other workgroups are fetched before the ticket
-    float4* hp = reinterpret_cast<float4*>(a.h + (size_t)m * a.ld_out + col);
-    float4 h = make_float4(0.f, 0.f, 0.f, 0.f), gn = h;
-    if (live) {
-      h = *hp;
-      if (a.Xout != nullptr) gn = *reinterpret_cast<const float4*>(a.gain + col);
-    }
-    if (a.n_split > 1) {
-      if (live) {
-        float* dst = a.out + (size_t)split * a.part_stride + (size_t)m * a.ld_out + col;
-        st_agent2(dst, y[0][0], y[0][1]);
-        st_agent2(dst + 2, y[0][2], y[0][3]);
-      }
-      if (!last_arrival(a.counters + b, a.n_split, &s_last)) return;
-    }
-    if (!live) return;
-    float4 sum = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
-    if (a.n_split > 1) {
-      float2 pa[GEMM_MAX_SPLIT], pb[GEMM_MAX_SPLIT];
-#pragma unroll
-      for (int sp = 0; sp < GEMM_MAX_SPLIT; ++sp)
-        if (sp < a.n_split) {
-          const float* src = a.out + (size_t)sp * a.part_stride + (size_t)m * a.ld_out + col;
-          pa[sp] = ld_agent2(src); pb[sp] = ld_agent2(src + 2);
-        }
-      sum = make_float4(pa[0].x, pa[0].y, pb[0].x, pb[0].y);
-#pragma unroll
-      for (int sp = 1; sp < GEMM_MAX_SPLIT; ++sp)
-        if (sp < a.n_split) { sum.x += pa[sp].x; sum.y += pa[sp].y; sum.z += pb[sp].x; sum.w += pb[sp].y; }
-    }
-    h.x += sum.x; h.y += sum.y; h.z += sum.z; h.w += sum.w;
+    h.x += y[0][0]; h.y += y[0][1]; h.z += y[0][2]; h.w += y[0][3];
     *hp = h;
     if (a.Xout != nullptr) {
       // feed the next RMSNorm'ed GEMM: panels of gain * h and this tile's sum of squares
@@ -479,6 +501,14 @@ __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
 }
 
 template <int P, int RT, int EPI, int NW, int U>
+__global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
+  if (gated(a.gate)) return;
+  const int split = blockIdx.y;
+  const int kt_begin = (int)((int64_t)a.KT * split / a.n_split), kt_end = (int)((int64_t)a.KT * (split + 1) / a.n_split);
+  gemm_unit<P, RT, EPI, NW, U>(a, blockIdx.x, kt_begin, kt_end, split, a.n_split);
+}
+
+template <int P, int RT, int EPI, int NW, int U>
 static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t s) {
   constexpr int rows = RT * 16;
   if (a.n_rows % rows) return hipErrorInvalidValue;
@@ -487,17 +517,21 @@ static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t s) {
 }
 
 #ifndef DISCO_GEMM_NO_DISPATCH
-// Launch shapes, from measurements on MI355X at the 13B-class sizes: weight streaming needs >= ~500
-// workgroups in flight, and the activation panels (re-read from L2 by every workgroup) cost as much
-// bandwidth as the weights unless a workgroup covers 32-64 rows.  Wide outputs therefore take 4 row
-// tiles per workgroup; narrow outputs (d_model rows) take 2 and split K across workgroups.
+// Launch shapes, from sweeps on MI355X at the 13B-class and 68M-class sizes.  Eight wavefronts per
+// workgroup and one k-tile per wavefront and step (two register buffers) were best everywhere.  The
+// activation panels are re-read from L2 by every workgroup, so wide outputs take 64 or 128 rows per
+// workgroup; narrow outputs (d_model rows) take 64 rows and split K so that about 480 workgroups are
+// in flight, small matrices take 16-row workgroups.
 int gemm_split_for(int n_rows, int KT, int M) {
-  (void)n_rows;
-  if (M > 8 && KT > 200) {               // two panels, long K: 64-row workgroups of 16 wavefronts
-    const int s = (KT + 36) / 72;
-    return s < 1 ? 1 : (s > GEMM_MAX_SPLIT ? GEMM_MAX_SPLIT : s);
+  (void)M;
+  int s;
+  if (n_rows % 64 == 0 && n_rows >= 2048) {
+    const int groups = n_rows / 64;
+    s = (480 + groups / 2) / groups;
+    if (s > KT / 16) s = KT / 16;
+  } else {
+    s = KT / 24;
   }
-  const int s = KT / 40;
   return s < 1 ? 1 : (s > GEMM_MAX_SPLIT ? GEMM_MAX_SPLIT : s);
 }
 
@@ -506,22 +540,17 @@ static hipError_t launch_gemm_p(const GemmArgs& a, hipStream_t s) {
   constexpr bool PAIR = EpiTraits<EPI>::pair;
   const int n = a.n_rows;
   if constexpr (EPI == EPI_PARTIAL) {
-    const int64_t wg4 = (int64_t)(n / 64) * a.n_split, wg2 = (int64_t)(n / 32) * a.n_split;
-    if (P == 2 && a.KT > 200 && n % 64 == 0 && wg4 >= 400) return launch_gemm_cfg<P, 4, EPI, 16, 2>(a, s);
-    if (n % 64 == 0 && wg4 >= 1024) return launch_gemm_cfg<P, 4, EPI, 8, 2>(a, s);
-    if (n % 32 == 0 && wg2 >= 480) {
-      if (a.KT / a.n_split <= 40) return launch_gemm_cfg<P, 2, EPI, 4, 4>(a, s);
-      return launch_gemm_cfg<P, 2, EPI, 8, 4>(a, s);
-    }
-    return launch_gemm_cfg<P, 1, EPI, 8, 4>(a, s);
+    if (n % 64 == 0 && n >= 2048) return launch_gemm_cfg<P, 4, EPI, 8, 1>(a, s);
+    if (n % 32 == 0 && (int64_t)(n / 32) * a.n_split >= 200) return launch_gemm_cfg<P, 2, EPI, 8, 1>(a, s);
+    return launch_gemm_cfg<P, 1, EPI, 8, 1>(a, s);
   } else {
-    if (n % 64 == 0 && n / 64 >= 400) return launch_gemm_cfg<P, 4, EPI, 8, 2>(a, s);
-    if (P == 2 && n % 64 == 0 && n / 64 >= 200) return launch_gemm_cfg<P, 4, EPI, 16, 2>(a, s);
+    if (EPI != EPI_QKV && a.KT >= 64 && n % 128 == 0 && n / 128 >= 200) return launch_gemm_cfg<P, 8, EPI, 8, 1>(a, s);
+    if (n % 64 == 0 && n / 64 >= 200) return launch_gemm_cfg<P, 4, EPI, 8, 1>(a, s);
     if constexpr (PAIR) {
-      return launch_gemm_cfg<P, 2, EPI, 8, 4>(a, s);
+      return launch_gemm_cfg<P, 2, EPI, 8, 1>(a, s);
     } else {
-      if (n % 32 == 0 && n / 32 >= 200) return launch_gemm_cfg<P, 2, EPI, 8, 4>(a, s);
-      return launch_gemm_cfg<P, 1, EPI, 8, 4>(a, s);
+      if (n % 32 == 0 && n / 32 >= 200) return launch_gemm_cfg<P, 2, EPI, 8, 1>(a, s);
+      return launch_gemm_cfg<P, 1, EPI, 8, 1>(a, s);
     }
   }
 }
@@ -531,7 +560,7 @@ hipError_t launch_gemm(const GemmArgs& a0, int epi, hipStream_t s) {
   GemmArgs a = a0;
   if (a.n_split < 1) a.n_split = 1;
   if (epi != EPI_PARTIAL && a.n_split != 1) return hipErrorInvalidValue;
-  if (epi == EPI_PARTIAL && (a.h == nullptr || a.n_split > GEMM_MAX_SPLIT || (a.n_split > 1 && a.counters == nullptr))) return hipErrorInvalidValue;
+  if (epi == EPI_PARTIAL && (a.h == nullptr || a.n_split > GEMM_MAX_SPLIT || (a.n_split > 1 && (a.counters == nullptr || a.planes == nullptr)))) return hipErrorInvalidValue;
   if (a.ssq != nullptr && (a.n_ssq < 1 || a.n_ssq > 512)) return hipErrorInvalidValue;
   if (a.n_split > a.KT) return hipErrorInvalidValue;
   if (epi != EPI_QKV) a.grp = 1;
