@@ -123,13 +123,15 @@ int disco_pack_gate_up(const void* dev_gate, const void* dev_up, int64_t d_ff, i
 int disco_model_create(const disco_model_desc* desc, const disco_model_weights* w, disco_model** out);
 void disco_model_destroy(disco_model* m);
 
-/* Bytes of KV page storage for capacity_tokens positions (rounded up to whole pages).              */
+/* Bytes of KV storage for capacity_tokens positions (rounded up to whole pages): the page order, for
+ * family B the rotary table (cos, sin per position and channel pair, fp32), and the pages.          */
 size_t disco_kv_bytes(const disco_model* m, int capacity_tokens, int page_tokens);
 /* dev_pages: caller's buffer of at least disco_kv_bytes(...), 256-byte aligned.  Logical page i of
  * the sequence lives in physical page host_page_order[i] (a permutation of 0..n_pages-1), or in
  * page i when host_page_order is NULL.  page_tokens must be a multiple of 4.  Page layout:
  * [layer][physical page][K | V][kv head] blocks of page_tokens x d_head bf16; K blocks are
- * [token][d_head], V blocks are stored transposed, [d_head][token].                               */
+ * [token][d_head], V blocks are stored transposed, [d_head][token].  The rotary table of a family B
+ * cache is written by the first forward that uses the cache, on that call's stream.               */
 int disco_kv_create(const disco_model* m, void* dev_pages, size_t bytes, int capacity_tokens,
                     int page_tokens, const int32_t* host_page_order, disco_kv** out);
 void disco_kv_destroy(disco_kv* kv);

@@ -49,6 +49,8 @@ struct disco_kv {
   const disco_model* model;
   bf16_t* pages;
   int32_t* dev_page_table;   // inside the caller's buffer, or nullptr for the identity order
+  float* dev_rope;           // inside the caller's buffer: [capacity][d_head / 2][cos, sin] (family B), else nullptr
+  bool rope_ready;           // the table is written by the first forward that uses the cache, on its stream
   int page_tokens, n_pages, capacity, len;
   size_t layer_stride;       // elements between layers
 };
@@ -122,6 +124,10 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   const disco_model_desc& d = m->d;
   const int pos0 = kv->len;
   const bool fam_a = d.family == DISCO_FAMILY_A;
+  if (kv->dev_rope && !kv->rope_ready) {
+    HIP_TRY(launch_rope_fill(kv->dev_rope, kv->capacity, d.d_head, d.rope_base, s), "rotary table launch");
+    kv->rope_ready = true;
+  }
 
   const int n_tiles = d.d_model / 16;            // one sum-of-squares slot per 16 columns of h
   const int split_o = gemm_split_for(d.d_model, m->d_q / 32, n), split_dn = gemm_split_for(d.d_model, d.d_ff / 32, n);
@@ -162,7 +168,7 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     // QKV projection, rotary, KV append
     g.W = static_cast<const bf16_t*>(L.wqkv); normed_input(g); g.n_rows = m->d_qkv;
     g.grp = d.d_head / 32; g.q = ws.q; g.ldq = m->d_q; g.nq = d.n_heads; g.nkv = d.n_kv_heads; g.dh = d.d_head;
-    g.pos0 = pos0; g.rope = fam_a ? 0 : 1; g.rope_base = d.rope_base;
+    g.pos0 = pos0; g.rope_tab = kv->dev_rope;
     g.kv_layer = kv->pages + (size_t)l * kv->layer_stride; g.page_table = kv->dev_page_table;
     g.page_tokens = kv->page_tokens;
     HIP_TRY(launch_gemm(g, EPI_QKV, s), "qkv launch");
@@ -275,12 +281,17 @@ int disco_model_create(const disco_model_desc* desc, const disco_model_weights* 
 void disco_model_destroy(disco_model* m) { delete m; }
 
 static size_t kv_table_bytes(int n_pages) { return round_up(sizeof(int32_t) * (size_t)n_pages, 256); }
+// rotary table of a family B cache: (cos, sin) per position and channel pair
+static size_t kv_rope_bytes(const disco_model* m, int n_pages, int page_tokens) {
+  if (m->d.family != DISCO_FAMILY_B) return 0;
+  return round_up(sizeof(float) * 2 * (size_t)n_pages * page_tokens * (m->d.d_head / 2), 256);
+}
 
 size_t disco_kv_bytes(const disco_model* m, int capacity_tokens, int page_tokens) {
   if (!m || capacity_tokens < 1 || page_tokens < 1) return 0;
   const int n_pages = (capacity_tokens + page_tokens - 1) / page_tokens;
   const size_t page_elems = (size_t)2 * m->d.n_kv_heads * page_tokens * m->d.d_head;
-  return kv_table_bytes(n_pages) + sizeof(bf16_t) * page_elems * n_pages * m->d.n_layers;
+  return kv_table_bytes(n_pages) + kv_rope_bytes(m, n_pages, page_tokens) + sizeof(bf16_t) * page_elems * n_pages * m->d.n_layers;
 }
 
 int disco_kv_create(const disco_model* m, void* dev_pages, size_t bytes, int capacity_tokens, int page_tokens,
@@ -303,7 +314,9 @@ int disco_kv_create(const disco_model* m, void* dev_pages, size_t bytes, int cap
   if (!kv) return fail(DISCO_EINVAL, "out of host memory");
   kv->model = m; kv->page_tokens = page_tokens; kv->n_pages = n_pages;
   kv->capacity = n_pages * page_tokens; kv->len = 0;
-  kv->pages = reinterpret_cast<bf16_t*>(static_cast<char*>(dev_pages) + kv_table_bytes(n_pages));
+  const size_t rope_bytes = kv_rope_bytes(m, n_pages, page_tokens);
+  kv->dev_rope = rope_bytes ? reinterpret_cast<float*>(static_cast<char*>(dev_pages) + kv_table_bytes(n_pages)) : nullptr;
+  kv->pages = reinterpret_cast<bf16_t*>(static_cast<char*>(dev_pages) + kv_table_bytes(n_pages) + rope_bytes);
   kv->layer_stride = (size_t)2 * m->d.n_kv_heads * page_tokens * m->d.d_head * n_pages;
   kv->dev_page_table = nullptr;
   if (host_page_order) {
@@ -311,6 +324,7 @@ int disco_kv_create(const disco_model* m, void* dev_pages, size_t bytes, int cap
     hipError_t e = hipMemcpy(kv->dev_page_table, host_page_order, sizeof(int32_t) * n_pages, hipMemcpyHostToDevice);
     if (e != hipSuccess) { delete kv; return hip_fail(e, "page table upload"); }
   }
+  kv->rope_ready = false;
   *out = kv;
   return DISCO_OK;
 }

@@ -38,7 +38,8 @@ struct GemmArgs {
   int64_t ld_out;
   int only_row;         // STORE: write only this token's row to out[0..N) (-1: all rows)
   // QKV epilogue
-  float* q; int ldq; int nq, nkv, dh; int pos0; int rope; float rope_base;
+  float* q; int ldq; int nq, nkv, dh; int pos0;
+  const float* rope_tab;  // rotary table [position][d_head / 2][cos, sin], or nullptr for no rotation
   bf16_t* kv_layer; const int32_t* page_table; int page_tokens;
   // packed-activation epilogues
   bf16_t* Xout; int KT_out;
@@ -88,6 +89,7 @@ hipError_t launch_accept(const int32_t* block, const int32_t* argmax, int n_bloc
 hipError_t launch_kv_fill(const bf16_t* src, bf16_t* pages, const int32_t* page_table, int n_layers,
                           int n_pages, int page_tokens, int nkv, int dh, int ctx, hipStream_t s);
 hipError_t launch_zero(int* p, int n, hipStream_t s);
+hipError_t launch_rope_fill(float* tab, int n_pos, int dh, float base, hipStream_t s);
 hipError_t launch_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in,
                             void* dev_loop_out, hipStream_t s);
 hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void* host_loop_out,

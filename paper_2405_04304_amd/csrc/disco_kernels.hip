@@ -444,15 +444,16 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
     for (int v = 0; v < 4; ++v) { lo4[v] = y[0][v]; hi4[v] = y[TPU - 1][v]; }
     const int pos = a.pos0 + m;
     const bool is_v = head >= a.nq + a.nkv;
-    if (a.rope && !is_v) {
+    if (a.rope_tab != nullptr && !is_v) {
+      // (cos, sin) of pos * base^(-2 (c + v) / d_head), tabulated per cached position
+      const float4* tab = reinterpret_cast<const float4*>(a.rope_tab + ((size_t)pos * half + c) * 2);
+      const float4 t0 = tab[0], t1 = tab[1];
+      const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const double inv_freq = exp2(-(2.0 * (double)(c + v) / (double)a.dh) * log2((double)a.rope_base));
-        double sn, cs;
-        sincos((double)pos * inv_freq, &sn, &cs);
         const float x0 = lo4[v], x1 = hi4[v];
-        lo4[v] = x0 * (float)cs - x1 * (float)sn;
-        hi4[v] = x1 * (float)cs + x0 * (float)sn;
+        lo4[v] = x0 * cs[v] - x1 * sn[v];
+        hi4[v] = x1 * cs[v] + x0 * sn[v];
       }
     }
     if (head < a.nq) {
@@ -712,31 +713,10 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
   const size_t kv_head_elems = (size_t)pt * DH;                  // one head's K (or V) block in a page
   const size_t page_elems = 2 * (size_t)a.nkv * kv_head_elems;
 
-  // query operand: column j holds query min(j, M-1) (surplus columns are never stored)
-  bf16x8 qh[KS], ql[KS];
-  {
-    const float* qp = a.q + (size_t)min(j, a.M - 1) * a.ldq + head * DH + 8 * g;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const float4 x0 = *reinterpret_cast<const float4*>(qp + ks * 32), x1 = *reinterpret_cast<const float4*>(qp + ks * 32 + 4);
-      const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
-      union { bf16_t u[8]; bf16x8 v; } h, l;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) { h.u[i] = f32_to_bf16(xv[i]); l.u[i] = f32_to_bf16(xv[i] - bf16_to_f32(h.u[i])); }
-      qh[ks] = h.v; ql[ks] = l.v;
-    }
-  }
-  f32x4 O[CT];
-#pragma unroll
-  for (int c = 0; c < CT; ++c) O[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = NEG_BIG, l_run = 0.f;
-  const int qpos = a.pos0 + j;                                    // last position query j may see
-
-  for (int base = s0 + w * WKEYS; base < s1; base += NWV * WKEYS) {
-    f32x4 S[2];
-    uint2 vraw[2][CT];
-    // issue every load of this step first: K rows of both 16-position tiles, then the V^T tiles
-    u32x4 kraw[2][KS];
+  // every load of a step is issued first: K rows of both 16-position tiles, then the V^T tiles
+  u32x4 kraw[2][KS];
+  uint2 vraw[2][CT];
+  auto issue_step = [&](const int base) {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int kb = base + 16 * t;
@@ -761,6 +741,36 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
         for (int c = 0; c < CT; ++c) vraw[t][c] = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * pt);
       }
     }
+  };
+  // the first step's cache loads do not depend on the queries: they go out ahead of the q loads
+  int base = s0 + w * WKEYS;
+  bool issued = false;
+  if (base < s1) { issue_step(base); issued = true; }
+
+  // query operand: column j holds query min(j, M-1) (surplus columns are never stored)
+  bf16x8 qh[KS], ql[KS];
+  {
+    const float* qp = a.q + (size_t)min(j, a.M - 1) * a.ldq + head * DH + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const float4 x0 = *reinterpret_cast<const float4*>(qp + ks * 32), x1 = *reinterpret_cast<const float4*>(qp + ks * 32 + 4);
+      const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
+      union { bf16_t u[8]; bf16x8 v; } h, l;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { h.u[i] = f32_to_bf16(xv[i]); l.u[i] = f32_to_bf16(xv[i] - bf16_to_f32(h.u[i])); }
+      qh[ks] = h.v; ql[ks] = l.v;
+    }
+  }
+  f32x4 O[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) O[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  float m_run = NEG_BIG, l_run = 0.f;
+  const int qpos = a.pos0 + j;                                    // last position query j may see
+
+  for (; base < s1; base += NWV * WKEYS) {
+    f32x4 S[2];
+    if (!issued) issue_step(base);
+    issued = false;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int kb = base + 16 * t;
@@ -1083,6 +1093,41 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
 constexpr int CM_NT = 256;
 constexpr int CM_REC = 16;     // floats per record
 
+// The ten largest of the N values per lane held by one wavefront, descending, written by lane 0 to
+// out10: ten cross-lane arg-max rounds, the winning lane drops the value it gave.  No LDS traffic and
+// no workgroup barrier inside.
+template <int N>
+__device__ __forceinline__ void wave_top10(float (&c)[N], float* out10) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll 1
+  for (int rnd = 0; rnd < 10; ++rnd) {
+    VI cur; cur.v = c[0]; cur.i = lane;
+#pragma unroll
+    for (int e = 1; e < N; ++e) cur.v = fmaxf(cur.v, c[e]);
+    const VI w = wave_argmax(cur);
+    if (lane == 0) out10[rnd] = w.v;
+    if (w.i == lane) {
+      bool done = false;
+#pragma unroll
+      for (int e = 0; e < N; ++e) if (!done && c[e] == w.v) { c[e] = -INFINITY; done = true; }
+    }
+  }
+}
+
+// Ten largest of a workgroup's values: every wavefront's ten, then wavefront 0 picks from those.
+template <int N>
+__device__ __forceinline__ void block_top10(float (&c)[N], float (*wtop)[10], float* top_s) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  wave_top10<N>(c, wtop[wv]);
+  __syncthreads();
+  if (wv == 0) {
+    float cand[1];
+    cand[0] = lane < (CM_NT / 64) * 10 ? wtop[lane / 10][lane % 10] : -INFINITY;
+    wave_top10<1>(cand, top_s);
+  }
+  __syncthreads();
+}
+
 __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
   ClfOut* out = reinterpret_cast<ClfOut*>(a.out);
   if (a.gate != nullptr && *a.gate != 0u) {
@@ -1092,6 +1137,7 @@ __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
   __shared__ float sv[CM_NT / 64 + 1];
   __shared__ int si[CM_NT / 64 + 1];
   __shared__ float top_s[10];
+  __shared__ float wtop[CM_NT / 64][10];
   __shared__ float feat_s[12];
   __shared__ int s_last;
   const int t = threadIdx.x, V = a.vocab, b = blockIdx.x, nb = gridDim.x;
@@ -1106,6 +1152,24 @@ __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) r4[e] = idx + e < V ? x[idx + e] : -INFINITY;
   }
+  // operands of the final stage that depend on no reduction are fetched now, so that the merging
+  // workgroup does not pay their round trips one after another at the end
+  int force = -1;
+  float xf = 0.f;
+  if (a.force_token) { force = *a.force_token; if (force >= V) force = -1; }
+  if (force >= 0) xf = x[force];
+  float w1[12], cb1 = 0.f, cw2 = 0.f, cb2 = 0.f;
+#pragma unroll
+  for (int i = 0; i < 12; ++i) w1[i] = 0.f;
+  if (a.clf_params) {
+    cb2 = a.clf_params[a.hidden * 14];
+    if (t < a.hidden) {
+#pragma unroll
+      for (int i = 0; i < 12; ++i) w1[i] = a.clf_params[t * 12 + i];
+      cb1 = a.clf_params[a.hidden * 12 + t];
+      cw2 = a.clf_params[a.hidden * 13 + t];
+    }
+  }
   VI mine; mine.v = -INFINITY; mine.i = 0x7fffffff;
 #pragma unroll
   for (int e = 0; e < 4; ++e) { VI y; y.v = r4[e]; y.i = idx + e; mine = vi_best(mine, y); }
@@ -1118,21 +1182,11 @@ __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
   }
   S = block_sum<CM_NT>(S, sv);
   T = block_sum<CM_NT>(T, sv);
-  // this workgroup's ten largest values: ten arg-max rounds, the winner drops the value it gave
+  // this workgroup's ten largest values
   {
     float c4[4] = {r4[0], r4[1], r4[2], r4[3]};
-    for (int rnd = 0; rnd < 10; ++rnd) {
-      VI cur; cur.v = fmaxf(fmaxf(c4[0], c4[1]), fmaxf(c4[2], c4[3])); cur.i = t;
-      const VI w = block_argmax<CM_NT>(cur, sv, si);
-      if (t == 0) top_s[rnd] = w.v;
-      if (w.i == t) {
-        bool done = false;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) if (!done && c4[e] == w.v) { c4[e] = -INFINITY; done = true; }
-      }
-    }
+    block_top10<4>(c4, wtop, top_s);
   }
-  __syncthreads();
   if (t == 0) { st_agent2(rec, best.v, __int_as_float(best.i)); st_agent2(rec + 2, S, T); }
   if (t >= 2 && t < 7) st_agent2(rec + 2 * t, top_s[2 * t - 4], top_s[2 * t - 3]);
   if (!last_arrival(reinterpret_cast<int*>(a.scratch), nb, &s_last)) return;
@@ -1164,24 +1218,12 @@ __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
       c3[k] = (sl & 1) ? p.y : p.x;
     }
   }
-  for (int rnd = 0; rnd < 10; ++rnd) {
-    VI cur; cur.v = fmaxf(fmaxf(c3[0], c3[1]), c3[2]); cur.i = t;
-    const VI w = block_argmax<CM_NT>(cur, sv, si);
-    if (t == 0) top_s[rnd] = w.v;
-    if (w.i == t) {
-      bool done = false;
-#pragma unroll
-      for (int k = 0; k < 3; ++k) if (!done && c3[k] == w.v) { c3[k] = -INFINITY; done = true; }
-    }
-  }
-  __syncthreads();
-  int force = -1;
-  if (a.force_token) { force = *a.force_token; if (force >= V) force = -1; }
+  block_top10<3>(c3, wtop, top_s);
   float mx = gbest.v;
   if (force >= 0) {
     // raise logit[force] from x_f to M + 4: shift every term to the new maximum, take the old
     // contribution of x_f out and put the new one (e^0 = 1, with (x - max) = 0) in
-    const float xf = x[force], mnew = gbest.v + 4.0f;
+    const float mnew = gbest.v + 4.0f;
     const float sh = expf(-4.0f), ef = expf(xf - mnew);
     Tg = sh * (Tg - 4.0f * Sg) - (ef > 0.f ? ef * (xf - mnew) : 0.f);
     Sg = sh * Sg - ef + 1.0f;
@@ -1204,18 +1246,17 @@ __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
   __syncthreads();
   float contrib = 0.f;
   if (a.clf_params && t < a.hidden) {
-    const float* W1 = a.clf_params + t * 12;
-    float acc = a.clf_params[a.hidden * 12 + t];
+    float acc = cb1;
 #pragma unroll
-    for (int i = 0; i < 12; ++i) acc += W1[i] * feat_s[i];
-    contrib = fmaxf(acc, 0.f) * a.clf_params[a.hidden * 13 + t];
+    for (int i = 0; i < 12; ++i) acc += w1[i] * feat_s[i];
+    contrib = fmaxf(acc, 0.f) * cw2;
   }
   const float z = block_sum<CM_NT>(contrib, sv);
   if (t == 0) {
     float score = __builtin_nanf("");
     uint32_t halt = a.force_halt ? 1u : 0u;
     if (a.clf_params) {
-      score = 1.0f / (1.0f + expf(-(z + a.clf_params[a.hidden * 14])));
+      score = 1.0f / (1.0f + expf(-(z + cb2)));
       if (score < a.tau) halt = 1u;
     }
     out->token = gbest.i;
@@ -1340,6 +1381,30 @@ __global__ void k_loop_finish(const int32_t* sl_count, LoopOut* out, LoopOut* ho
 
 __global__ __launch_bounds__(256) void k_zero(int* p, int n) {
   for (int i = blockIdx.x * 256 + threadIdx.x; i < n; i += gridDim.x * 256) p[i] = 0;
+}
+
+// Rotary table: (cos, sin) of pos * base^(-2 i / d_head) for every cached position and channel pair
+// i; the angle is formed in double precision, the table holds floats.
+__global__ __launch_bounds__(256) void k_rope_fill(float* tab, int n_pos, int dh, float base) {
+  const int half = dh >> 1;
+  const int64_t total = (int64_t)n_pos * half;
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+    const int pos = (int)(idx / half), i = (int)(idx % half);
+    const double inv_freq = exp2(-(2.0 * (double)i / (double)dh) * log2((double)base));
+    double sn, cs;
+    sincos((double)pos * inv_freq, &sn, &cs);
+    tab[idx * 2] = (float)cs;
+    tab[idx * 2 + 1] = (float)sn;
+  }
+}
+
+hipError_t launch_rope_fill(float* tab, int n_pos, int dh, float base, hipStream_t s) {
+  const int64_t total = (int64_t)n_pos * (dh / 2);
+  int64_t blocks = (total + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(k_rope_fill, dim3((unsigned)blocks), dim3(256), 0, s, tab, n_pos, dh, base);
+  return hipGetLastError();
 }
 
 hipError_t launch_zero(int* p, int n, hipStream_t s) {
