@@ -93,6 +93,9 @@ def main():
     ap.add_argument("--prompt-len", type=int, default=512)
     ap.add_argument("--layers", type=int, default=0, help="debug: truncate the target (invalidates the number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the single timed run: static lookahead 1..sl-max and DISCO halting on the same "
+                         "prompt and forcing, one JSON line with a row per policy")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run plain device copies of known size and exit (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -153,6 +156,44 @@ def main():
     policy = ({"mode": "static", "gamma": args.gamma} if args.policy == "static" else
               {"mode": "disco", "tau": args.tau, "sl_max": args.sl_max, "pos_mode": "absolute"})
 
+    # algorithmic bytes (bf16 weights once per forward, live KV once per forward, fp32 logits)
+    def fwd_bytes(s, ctx, m):
+        w = sum(int(torch.tensor(sh).prod()) for n_, sh, kind in W.weight_specs(s)
+                if kind == "matrix" and n_ not in ("tok_emb", "pos_emb")) * 2
+        kv = s.n_layers * 2 * ctx * s.d_kv * 2
+        return w + kv + m * s.n_layers * 2 * s.d_kv * 2 + m * s.vocab * 4
+
+    if args.sweep:
+        rows = []
+        pols = [{"mode": "static", "gamma": g} for g in range(1, args.sl_max + 1)] + [policy]
+        for pol in pols:
+            stamps = []
+
+            def tick(it):
+                torch.cuda.synchronize()
+                stamps.append(time.perf_counter())
+
+            eng.reset()
+            eng.prefill(prompt[:-1])
+            torch.cuda.synchronize()
+            stamps.append(time.perf_counter())
+            res = eng.generate(prompt, max_new, pol, force=force, do_prefill=False, on_iteration=tick,
+                               max_iterations=n_iter)
+            its = res["iterations"][args.warmup:]
+            dt = stamps[n_iter] - stamps[args.warmup]
+            emitted = sum(len(it["emit"]) for it in its)
+            drafted = sum(it["sl"] for it in its)
+            ctx_mid = args.prompt_len + emitted // 2
+            nbytes = len(its) * fwd_bytes(target_shape, ctx_mid, 1) + drafted * fwd_bytes(draft_shape, ctx_mid, 1)
+            rows.append({"policy": pol, "iterations_per_s": len(its) / dt, "tokens_per_s": emitted / dt,
+                         "tokens_per_iteration": emitted / len(its), "drafted_per_iteration": drafted / len(its),
+                         "accepted_per_iteration": sum(it["n"] for it in its) / len(its),
+                         "hbm_gbs": nbytes / dt / 1e9, "ms_per_iteration": 1e3 * dt / len(its)})
+            log(f"[bench] sweep {pol}: {rows[-1]['tokens_per_s']:.1f} tokens/s, {rows[-1]['iterations_per_s']:.1f} it/s")
+        print(json.dumps({"sweep": rows, "steps": args.steps, "warmup": args.warmup, "alpha": args.alpha,
+                          "prompt_len": args.prompt_len, "n_gpus": 1, "data": "synthetic", "dtype": "bf16"}), flush=True)
+        return
+
     # the timed region: a hand-rolled loop over engine iterations so that exactly K are timed
     probe_layer = target_shape.n_layers // 2
     B.disco_probe_enable(probe_layer)
@@ -183,12 +224,6 @@ def main():
     ms_per_step = 1e3 * t_timed / args.steps
     value = emitted / t_timed
 
-    # algorithmic bytes (bf16 weights once per forward, live KV once per forward, fp32 logits)
-    def fwd_bytes(s, ctx, m):
-        w = sum(int(torch.tensor(sh).prod()) for n_, sh, kind in W.weight_specs(s)
-                if kind == "matrix" and n_ not in ("tok_emb", "pos_emb")) * 2
-        kv = s.n_layers * 2 * ctx * s.d_kv * 2
-        return w + kv + m * s.n_layers * 2 * s.d_kv * 2 + m * s.vocab * 4
     ctx_mid = args.prompt_len + sum(len(it["emit"]) for it in its[:args.warmup]) + emitted // 2
     iter_bytes = fwd_bytes(target_shape, ctx_mid, 1 + drafted / args.steps) + (drafted / args.steps) * fwd_bytes(draft_shape, ctx_mid, 1)
     gemm_bytes = 2 * target_shape.d_ff * target_shape.d_model * 2          # gate + up matrices, bf16

@@ -15,6 +15,12 @@ Written from the paper (arXiv 2405.04304):
   * Sec. 4 "SL classifier training": the FFN is a shallow two-layer network.
   * App. D.1: features are the top-k probabilities, the entropy, and the token position counted
     from the start of generation.
+  * Sec. 3 (end) and App. F: the method keeps the rejection-sampling scheme of speculative decoding
+    [Leviathan et al. 2023; Chen et al. 2023], which preserves the target's distribution, and is
+    reported at temperature 1 as well: a draft token x drawn from the draft distribution q is kept
+    with probability min(1, p(x) / q(x)) (p = target distribution at that position); at the first
+    rejection a token is drawn from norm(max(0, p - q)); if every draft token is kept, a bonus
+    token is drawn from the target's next distribution.
 The two transformer families are not the paper's subject (it uses published checkpoints as black
 boxes); their definitions below are the standard pre-norm decoder equations.
 
@@ -25,6 +31,10 @@ Readings of points the paper leaves open (all listed with reasons in the design 
   position feature i counts generated tokens from 1 (mode "absolute") or restarts at 1 in every
   block (mode "block"); LayerNorm eps 1e-5, RMSNorm eps 1e-6, exact (erf) GELU, rotary base 10000
   with half-split pairing (c, c + d_head/2), no linear biases, untied LM head.
+  Sampling (temperature > 0): distributions are softmax(logits / T); a token is drawn from a
+  distribution by inverting its cumulative sum in vocabulary order at u * total, u uniform in
+  [0, 1) and supplied by the caller (so oracle and GPU consume the same random numbers); the
+  classifier's features stay those of the temperature-1 softmax of the raw draft logits.
 
 Parity pins: every function here is pinned by tests/test_oracle_*.py (closed forms, library
 routines, invariants, brute force); none is "parity unpinned".
@@ -252,6 +262,68 @@ def accept(block: Sequence[int], target_argmax: Sequence[int]):
 
 
 # --------------------------------------------------------------------------------------------
+# sampling at temperature > 0: the rejection-sampling scheme the method keeps (Sec. 3, App. F)
+# --------------------------------------------------------------------------------------------
+
+def softmax_t(logits: torch.Tensor, temperature: float) -> torch.Tensor:
+    """softmax(logits / T) in float64."""
+    x = logits.to(F64) / float(temperature)
+    e = torch.exp(x - x.max())
+    return e / e.sum()
+
+
+def sample_index(weights: torch.Tensor, u: float):
+    """Draw from the distribution proportional to `weights` (non-negative, not necessarily
+    normalised) by inverting its cumulative sum in index order: the smallest v with
+    cumsum(weights)[v] > u * total.  Returns (v, margin) where margin is the distance, as a fraction
+    of the total, between u * total and the nearest boundary of v's interval: a draw with a tiny
+    margin is one that arithmetic in another precision may place in the neighbouring interval."""
+    w = weights.to(F64)
+    cdf = torch.cumsum(w, dim=0)
+    total = float(cdf[-1])
+    x = float(u) * total
+    v = int(torch.searchsorted(cdf, torch.tensor(x, dtype=F64), right=True))
+    pos = torch.nonzero(w > 0)
+    last = int(pos[-1, 0])
+    if v > last:                      # u * total landed on the end of the support
+        v = last
+    lo = float(cdf[v - 1]) if v > 0 else 0.0
+    hi = float(cdf[v])
+    margin = min(x - lo, hi - x) / total
+    return v, margin
+
+
+def accept_stochastic(block: Sequence[int], q_rows: Sequence[torch.Tensor], p_rows: Sequence[torch.Tensor],
+                      u_accept: Sequence[float], u_resample: Sequence[float]):
+    """Speculative sampling over one block.
+
+    block = [t_0, d_1 .. d_SL]; q_rows[j-1] = the draft distribution d_j was drawn from;
+    p_rows[j] = the target distribution after block[0..j] (j = 0..SL).  d_j is kept iff
+    u_accept[j-1] < min(1, p_rows[j-1][d_j] / q_rows[j-1][d_j]).  At the first rejection (j = n + 1)
+    the iteration's last token is drawn from norm(max(0, p_rows[n] - q_rows[n])); when all SL are
+    kept it is drawn from p_rows[SL]; that draw uses u_resample[n].  Returns n, the emitted tokens,
+    and per-decision margins."""
+    sl = len(block) - 1
+    n = 0
+    acc_margins = []
+    while n < sl:
+        x = int(block[n + 1])
+        p, q = float(p_rows[n][x]), float(q_rows[n][x])
+        # u < min(1, p / q)  <=>  u * q < p  (u < 1 always)
+        acc_margins.append(abs(float(u_accept[n]) * q - p) / max(q, 1e-300))
+        if float(u_accept[n]) * q < p:
+            n += 1
+        else:
+            break
+    if n < sl:
+        resid = torch.clamp(p_rows[n].to(F64) - q_rows[n].to(F64), min=0.0)
+        last, smargin = sample_index(resid, float(u_resample[n]))
+    else:
+        last, smargin = sample_index(p_rows[sl], float(u_resample[n]))
+    return n, [int(t) for t in block[1:n + 1]] + [last], {"accept_margins": acc_margins, "sample_margin": smargin}
+
+
+# --------------------------------------------------------------------------------------------
 # generation loops
 # --------------------------------------------------------------------------------------------
 
@@ -347,6 +419,68 @@ def spec_decode(target: Model, draft: Model, clf: Optional[Dict], prompt: Sequen
                       "target_margins": [top2_margin(logits_t[r]) for r in range(sl + 1)]})
     return {"tokens": seq[n_prompt:], "iterations": iters, "n_iterations": len(iters),
             "n_draft_forwards": n_draft_fwd, "n_target_forwards": n_target_fwd,
+            "sl_hist": _hist([it["sl"] for it in iters])}
+
+
+def spec_decode_sampling(target: Model, draft: Model, clf: Optional[Dict], prompt: Sequence[int],
+                         max_new: int, policy: Dict, temperature: float, uniforms: Dict,
+                         prefill_chunk: int = 64) -> Dict:
+    """Speculative decoding at temperature > 0 with a lookahead policy ("static" or "disco").
+
+    uniforms: {"draft": [max_new + cap] floats, one per generated index (the draw of the draft token
+    guessed for that index), "accept": the same shape (the keep / reject draw for that index),
+    "resample": the same shape, indexed by the generated index of the iteration's last token}.
+    Indexing by generated position makes the random numbers a function of the position alone, as
+    the forcing mask of the greedy workloads is.  The classifier's features come from the
+    temperature-1 softmax of the raw draft logits; its position feature as in spec_decode."""
+    mode = policy["mode"]
+    assert mode in ("static", "disco")
+    pos_mode = policy.get("pos_mode", "absolute")
+    cap_policy = policy["gamma"] if mode == "static" else policy["sl_max"]
+    room = len(prompt) + max_new + cap_policy + 2
+    kv_t, kv_d = target.new_cache(room), draft.new_cache(room)
+    target.prefill(list(prompt[:-1]), kv_t, prefill_chunk)
+    draft.prefill(list(prompt[:-1]), kv_d, prefill_chunk)
+    seq = [int(t) for t in prompt]
+    n_prompt = len(seq)
+    iters: List[Dict] = []
+    while len(seq) - n_prompt < max_new:
+        emitted = len(seq) - n_prompt
+        remaining = max_new - emitted
+        cap = min(cap_policy, remaining - 1)
+        pending = seq[kv_d.len:]
+        block, q_rows, steps = [seq[-1]], [], []
+        j = 0
+        while j < cap:
+            j += 1
+            logits = draft.forward(pending, kv_d)[-1]
+            gen_index = emitted + j - 1
+            q = softmax_t(logits, temperature)
+            d, dmargin = sample_index(q, float(uniforms["draft"][gen_index]))
+            i_feat = (emitted + j) if pos_mode == "absolute" else j
+            ft = features(logits, i_feat)
+            score = classifier(ft["feats"], clf) if clf is not None else float("nan")
+            block.append(d)
+            q_rows.append(q)
+            pending = [d]
+            halt = (j == cap) if mode == "static" else (score < policy["tau"] or j == cap)
+            steps.append({"j": j, "token": d, "score": score, "halt": bool(halt), "sample_margin": dmargin,
+                          "pos_feature": i_feat, "gen_index": gen_index, "feats": ft["feats"]})
+            if halt:
+                break
+        sl = len(block) - 1
+        ctx_t = kv_t.len
+        logits_t = target.forward(block, kv_t)
+        p_rows = [softmax_t(logits_t[r], temperature) for r in range(sl + 1)]
+        u_acc = [float(uniforms["accept"][emitted + r]) for r in range(sl)]
+        u_res = [float(uniforms["resample"][emitted + r]) for r in range(sl + 1)]
+        n, emit, info = accept_stochastic(block, q_rows, p_rows, u_acc, u_res)
+        emit = emit[:remaining]
+        seq.extend(emit)
+        kv_t.rollback(ctx_t + n + 1)
+        kv_d.rollback(min(kv_d.len, ctx_t + n + 1))
+        iters.append({"sl": sl, "n": n, "block": block, "emit": emit, "steps": steps, "ctx": ctx_t, **info})
+    return {"tokens": seq[n_prompt:], "iterations": iters, "n_iterations": len(iters),
             "sl_hist": _hist([it["sl"] for it in iters])}
 
 

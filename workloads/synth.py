@@ -23,7 +23,7 @@ __all__ = [
     "ModelShape", "ClassifierShape", "CFG0_TARGET", "CFG0_DRAFT", "CFG1_DRAFT", "CFG2_TARGET",
     "CFG3_TARGET", "CFG3_DRAFT", "CLF_SHAPE", "weight_specs", "make_weights", "early_exit_draft",
     "make_classifier", "make_prompt", "make_tokens", "make_kv_fill", "make_force_mask",
-    "scaled_shape", "bf16_round", "n_params",
+    "scaled_shape", "bf16_round", "n_params", "make_uniforms",
 ]
 
 
@@ -213,3 +213,10 @@ def make_force_mask(seed: int, n: int, alpha: float) -> torch.Tensor:
     """Bernoulli(alpha) per generated position (bool[n]); a function of the position only."""
     g = np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFF, _tid("force")]))
     return torch.from_numpy(g.random(n) < alpha)
+
+
+def make_uniforms(seed: int, n: int, name: str) -> torch.Tensor:
+    """n float32 uniforms on [0, 1), a function of (seed, name, index) only: the random numbers a
+    sampling run consumes are inputs of the run, shared by the CPU oracle and the GPU path."""
+    g = np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFF, _tid("u." + name)]))
+    return torch.from_numpy(g.random(n, dtype=np.float32))
