@@ -232,6 +232,42 @@ int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* cl
                      float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out,
                      disco_loop_out* host_out, void* dev_ws, size_t ws_bytes, disco_stream s);
 
+/* ---- sampling at temperature > 0 (Sec. 3, last sentence; App. F) ----------------------------- */
+/* The method keeps the rejection-sampling scheme of speculative decoding, which preserves the target
+ * model's distribution, and is reported at temperature 1 as well.  Distributions are
+ * softmax(logits / temperature); a token is drawn from a distribution by inverting its cumulative sum
+ * in vocabulary order at u * total, with u uniform on [0, 1) SUPPLIED BY THE CALLER (device memory),
+ * so that a run is a function of its inputs.  vocab % 4 == 0, vocab <= 65536, temperature > 0.       */
+
+/* Draw one token per row from softmax(dev_logits[row] / temperature), rows n_rows x vocab with row
+ * stride ld_logits floats (a multiple of 4).  dev_u: n_rows uniforms.  dev_probs (may be NULL)
+ * receives the fp32 probability rows [n_rows x vocab]; dev_tokens the drawn ids [n_rows].             */
+int disco_sample(const float* dev_logits, int n_rows, int vocab, int64_t ld_logits, float temperature,
+                 const float* dev_u, float* dev_probs, int32_t* dev_tokens, disco_stream s);
+
+/* Speculative sampling over one block.  dev_block = [last emitted token, d_1 .. d_SL];
+ * dev_draft_probs[j - 1] = the distribution d_j was drawn from (rows of vocab floats);
+ * dev_target_logits[j] = the target's logits after block[0..j] (n_block rows).  d_j is kept while
+ * u_accept[j - 1] * q(d_j) < p(d_j); at the first rejection (after n kept tokens) the iteration's
+ * last token is drawn from norm(max(0, p_n - q_n)), and from p_SL when all are kept, with
+ * dev_u_resample[n] (n_block entries).  Writes n and the emitted tokens as disco_accept does.
+ * dev_n_block (may be NULL) overrides n_block with a device-resident value in [1, n_block].          */
+int disco_accept_sample(const int32_t* dev_block, int n_block, const int32_t* dev_n_block,
+                        const float* dev_draft_probs, const float* dev_target_logits, int vocab,
+                        float temperature, const float* dev_u_accept, const float* dev_u_resample,
+                        disco_accept_out* dev_out, disco_accept_out* host_out, disco_stream s);
+
+/* disco_draft_loop with sampled draft tokens: step j draws its token from
+ * softmax(draft logits / temperature) with dev_u_draft[j - 1] and stores the probability row in
+ * dev_draft_probs[j - 1] (cap rows of vocab floats); the classifier's features stay those of the
+ * temperature-1 softmax of the raw logits.  No forced tokens.  Other arguments as disco_draft_loop.  */
+int disco_draft_loop_sampled(const disco_model* draft, disco_kv* kv, const disco_clf* clf,
+                             const int32_t* dev_tokens_in, int n_in, int cap, int static_sl,
+                             float pos_feature0, float tau, float temperature, const float* dev_u_draft,
+                             float* dev_draft_probs, float* dev_logits, disco_clf_out* dev_steps,
+                             disco_loop_out* dev_out, disco_loop_out* host_out, void* dev_ws,
+                             size_t ws_bytes, disco_stream s);
+
 /* ---- measurement probe ------------------------------------------------------------------------- */
 
 /* Brackets, with two HIP events on the launch stream, the MLP-input GEMM (gate/up + SwiGLU, or

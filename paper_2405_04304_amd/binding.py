@@ -87,6 +87,14 @@ _SIGNATURES = {
     "disco_draft_loop": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(Clf), C.c_void_p, C.c_int, C.c_int,
                                    C.c_int, C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "disco_sample": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int64, C.c_float, C.c_void_p, C.c_void_p,
+                               C.c_void_p, C.c_void_p]),
+    "disco_accept_sample": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                      C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "disco_draft_loop_sampled": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(Clf), C.c_void_p, C.c_int, C.c_int,
+                                           C.c_int, C.c_float, C.c_float, C.c_float, C.c_void_p, C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_size_t, C.c_void_p]),
     "disco_probe_enable": (C.c_int, [C.c_int]),
     "disco_probe_read_ms": (C.c_float, []),
 }
@@ -186,6 +194,27 @@ def disco_draft_loop(model, kv, clf, tokens_in, n_in, cap, static_sl, pos_featur
                                   _ptr(force_tokens), _ptr(logits), _ptr(steps), _ptr(out),
                                   _ptr(host_out), _ptr(ws.buf), ws.nbytes,
                                   _stream() if stream is None else stream))
+
+
+def disco_sample(logits, n_rows, vocab, ld_logits, temperature, u, probs, tokens, stream=None):
+    _check(lib().disco_sample(_ptr(logits), n_rows, vocab, ld_logits, temperature, _ptr(u), _ptr(probs),
+                              _ptr(tokens), _stream() if stream is None else stream))
+
+
+def disco_accept_sample(block, n_block, draft_probs, target_logits, vocab, temperature, u_accept, u_resample,
+                        out, host_out=None, dev_n_block=None, stream=None):
+    _check(lib().disco_accept_sample(_ptr(block), n_block, _ptr(dev_n_block), _ptr(draft_probs),
+                                     _ptr(target_logits), vocab, temperature, _ptr(u_accept), _ptr(u_resample),
+                                     _ptr(out), _ptr(host_out), _stream() if stream is None else stream))
+
+
+def disco_draft_loop_sampled(model, kv, clf, tokens_in, n_in, cap, static_sl, pos_feature0, tau, temperature,
+                             u_draft, draft_probs, logits, steps, out, host_out, ws, stream=None):
+    _check(lib().disco_draft_loop_sampled(model.handle, kv.handle, C.byref(clf.c) if clf is not None else None,
+                                          _ptr(tokens_in), n_in, cap, static_sl, pos_feature0, tau, temperature,
+                                          _ptr(u_draft), _ptr(draft_probs), _ptr(logits), _ptr(steps), _ptr(out),
+                                          _ptr(host_out), _ptr(ws.buf), ws.nbytes,
+                                          _stream() if stream is None else stream))
 
 
 def disco_probe_enable(layer: int) -> None:

@@ -433,10 +433,17 @@ int disco_kv_rollback(disco_kv* kv, int new_len) {
   return DISCO_OK;
 }
 
-int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in, int n_in,
-                     int cap, int static_sl, float pos_feature0, float tau, const int32_t* dev_force_tokens,
-                     float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
-                     void* dev_ws, size_t ws_bytes, disco_stream s) {
+static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in, int n_in,
+                           int cap, int static_sl, float pos_feature0, float tau, const int32_t* dev_force_tokens,
+                           float temperature, const float* dev_u_draft, float* dev_draft_probs,
+                           float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
+                           void* dev_ws, size_t ws_bytes, disco_stream s) {
+  const bool sampled = dev_u_draft != nullptr;
+  if (sampled) {
+    if (!(temperature > 0.f)) return fail(DISCO_EINVAL, "temperature must be positive");
+    if (!dev_draft_probs || !aligned(dev_u_draft, 4) || !aligned(dev_draft_probs, 16)) return fail(DISCO_EINVAL, "sampling buffers null or misaligned");
+    if (draft && (draft->d.vocab > 65536)) return fail(DISCO_EINVAL, "vocab above 65536 unsupported for sampling");
+  }
   if (cap < 1 || cap > DISCO_MAX_BLOCK - 1) return fail(DISCO_ECAP, "cap %d outside [1, %d]", cap, DISCO_MAX_BLOCK - 1);
   if (static_sl < 0 || static_sl > cap) return fail(DISCO_EINVAL, "static_sl %d outside [0, cap]", static_sl);
   if (n_in < 1 || n_in > 2) return fail(DISCO_EINVAL, "n_in must be 1 or 2");
@@ -458,17 +465,77 @@ int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* cl
   for (int j = 1; j <= steps; ++j) {
     rc = forward_block(draft, kv, j == 1 ? dev_tokens_in : ws.tok_next, j == 1 ? n_in : 1, dev_logits, true, ws, ws.gate, st);
     if (rc) return rc;
+    if (sampled) {
+      // the draft token of this step is drawn before the classifier may close the gate on it
+      SampleArgs sa{};
+      sa.logits = dev_logits; sa.ld = draft->d.vocab; sa.vocab = draft->d.vocab; sa.inv_t = 1.0f / temperature;
+      sa.u = dev_u_draft + (j - 1); sa.probs = dev_draft_probs + (size_t)(j - 1) * draft->d.vocab;
+      sa.tokens = ws.tok_next; sa.block_slot = dev_out->block + j; sa.gate = ws.gate;
+      HIP_TRY(launch_sample_rows(sa, 1, st), "sample launch");
+    }
     ClassifyArgs a{};
     a.logits = dev_logits; a.vocab = draft->d.vocab; a.clf_params = clf ? clf->dev_params : nullptr; a.hidden = clf ? clf->hidden : 0;
     a.pos_feature = pos_feature0 + (float)(j - 1);
     a.tau = static_sl > 0 ? -1.0e30f : tau;
     a.force_halt = (j == steps) ? 1 : 0;
-    a.out = dev_steps + (j - 1); a.token_next = ws.tok_next; a.block_slot = dev_out->block + j; a.gate = ws.gate;
+    a.out = dev_steps + (j - 1); a.token_next = sampled ? nullptr : ws.tok_next;
+    a.block_slot = sampled ? nullptr : dev_out->block + j; a.gate = ws.gate;
     a.sl_count = ws.sl_count; a.force_token = dev_force_tokens ? dev_force_tokens + (j - 1) : nullptr;
     a.scratch = ws.clf_scratch;
     HIP_TRY(launch_classify(a, st), "classify launch");
   }
   HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, st), "loop finish launch");
+  return DISCO_OK;
+}
+
+int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in, int n_in,
+                     int cap, int static_sl, float pos_feature0, float tau, const int32_t* dev_force_tokens,
+                     float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
+                     void* dev_ws, size_t ws_bytes, disco_stream s) {
+  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, dev_force_tokens, 0.f, nullptr,
+                         nullptr, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
+}
+
+int disco_draft_loop_sampled(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in,
+                             int n_in, int cap, int static_sl, float pos_feature0, float tau, float temperature,
+                             const float* dev_u_draft, float* dev_draft_probs, float* dev_logits, disco_clf_out* dev_steps,
+                             disco_loop_out* dev_out, disco_loop_out* host_out, void* dev_ws, size_t ws_bytes, disco_stream s) {
+  if (!dev_u_draft) return fail(DISCO_EINVAL, "null argument");
+  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, nullptr, temperature, dev_u_draft,
+                         dev_draft_probs, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
+}
+
+int disco_sample(const float* dev_logits, int n_rows, int vocab, int64_t ld_logits, float temperature, const float* dev_u,
+                 float* dev_probs, int32_t* dev_tokens, disco_stream s) {
+  if (!dev_logits || !dev_u || !dev_tokens) return fail(DISCO_EINVAL, "null argument");
+  if (n_rows < 1 || n_rows > 65535) return fail(DISCO_EINVAL, "n_rows %d outside [1, 65535]", n_rows);
+  if (vocab < 4 || vocab % 4 || vocab > 65536) return fail(DISCO_EINVAL, "vocab %d: must be a multiple of 4 in [4, 65536]", vocab);
+  if (ld_logits < vocab || ld_logits % 4) return fail(DISCO_EINVAL, "row stride must be a multiple of 4 and at least vocab");
+  if (!(temperature > 0.f)) return fail(DISCO_EINVAL, "temperature must be positive");
+  if (!aligned(dev_logits, 16) || !aligned(dev_u, 4) || !aligned(dev_probs, 16) || !aligned(dev_tokens, 4)) return fail(DISCO_EINVAL, "misaligned pointer");
+  SampleArgs a{};
+  a.logits = dev_logits; a.ld = ld_logits; a.vocab = vocab; a.inv_t = 1.0f / temperature; a.u = dev_u; a.probs = dev_probs;
+  a.tokens = dev_tokens;
+  HIP_TRY(launch_sample_rows(a, n_rows, static_cast<hipStream_t>(s)), "sample launch");
+  return DISCO_OK;
+}
+
+int disco_accept_sample(const int32_t* dev_block, int n_block, const int32_t* dev_n_block, const float* dev_draft_probs,
+                        const float* dev_target_logits, int vocab, float temperature, const float* dev_u_accept,
+                        const float* dev_u_resample, disco_accept_out* dev_out, disco_accept_out* host_out, disco_stream s) {
+  if (!dev_block || !dev_target_logits || !dev_u_resample || !dev_out) return fail(DISCO_EINVAL, "null argument");
+  if (n_block < 1 || n_block > DISCO_MAX_BLOCK) return fail(DISCO_ECAP, "block of %d tokens outside [1, %d]", n_block, DISCO_MAX_BLOCK);
+  if (n_block > 1 && (!dev_draft_probs || !dev_u_accept)) return fail(DISCO_EINVAL, "null argument");
+  if (vocab < 4 || vocab % 4 || vocab > 65536) return fail(DISCO_EINVAL, "vocab %d: must be a multiple of 4 in [4, 65536]", vocab);
+  if (!(temperature > 0.f)) return fail(DISCO_EINVAL, "temperature must be positive");
+  if (!aligned(dev_block, 4) || !aligned(dev_n_block, 4) || !aligned(dev_draft_probs, 16) || !aligned(dev_target_logits, 16) ||
+      !aligned(dev_u_accept, 4) || !aligned(dev_u_resample, 4) || !aligned(dev_out, 4) || !aligned(host_out, 4))
+    return fail(DISCO_EINVAL, "misaligned pointer");
+  AcceptSampleArgs a{};
+  a.block = dev_block; a.n_block = n_block; a.dev_n_block = dev_n_block; a.draft_probs = dev_draft_probs;
+  a.target_logits = dev_target_logits; a.vocab = vocab; a.inv_t = 1.0f / temperature; a.u_accept = dev_u_accept;
+  a.u_resample = dev_u_resample; a.out = dev_out; a.host_out = host_out;
+  HIP_TRY(launch_accept_sample(a, static_cast<hipStream_t>(s)), "accept launch");
   return DISCO_OK;
 }
 

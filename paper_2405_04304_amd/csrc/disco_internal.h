@@ -74,6 +74,25 @@ struct ClassifyArgs {
   const int32_t* force_token;
   float* scratch;                    // optional: >= CLASSIFY_SCRATCH_BYTES, first word zero (ticket counter)
 };
+struct SampleArgs {
+  const float* logits; int64_t ld; int vocab; float inv_t;
+  const float* u;                    // one uniform in [0, 1) per row
+  float* probs;                      // optional [rows x vocab] probability rows
+  int32_t* tokens;                   // [rows]
+  int32_t* token_next; int32_t* block_slot;   // optional extra copies of row 0's token
+  const uint32_t* gate;
+};
+
+struct AcceptSampleArgs {
+  const int32_t* block; int n_block; const int32_t* dev_n_block;
+  const float* draft_probs;          // [n_block - 1][vocab], row j - 1 = distribution of block[j]
+  const float* target_logits;        // [n_block][vocab]
+  int vocab; float inv_t;
+  const float* u_accept;             // [n_block - 1]
+  const float* u_resample;           // [n_block], entry n is used
+  void* out; void* host_out;         // disco_accept_out
+};
+
 constexpr size_t CLASSIFY_SCRATCH_BYTES = 256 + 64 * 16 * sizeof(float);
 
 hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int64_t tile_mul,
@@ -83,6 +102,8 @@ int gemm_split_for(int n_rows, int KT, int M);   // K ranges the PARTIAL epilogu
 hipError_t launch_norm(const NormArgs& a, hipStream_t s);
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s);
+hipError_t launch_sample_rows(const SampleArgs& a, int n_rows, hipStream_t s);
+hipError_t launch_accept_sample(const AcceptSampleArgs& a, hipStream_t s);
 hipError_t launch_argmax_rows(const float* logits, int M, int vocab, int32_t* out, hipStream_t s);
 hipError_t launch_accept(const int32_t* block, const int32_t* argmax, int n_block,
                          const int32_t* dev_n_block, void* dev_out, void* host_out, hipStream_t s);

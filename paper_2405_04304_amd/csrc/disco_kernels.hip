@@ -1363,6 +1363,243 @@ hipError_t launch_kv_fill(const bf16_t* src, bf16_t* pages, const int32_t* page_
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// sampling at temperature > 0: draws by inverse CDF in vocabulary order, speculative acceptance
+// ---------------------------------------------------------------------------------------------
+//
+// One workgroup of 1024 threads per row; the row lives in registers (V4 float4 per thread, element
+// (i * 1024 + t) * 4 + e in slot i of thread t, one round of coalesced 128-bit loads).  Cumulative
+// sums follow the vocabulary order: segment i (4096 elements) before segment i + 1, inside a segment
+// thread by thread.  Every wavefront scans its 64 per-thread sums of every segment across lanes, the
+// (segment, wavefront) totals go through LDS once, and every thread then knows the cumulative sum at
+// the start of each of its float4 groups.  The group that holds u * total is walked by its owner.
+// All sums are fp32.
+
+constexpr int SMP_NT = 1024;
+constexpr int SMP_NW = SMP_NT / 64;
+
+template <int V4>
+struct SmpRow { float4 w[V4]; };     // weights (or raw logits) of one row, register resident
+
+template <int V4>
+__device__ __forceinline__ void smp_load(SmpRow<V4>& r, const float* x, int V, float pad) {
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    const int idx = (i * SMP_NT + threadIdx.x) * 4;
+    r.w[i] = (idx < V) ? *reinterpret_cast<const float4*>(x + idx) : make_float4(pad, pad, pad, pad);   // V % 4 == 0
+  }
+}
+
+template <int V4>
+__device__ __forceinline__ float smp_block_max(const SmpRow<V4>& r, float* smem) {
+  float mx = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < V4; ++i) mx = fmaxf(mx, fmaxf(fmaxf(r.w[i].x, r.w[i].y), fmaxf(r.w[i].z, r.w[i].w)));
+  mx = wave_max(mx);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) smem[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  float t = smem[0];
+#pragma unroll
+  for (int i = 1; i < SMP_NW; ++i) t = fmaxf(t, smem[i]);
+  __syncthreads();
+  return t;
+}
+
+// Cumulative sum (vocabulary order) of the weights before each of this thread's float4 groups, and
+// the row total.  seg_tot: LDS [V4][SMP_NW].
+template <int V4>
+__device__ __forceinline__ float smp_prefix(const SmpRow<V4>& r, float (&excl)[V4], float* seg_tot) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  float own[V4];
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    own[i] = (r.w[i].x + r.w[i].y) + (r.w[i].z + r.w[i].w);
+    float inc = own[i];
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const float o = __shfl_up(inc, d);
+      if (lane >= d) inc += o;
+    }
+    excl[i] = inc - own[i];                                   // inside the wavefront so far
+    if (lane == 63) seg_tot[i * SMP_NW + wv] = inc;
+  }
+  __syncthreads();
+  float run = 0.f;
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    float before = 0.f, seg = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < SMP_NW; ++ww) { const float v = seg_tot[i * SMP_NW + ww]; if (ww < wv) before += v; seg += v; }
+    excl[i] += run + before;
+    run += seg;
+  }
+  __syncthreads();
+  return run;
+}
+
+// Inverse CDF at u * total: the smallest index whose cumulative sum exceeds the target (the last
+// index with a positive weight if rounding leaves the target at the very end).
+template <int V4>
+__device__ __forceinline__ int smp_draw(const SmpRow<V4>& r, float u, float* seg_tot, int* ismem) {
+  float excl[V4];
+  const float total = smp_prefix<V4>(r, excl, seg_tot);
+  const float target = u * total;
+  int key = -1;                                               // last group (in order) that starts at or before the target
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    const float own = (r.w[i].x + r.w[i].y) + (r.w[i].z + r.w[i].w);
+    if (own > 0.f && excl[i] <= target) key = i * SMP_NT + threadIdx.x;
+  }
+  int best = key;
+  best = max(best, __shfl_xor(best, 1)); best = max(best, __shfl_xor(best, 2)); best = max(best, __shfl_xor(best, 4));
+  best = max(best, __shfl_xor(best, 8)); best = max(best, __shfl_xor(best, 16)); best = max(best, __shfl_xor(best, 32));
+  if ((threadIdx.x & 63) == 0) ismem[threadIdx.x >> 6] = best;
+  __syncthreads();
+  int win = -1;
+#pragma unroll
+  for (int i = 0; i < SMP_NW; ++i) win = max(win, ismem[i]);
+  __syncthreads();
+  if (win >= 0 && key == win) {
+    float4 g = r.w[0]; float c = excl[0];
+#pragma unroll
+    for (int i = 1; i < V4; ++i) if (i == win / SMP_NT) { g = r.w[i]; c = excl[i]; }
+    const float w4[4] = {g.x, g.y, g.z, g.w};
+    int pick = -1, last_pos = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (w4[e] > 0.f) last_pos = e;
+      c += w4[e];
+      if (pick < 0 && c > target) pick = e;
+    }
+    ismem[0] = win * 4 + (pick >= 0 ? pick : last_pos);
+  }
+  __syncthreads();
+  const int res = win >= 0 ? ismem[0] : 0;
+  __syncthreads();
+  return res;
+}
+
+// r := e^((x - max) / T) elementwise (padding becomes 0); returns max, *sum gets the row sum.
+template <int V4>
+__device__ __forceinline__ float smp_exp(SmpRow<V4>& r, float inv_t, float* smem, float* seg_tot, float* sum) {
+  const float m = smp_block_max<V4>(r, smem);
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    r.w[i].x = expf((r.w[i].x - m) * inv_t); r.w[i].y = expf((r.w[i].y - m) * inv_t);
+    r.w[i].z = expf((r.w[i].z - m) * inv_t); r.w[i].w = expf((r.w[i].w - m) * inv_t);
+  }
+  float excl[V4];
+  *sum = smp_prefix<V4>(r, excl, seg_tot);
+  return m;
+}
+
+// Draw one token per row from softmax(logits / T); optionally store the probability row.
+template <int V4>
+__global__ __launch_bounds__(SMP_NT) void k_sample_rows(SampleArgs a) {
+  if (gated(a.gate)) return;
+  __shared__ float smem[SMP_NW];
+  __shared__ float seg_tot[V4 * SMP_NW];
+  __shared__ int ismem[SMP_NW];
+  const int row = blockIdx.x, V = a.vocab;
+  SmpRow<V4> r;
+  smp_load<V4>(r, a.logits + (size_t)row * a.ld, V, -INFINITY);
+  float S;
+  smp_exp<V4>(r, a.inv_t, smem, seg_tot, &S);
+  const int tok = smp_draw<V4>(r, a.u[row], seg_tot, ismem);
+  if (a.probs) {
+    float* p = a.probs + (size_t)row * V;
+    const float inv_s = 1.0f / S;
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+      const int idx = (i * SMP_NT + threadIdx.x) * 4;
+      if (idx < V) *reinterpret_cast<float4*>(p + idx) = make_float4(r.w[i].x * inv_s, r.w[i].y * inv_s, r.w[i].z * inv_s, r.w[i].w * inv_s);
+    }
+  }
+  if (threadIdx.x == 0) {
+    a.tokens[row] = tok;
+    if (row == 0 && a.token_next) *a.token_next = tok;
+    if (row == 0 && a.block_slot) *a.block_slot = tok;
+  }
+}
+
+hipError_t launch_sample_rows(const SampleArgs& a, int n_rows, hipStream_t s) {
+  if (n_rows < 1 || a.vocab < 4 || (a.vocab & 3) || a.vocab > 65536 || (a.ld & 3)) return hipErrorInvalidValue;
+  if (a.vocab <= 8192) hipLaunchKernelGGL(k_sample_rows<2>, dim3(n_rows), dim3(SMP_NT), 0, s, a);
+  else if (a.vocab <= 32768) hipLaunchKernelGGL(k_sample_rows<8>, dim3(n_rows), dim3(SMP_NT), 0, s, a);
+  else hipLaunchKernelGGL(k_sample_rows<16>, dim3(n_rows), dim3(SMP_NT), 0, s, a);
+  return hipGetLastError();
+}
+
+// Speculative sampling over one block: keep d_j while u_j q_j(d_j) < p_{j-1}(d_j); the last token is
+// drawn from norm(max(0, p_n - q_n)) at the first rejection, from p_SL when everything is kept.
+template <int V4>
+__global__ __launch_bounds__(SMP_NT) void k_accept_sample(AcceptSampleArgs a) {
+  __shared__ float smem[SMP_NW];
+  __shared__ float seg_tot[V4 * SMP_NW];
+  __shared__ int ismem[SMP_NW];
+  __shared__ float p_tok;
+  const int V = a.vocab;
+  int nb = a.n_block;
+  if (a.dev_n_block) { const int v = *a.dev_n_block; nb = v < 1 ? 1 : (v > a.n_block ? a.n_block : v); }
+  const int sl = nb - 1;
+  int n = 0;
+  bool rejected = false;
+  SmpRow<V4> r;
+  float S = 1.f;
+  for (;;) {
+    // target distribution after block[0..n]
+    smp_load<V4>(r, a.target_logits + (size_t)n * V, V, -INFINITY);
+    smp_exp<V4>(r, a.inv_t, smem, seg_tot, &S);
+    if (n == sl) break;
+    int tok = a.block[n + 1];
+    tok = tok < 0 ? 0 : (tok >= V ? V - 1 : tok);
+    // the thread that holds the draft token publishes its target probability
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+      const int idx = (i * SMP_NT + threadIdx.x) * 4;
+      if (tok >= idx && tok < idx + 4) {
+        const float w4[4] = {r.w[i].x, r.w[i].y, r.w[i].z, r.w[i].w};
+        p_tok = w4[tok - idx] * (1.0f / S);
+      }
+    }
+    __syncthreads();
+    const float p = p_tok;
+    const float q = a.draft_probs[(size_t)n * V + tok];
+    __syncthreads();
+    if (a.u_accept[n] * q < p) ++n; else { rejected = true; break; }
+  }
+  if (rejected) {
+    // residual max(0, p - q) of row n
+    const float inv_s = 1.0f / S;
+    const float* q = a.draft_probs + (size_t)n * V;
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+      const int idx = (i * SMP_NT + threadIdx.x) * 4;
+      float4 qq = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (idx < V) qq = *reinterpret_cast<const float4*>(q + idx);
+      r.w[i].x = fmaxf(0.f, r.w[i].x * inv_s - qq.x); r.w[i].y = fmaxf(0.f, r.w[i].y * inv_s - qq.y);
+      r.w[i].z = fmaxf(0.f, r.w[i].z * inv_s - qq.z); r.w[i].w = fmaxf(0.f, r.w[i].w * inv_s - qq.w);
+    }
+  }
+  const int last = smp_draw<V4>(r, a.u_resample[n], seg_tot, ismem);
+  if (threadIdx.x == 0) {
+    AcceptOut o;
+    o.n = n; o.n_emit = n + 1;
+    for (int i = 0; i < 16; ++i) o.emit[i] = (i < n) ? a.block[i + 1] : (i == n ? last : -1);
+    *reinterpret_cast<AcceptOut*>(a.out) = o;
+    if (a.host_out) { *reinterpret_cast<AcceptOut*>(a.host_out) = o; __threadfence_system(); }
+  }
+}
+
+hipError_t launch_accept_sample(const AcceptSampleArgs& a, hipStream_t s) {
+  if (a.n_block < 1 || a.n_block > 16 || a.vocab < 4 || (a.vocab & 3) || a.vocab > 65536) return hipErrorInvalidValue;
+  if (a.vocab <= 8192) hipLaunchKernelGGL(k_accept_sample<2>, dim3(1), dim3(SMP_NT), 0, s, a);
+  else if (a.vocab <= 32768) hipLaunchKernelGGL(k_accept_sample<8>, dim3(1), dim3(SMP_NT), 0, s, a);
+  else hipLaunchKernelGGL(k_accept_sample<16>, dim3(1), dim3(SMP_NT), 0, s, a);
+  return hipGetLastError();
+}
+
 struct LoopOut { int32_t sl; int32_t block[16]; };
 
 __global__ void k_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in, LoopOut* out) {

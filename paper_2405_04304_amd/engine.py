@@ -153,3 +153,70 @@ class SpecEngine:
         return {"tokens": seq[n_prompt:], "iterations": iters, "n_iterations": len(iters),
                 "n_draft_forwards": n_draft_fwd, "n_target_forwards": n_target_fwd,
                 "sl_hist": dict(sorted(hist.items()))}
+
+    def generate_sampling(self, prompt: Sequence[int], max_new: int, policy: Dict, temperature: float,
+                          uniforms: Dict, do_prefill: bool = True) -> Dict:
+        """The loop at temperature > 0: sampled draft tokens, speculative-sampling acceptance.
+        uniforms: {"draft", "accept", "resample"}: float32 tensors indexed by generated position (at
+        least max_new + cap entries); they are copied to the device once."""
+        mode = policy["mode"]
+        assert mode in ("static", "disco")
+        pos_mode = policy.get("pos_mode", "absolute")
+        cap_policy = policy["gamma"] if mode == "static" else policy["sl_max"]
+        tau = float(policy.get("tau", 0.0))
+        vocab = self.target.shape.vocab
+        if do_prefill:
+            self.reset()
+            self.prefill(prompt[:-1])
+        pad = torch.zeros(B.MAX_BLOCK, dtype=torch.float32)
+        u_dev = {k: torch.cat([uniforms[k].to(torch.float32), pad]).to(self.dev) for k in ("draft", "accept", "resample")}
+        q_rows = torch.zeros(B.MAX_BLOCK, vocab, dtype=torch.float32, device=self.dev)
+        t_logits = torch.zeros(B.MAX_BLOCK, vocab, dtype=torch.float32, device=self.dev)
+        seq = [int(t) for t in prompt]
+        n_prompt = len(seq)
+        iters: List[Dict] = []
+        loop_block_ptr = self.loop_dev.data_ptr() + 4
+        while len(seq) - n_prompt < max_new:
+            emitted = len(seq) - n_prompt
+            remaining = max_new - emitted
+            cap = min(cap_policy, remaining - 1)
+            ctx_t = self.kv_t.len
+            if cap >= 1:
+                len_d0 = self.kv_d.len
+                pending = seq[len_d0:]
+                assert 1 <= len(pending) <= 2
+                self._put_tokens(pending)
+                B.disco_draft_loop_sampled(self.draft, self.kv_d, self.clf, self.tok_in, len(pending), cap,
+                                           cap if mode == "static" else 0,
+                                           float(emitted + 1) if pos_mode == "absolute" else 1.0, tau, temperature,
+                                           u_dev["draft"].data_ptr() + 4 * emitted, q_rows, self.logits_d,
+                                           self.steps, self.loop_dev, self.loop_host, self.ws_d)
+                torch.cuda.current_stream().synchronize()
+                lo = B.LoopOut.from_buffer_copy(self.loop_host.numpy().tobytes())
+                sl = lo.sl
+                block = list(lo.block[:sl + 1])
+                B.disco_kv_rollback(self.kv_d, len_d0 + len(pending) + sl - 1)
+            else:
+                sl, block = 0, [seq[-1]]
+                lo = B.LoopOut()
+                lo.sl = 0
+                lo.block[0] = seq[-1]
+                self.loop_dev.copy_(torch.frombuffer(bytearray(bytes(lo)), dtype=torch.uint8))
+            B.disco_verify(self.target, self.kv_t, loop_block_ptr, sl + 1, self.argmax, t_logits, self.ws_t)
+            B.disco_accept_sample(loop_block_ptr, sl + 1, q_rows, t_logits, vocab, temperature,
+                                  u_dev["accept"].data_ptr() + 4 * emitted, u_dev["resample"].data_ptr() + 4 * emitted,
+                                  self.acc_dev, self.acc_host)
+            torch.cuda.current_stream().synchronize()
+            acc = B.AcceptOut.from_buffer_copy(self.acc_host.numpy().tobytes())
+            n = acc.n
+            emit = list(acc.emit[:n + 1])[:remaining]
+            seq.extend(emit)
+            B.disco_kv_rollback(self.kv_t, ctx_t + n + 1)
+            if self.draft is not None and self.kv_d.len > ctx_t + n + 1:
+                B.disco_kv_rollback(self.kv_d, ctx_t + n + 1)
+            iters.append({"sl": sl, "n": n, "block": block, "emit": emit, "ctx": ctx_t})
+        hist: Dict[int, int] = {}
+        for it in iters:
+            hist[it["sl"]] = hist.get(it["sl"], 0) + 1
+        return {"tokens": seq[n_prompt:], "iterations": iters, "n_iterations": len(iters),
+                "sl_hist": dict(sorted(hist.items()))}
