@@ -13,6 +13,7 @@ Prints ONE JSON line (see README for the fields).
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -176,9 +177,12 @@ def main():
             eng.reset()
             eng.prefill(prompt[:-1])
             torch.cuda.synchronize()
+            gc.collect()
+            gc.disable()                      # no collector pauses inside the timed iterations
             stamps.append(time.perf_counter())
             res = eng.generate(prompt, max_new, pol, force=force, do_prefill=False, on_iteration=tick,
                                max_iterations=n_iter)
+            gc.enable()
             its = res["iterations"][args.warmup:]
             dt = stamps[n_iter] - stamps[args.warmup]
             emitted = sum(len(it["emit"]) for it in its)
@@ -188,7 +192,9 @@ def main():
             rows.append({"policy": pol, "iterations_per_s": len(its) / dt, "tokens_per_s": emitted / dt,
                          "tokens_per_iteration": emitted / len(its), "drafted_per_iteration": drafted / len(its),
                          "accepted_per_iteration": sum(it["n"] for it in its) / len(its),
-                         "hbm_gbs": nbytes / dt / 1e9, "ms_per_iteration": 1e3 * dt / len(its)})
+                         "hbm_gbs": nbytes / dt / 1e9, "ms_per_iteration": 1e3 * dt / len(its),
+                         "ms_per_iteration_median": 1e3 * sorted(
+                             stamps[i + 1] - stamps[i] for i in range(args.warmup, n_iter))[len(its) // 2]})
             log(f"[bench] sweep {pol}: {rows[-1]['tokens_per_s']:.1f} tokens/s, {rows[-1]['iterations_per_s']:.1f} it/s")
         print(json.dumps({"sweep": rows, "steps": args.steps, "warmup": args.warmup, "alpha": args.alpha,
                           "prompt_len": args.prompt_len, "n_gpus": 1, "data": "synthetic", "dtype": "bf16"}), flush=True)
@@ -209,10 +215,13 @@ def main():
     eng.reset()
     eng.prefill(prompt[:-1])
     torch.cuda.synchronize()
+    gc.collect()
+    gc.disable()                              # no collector pauses inside the timed iterations
     stamps.append(time.perf_counter())
     res = eng.generate(prompt, max_new, policy, force=force, do_prefill=False, on_iteration=on_iter,
                        max_iterations=n_iter)
     torch.cuda.synchronize()
+    gc.enable()
     B.disco_probe_enable(-1)
     its = res["iterations"]
     assert len(its) == n_iter, (len(its), n_iter)
@@ -234,7 +243,9 @@ def main():
     out = {
         "metric": "accepted tokens/s at 13B/68M bf16 (verify+draft achieved HBM GB/s in roofline)",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step,
+        "ms_per_step_median": 1e3 * sorted(stamps[i + 1] - stamps[i] for i in range(args.warmup, n_iter))[args.steps // 2],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {
             "workload": ("full DISCO loop, 13B-class target (40 layers, d 5120, 40x128 heads, SwiGLU 13824, vocab 32000) "
