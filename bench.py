@@ -167,6 +167,8 @@ def main():
     if args.sweep:
         rows = []
         pols = [{"mode": "static", "gamma": g} for g in range(1, args.sl_max + 1)] + [policy]
+        # upper bound (Sec. 3, oracle SL): draft until the first token that leaves the target's known text
+        pols.append({"mode": "oracle", "reference": greedy, "sl_max": 15})
         for pol in pols:
             stamps = []
 
@@ -189,13 +191,13 @@ def main():
             drafted = sum(it["sl"] for it in its)
             ctx_mid = args.prompt_len + emitted // 2
             nbytes = len(its) * fwd_bytes(target_shape, ctx_mid, 1) + drafted * fwd_bytes(draft_shape, ctx_mid, 1)
-            rows.append({"policy": pol, "iterations_per_s": len(its) / dt, "tokens_per_s": emitted / dt,
+            rows.append({"policy": {k: v for k, v in pol.items() if k != "reference"}, "iterations_per_s": len(its) / dt, "tokens_per_s": emitted / dt,
                          "tokens_per_iteration": emitted / len(its), "drafted_per_iteration": drafted / len(its),
                          "accepted_per_iteration": sum(it["n"] for it in its) / len(its),
                          "hbm_gbs": nbytes / dt / 1e9, "ms_per_iteration": 1e3 * dt / len(its),
                          "ms_per_iteration_median": 1e3 * sorted(
                              stamps[i + 1] - stamps[i] for i in range(args.warmup, n_iter))[len(its) // 2]})
-            log(f"[bench] sweep {pol}: {rows[-1]['tokens_per_s']:.1f} tokens/s, {rows[-1]['iterations_per_s']:.1f} it/s")
+            log(f"[bench] sweep {rows[-1]['policy']}: {rows[-1]['tokens_per_s']:.1f} tokens/s, {rows[-1]['iterations_per_s']:.1f} it/s")
         print(json.dumps({"sweep": rows, "steps": args.steps, "warmup": args.warmup, "alpha": args.alpha,
                           "prompt_len": args.prompt_len, "n_gpus": 1, "data": "synthetic", "dtype": "bf16"}), flush=True)
         return

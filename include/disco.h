@@ -97,7 +97,8 @@ typedef struct disco_clf_out {
   int32_t token;              /* arg-max of the draft logits, lowest id on ties                     */
   float feats[DISCO_N_FEAT];  /* top-10 probabilities (descending), entropy (nats), position        */
   float score;                /* C_i                                                                */
-  uint32_t halt;              /* 1: stop drafting after this token                                  */
+  uint32_t halt;              /* bit 0: stop drafting after this token; bit 1 (reference lookahead    */
+                              /* only): the token differs from the reference and is not in the block  */
   uint32_t executed;          /* 1 if the call ran, 0 if it was gated off                            */
 } disco_clf_out;
 
@@ -231,6 +232,28 @@ int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* cl
                      float pos_feature0, float tau, const int32_t* dev_force_tokens,
                      float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out,
                      disco_loop_out* host_out, void* dev_ws, size_t ws_bytes, disco_stream s);
+
+/* Options of disco_draft_loop_ex (any pointer may be NULL; a NULL opts means none).
+ *   dev_force_tokens: as in disco_draft_loop.
+ *   dev_ref_tokens: cap entries, the known continuation (the target's greedy tokens at the positions
+ *     being drafted; entries < 0 are ignored).  Drafting stops at the first draft token that differs
+ *     from it, and that token is NOT part of the block: the "oracle" lookahead of Sec. 3 ("Finding the
+ *     optimal SL per iteration"), an upper bound that needs the target's text in advance.  Then sl counts
+ *     the matching tokens and sl + 1 draft steps have run (sl == cap: cap steps).
+ *   dev_u_draft / dev_draft_probs / temperature: as in disco_draft_loop_sampled (not with the two above). */
+typedef struct disco_loop_opts {
+  const int32_t* dev_force_tokens;
+  const int32_t* dev_ref_tokens;
+  float temperature;
+  const float* dev_u_draft;
+  float* dev_draft_probs;
+} disco_loop_opts;
+
+int disco_draft_loop_ex(const disco_model* draft, disco_kv* kv, const disco_clf* clf,
+                        const int32_t* dev_tokens_in, int n_in, int cap, int static_sl,
+                        float pos_feature0, float tau, const disco_loop_opts* opts, float* dev_logits,
+                        disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
+                        void* dev_ws, size_t ws_bytes, disco_stream s);
 
 /* ---- sampling at temperature > 0 (Sec. 3, last sentence; App. F) ----------------------------- */
 /* The method keeps the rejection-sampling scheme of speculative decoding, which preserves the target

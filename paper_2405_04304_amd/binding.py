@@ -54,6 +54,11 @@ class AcceptOut(C.Structure):
     _fields_ = [("n", C.c_int32), ("n_emit", C.c_int32), ("emit", C.c_int32 * MAX_BLOCK)]
 
 
+class LoopOpts(C.Structure):
+    _fields_ = [("dev_force_tokens", C.c_void_p), ("dev_ref_tokens", C.c_void_p), ("temperature", C.c_float),
+                ("dev_u_draft", C.c_void_p), ("dev_draft_probs", C.c_void_p)]
+
+
 class LoopOut(C.Structure):
     _fields_ = [("sl", C.c_int32), ("block", C.c_int32 * MAX_BLOCK)]
 
@@ -95,6 +100,9 @@ _SIGNATURES = {
                                            C.c_int, C.c_float, C.c_float, C.c_float, C.c_void_p, C.c_void_p,
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_size_t, C.c_void_p]),
+    "disco_draft_loop_ex": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(Clf), C.c_void_p, C.c_int, C.c_int,
+                                      C.c_int, C.c_float, C.c_float, C.POINTER(LoopOpts), C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "disco_probe_enable": (C.c_int, [C.c_int]),
     "disco_probe_read_ms": (C.c_float, []),
 }
@@ -194,6 +202,16 @@ def disco_draft_loop(model, kv, clf, tokens_in, n_in, cap, static_sl, pos_featur
                                   _ptr(force_tokens), _ptr(logits), _ptr(steps), _ptr(out),
                                   _ptr(host_out), _ptr(ws.buf), ws.nbytes,
                                   _stream() if stream is None else stream))
+
+
+def disco_draft_loop_ex(model, kv, clf, tokens_in, n_in, cap, static_sl, pos_feature0, tau, logits, steps, out,
+                        host_out, ws, force_tokens=None, ref_tokens=None, temperature=0.0, u_draft=None,
+                        draft_probs=None, stream=None):
+    opts = LoopOpts(_ptr(force_tokens), _ptr(ref_tokens), temperature, _ptr(u_draft), _ptr(draft_probs))
+    _check(lib().disco_draft_loop_ex(model.handle, kv.handle, C.byref(clf.c) if clf is not None else None,
+                                     _ptr(tokens_in), n_in, cap, static_sl, pos_feature0, tau, C.byref(opts),
+                                     _ptr(logits), _ptr(steps), _ptr(out), _ptr(host_out), _ptr(ws.buf), ws.nbytes,
+                                     _stream() if stream is None else stream))
 
 
 def disco_sample(logits, n_rows, vocab, ld_logits, temperature, u, probs, tokens, stream=None):

@@ -435,10 +435,12 @@ int disco_kv_rollback(disco_kv* kv, int new_len) {
 
 static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in, int n_in,
                            int cap, int static_sl, float pos_feature0, float tau, const int32_t* dev_force_tokens,
-                           float temperature, const float* dev_u_draft, float* dev_draft_probs,
+                           const int32_t* dev_ref_tokens, float temperature, const float* dev_u_draft, float* dev_draft_probs,
                            float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
                            void* dev_ws, size_t ws_bytes, disco_stream s) {
   const bool sampled = dev_u_draft != nullptr;
+  if (!aligned(dev_ref_tokens, 4)) return fail(DISCO_EINVAL, "misaligned pointer");
+  if (sampled && (dev_ref_tokens || dev_force_tokens)) return fail(DISCO_EINVAL, "sampling excludes forced and reference tokens");
   if (sampled) {
     if (!(temperature > 0.f)) return fail(DISCO_EINVAL, "temperature must be positive");
     if (!dev_draft_probs || !aligned(dev_u_draft, 4) || !aligned(dev_draft_probs, 16)) return fail(DISCO_EINVAL, "sampling buffers null or misaligned");
@@ -481,6 +483,7 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
     a.out = dev_steps + (j - 1); a.token_next = sampled ? nullptr : ws.tok_next;
     a.block_slot = sampled ? nullptr : dev_out->block + j; a.gate = ws.gate;
     a.sl_count = ws.sl_count; a.force_token = dev_force_tokens ? dev_force_tokens + (j - 1) : nullptr;
+    a.ref_token = dev_ref_tokens ? dev_ref_tokens + (j - 1) : nullptr;
     a.scratch = ws.clf_scratch;
     HIP_TRY(launch_classify(a, st), "classify launch");
   }
@@ -492,8 +495,19 @@ int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* cl
                      int cap, int static_sl, float pos_feature0, float tau, const int32_t* dev_force_tokens,
                      float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
                      void* dev_ws, size_t ws_bytes, disco_stream s) {
-  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, dev_force_tokens, 0.f, nullptr,
-                         nullptr, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
+  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, dev_force_tokens, nullptr, 0.f,
+                         nullptr, nullptr, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
+}
+
+int disco_draft_loop_ex(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in, int n_in,
+                        int cap, int static_sl, float pos_feature0, float tau, const disco_loop_opts* opts, float* dev_logits,
+                        disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out, void* dev_ws,
+                        size_t ws_bytes, disco_stream s) {
+  disco_loop_opts o{};
+  if (opts) o = *opts;
+  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, o.dev_force_tokens,
+                         o.dev_ref_tokens, o.temperature, o.dev_u_draft, o.dev_draft_probs, dev_logits, dev_steps, dev_out,
+                         host_out, dev_ws, ws_bytes, s);
 }
 
 int disco_draft_loop_sampled(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in,
@@ -501,8 +515,8 @@ int disco_draft_loop_sampled(const disco_model* draft, disco_kv* kv, const disco
                              const float* dev_u_draft, float* dev_draft_probs, float* dev_logits, disco_clf_out* dev_steps,
                              disco_loop_out* dev_out, disco_loop_out* host_out, void* dev_ws, size_t ws_bytes, disco_stream s) {
   if (!dev_u_draft) return fail(DISCO_EINVAL, "null argument");
-  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, nullptr, temperature, dev_u_draft,
-                         dev_draft_probs, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
+  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, nullptr, nullptr, temperature,
+                         dev_u_draft, dev_draft_probs, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
 }
 
 int disco_sample(const float* dev_logits, int n_rows, int vocab, int64_t ld_logits, float temperature, const float* dev_u,

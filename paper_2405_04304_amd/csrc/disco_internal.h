@@ -72,6 +72,7 @@ struct ClassifyArgs {
   void* out;                         // disco_clf_out*
   int32_t* token_next; int32_t* block_slot; uint32_t* gate; int32_t* sl_count;
   const int32_t* force_token;
+  const int32_t* ref_token;          // optional: known continuation; a different arg-max ends the block and stays out of it
   float* scratch;                    // optional: >= CLASSIFY_SCRATCH_BYTES, first word zero (ticket counter)
 };
 struct SampleArgs {

@@ -1073,13 +1073,20 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
       score = 1.0f / (1.0f + expf(-(z + a.clf_params[a.hidden * 14])));
       if (score < a.tau) halt = 1u;
     }
+    // reference lookahead: a token that differs from the known continuation ends the block and is
+    // not part of it (bit 1 of halt)
+    bool mismatch = false;
+    if (a.ref_token) { const int ref = *a.ref_token; mismatch = ref >= 0 && best.i != ref; }
+    if (mismatch) halt = 3u;
     out->token = best.i;
 #pragma unroll
     for (int i = 0; i < 12; ++i) out->feats[i] = feat_s[i];
     out->score = score; out->halt = halt; out->executed = 1u;
-    if (a.token_next) *a.token_next = best.i;
-    if (a.block_slot) *a.block_slot = best.i;
-    if (a.sl_count) *a.sl_count += 1;
+    if (!mismatch) {
+      if (a.token_next) *a.token_next = best.i;
+      if (a.block_slot) *a.block_slot = best.i;
+      if (a.sl_count) *a.sl_count += 1;
+    }
     if (a.gate && halt) *a.gate = 1u;
   }
 }
@@ -1259,13 +1266,20 @@ __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
       score = 1.0f / (1.0f + expf(-(z + cb2)));
       if (score < a.tau) halt = 1u;
     }
+    // reference lookahead: a token that differs from the known continuation ends the block and is
+    // not part of it (bit 1 of halt)
+    bool mismatch = false;
+    if (a.ref_token) { const int ref = *a.ref_token; mismatch = ref >= 0 && gbest.i != ref; }
+    if (mismatch) halt = 3u;
     out->token = gbest.i;
 #pragma unroll
     for (int i = 0; i < 12; ++i) out->feats[i] = feat_s[i];
     out->score = score; out->halt = halt; out->executed = 1u;
-    if (a.token_next) *a.token_next = gbest.i;
-    if (a.block_slot) *a.block_slot = gbest.i;
-    if (a.sl_count) *a.sl_count += 1;
+    if (!mismatch) {
+      if (a.token_next) *a.token_next = gbest.i;
+      if (a.block_slot) *a.block_slot = gbest.i;
+      if (a.sl_count) *a.sl_count += 1;
+    }
     if (a.gate && halt) *a.gate = 1u;
   }
 }

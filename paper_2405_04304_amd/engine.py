@@ -77,13 +77,19 @@ class SpecEngine:
                  trace: bool = False, do_prefill: bool = True, on_iteration=None,
                  max_iterations: Optional[int] = None) -> Dict:
         mode = policy["mode"]
-        assert mode in ("static", "disco")
+        assert mode in ("static", "disco", "oracle")
         pos_mode = policy.get("pos_mode", "absolute")
-        cap_policy = policy["gamma"] if mode == "static" else policy["sl_max"]
-        tau = float(policy.get("tau", 0.0))
+        cap_policy = {"static": policy.get("gamma"), "disco": policy.get("sl_max"),
+                      "oracle": policy.get("sl_max", B.MAX_BLOCK - 1)}[mode]
+        tau = float(policy.get("tau", 0.0)) if mode == "disco" else -1.0e30
         if do_prefill:
             self.reset()
             self.prefill(prompt[:-1])
+        ref_dev = None
+        if mode == "oracle":
+            # the target's greedy text, known in advance: drafting stops at the first token that leaves it
+            ref = torch.as_tensor(list(policy["reference"][:max_new]), dtype=torch.int32)
+            ref_dev = torch.cat([ref, torch.full((B.MAX_BLOCK,), -1, dtype=torch.int32)]).to(self.dev)
         force_dev = None
         if force is not None:
             ft = torch.where(torch.as_tensor(force["mask"][:max_new]),
@@ -108,21 +114,24 @@ class SpecEngine:
                 pending = seq[len_d0:]
                 assert 1 <= len(pending) <= 2
                 self._put_tokens(pending)
-                B.disco_draft_loop(self.draft, self.kv_d, self.clf, self.tok_in,
-                                   len(pending), cap, cap if mode == "static" else 0,
-                                   float(emitted + 1) if pos_mode == "absolute" else 1.0, tau,
-                                   (force_dev.data_ptr() + 4 * emitted) if force_dev is not None else None,
-                                   self.logits_d, self.steps, self.loop_dev, self.loop_host, self.ws_d)
+                B.disco_draft_loop_ex(self.draft, self.kv_d, self.clf, self.tok_in,
+                                      len(pending), cap, cap if mode == "static" else 0,
+                                      float(emitted + 1) if pos_mode == "absolute" else 1.0, tau,
+                                      self.logits_d, self.steps, self.loop_dev, self.loop_host, self.ws_d,
+                                      force_tokens=(force_dev.data_ptr() + 4 * emitted) if force_dev is not None else None,
+                                      ref_tokens=(ref_dev.data_ptr() + 4 * emitted) if ref_dev is not None else None)
                 torch.cuda.current_stream().synchronize()
                 lo = B.LoopOut.from_buffer_copy(self.loop_host.numpy().tobytes())
                 sl = lo.sl
                 block = list(lo.block[:sl + 1])
-                B.disco_kv_rollback(self.kv_d, len_d0 + len(pending) + sl - 1)
-                n_draft_fwd += sl
+                # draft steps that ran: with a reference, the step whose token left it ran too
+                ran = sl + (1 if (mode == "oracle" and sl < cap) else 0)
+                B.disco_kv_rollback(self.kv_d, len_d0 + len(pending) + ran - 1)
+                n_draft_fwd += ran
                 if trace:
                     raw = self.steps.cpu().numpy().tobytes()
                     sz = C.sizeof(B.ClfOut)
-                    steps_rec = [B.ClfOut.from_buffer_copy(raw[i * sz:(i + 1) * sz]) for i in range(sl)]
+                    steps_rec = [B.ClfOut.from_buffer_copy(raw[i * sz:(i + 1) * sz]) for i in range(ran)]
             else:
                 sl, block = 0, [seq[-1]]
                 lo = B.LoopOut()

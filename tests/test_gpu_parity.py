@@ -404,6 +404,42 @@ def test_loop_forced_acceptance_small_pair():
         assert sum(it["n"] for it in gpu["iterations"]) > n_new // 4      # forcing does produce acceptance
 
 
+def test_loop_reference_lookahead_matches_oracle():
+    """Sec. 3, 'Finding the optimal SL per iteration': draft until the first token that leaves the target's
+    greedy text; that token stays out of the block, so every drafted token is accepted."""
+    st = W.ModelShape("B", 2, 128, 2, 64, 2, 256, 512)
+    sd = W.ModelShape("B", 1, 128, 2, 64, 2, 256, 512)
+    tw, dw = W.make_weights(st, 0, "bf16", sigma=0.1), W.make_weights(sd, 10, "bf16", sigma=0.1)
+    ot, od = O.Model(st, tw, kv_bf16=True), O.Model(sd, dw, kv_bf16=True)
+    clf = W.make_classifier(100)
+    prompt = W.make_prompt(1, 40, st.vocab).tolist()
+    n_new = 96
+    ref, margins = O.greedy_target(ot, prompt, n_new)
+    force = {"mask": W.make_force_mask(5, n_new, 0.6), "tokens": ref}
+    d = dev()
+    eng = SpecEngine(B.DiscoModel(st, tw, d), B.DiscoModel(sd, dw, d), B.DiscoClf(clf, d), max_ctx=160, page_tokens=8)
+    for cap in (15, 3):
+        pol = {"mode": "oracle", "reference": ref, "sl_max": cap}
+        orc = O.spec_decode(ot, od, clf, prompt, n_new, pol, force=force)
+        assert orc["tokens"] == ref and all(it["n"] == it["sl"] for it in orc["iterations"])
+        gpu = eng.generate(prompt, n_new, pol, force=force, trace=True)
+        div = _compare_runs(gpu, orc)
+        if not div:
+            assert gpu["tokens"] == ref and gpu["sl_hist"] == orc["sl_hist"]
+            assert gpu["n_draft_forwards"] == orc["n_draft_forwards"]
+            assert all(it["n"] == it["sl"] <= cap for it in gpu["iterations"])
+            # the step whose token left the reference is recorded with bit 1 of halt set
+            for gi, oi in zip(gpu["iterations"], orc["iterations"]):
+                assert len(gi["steps"]) == len(oi["steps"])
+                for gs, os_ in zip(gi["steps"], oi["steps"]):
+                    assert gs.token == os_["token"] and bool(gs.halt & 2) == bool(os_.get("mismatch", False))
+        assert max(gpu["sl_hist"]) > 1 and min(gpu["sl_hist"]) == 0          # lookaheads do vary
+    # static lookahead can never accept more than the reference lookahead allows (its definition)
+    st5 = eng.generate(prompt, n_new, {"mode": "static", "gamma": 5}, force=force)
+    orc15 = O.spec_decode(ot, od, clf, prompt, n_new, {"mode": "oracle", "reference": ref, "sl_max": 15}, force=force)
+    assert st5["n_iterations"] >= orc15["n_iterations"]
+
+
 # ---- full-size verification block, fused draft loop, reproducibility -----------------------------------
 
 def test_verify_13b_full_depth_block_of_11():
