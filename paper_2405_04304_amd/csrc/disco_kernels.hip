@@ -527,8 +527,9 @@ int gemm_split_for(int n_rows, int KT, int M) {
   (void)M;
   int s;
   if (n_rows % 64 == 0 && n_rows >= 2048) {
-    const int groups = n_rows / 64;
-    s = (480 + groups / 2) / groups;
+    // about 480 workgroups for a short K, about 240 for a long one (fewer, longer streams)
+    const int groups = n_rows / 64, target = KT > 256 ? 240 : 480;
+    s = (target + groups / 2) / groups;
     if (s > KT / 16) s = KT / 16;
   } else {
     s = KT / 24;
@@ -697,26 +698,34 @@ hipError_t launch_norm(const NormArgs& a, hipStream_t s) {
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-
+// One wavefront's share of the attention of one head: 32 cached positions per step.
 template <int DH>
-__global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
-  if (gated(a.gate)) return;
-  constexpr int KS = DH / 32, CT = DH / 16, NWV = 4, WKEYS = 32;
-  __shared__ f32x4 o_s[NWV][CT][64];
-  __shared__ float m_s[NWV][16], l_s[NWV][16];
-  const int head = blockIdx.x, split = blockIdx.y;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int j = lane & 15, g = lane >> 4;
-  const int kvh = head / (a.nq / a.nkv);
-  const int total = a.pos0 + a.M, pt = a.page_tokens;
-  const int s0 = split * a.split_len, s1 = min(s0 + a.split_len, total);
-  const size_t kv_head_elems = (size_t)pt * DH;                  // one head's K (or V) block in a page
-  const size_t page_elems = 2 * (size_t)a.nkv * kv_head_elems;
+struct AttnWave {
+  static constexpr int KS = DH / 32, CT = DH / 16;
+  // raw operands of one step: K rows of two 16-position tiles, V^T tiles of the same positions
+  struct Raw { u32x4 k[2][KS]; uint2 v[2][CT]; };
+  const AttnArgs& a;
+  int j, g, kvh, total, s1, pt, qpos;
+  size_t kv_head_elems, page_elems;
+  bf16x8 qh[KS], ql[KS];
+  f32x4 O[CT];
+  float m_run, l_run;
 
-  // every load of a step is issued first: K rows of both 16-position tiles, then the V^T tiles
-  u32x4 kraw[2][KS];
-  uint2 vraw[2][CT];
-  auto issue_step = [&](const int base) {
+  __device__ __forceinline__ AttnWave(const AttnArgs& a_, int head, int s1_) : a(a_) {
+    const int lane = threadIdx.x & 63;
+    j = lane & 15; g = lane >> 4;
+    kvh = head / (a.nq / a.nkv);
+    total = a.pos0 + a.M; s1 = s1_; pt = a.page_tokens;
+    qpos = a.pos0 + j;                                            // last position query j may see
+    kv_head_elems = (size_t)pt * DH;                              // one head's K (or V) block in a page
+    page_elems = 2 * (size_t)a.nkv * kv_head_elems;
+#pragma unroll
+    for (int c = 0; c < CT; ++c) O[c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    m_run = NEG_BIG; l_run = 0.f;
+  }
+
+  // every load of a step is issued at once; none depends on the queries
+  __device__ __forceinline__ void issue(Raw& r, const int base) const {
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int kb = base + 16 * t;
@@ -725,7 +734,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
         const int pp = a.page_table ? a.page_table[lp] : lp;
         const bf16_t* kp = a.kv_layer + (size_t)pp * page_elems + (size_t)kvh * kv_head_elems + (size_t)off * DH + 8 * g;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kraw[t][ks] = *reinterpret_cast<const u32x4*>(kp + ks * 32);
+        for (int ks = 0; ks < KS; ++ks) r.k[t][ks] = *reinterpret_cast<const u32x4*>(kp + ks * 32);
       }
     }
 #pragma unroll
@@ -738,18 +747,13 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
         const int pp = a.page_table ? a.page_table[lp] : lp;
         const bf16_t* vp = a.kv_layer + (size_t)pp * page_elems + (size_t)(a.nkv + kvh) * kv_head_elems + (size_t)j * pt + off;
 #pragma unroll
-        for (int c = 0; c < CT; ++c) vraw[t][c] = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * pt);
+        for (int c = 0; c < CT; ++c) r.v[t][c] = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * pt);
       }
     }
-  };
-  // the first step's cache loads do not depend on the queries: they go out ahead of the q loads
-  int base = s0 + w * WKEYS;
-  bool issued = false;
-  if (base < s1) { issue_step(base); issued = true; }
+  }
 
   // query operand: column j holds query min(j, M-1) (surplus columns are never stored)
-  bf16x8 qh[KS], ql[KS];
-  {
+  __device__ __forceinline__ void load_q(int head) {
     const float* qp = a.q + (size_t)min(j, a.M - 1) * a.ldq + head * DH + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -761,16 +765,10 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
       qh[ks] = h.v; ql[ks] = l.v;
     }
   }
-  f32x4 O[CT];
-#pragma unroll
-  for (int c = 0; c < CT; ++c) O[c] = f32x4{0.f, 0.f, 0.f, 0.f};
-  float m_run = NEG_BIG, l_run = 0.f;
-  const int qpos = a.pos0 + j;                                    // last position query j may see
 
-  for (; base < s1; base += NWV * WKEYS) {
+  // scores, running soft-max and P.V of one step
+  __device__ __forceinline__ void step(const Raw& r, const int base) {
     f32x4 S[2];
-    if (!issued) issue_step(base);
-    issued = false;
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int kb = base + 16 * t;
@@ -779,7 +777,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-          const bf16x8 kk = as_bf16x8(kraw[t][ks]);
+          const bf16x8 kk = as_bf16x8(r.k[t][ks]);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[ks], acc, 0, 0, 0);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[ks], acc, 0, 0, 0);
         }
@@ -822,7 +820,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
         keep.y = (p0 + 2 < total ? 0x0000FFFFu : 0u) | (p0 + 3 < total ? 0xFFFF0000u : 0u);
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
-          uint2 raw = vraw[t][c];
+          uint2 raw = r.v[t][c];
           raw.x &= keep.x; raw.y &= keep.y;
           union { uint2 u; s16x4 v; } vv; vv.u = raw;
           O[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vv.v, ph.v, O[c], 0, 0, 0);
@@ -831,11 +829,36 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
       }
     }
   }
+};
+
+template <int DH>
+__global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
+  if (gated(a.gate)) return;
+  constexpr int CT = DH / 16, NWV = 4, WKEYS = 32;
+  __shared__ f32x4 o_s[NWV][CT][64];
+  __shared__ float m_s[NWV][16], l_s[NWV][16];
+  const int head = blockIdx.x, split = blockIdx.y;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int total = a.pos0 + a.M;
+  const int s0 = split * a.split_len, s1 = min(s0 + a.split_len, total);
+  AttnWave<DH> aw(a, head, s1);
+  typename AttnWave<DH>::Raw raw;
+  // the first step's cache loads go out ahead of the q loads
+  int base = s0 + w * WKEYS;
+  bool issued = false;
+  if (base < s1) { aw.issue(raw, base); issued = true; }
+  aw.load_q(head);
+  for (; base < s1; base += NWV * WKEYS) {
+    if (!issued) aw.issue(raw, base);
+    issued = false;
+    aw.step(raw, base);
+  }
 
   // merge the four wavefronts (fixed order), then one record per query: o[DH], max, sum
 #pragma unroll
-  for (int c = 0; c < CT; ++c) o_s[w][c][lane] = O[c];
-  if (g == 0) { m_s[w][j] = m_run; l_s[w][j] = l_run; }
+  for (int c = 0; c < CT; ++c) o_s[w][c][lane] = aw.O[c];
+  if (g == 0) { m_s[w][j] = aw.m_run; l_s[w][j] = aw.l_run; }
   __syncthreads();
   float mm = m_s[0][j];
 #pragma unroll
@@ -863,13 +886,13 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
   constexpr int TPQ = DH / 4;                                    // threads per query, 4 channels each
   const int tq = threadIdx.x % TPQ;
   for (int qm = threadIdx.x / TPQ; qm < a.M; qm += 256 / TPQ) {
-    const float* base = a.part + (((size_t)head * a.n_splits) * 16 + qm) * (DH + 2);
+    const float* rbase = a.part + (((size_t)head * a.n_splits) * 16 + qm) * (DH + 2);
     const size_t stride = (size_t)16 * (DH + 2);
     float mx = NEG_BIG;
-    for (int sp = 0; sp < a.n_splits; ++sp) mx = fmaxf(mx, ld_agent2(base + sp * stride + DH).x);
+    for (int sp = 0; sp < a.n_splits; ++sp) mx = fmaxf(mx, ld_agent2(rbase + sp * stride + DH).x);
     float L = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
     for (int sp = 0; sp < a.n_splits; ++sp) {
-      const float* rc = base + sp * stride;
+      const float* rc = rbase + sp * stride;
       const float2 ml = ld_agent2(rc + DH);
       const float wgt = expf(ml.x - mx);
       L += ml.y * wgt;
@@ -883,8 +906,65 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
   }
 }
 
+// Short contexts: one workgroup of eight wavefronts takes a whole head (256 positions per step, the
+// loads of step i + 1 in flight during the arithmetic of step i), merges its wavefronts through LDS
+// and writes the O-projection panels itself: no partial records, no hand-off between workgroups.
+template <int DH>
+__global__ __launch_bounds__(512) void k_attn_head(AttnArgs a) {
+  if (gated(a.gate)) return;
+  constexpr int CT = DH / 16, NWV = 8, WKEYS = 32, STEP = NWV * WKEYS;
+  __shared__ f32x4 o_s[NWV][CT][64];
+  __shared__ float m_s[NWV][16], l_s[NWV][16];
+  const int head = blockIdx.x;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int total = a.pos0 + a.M;
+  AttnWave<DH> aw(a, head, total);
+  typename AttnWave<DH>::Raw r0, r1;
+  int base = w * WKEYS;
+  if (base < total) aw.issue(r0, base);
+  aw.load_q(head);
+  while (base < total) {
+    if (base + STEP < total) aw.issue(r1, base + STEP);
+    aw.step(r0, base);
+    base += STEP;
+    if (base >= total) break;
+    if (base + STEP < total) aw.issue(r0, base + STEP);
+    aw.step(r1, base);
+    base += STEP;
+  }
+#pragma unroll
+  for (int c = 0; c < CT; ++c) o_s[w][c][lane] = aw.O[c];
+  if (g == 0) { m_s[w][j] = aw.m_run; l_s[w][j] = aw.l_run; }
+  __syncthreads();
+  if (w >= CT || j >= a.M) return;                               // wavefront w finishes channel tile w
+  float mm = m_s[0][j];
+#pragma unroll
+  for (int ww = 1; ww < NWV; ++ww) mm = fmaxf(mm, m_s[ww][j]);
+  float ll = 0.f;
+  f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int ww = 0; ww < NWV; ++ww) {                             // fixed order: deterministic
+    const float f = expf(m_s[ww][j] - mm);
+    ll += l_s[ww][j] * f;
+    o += o_s[ww][w][lane] * f;
+  }
+  const float inv = 1.0f / ll;
+  const float out4[4] = {o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
+  xpack_store4(a.Xout, (a.nq * DH) >> 5, a.M, j, head * DH + w * 16 + 4 * g, out4);
+}
+
+constexpr int ATTN_HEAD_MAX_CTX = 256;    // positions up to which the whole-head kernel is used (one step per wavefront);
+                                          // beyond it the arithmetic of a head is worth spreading over several compute units
+
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s) {
   if (a.M < 1 || a.M > 16 || a.n_splits < 1 || a.counters == nullptr) return hipErrorInvalidValue;
+  if (a.pos0 + a.M <= ATTN_HEAD_MAX_CTX) {
+    if (a.dh == 128) hipLaunchKernelGGL(k_attn_head<128>, dim3(a.nq), dim3(512), 0, s, a);
+    else if (a.dh == 64) hipLaunchKernelGGL(k_attn_head<64>, dim3(a.nq), dim3(512), 0, s, a);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+  }
   const dim3 g1(a.nq, a.n_splits);
   if (a.dh == 128) hipLaunchKernelGGL(k_attn_partial<128>, g1, dim3(256), 0, s, a);
   else if (a.dh == 64) hipLaunchKernelGGL(k_attn_partial<64>, g1, dim3(256), 0, s, a);
