@@ -81,6 +81,72 @@ def cpu_baseline(target_shape, draft_shape, tw_host, dw_host, clf, gamma, tokens
     }
 
 
+def micro(B, W, dev, reps):
+    """Draft-step and verification-block micro-benchmarks: wall time per call (host enqueue to device
+    idle, `reps` calls back to back) and algorithmic bytes per call / time."""
+    def weight_bytes(s):
+        return sum(int(torch.tensor(sh).prod()) for n_, sh, kind in W.weight_specs(s)
+                   if kind == "matrix" and n_ not in ("tok_emb", "pos_emb")) * 2
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    out = {"micro": True, "reps": reps, "n_gpus": 1, "dtype": "bf16", "data": "synthetic", "hbm_peak_gbs": HBM_PEAK_GBS,
+           "draft_step": [], "verify_block": []}
+    ds = W.CFG1_DRAFT
+    gd = B.DiscoModel(ds, W.make_weights(ds, 0, "bf16"), dev)
+    clf = B.DiscoClf(W.make_classifier(100), dev)
+    steps_rec = B.struct_tensor(B.ClfOut, B.MAX_BLOCK, dev)
+    lo_d, lo_h = B.struct_tensor(B.LoopOut, 1, dev), B.struct_tensor(B.LoopOut, 1, pinned=True)
+    logits = torch.empty(ds.vocab, dtype=torch.float32, device=dev)
+    tok = W.make_tokens(3, 2, ds.vocab).to(dev)
+    for ctx in (512, 1024, 2048):
+        kv = B.DiscoKV(gd, ctx + 64, 16)
+        kv.fill(W.make_kv_fill(ds, ctx, 2).to(dev))
+        ws = gd.workspace(B.MAX_BLOCK, ctx + 64)
+
+        def loop10():
+            # ten draft steps, each followed by the feature / classifier kernel, no host round trip
+            B.disco_draft_loop(gd, kv, clf, tok, 1, 10, 10, 1.0, 0.5, None, logits, steps_rec, lo_d, lo_h, ws)
+            B.disco_kv_rollback(kv, ctx)
+
+        t = timed(loop10) / 10
+        nbytes = weight_bytes(ds) + ds.n_layers * 2 * ctx * ds.d_kv * 2 + ds.vocab * 4
+        out["draft_step"].append({"ctx": ctx, "us_per_step": 1e6 * t, "bytes": nbytes, "gbs": nbytes / t / 1e9,
+                                  "frac": nbytes / t / 1e9 / HBM_PEAK_GBS})
+        log(f"[bench] draft step ctx {ctx}: {1e6 * t:.1f} us, {nbytes / t / 1e9:.0f} GB/s")
+    del gd
+    ts = W.CFG2_TARGET
+    gt = B.DiscoModel(ts, W.make_weights(ts, 0, "bf16", device=dev), dev)
+    torch.cuda.empty_cache()
+    ctx = 1024
+    kv = B.DiscoKV(gt, ctx + 64, 16)
+    kv.fill(W.make_kv_fill(ts, ctx, 2, device=dev))
+    ws = gt.workspace(B.MAX_BLOCK, ctx + 64)
+    blk = W.make_tokens(3, B.MAX_BLOCK, ts.vocab).to(dev)
+    am = torch.zeros(B.MAX_BLOCK, dtype=torch.int32, device=dev)
+    acc = B.struct_tensor(B.AcceptOut, 1, dev)
+    for m in (1, 2, 4, 8, 11):
+        def verify():
+            B.disco_verify(gt, kv, blk, m, am, None, ws)
+            B.disco_accept(blk, am, m, acc)
+            B.disco_kv_rollback(kv, ctx)
+
+        t = timed(verify)
+        nbytes = weight_bytes(ts) + ts.n_layers * 2 * ctx * ts.d_kv * 2 + m * ts.n_layers * 2 * ts.d_kv * 2 + m * ts.vocab * 4
+        out["verify_block"].append({"m": m, "ctx": ctx, "ms": 1e3 * t, "bytes": nbytes, "gbs": nbytes / t / 1e9,
+                                    "frac": nbytes / t / 1e9 / HBM_PEAK_GBS})
+        log(f"[bench] verify block of {m} at ctx {ctx}: {1e3 * t:.3f} ms, {nbytes / t / 1e9:.0f} GB/s")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -97,6 +163,10 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the single timed run: static lookahead 1..sl-max and DISCO halting on the same "
                          "prompt and forcing, one JSON line with a row per policy")
+    ap.add_argument("--micro", action="store_true",
+                    help="instead of the loop: the draft-step micro-benchmark (68M-class shape, KV context 512 / 1024 / "
+                         "2048) and the verification-block micro-benchmark (13B-class shape, context 1024, blocks of "
+                         "1, 2, 4, 8, 11 tokens); one JSON line")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run plain device copies of known size and exit (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -120,6 +190,10 @@ def main():
     from paper_2405_04304_amd import binding as B
     from paper_2405_04304_amd.engine import SpecEngine
     from workloads import synth as W
+
+    if args.micro:
+        print(json.dumps(micro(B, W, dev, args.steps)), flush=True)
+        return
 
     target_shape = W.CFG2_TARGET if not args.layers else W.scaled_shape(W.CFG2_TARGET, n_layers=args.layers)
     draft_shape = W.CFG1_DRAFT

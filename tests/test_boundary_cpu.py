@@ -119,6 +119,43 @@ def test_forward_calls_reject_bad_arguments_before_any_launch():
     lib.disco_model_destroy(other)
 
 
+def test_sampling_and_loop_options_reject_bad_arguments_before_any_launch():
+    rc, m = _model()
+    lib = B.lib()
+    rc, kv, _ = _kv(m)
+    ws = lib.disco_workspace_bytes(m, 16, 48)
+    # disco_sample: temperature, vocabulary, stride, pointers
+    assert lib.disco_sample(FAKE, 1, 256, 256, 0.0, FAKE, None, FAKE, None) == B.EINVAL
+    assert lib.disco_sample(FAKE, 1, 256, 256, -1.0, FAKE, None, FAKE, None) == B.EINVAL
+    assert lib.disco_sample(FAKE, 1, 254, 256, 1.0, FAKE, None, FAKE, None) == B.EINVAL
+    assert lib.disco_sample(FAKE, 1, 256, 128, 1.0, FAKE, None, FAKE, None) == B.EINVAL
+    assert lib.disco_sample(FAKE, 0, 256, 256, 1.0, FAKE, None, FAKE, None) == B.EINVAL
+    assert lib.disco_sample(None, 1, 256, 256, 1.0, FAKE, None, FAKE, None) == B.EINVAL
+    assert lib.disco_sample(FAKE, 1, 256, 256, 1.0, None, None, FAKE, None) == B.EINVAL
+    assert lib.disco_sample(FAKE, 1, 70000, 70000, 1.0, FAKE, None, FAKE, None) == B.EINVAL
+    # disco_accept_sample: block length, missing draft rows for a block with draft tokens, temperature
+    assert lib.disco_accept_sample(FAKE, 0, None, FAKE, FAKE, 256, 1.0, FAKE, FAKE, FAKE, None, None) == B.ECAP
+    assert lib.disco_accept_sample(FAKE, 17, None, FAKE, FAKE, 256, 1.0, FAKE, FAKE, FAKE, None, None) == B.ECAP
+    assert lib.disco_accept_sample(FAKE, 3, None, None, FAKE, 256, 1.0, FAKE, FAKE, FAKE, None, None) == B.EINVAL
+    assert lib.disco_accept_sample(FAKE, 3, None, FAKE, FAKE, 256, 0.0, FAKE, FAKE, FAKE, None, None) == B.EINVAL
+    assert lib.disco_accept_sample(FAKE, 3, None, FAKE, FAKE, 256, 1.0, FAKE, None, FAKE, None, None) == B.EINVAL
+    assert lib.disco_accept_sample(FAKE, 3, None, FAKE, FAKE + 4, 256, 1.0, FAKE, FAKE, FAKE, None, None) == B.EINVAL
+    # sampled draft loop: needs uniforms, a positive temperature and a place for the probability rows
+    args_tail = (FAKE, FAKE, FAKE, None, FAKE, ws, None)
+    assert lib.disco_draft_loop_sampled(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, 1.0, None, FAKE, *args_tail) == B.EINVAL
+    assert lib.disco_draft_loop_sampled(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, 0.0, FAKE, FAKE, *args_tail) == B.EINVAL
+    assert lib.disco_draft_loop_sampled(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, 1.0, FAKE, None, *args_tail) == B.EINVAL
+    # options: sampling excludes forced and reference tokens; misaligned reference pointer
+    o = B.LoopOpts(None, FAKE, 1.0, FAKE, FAKE)
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.EINVAL
+    o = B.LoopOpts(None, FAKE + 2, 0.0, None, None)
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.EINVAL
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 16, 0, 1.0, 0.5, None, *args_tail) == B.ECAP
+    assert lib.disco_kv_len(kv) == 0
+    lib.disco_kv_destroy(kv)
+    lib.disco_model_destroy(m)
+
+
 def test_kv_capacity_is_enforced_on_the_host():
     rc, m = _model(family=0)
     lib = B.lib()
