@@ -981,14 +981,11 @@ struct ClfOut {  // mirrors disco_clf_out
 };
 
 constexpr int FEAT_NT = 1024;
-constexpr int FEAT_CAND = 1024;
 
 // One workgroup, the whole logit vector in registers (V4 float4 per thread, one round of 128-bit
 // loads).  Arg-max, soft-max sums and entropy are DPP wave reductions merged across the 16
-// wavefronts in a fixed order.  Top-10: every wavefront takes the 10th largest of its lanes' maxima
-// (ten DPP arg-max rounds, no rescans); the largest of those 16 values is a lower bound of the 10th
-// largest logit, the few logits at or above it are collected in LDS, and one wavefront picks the ten
-// largest of them.
+// wavefronts in a fixed order.  Top-10: every wavefront finds the ten largest of the values its
+// lanes hold by ten cross-lane arg-max rounds, and one wavefront picks the ten largest of those 160.
 template <int V4>
 __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
   ClfOut* out = reinterpret_cast<ClfOut*>(a.out);
@@ -998,8 +995,7 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
   }
   __shared__ float sv[FEAT_NT / 64 + 1];
   __shared__ int si[FEAT_NT / 64 + 1];
-  __shared__ float cand[FEAT_CAND];
-  __shared__ int n_cand;
+  __shared__ float wtop[FEAT_NT / 64][10];
   __shared__ float top_s[10];
   __shared__ float feat_s[12];
   const int t = threadIdx.x, V = a.vocab, lane = t & 63, wv = t >> 6;
@@ -1018,7 +1014,6 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
       r[i].w = -INFINITY;
     }
   }
-  if (t == 0) n_cand = 0;
 
   // maximum and arg-max (lowest index on ties); `mine` is this thread's own maximum
   VI mine; mine.v = -INFINITY; mine.i = 0x7fffffff;
@@ -1062,72 +1057,47 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
   S = block_sum<FEAT_NT>(S, sv);
   T = block_sum<FEAT_NT>(T, sv);
 
-  // lower bound of the 10th largest logit
+  // ten largest logits: every wavefront's ten by cross-lane arg-max rounds over the values its lanes
+  // hold (the winning lane drops the value it gave; the row is not needed afterwards), then
+  // wavefront 0 picks from the 160 candidates
   {
-    VI cur; cur.v = mine.v; cur.i = lane;
-    float bound_w = -INFINITY;
 #pragma unroll 1
     for (int rnd = 0; rnd < 10; ++rnd) {
-      const VI b = wave_argmax(cur);
-      bound_w = b.v;
-      if (b.i == lane) cur.v = -INFINITY;
-    }
-    __syncthreads();
-    if (lane == 0) sv[wv] = bound_w;
-    __syncthreads();
-  }
-  float bound = sv[0];
+      VI cur; cur.v = -INFINITY; cur.i = lane;
 #pragma unroll
-  for (int i = 1; i < FEAT_NT / 64; ++i) bound = fmaxf(bound, sv[i]);
+      for (int i = 0; i < V4; ++i) cur.v = fmaxf(cur.v, fmaxf(fmaxf(r[i].x, r[i].y), fmaxf(r[i].z, r[i].w)));
+      const VI wn = wave_argmax(cur);
+      if (lane == 0) wtop[wv][rnd] = wn.v;
+      if (wn.i == lane) {
+        bool done = false;
 #pragma unroll
-  for (int i = 0; i < V4; ++i) {
-    const float vals[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      if (vals[e] >= bound && vals[e] > -INFINITY) {
-        const int slot = atomicAdd(&n_cand, 1);
-        if (slot < FEAT_CAND) cand[slot] = vals[e];
-      }
-    }
-  }
-  __syncthreads();
-  const int nc = n_cand;
-  if (nc <= 64) {
-    if (wv == 0) {
-      VI cur; cur.v = (lane < nc) ? cand[lane] : -INFINITY; cur.i = lane;
-#pragma unroll 1
-      for (int rnd = 0; rnd < 10; ++rnd) {
-        const VI b = wave_argmax(cur);
-        if (lane == 0) top_s[rnd] = b.v;
-        if (b.i == lane) cur.v = -INFINITY;
-      }
-    }
-  } else if (nc <= FEAT_CAND) {
-    VI cur; cur.v = (t < nc) ? cand[t] : -INFINITY; cur.i = t;
-    for (int rnd = 0; rnd < 10; ++rnd) {
-      const VI b = block_argmax<FEAT_NT>(cur, sv, si);
-      if (t == 0) top_s[rnd] = b.v;
-      if (b.i == t) cur.v = -INFINITY;
-    }
-  } else {
-    // more candidates than the list holds (massive ties): ten full selection rounds, each taking
-    // the largest element that comes after the previous pick in (value desc, index asc) order
-    VI prev; prev.v = INFINITY; prev.i = -1;
-    for (int rnd = 0; rnd < 10; ++rnd) {
-      VI c; c.v = -INFINITY; c.i = 0x7fffffff;
-#pragma unroll
-      for (int i = 0; i < V4; ++i) {
-        const int idx = (i * FEAT_NT + t) * 4;
-        const float vals[4] = {r[i].x, r[i].y, r[i].z, r[i].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const float v = vals[e];
-          const bool after = (v < prev.v) || (v == prev.v && idx + e > prev.i);
-          if (after && idx + e < V) { VI y; y.v = v; y.i = idx + e; c = vi_best(c, y); }
+        for (int i = 0; i < V4; ++i) {
+          if (!done && r[i].x == wn.v) { r[i].x = -INFINITY; done = true; }
+          if (!done && r[i].y == wn.v) { r[i].y = -INFINITY; done = true; }
+          if (!done && r[i].z == wn.v) { r[i].z = -INFINITY; done = true; }
+          if (!done && r[i].w == wn.v) { r[i].w = -INFINITY; done = true; }
         }
       }
-      prev = block_argmax<FEAT_NT>(c, sv, si);
-      if (t == 0) top_s[rnd] = prev.v;
+    }
+    __syncthreads();
+    if (wv == 0) {
+      float c3[3];
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        const int ci = lane + 64 * k;
+        c3[k] = ci < (FEAT_NT / 64) * 10 ? wtop[ci / 10][ci % 10] : -INFINITY;
+      }
+#pragma unroll 1
+      for (int rnd = 0; rnd < 10; ++rnd) {
+        VI cur; cur.v = fmaxf(fmaxf(c3[0], c3[1]), c3[2]); cur.i = lane;
+        const VI wn = wave_argmax(cur);
+        if (lane == 0) top_s[rnd] = wn.v;
+        if (wn.i == lane) {
+          bool done = false;
+#pragma unroll
+          for (int k = 0; k < 3; ++k) if (!done && c3[k] == wn.v) { c3[k] = -INFINITY; done = true; }
+        }
+      }
     }
   }
   __syncthreads();
