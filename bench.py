@@ -160,6 +160,9 @@ def main():
     ap.add_argument("--prompt-len", type=int, default=512)
     ap.add_argument("--layers", type=int, default=0, help="debug: truncate the target (invalidates the number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="> 0: sampled draft tokens and speculative-sampling acceptance at this temperature "
+                         "(no forced agreement); 0: the greedy workload")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the single timed run: static lookahead 1..sl-max and DISCO halting on the same "
                          "prompt and forcing, one JSON line with a row per policy")
@@ -294,8 +297,13 @@ def main():
     gc.collect()
     gc.disable()                              # no collector pauses inside the timed iterations
     stamps.append(time.perf_counter())
-    res = eng.generate(prompt, max_new, policy, force=force, do_prefill=False, on_iteration=on_iter,
-                       max_iterations=n_iter)
+    if args.temperature > 0:
+        uni = {k: W.make_uniforms(21, max_new + 16, k) for k in ("draft", "accept", "resample")}
+        res = eng.generate_sampling(prompt, max_new, policy, args.temperature, uni, do_prefill=False,
+                                    on_iteration=on_iter, max_iterations=n_iter)
+    else:
+        res = eng.generate(prompt, max_new, policy, force=force, do_prefill=False, on_iteration=on_iter,
+                           max_iterations=n_iter)
     torch.cuda.synchronize()
     gc.enable()
     B.disco_probe_enable(-1)
@@ -326,7 +334,9 @@ def main():
         "config": {
             "workload": ("full DISCO loop, 13B-class target (40 layers, d 5120, 40x128 heads, SwiGLU 13824, vocab 32000) "
                          "+ 68M-class draft (2 layers, d 768), bf16 weights and KV, batch 1, "
-                         f"{args.prompt_len}-token random prompt, greedy, forced acceptance {args.alpha}"),
+                         f"{args.prompt_len}-token random prompt, "
+                         + (f"greedy, forced acceptance {args.alpha}" if args.temperature <= 0 else
+                            f"sampling at temperature {args.temperature} (speculative-sampling acceptance, caller-supplied uniforms)")),
             "policy": policy, "target_layers": target_shape.n_layers,
             "tokens_counted": "accepted draft tokens + the target's token of each iteration",
         },

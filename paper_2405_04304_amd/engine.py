@@ -164,7 +164,8 @@ class SpecEngine:
                 "sl_hist": dict(sorted(hist.items()))}
 
     def generate_sampling(self, prompt: Sequence[int], max_new: int, policy: Dict, temperature: float,
-                          uniforms: Dict, do_prefill: bool = True) -> Dict:
+                          uniforms: Dict, do_prefill: bool = True, on_iteration=None,
+                          max_iterations: Optional[int] = None) -> Dict:
         """The loop at temperature > 0: sampled draft tokens, speculative-sampling acceptance.
         uniforms: {"draft", "accept", "resample"}: float32 tensors indexed by generated position (at
         least max_new + cap entries); they are copied to the device once."""
@@ -186,6 +187,8 @@ class SpecEngine:
         iters: List[Dict] = []
         loop_block_ptr = self.loop_dev.data_ptr() + 4
         while len(seq) - n_prompt < max_new:
+            if max_iterations is not None and len(iters) >= max_iterations:
+                break
             emitted = len(seq) - n_prompt
             remaining = max_new - emitted
             cap = min(cap_policy, remaining - 1)
@@ -224,6 +227,8 @@ class SpecEngine:
             if self.draft is not None and self.kv_d.len > ctx_t + n + 1:
                 B.disco_kv_rollback(self.kv_d, ctx_t + n + 1)
             iters.append({"sl": sl, "n": n, "block": block, "emit": emit, "ctx": ctx_t})
+            if on_iteration is not None:
+                on_iteration(iters[-1])
         hist: Dict[int, int] = {}
         for it in iters:
             hist[it["sl"]] = hist.get(it["sl"], 0) + 1
