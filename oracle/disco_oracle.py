@@ -21,6 +21,9 @@ Written from the paper (arXiv 2405.04304):
     with probability min(1, p(x) / q(x)) (p = target distribution at that position); at the first
     rejection a token is drawn from norm(max(0, p - q)); if every draft token is kept, a bonus
     token is drawn from the target's next distribution.
+  * Sec. 4 "SL classifier training" and App. D.1: the classifier is trained with a cross-entropy
+    loss on (features, accepted / rejected) pairs from a labelling run in which the draft predicts one
+    token from the prompt plus the target's own continuation; its quality is reported as F1.
 The two transformer families are not the paper's subject (it uses published checkpoints as black
 boxes); their definitions below are the standard pre-norm decoder equations.
 
@@ -35,6 +38,11 @@ Readings of points the paper leaves open (all listed with reasons in the design 
   distribution by inverting its cumulative sum in vocabulary order at u * total, u uniform in
   [0, 1) and supplied by the caller (so oracle and GPU consume the same random numbers); the
   classifier's features stay those of the temperature-1 softmax of the raw draft logits.
+  Training (the paper names only the loss): mean binary cross-entropy on the boolean labels,
+  features standardised per component (mean, standard deviation of the training set), full-batch
+  gradient descent with a fixed step for a fixed number of epochs from given initial parameters;
+  the standardisation is folded into W1 and b1 afterwards, so the classifier keeps consuming raw
+  features.  "Accepted" is predicted when C >= tau (the loop's continue condition).
 
 Parity pins: every function here is pinned by tests/test_oracle_*.py (closed forms, library
 routines, invariants, brute force); none is "parity unpinned".
@@ -321,6 +329,84 @@ def accept_stochastic(block: Sequence[int], q_rows: Sequence[torch.Tensor], p_ro
     else:
         last, smargin = sample_index(p_rows[sl], float(u_resample[n]))
     return n, [int(t) for t in block[1:n + 1]] + [last], {"accept_margins": acc_margins, "sample_margin": smargin}
+
+
+# --------------------------------------------------------------------------------------------
+# classifier training (Sec. 4 "SL classifier training", App. D.1)
+# --------------------------------------------------------------------------------------------
+
+def label_run(draft: Model, prompt: Sequence[int], reference: Sequence[int], force: Optional[Dict] = None,
+              prefill_chunk: int = 64) -> Dict:
+    """App. D.1: at every generated position the draft predicts ONE token from the prompt plus the
+    target's own continuation (`reference`, the target's greedy text); the pair (Eq. 2 features of
+    that prediction, draft token == target token) is one training example.  Position feature: 1 for
+    the first generated token.  force: as in spec_decode."""
+    kv = draft.new_cache(len(prompt) + len(reference) + 1)
+    draft.prefill(list(prompt[:-1]), kv, prefill_chunk)
+    feats, labels, margins = [], [], []
+    last = int(prompt[-1])
+    for p, ref_tok in enumerate(reference):
+        logits = draft.forward([last], kv)[0].clone()
+        if force is not None and bool(force["mask"][p]):
+            logits[int(force["tokens"][p])] = logits.max() + 4.0
+        ft = features(logits, p + 1)
+        feats.append(ft["feats"])
+        labels.append(int(ft["token"] == int(ref_tok)))
+        margins.append(ft["margin"])
+        last = int(ref_tok)
+    return {"feats": torch.stack(feats), "labels": torch.tensor(labels, dtype=torch.int32), "margins": margins}
+
+
+def _bce_with_logits(z: torch.Tensor, y: torch.Tensor) -> torch.Tensor:
+    """-(y ln C + (1 - y) ln (1 - C)) with C = sigmoid(z), in the overflow-free form."""
+    return torch.clamp(z, min=0.0) - z * y + torch.log1p(torch.exp(-z.abs()))
+
+
+def clf_train(feats: torch.Tensor, labels: torch.Tensor, init: Dict[str, torch.Tensor], epochs: int, lr: float):
+    """Train C = sigmoid(w2 . relu(W1 f + b1) + b2) on (features [N, 12], labels [N] in {0, 1}).
+
+    Features are standardised, s = (f - mean) / max(std, 1e-6) (population standard deviation of the
+    training set); the loss is the mean binary cross-entropy; every epoch takes one full-batch
+    gradient step of size lr starting from `init` (read as parameters in the standardised space).
+    Returns the parameters folded back to raw features, W1' = W1 / std, b1' = b1 - W1 (mean / std),
+    and the loss before each step."""
+    f = feats.to(F64)
+    y = labels.to(F64)
+    n = f.shape[0]
+    mu = f.mean(dim=0)
+    sd = torch.sqrt(((f - mu) ** 2).mean(dim=0)).clamp(min=1e-6)
+    s = (f - mu) / sd
+    W1, b1 = init["W1"].to(F64).clone(), init["b1"].to(F64).clone()
+    w2, b2 = init["w2"].to(F64).clone(), init["b2"].to(F64).clone()
+    losses = []
+    for _ in range(epochs):
+        a = s @ W1.T + b1                        # [N, hidden]
+        act = torch.relu(a)
+        z = act @ w2 + b2[0]
+        losses.append(float(_bce_with_logits(z, y).mean()))
+        dz = (torch.sigmoid(z) - y) / n          # d loss / d z
+        g_w2 = act.T @ dz
+        g_b2 = dz.sum()
+        da = (dz[:, None] * w2[None, :]) * (a > 0).to(F64)
+        g_W1 = da.T @ s
+        g_b1 = da.sum(dim=0)
+        W1 -= lr * g_W1; b1 -= lr * g_b1; w2 -= lr * g_w2; b2 -= lr * g_b2
+    folded = {"W1": (W1 / sd).to(torch.float32), "b1": (b1 - (W1 * (mu / sd)).sum(dim=1)).to(torch.float32),
+              "w2": w2.to(torch.float32), "b2": b2.to(torch.float32)}
+    return folded, losses
+
+
+def clf_eval(feats: torch.Tensor, labels: torch.Tensor, clf: Dict[str, torch.Tensor], tau: float) -> Dict:
+    """Scores, confusion counts and F1 of the prediction "accepted iff C >= tau" (App. D.2)."""
+    scores = [classifier(feats[i], clf) for i in range(feats.shape[0])]
+    pred = [int(c >= tau) for c in scores]
+    y = [int(v) for v in labels]
+    tp = sum(1 for p_, t in zip(pred, y) if p_ and t)
+    fp = sum(1 for p_, t in zip(pred, y) if p_ and not t)
+    fn = sum(1 for p_, t in zip(pred, y) if not p_ and t)
+    tn = len(y) - tp - fp - fn
+    f1 = 2 * tp / (2 * tp + fp + fn) if (2 * tp + fp + fn) else 0.0
+    return {"scores": scores, "tp": tp, "fp": fp, "fn": fn, "tn": tn, "f1": f1}
 
 
 # --------------------------------------------------------------------------------------------
