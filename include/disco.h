@@ -291,6 +291,26 @@ int disco_draft_loop_sampled(const disco_model* draft, disco_kv* kv, const disco
                              disco_loop_out* dev_out, disco_loop_out* host_out, void* dev_ws,
                              size_t ws_bytes, disco_stream s);
 
+/* ---- classifier training and evaluation (Sec. 4 "SL classifier training", App. D.1 / D.2) ----- */
+/* The paper trains the shallow FFN of Eq. 2 with a cross-entropy loss on (features, accepted /
+ * rejected) pairs from a labelling run and reports F1; it names no optimiser.  Here: features are
+ * standardised per component over the training set, the loss is the mean binary cross-entropy, and
+ * `epochs` full-batch gradient steps of size lr are taken from the initial parameters.
+ * dev_feats: [n x 12] fp32 (records of disco_classify, position feature included); dev_labels: [n]
+ * int32 in {0, 1}; n <= DISCO_TRAIN_MAX_N.  dev_params: layout of disco_clf.dev_params; on entry the
+ * initial parameters (read in the standardised feature space), on return the trained parameters with
+ * the standardisation folded into W1 and b1, so that they apply to raw features.  dev_loss (may be
+ * NULL): [epochs], the mean loss before each step.  One workgroup; results are reproducible.          */
+#define DISCO_TRAIN_MAX_N 2560
+int disco_clf_train(const float* dev_feats, const int32_t* dev_labels, int n, int hidden, int epochs,
+                    float lr, float* dev_params, float* dev_loss, disco_stream s);
+
+/* Scores C of n feature vectors and, if dev_labels and dev_counts are given, the confusion counts of
+ * "accepted iff C >= tau" added to dev_counts[4] = {true pos., false pos., false neg., true neg.}
+ * (the caller zeroes them; F1 = 2 TP / (2 TP + FP + FN)).  dev_scores may be NULL.                    */
+int disco_clf_eval(const disco_clf* clf, const float* dev_feats, const int32_t* dev_labels, int n,
+                   float tau, float* dev_scores, int32_t* dev_counts, disco_stream s);
+
 /* ---- measurement probe ------------------------------------------------------------------------- */
 
 /* Brackets, with two HIP events on the launch stream, the MLP-input GEMM (gate/up + SwiGLU, or

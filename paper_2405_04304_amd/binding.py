@@ -103,6 +103,10 @@ _SIGNATURES = {
     "disco_draft_loop_ex": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(Clf), C.c_void_p, C.c_int, C.c_int,
                                       C.c_int, C.c_float, C.c_float, C.POINTER(LoopOpts), C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "disco_clf_train": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float, C.c_void_p,
+                                  C.c_void_p, C.c_void_p]),
+    "disco_clf_eval": (C.c_int, [C.POINTER(Clf), C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p,
+                                 C.c_void_p, C.c_void_p]),
     "disco_probe_enable": (C.c_int, [C.c_int]),
     "disco_probe_read_ms": (C.c_float, []),
 }
@@ -233,6 +237,19 @@ def disco_draft_loop_sampled(model, kv, clf, tokens_in, n_in, cap, static_sl, po
                                           _ptr(u_draft), _ptr(draft_probs), _ptr(logits), _ptr(steps), _ptr(out),
                                           _ptr(host_out), _ptr(ws.buf), ws.nbytes,
                                           _stream() if stream is None else stream))
+
+
+TRAIN_MAX_N = 2560
+
+
+def disco_clf_train(feats, labels, n, hidden, epochs, lr, params, loss=None, stream=None):
+    _check(lib().disco_clf_train(_ptr(feats), _ptr(labels), n, hidden, epochs, lr, _ptr(params), _ptr(loss),
+                                 _stream() if stream is None else stream))
+
+
+def disco_clf_eval(clf, feats, labels, n, tau, scores=None, counts=None, stream=None):
+    _check(lib().disco_clf_eval(C.byref(clf.c), _ptr(feats), _ptr(labels), n, tau, _ptr(scores), _ptr(counts),
+                                _stream() if stream is None else stream))
 
 
 def disco_probe_enable(layer: int) -> None:
@@ -383,7 +400,14 @@ class DiscoClf:
         flat = torch.cat([params["W1"].reshape(-1), params["b1"].reshape(-1), params["w2"].reshape(-1),
                           params["b2"].reshape(-1)]).to(torch.float32)
         self.dev = flat.to(device).contiguous()
-        self.c = Clf(self.dev.data_ptr(), params["W1"].shape[0])
+        self.hidden = params["W1"].shape[0]
+        self.c = Clf(self.dev.data_ptr(), self.hidden)
+
+    def params(self) -> Dict[str, torch.Tensor]:
+        """The parameter vector back as host tensors W1, b1, w2, b2."""
+        h, v = self.hidden, self.dev.cpu()
+        return {"W1": v[:12 * h].view(h, 12).clone(), "b1": v[12 * h:13 * h].clone(), "w2": v[13 * h:14 * h].clone(),
+                "b2": v[14 * h:14 * h + 1].clone()}
 
 
 def struct_tensor(ctype, n: int = 1, device="cuda", pinned: bool = False) -> torch.Tensor:

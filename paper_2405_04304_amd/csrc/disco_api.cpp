@@ -553,6 +553,35 @@ int disco_accept_sample(const int32_t* dev_block, int n_block, const int32_t* de
   return DISCO_OK;
 }
 
+int disco_clf_train(const float* dev_feats, const int32_t* dev_labels, int n, int hidden, int epochs, float lr,
+                    float* dev_params, float* dev_loss, disco_stream s) {
+  if (!dev_feats || !dev_labels || !dev_params) return fail(DISCO_EINVAL, "null argument");
+  if (n < 1 || n > DISCO_TRAIN_MAX_N) return fail(DISCO_ECAP, "%d training samples outside [1, %d]", n, DISCO_TRAIN_MAX_N);
+  if (hidden < 1 || hidden > DISCO_CLF_HIDDEN_MAX) return fail(DISCO_EINVAL, "classifier hidden size %d outside [1, %d]", hidden, DISCO_CLF_HIDDEN_MAX);
+  if (epochs < 0 || !(lr > 0.f)) return fail(DISCO_EINVAL, "epochs must be >= 0 and the step positive");
+  if (!aligned(dev_feats, 4) || !aligned(dev_labels, 4) || !aligned(dev_params, 4) || !aligned(dev_loss, 4)) return fail(DISCO_EINVAL, "misaligned pointer");
+  TrainArgs a{};
+  a.feats = dev_feats; a.labels = dev_labels; a.n = n; a.hidden = hidden; a.epochs = epochs; a.lr = lr; a.params = dev_params;
+  a.loss = dev_loss;
+  HIP_TRY(launch_clf_train(a, static_cast<hipStream_t>(s)), "train launch");
+  return DISCO_OK;
+}
+
+int disco_clf_eval(const disco_clf* clf, const float* dev_feats, const int32_t* dev_labels, int n, float tau,
+                   float* dev_scores, int32_t* dev_counts, disco_stream s) {
+  if (!clf || !clf->dev_params || !dev_feats) return fail(DISCO_EINVAL, "null argument");
+  if (clf->hidden < 1 || clf->hidden > DISCO_CLF_HIDDEN_MAX) return fail(DISCO_EINVAL, "classifier hidden size %d outside [1, %d]", clf->hidden, DISCO_CLF_HIDDEN_MAX);
+  if (n < 1) return fail(DISCO_EINVAL, "n must be positive");
+  if ((dev_counts != nullptr) != (dev_labels != nullptr)) return fail(DISCO_EINVAL, "labels and counts go together");
+  if (!aligned(dev_feats, 4) || !aligned(dev_labels, 4) || !aligned(dev_scores, 4) || !aligned(dev_counts, 4) || !aligned(clf->dev_params, 4))
+    return fail(DISCO_EINVAL, "misaligned pointer");
+  EvalArgs a{};
+  a.feats = dev_feats; a.labels = dev_labels; a.n = n; a.params = clf->dev_params; a.hidden = clf->hidden; a.tau = tau;
+  a.scores = dev_scores; a.counts = dev_counts;
+  HIP_TRY(launch_clf_eval(a, static_cast<hipStream_t>(s)), "eval launch");
+  return DISCO_OK;
+}
+
 int disco_probe_enable(int layer) {
   g_probe_taken = false;
   if (layer < 0) { g_probe_layer = -1; return DISCO_OK; }

@@ -94,6 +94,17 @@ struct AcceptSampleArgs {
   void* out; void* host_out;         // disco_accept_out
 };
 
+struct TrainArgs {
+  const float* feats; const int32_t* labels; int n; int hidden; int epochs; float lr;
+  float* params;                     // in: initial (standardised space), out: trained, folded to raw features
+  float* loss;                       // optional [epochs]: mean loss before each step
+};
+
+struct EvalArgs {
+  const float* feats; const int32_t* labels; int n; const float* params; int hidden; float tau;
+  float* scores; int* counts;
+};
+
 constexpr size_t CLASSIFY_SCRATCH_BYTES = 256 + 64 * 16 * sizeof(float);
 
 hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int64_t tile_mul,
@@ -105,6 +116,8 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s);
 hipError_t launch_sample_rows(const SampleArgs& a, int n_rows, hipStream_t s);
 hipError_t launch_accept_sample(const AcceptSampleArgs& a, hipStream_t s);
+hipError_t launch_clf_train(const TrainArgs& a, hipStream_t s);
+hipError_t launch_clf_eval(const EvalArgs& a, hipStream_t s);
 hipError_t launch_argmax_rows(const float* logits, int M, int vocab, int32_t* out, hipStream_t s);
 hipError_t launch_accept(const int32_t* block, const int32_t* argmax, int n_block,
                          const int32_t* dev_n_block, void* dev_out, void* host_out, hipStream_t s);

@@ -1664,6 +1664,127 @@ hipError_t launch_accept_sample(const AcceptSampleArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// classifier training and evaluation (the step after the loop: features and labels in, parameters out)
+// ---------------------------------------------------------------------------------------------
+//
+// One workgroup; thread h owns hidden unit h (its row of W1, b1[h], w2[h]) and its gradients, so the
+// only cross-thread quantity is the pre-sigmoid output z of a sample (a workgroup sum per sample).
+// The standardised training set sits in LDS for the whole run.  Full-batch gradient descent on the
+// mean binary cross-entropy; all arithmetic fp32 except the feature statistics (double).
+
+constexpr int TRAIN_MAX_N = 2560;               // samples that fit in LDS (12 floats each)
+
+__global__ __launch_bounds__(256) void k_clf_train(TrainArgs a) {
+  __shared__ float fs[TRAIN_MAX_N * 12];
+  __shared__ float mu_s[12], isd_s[12];
+  __shared__ float zpart[4];
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6, nw = blockDim.x >> 6;
+  const int N = a.n, H = a.hidden;
+  if (t < 12) {
+    double sum = 0.0;
+    for (int n = 0; n < N; ++n) sum += (double)a.feats[(size_t)n * 12 + t];
+    const double mu = sum / N;
+    double var = 0.0;
+    for (int n = 0; n < N; ++n) { const double d = (double)a.feats[(size_t)n * 12 + t] - mu; var += d * d; }
+    double sd = sqrt(var / N);
+    if (sd < 1e-6) sd = 1e-6;
+    mu_s[t] = (float)mu; isd_s[t] = (float)(1.0 / sd);
+  }
+  __syncthreads();
+  for (int i = t; i < N * 12; i += blockDim.x) fs[i] = (a.feats[i] - mu_s[i % 12]) * isd_s[i % 12];
+  const bool live = t < H;
+  float w1[12], b1 = 0.f, w2 = 0.f, b2 = a.params[H * 14];
+#pragma unroll
+  for (int i = 0; i < 12; ++i) w1[i] = live ? a.params[t * 12 + i] : 0.f;
+  if (live) { b1 = a.params[H * 12 + t]; w2 = a.params[H * 13 + t]; }
+  __syncthreads();
+  const float inv_n = 1.0f / (float)N;
+  for (int ep = 0; ep < a.epochs; ++ep) {
+    float gw1[12], gb1 = 0.f, gw2 = 0.f, gb2 = 0.f, loss = 0.f;
+#pragma unroll
+    for (int i = 0; i < 12; ++i) gw1[i] = 0.f;
+    for (int n = 0; n < N; ++n) {
+      const float* f = fs + n * 12;
+      float pre = b1;
+#pragma unroll
+      for (int i = 0; i < 12; ++i) pre += w1[i] * f[i];
+      const float act = live ? fmaxf(pre, 0.f) : 0.f;
+      float z = wave_sum(w2 * act);
+      if (nw > 1) {
+        if (lane == 0) zpart[wv] = z;
+        __syncthreads();
+        z = zpart[0];
+        for (int ww = 1; ww < nw; ++ww) z += zpart[ww];
+        __syncthreads();
+      }
+      z += b2;
+      const float y = (float)a.labels[n];
+      loss += fmaxf(z, 0.f) - z * y + log1pf(expf(-fabsf(z)));
+      const float dz = (1.0f / (1.0f + expf(-z)) - y) * inv_n;
+      gw2 += dz * act;
+      gb2 += dz;
+      const float da = pre > 0.f ? dz * w2 : 0.f;
+      gb1 += da;
+#pragma unroll
+      for (int i = 0; i < 12; ++i) gw1[i] += da * f[i];
+    }
+    if (t == 0 && a.loss) a.loss[ep] = loss * inv_n;
+#pragma unroll
+    for (int i = 0; i < 12; ++i) w1[i] -= a.lr * gw1[i];
+    b1 -= a.lr * gb1; w2 -= a.lr * gw2; b2 -= a.lr * gb2;
+  }
+  // fold the standardisation into W1 and b1: the classifier consumes raw features
+  if (live) {
+    float shift = 0.f;
+#pragma unroll
+    for (int i = 0; i < 12; ++i) {
+      const float wf = w1[i] * isd_s[i];
+      a.params[t * 12 + i] = wf;
+      shift += wf * mu_s[i];
+    }
+    a.params[H * 12 + t] = b1 - shift;
+    a.params[H * 13 + t] = w2;
+  }
+  if (t == 0) a.params[H * 14] = b2;
+}
+
+hipError_t launch_clf_train(const TrainArgs& a, hipStream_t s) {
+  if (a.n < 1 || a.n > TRAIN_MAX_N || a.hidden < 1 || a.hidden > 256 || a.epochs < 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_clf_train, dim3(1), dim3(((a.hidden + 63) / 64) * 64), 0, s, a);
+  return hipGetLastError();
+}
+
+// Scores of given feature vectors and the confusion counts of "accepted iff C >= tau" against the
+// labels: counts[0..3] = true positives, false positives, false negatives, true negatives.
+__global__ __launch_bounds__(256) void k_clf_eval(EvalArgs a) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= a.n) return;
+  const int H = a.hidden;
+  float f[12];
+#pragma unroll
+  for (int i = 0; i < 12; ++i) f[i] = a.feats[(size_t)n * 12 + i];
+  float z = 0.f;
+  for (int h = 0; h < H; ++h) {                    // fixed order
+    float pre = a.params[H * 12 + h];
+#pragma unroll
+    for (int i = 0; i < 12; ++i) pre += a.params[h * 12 + i] * f[i];
+    z += fmaxf(pre, 0.f) * a.params[H * 13 + h];
+  }
+  const float c = 1.0f / (1.0f + expf(-(z + a.params[H * 14])));
+  if (a.scores) a.scores[n] = c;
+  if (a.counts && a.labels) {
+    const int pred = c >= a.tau ? 1 : 0, y = a.labels[n] != 0 ? 1 : 0;
+    atomicAdd(a.counts + (pred ? (y ? 0 : 1) : (y ? 2 : 3)), 1);
+  }
+}
+
+hipError_t launch_clf_eval(const EvalArgs& a, hipStream_t s) {
+  if (a.n < 1 || a.hidden < 1 || a.hidden > 256) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_clf_eval, dim3((a.n + 255) / 256), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 struct LoopOut { int32_t sl; int32_t block[16]; };
 
 __global__ void k_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in, LoopOut* out) {

@@ -72,7 +72,39 @@ class SpecEngine:
             out.append(last)
         return out
 
-    # -- the loop --------------------------------------------------------------------------------
+    # -- labelling run and classifier training (App. D.1, Sec. 4) ---------------------------------
+    def label_run(self, prompt: Sequence[int], reference: Sequence[int], force: Optional[Dict] = None):
+        """At every generated position the draft predicts one token from the prompt plus the target's
+        own continuation `reference`.  Returns device tensors: features [N, 12] (as disco_classify
+        records them, position feature 1, 2, ...), labels [N] int32 (draft token == reference token),
+        and the draft tokens."""
+        n = len(reference)
+        self.reset()
+        self.prefill(prompt[:-1])
+        fed = torch.as_tensor([int(prompt[-1])] + [int(t) for t in reference[:-1]], dtype=torch.int32).to(self.dev)
+        ref_dev = torch.as_tensor([int(t) for t in reference], dtype=torch.int32).to(self.dev)
+        force_dev = None
+        if force is not None:
+            force_dev = torch.where(torch.as_tensor(force["mask"][:n]),
+                                    torch.as_tensor(force["tokens"][:n], dtype=torch.int32),
+                                    torch.full((n,), -1, dtype=torch.int32)).to(torch.int32).to(self.dev)
+        rec = B.struct_tensor(B.ClfOut, n, self.dev)
+        sz = C.sizeof(B.ClfOut)
+        scratch = B.classify_scratch(self.dev)
+        for p in range(n):
+            B.disco_draft_step(self.draft, self.kv_d, fed.data_ptr() + 4 * p, 1, self.logits_d, self.ws_d)
+            B.disco_classify(self.clf, self.logits_d, self.draft.shape.vocab, float(p + 1), 0.0, 0,
+                             rec.data_ptr() + sz * p,
+                             force_token=(force_dev.data_ptr() + 4 * p) if force_dev is not None else None,
+                             scratch=scratch)
+        torch.cuda.synchronize(self.dev)
+        words = rec.view(torch.int32).view(n, sz // 4)
+        tokens = words[:, 0].contiguous()
+        feats = words[:, 1:13].contiguous().view(torch.float32)
+        labels = (tokens == ref_dev).to(torch.int32)
+        return feats, labels, tokens
+
+
     def generate(self, prompt: Sequence[int], max_new: int, policy: Dict, force: Optional[Dict] = None,
                  trace: bool = False, do_prefill: bool = True, on_iteration=None,
                  max_iterations: Optional[int] = None) -> Dict:
