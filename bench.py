@@ -246,6 +246,23 @@ def main():
         pols = [{"mode": "static", "gamma": g} for g in range(1, args.sl_max + 1)] + [policy]
         # upper bound (Sec. 3, oracle SL): draft until the first token that leaves the target's known text
         pols.append({"mode": "oracle", "reference": greedy, "sl_max": 15})
+        # DISCO with a TRAINED classifier (Sec. 4, App. D.1): labelling run on another prompt with the same
+        # forcing recipe, training on the GPU, F1 on this prompt's labelling run
+        n_lab = min(n_greedy, 200)
+        prompt2 = W.make_prompt(2, args.prompt_len, target_shape.vocab).tolist()
+        greedy2 = eng.greedy(prompt2, n_lab)
+        mask2 = W.make_force_mask(6, n_lab, args.alpha)
+        f_tr, y_tr, _ = eng.label_run(prompt2, greedy2, {"mask": mask2, "tokens": greedy2})
+        clf_plain, clf_trained = eng.clf, B.DiscoClf(clf, dev)
+        B.disco_clf_train(f_tr, y_tr, n_lab, clf_trained.hidden, 400, 0.5, clf_trained.dev, None)
+        f_va, y_va, _ = eng.label_run(prompt, greedy[:n_lab], {"mask": mask[:n_lab], "tokens": greedy})
+        counts = torch.zeros(4, dtype=torch.int32, device=dev)
+        B.disco_clf_eval(clf_trained, f_va, y_va, n_lab, args.tau, None, counts)
+        tp, fp, fn, tn = counts.cpu().tolist()
+        f1 = 2 * tp / max(2 * tp + fp + fn, 1)
+        log(f"[bench] trained classifier: validation F1 {f1:.3f} (tp {tp} fp {fp} fn {fn} tn {tn})")
+        pols.append({"mode": "disco", "tau": args.tau, "sl_max": args.sl_max, "pos_mode": "absolute", "classifier": "trained",
+                     "validation_f1": f1})
         for pol in pols:
             stamps = []
 
@@ -253,6 +270,7 @@ def main():
                 torch.cuda.synchronize()
                 stamps.append(time.perf_counter())
 
+            eng.clf = clf_trained if pol.get("classifier") == "trained" else clf_plain
             eng.reset()
             eng.prefill(prompt[:-1])
             torch.cuda.synchronize()
@@ -268,7 +286,7 @@ def main():
             drafted = sum(it["sl"] for it in its)
             ctx_mid = args.prompt_len + emitted // 2
             nbytes = len(its) * fwd_bytes(target_shape, ctx_mid, 1) + drafted * fwd_bytes(draft_shape, ctx_mid, 1)
-            rows.append({"policy": {k: v for k, v in pol.items() if k != "reference"}, "iterations_per_s": len(its) / dt, "tokens_per_s": emitted / dt,
+            rows.append({"policy": {k: v for k, v in pol.items() if k != "reference"}, "sl_hist": res["sl_hist"], "iterations_per_s": len(its) / dt, "tokens_per_s": emitted / dt,
                          "tokens_per_iteration": emitted / len(its), "drafted_per_iteration": drafted / len(its),
                          "accepted_per_iteration": sum(it["n"] for it in its) / len(its),
                          "hbm_gbs": nbytes / dt / 1e9, "ms_per_iteration": 1e3 * dt / len(its),
