@@ -177,7 +177,7 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     at.q = ws.q; at.ldq = m->d_q; at.kv_layer = g.kv_layer; at.page_table = kv->dev_page_table;
     at.page_tokens = kv->page_tokens; at.nq = d.n_heads; at.nkv = d.n_kv_heads; at.dh = d.d_head; at.M = n;
     at.pos0 = pos0; at.scale = 1.0f / sqrtf((float)d.d_head); at.part = ws.part;
-    at.split_len = ATTN_SPLIT_LEN; at.n_splits = (pos0 + n + ATTN_SPLIT_LEN - 1) / ATTN_SPLIT_LEN;
+    at.split_len = attn_split_len(pos0 + n); at.n_splits = (pos0 + n + at.split_len - 1) / at.split_len;
     at.Xout = ws.xattn; at.counters = ws.attn_counters; at.gate = gate;
     HIP_TRY(launch_attn(at, s), "attention launch");
 

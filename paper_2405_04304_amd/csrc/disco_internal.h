@@ -131,6 +131,7 @@ hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void*
                               hipStream_t s);
 
 constexpr int GEMM_MAX_SPLIT = 8;
-constexpr int ATTN_SPLIT_LEN = 128;  // cached positions per attention workgroup
+constexpr int ATTN_SPLIT_LEN = 128;  // fewest cached positions per attention workgroup
+int attn_split_len(int total);       // positions per workgroup for a context of `total` positions (a multiple of ATTN_SPLIT_LEN)
 
 }  // namespace disco

@@ -843,16 +843,21 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
   const int total = a.pos0 + a.M;
   const int s0 = split * a.split_len, s1 = min(s0 + a.split_len, total);
   AttnWave<DH> aw(a, head, s1);
-  typename AttnWave<DH>::Raw raw;
-  // the first step's cache loads go out ahead of the q loads
+  typename AttnWave<DH>::Raw r0, r1;
+  // the first step's cache loads go out ahead of the q loads; later steps' loads are in flight during
+  // the arithmetic of the step before
+  constexpr int STEP = NWV * WKEYS;
   int base = s0 + w * WKEYS;
-  bool issued = false;
-  if (base < s1) { aw.issue(raw, base); issued = true; }
+  if (base < s1) aw.issue(r0, base);
   aw.load_q(head);
-  for (; base < s1; base += NWV * WKEYS) {
-    if (!issued) aw.issue(raw, base);
-    issued = false;
-    aw.step(raw, base);
+  while (base < s1) {
+    if (base + STEP < s1) aw.issue(r1, base + STEP);
+    aw.step(r0, base);
+    base += STEP;
+    if (base >= s1) break;
+    if (base + STEP < s1) aw.issue(r0, base + STEP);
+    aw.step(r1, base);
+    base += STEP;
   }
 
   // merge the four wavefronts (fixed order), then one record per query: o[DH], max, sum
@@ -888,16 +893,27 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
   for (int qm = threadIdx.x / TPQ; qm < a.M; qm += 256 / TPQ) {
     const float* rbase = a.part + (((size_t)head * a.n_splits) * 16 + qm) * (DH + 2);
     const size_t stride = (size_t)16 * (DH + 2);
-    float mx = NEG_BIG;
-    for (int sp = 0; sp < a.n_splits; ++sp) mx = fmaxf(mx, ld_agent2(rbase + sp * stride + DH).x);
-    float L = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int sp = 0; sp < a.n_splits; ++sp) {
-      const float* rc = rbase + sp * stride;
-      const float2 ml = ld_agent2(rc + DH);
-      const float wgt = expf(ml.x - mx);
-      L += ml.y * wgt;
-      const float2 v0 = ld_agent2(rc + 4 * tq), v1 = ld_agent2(rc + 4 * tq + 2);
-      o[0] += v0.x * wgt; o[1] += v0.y * wgt; o[2] += v1.x * wgt; o[3] += v1.y * wgt;
+    // running (max, sum, o) over the ranges in range order; eight ranges' records are fetched at a
+    // time so that their round trips overlap
+    float mx = NEG_BIG, L = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int sp0 = 0; sp0 < a.n_splits; sp0 += 8) {
+      float2 ml[8], v0[8], v1[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (sp0 + i < a.n_splits) {
+          const float* rc = rbase + (size_t)(sp0 + i) * stride;
+          ml[i] = ld_agent2(rc + DH); v0[i] = ld_agent2(rc + 4 * tq); v1[i] = ld_agent2(rc + 4 * tq + 2);
+        }
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if (sp0 + i < a.n_splits) {
+          const float m_new = fmaxf(mx, ml[i].x);
+          const float f_old = expf(mx - m_new), f_new = expf(ml[i].x - m_new);
+          L = L * f_old + ml[i].y * f_new;
+          o[0] = o[0] * f_old + v0[i].x * f_new; o[1] = o[1] * f_old + v0[i].y * f_new;
+          o[2] = o[2] * f_old + v1[i].x * f_new; o[3] = o[3] * f_old + v1[i].y * f_new;
+          mx = m_new;
+        }
     }
     const float inv = 1.0f / L;
 #pragma unroll
@@ -956,6 +972,16 @@ __global__ __launch_bounds__(512) void k_attn_head(AttnArgs a) {
 
 constexpr int ATTN_HEAD_MAX_CTX = 256;    // positions up to which the whole-head kernel is used (one step per wavefront);
                                           // beyond it the arithmetic of a head is worth spreading over several compute units
+
+// Positions per attention workgroup: short ranges give many workgroups but one hand-off record per
+// range and query; measured best on MI355X at the 13B-class shape: 128 up to ~768 positions, then
+// about total / 4 .. total / 8.
+int attn_split_len(int total) {
+  if (total <= 768) return ATTN_SPLIT_LEN;
+  if (total <= 1536) return 2 * ATTN_SPLIT_LEN;
+  if (total <= 3072) return 4 * ATTN_SPLIT_LEN;
+  return 8 * ATTN_SPLIT_LEN;
+}
 
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s) {
   if (a.M < 1 || a.M > 16 || a.n_splits < 1 || a.counters == nullptr) return hipErrorInvalidValue;
