@@ -29,10 +29,8 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 __device__ __forceinline__ float bf16_to_f32(bf16_t u) { return __uint_as_float(((uint32_t)u) << 16); }
 
-__device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest even; inputs finite
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest even (the hardware conversion of gfx950)
+  return __builtin_bit_cast(bf16_t, (__bf16)f);
 }
 
 __device__ __forceinline__ bool gated(const uint32_t* gate) {
@@ -705,7 +703,7 @@ struct AttnWave {
   // raw operands of one step: K rows of two 16-position tiles, V^T tiles of the same positions
   struct Raw { u32x4 k[2][KS]; uint2 v[2][CT]; };
   const AttnArgs& a;
-  int j, g, kvh, total, s1, pt, qpos;
+  int j, g, kvh, total, s1, pt, pshift, qpos;
   size_t kv_head_elems, page_elems;
   bf16x8 qh[KS], ql[KS];
   f32x4 O[CT];
@@ -716,6 +714,7 @@ struct AttnWave {
     j = lane & 15; g = lane >> 4;
     kvh = head / (a.nq / a.nkv);
     total = a.pos0 + a.M; s1 = s1_; pt = a.page_tokens;
+    pshift = (pt & (pt - 1)) == 0 ? __builtin_ctz(pt) : -1;     // power-of-two pages: shifts instead of divisions
     qpos = a.pos0 + j;                                            // last position query j may see
     kv_head_elems = (size_t)pt * DH;                              // one head's K (or V) block in a page
     page_elems = 2 * (size_t)a.nkv * kv_head_elems;
@@ -730,7 +729,7 @@ struct AttnWave {
     for (int t = 0; t < 2; ++t) {
       const int kb = base + 16 * t;
       if (kb < s1) {
-        const int p = min(kb + j, total - 1), lp = p / pt, off = p - lp * pt;
+        const int p = min(kb + j, total - 1), lp = pshift >= 0 ? p >> pshift : p / pt, off = p - lp * pt;
         const int pp = a.page_table ? a.page_table[lp] : lp;
         const bf16_t* kp = a.kv_layer + (size_t)pp * page_elems + (size_t)kvh * kv_head_elems + (size_t)off * DH + 8 * g;
 #pragma unroll
@@ -743,7 +742,7 @@ struct AttnWave {
       if (kb < s1) {
         // V^T operand: channel row = lane % 16 of each 16-channel tile, 4 consecutive positions
         const int p0 = kb + 4 * g;
-        const int pc = min(p0, (total - 1) & ~3), lp = pc / pt, off = pc - lp * pt;
+        const int pc = min(p0, (total - 1) & ~3), lp = pshift >= 0 ? pc >> pshift : pc / pt, off = pc - lp * pt;
         const int pp = a.page_table ? a.page_table[lp] : lp;
         const bf16_t* vp = a.kv_layer + (size_t)pp * page_elems + (size_t)(a.nkv + kvh) * kv_head_elems + (size_t)j * pt + off;
 #pragma unroll
@@ -791,13 +790,13 @@ struct AttnWave {
     float mx = fmaxf(fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3])), fmaxf(fmaxf(S[1][0], S[1][1]), fmaxf(S[1][2], S[1][3])));
     mx = row4_max(mx);
     const float m_new = fmaxf(m_run, mx);
-    const float alpha = expf(m_run - m_new);
+    const float alpha = __expf(m_run - m_new);
     float sum = 0.f;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const float e = (S[t][v] > 0.5f * NEG_BIG) ? expf(S[t][v] - m_new) : 0.f;
+        const float e = (S[t][v] > 0.5f * NEG_BIG) ? __expf(S[t][v] - m_new) : 0.f;   // hardware exp2: a few ulp, far inside the bf16 split of P
         S[t][v] = e;
         sum += e;
       }
