@@ -28,6 +28,9 @@ The two transformer families are not the paper's subject (it uses published chec
 boxes); their definitions below are the standard pre-norm decoder equations.
 
 Readings of points the paper leaves open (all listed with reasons in the design notes):
+  the two rule-based baselines are named but not specified in the paper: the dynamic heuristic is
+  taken as "lookahead + 2 after a fully accepted block, otherwise - 1 (not below 1), starting at 5";
+  the perplexity rule as "stop when exp(-mean ln p) of the block's draft tokens exceeds a threshold";
   halt iff C_i < tau (strict); the token whose features triggered the halt stays in the block;
   entropy is over the full vocabulary in nats; features use the temperature-1 softmax of the raw
   draft logits; top-k values are in descending order; arg-max ties go to the lowest token id;
@@ -434,6 +437,12 @@ def spec_decode(target: Model, draft: Model, clf: Optional[Dict], prompt: Sequen
     policy: {"mode": "static", "gamma": g}
           | {"mode": "disco", "tau": t, "sl_max": c, "pos_mode": "absolute" | "block"}
           | {"mode": "oracle", "reference": greedy target tokens, "sl_max": optional cap}
+          | {"mode": "heuristic", "start": s, "up": u, "down": d, "sl_max": c}   (the dynamic heuristic the
+            paper compares with: the lookahead of the next iteration is SL + u after an iteration in which
+            every drafted token was accepted, max(1, SL - d) otherwise)
+          | {"mode": "ppl", "threshold": t, "sl_max": c}   (App. F's rule-based baseline: stop drafting
+            when the perplexity of the block's draft tokens so far, exp(-mean ln p_draft(token)),
+            exceeds t; the token that crosses the threshold stays in the block)
     force (synthetic acceptance): {"mask": bool per generated index, "tokens": the target's greedy
     tokens}; at a masked index the draft logit of the target's token is raised to max + 4 before
     the features are taken, so the draft agrees with the target there.
@@ -444,7 +453,9 @@ def spec_decode(target: Model, draft: Model, clf: Optional[Dict], prompt: Sequen
     mode = policy["mode"]
     pos_mode = policy.get("pos_mode", "absolute")
     cap_policy = {"static": policy.get("gamma"), "disco": policy.get("sl_max"),
-                  "oracle": policy.get("sl_max", 10 ** 9)}[mode]
+                  "oracle": policy.get("sl_max", 10 ** 9), "heuristic": policy.get("sl_max"),
+                  "ppl": policy.get("sl_max")}[mode]
+    heur_sl = int(policy.get("start", 5)) if mode == "heuristic" else None
     room = len(prompt) + max_new + (cap_policy if mode != "oracle" else max_new) + 2
     kv_t, kv_d = target.new_cache(room), draft.new_cache(room)
     target.prefill(list(prompt[:-1]), kv_t, prefill_chunk)
@@ -458,11 +469,14 @@ def spec_decode(target: Model, draft: Model, clf: Optional[Dict], prompt: Sequen
         emitted = len(seq) - n_prompt
         remaining = max_new - emitted
         cap = min(cap_policy, remaining - 1)
+        if mode == "heuristic":
+            cap = min(cap, heur_sl)
         # tokens the draft has not seen yet: 1 normally, 2 after a fully accepted block
         pending = seq[kv_d.len:]
         assert cap == 0 or 1 <= len(pending) <= 2
         block, steps = [seq[-1]], []
         j = 0
+        nll = 0.0                                  # -sum ln p_draft(token) over the block so far
         while j < cap:
             j += 1
             logits = draft.forward(pending, kv_d)[-1].clone()
@@ -484,8 +498,15 @@ def spec_decode(target: Model, draft: Model, clf: Optional[Dict], prompt: Sequen
                 break
             block.append(d)
             pending = [d]
-            halt = (j == cap) if mode != "disco" else (score < policy["tau"] or j == cap)
-            steps.append({"j": j, "token": d, "feats": ft["feats"], "score": score,
+            nll -= math.log(max(float(ft["probs"][d]), 1e-300))
+            ppl = math.exp(nll / j)
+            if mode == "disco":
+                halt = score < policy["tau"] or j == cap
+            elif mode == "ppl":
+                halt = ppl > policy["threshold"] or j == cap
+            else:
+                halt = j == cap
+            steps.append({"j": j, "token": d, "feats": ft["feats"], "score": score, "ppl": ppl,
                           "halt": bool(halt), "margin": ft["margin"], "forced": forced,
                           "pos_feature": i_feat, "gen_index": gen_index})
             if halt:
@@ -500,6 +521,9 @@ def spec_decode(target: Model, draft: Model, clf: Optional[Dict], prompt: Sequen
         seq.extend(emit)
         kv_t.rollback(ctx_t + n + 1)
         kv_d.rollback(min(kv_d.len, ctx_t + n + 1))
+        if mode == "heuristic" and sl > 0:
+            heur_sl = (min(heur_sl + int(policy.get("up", 2)), cap_policy) if n == sl
+                       else max(1, heur_sl - int(policy.get("down", 1))))
         iters.append({"sl": sl, "n": n, "block": block, "target_argmax": a, "emit": emit,
                       "steps": steps, "ctx": ctx_t,
                       "target_margins": [top2_margin(logits_t[r]) for r in range(sl + 1)]})

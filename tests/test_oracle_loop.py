@@ -194,3 +194,62 @@ def test_i5_eq1_expected_tokens_per_iteration():
     assert O.improvement_factor(0.6, 5, 0.0) == pytest.approx((1 - 0.6 ** 6) / 0.4)
     assert O.improvement_factor(0.6, 0, 0.3) == pytest.approx(1.0)
     assert O.improvement_factor(0.0, 5, 0.1) == pytest.approx(1 / 1.5)
+
+
+def test_i6_rule_based_baselines(cfg0):
+    """The two rule-based lookahead baselines the paper compares with (Sec. 2 footnote on the dynamic
+    heuristic; App. F on the perplexity threshold).  Both emit the greedy text (I1).  The heuristic's
+    lookahead sequence is pinned on the two inputs where it can be written down by hand: a draft that
+    always agrees (every block fully accepted: 5, 7, 9, then the cap) and one that never does (5, 4, 3,
+    2, 1, 1, ...).  The perplexity rule is pinned at its two ends (a threshold nothing exceeds is the
+    static cap; perplexity is > 1 whenever p < 1, so threshold 1 stops after every first token), and its
+    per-step value against the geometric mean of 1 / (largest probability) taken from the features."""
+    target, draft, clf, prompt, ref = cfg0
+    n_new = 64
+    v = W.CFG0_TARGET.vocab
+    always = {"mask": torch.ones(n_new, dtype=torch.bool), "tokens": ref}
+    never = {"mask": torch.ones(n_new, dtype=torch.bool), "tokens": [(t + 1) % v for t in ref]}
+    some = {"mask": W.make_force_mask(5, n_new, 0.6), "tokens": ref}
+    heur = {"mode": "heuristic", "start": 5, "up": 2, "down": 1, "sl_max": 10}
+    r = O.spec_decode(target, draft, clf, prompt, n_new, heur, force=always)
+    assert r["tokens"] == ref
+    sls = [it["sl"] for it in r["iterations"]]
+    # 6 + 8 + 10 + 11 * 3 = 57 tokens, then 7 remain: lookahead min(10, 7 - 1) = 6
+    assert sls == [5, 7, 9, 10, 10, 10, 6] and all(it["n"] == it["sl"] for it in r["iterations"])
+    r = O.spec_decode(target, draft, clf, prompt, n_new, heur, force=never)
+    assert r["tokens"] == ref and all(it["n"] == 0 for it in r["iterations"])
+    sls = [it["sl"] for it in r["iterations"]]
+    assert sls[:6] == [5, 4, 3, 2, 1, 1] and set(sls[6:-1]) == {1} and sls[-1] == 0 and len(sls) == n_new
+    r = O.spec_decode(target, draft, clf, prompt, n_new, heur, force=some)
+    assert r["tokens"] == ref
+    done = 0
+    for prev, nxt in zip(r["iterations"], r["iterations"][1:]):
+        done += len(prev["emit"])
+        if n_new - done - 1 < 10:                          # the end of the text limits the lookahead from here on
+            break
+        want = prev["sl"] + 2 if prev["n"] == prev["sl"] else max(1, prev["sl"] - 1)
+        assert nxt["sl"] == min(want, 10)
+    assert done > n_new // 2
+
+    r_inf = O.spec_decode(target, draft, clf, prompt, n_new, {"mode": "ppl", "threshold": 1e30, "sl_max": 6}, force=some)
+    r_st = O.spec_decode(target, draft, clf, prompt, n_new, {"mode": "static", "gamma": 6}, force=some)
+    assert r_inf["tokens"] == ref and r_inf["sl_hist"] == r_st["sl_hist"]
+    assert [it["block"] for it in r_inf["iterations"]] == [it["block"] for it in r_st["iterations"]]
+    r_one = O.spec_decode(target, draft, clf, prompt, n_new, {"mode": "ppl", "threshold": 1.0, "sl_max": 6}, force=some)
+    assert r_one["tokens"] == ref and set(r_one["sl_hist"]) <= {0, 1}
+    # a threshold inside the range of values seen: lookaheads vary, and each block ends exactly at the
+    # first step whose perplexity is above it
+    allp = sorted(s["ppl"] for it in r_inf["iterations"] for s in it["steps"])
+    thr = allp[len(allp) // 2] * 1.0001
+    r_mid = O.spec_decode(target, draft, clf, prompt, n_new, {"mode": "ppl", "threshold": thr, "sl_max": 6}, force=some)
+    assert r_mid["tokens"] == ref and len(r_mid["sl_hist"]) > 2
+    for it in r_mid["iterations"]:
+        p1 = [float(s["feats"][0]) for s in it["steps"]]
+        for j, s in enumerate(it["steps"], 1):
+            geo = math.prod(1.0 / p for p in p1[:j]) ** (1.0 / j)
+            assert abs(s["ppl"] - geo) <= 1e-6 * geo         # the features are stored in fp32
+        above = [s["ppl"] > thr for s in it["steps"]]
+        assert not any(above[:-1])                         # no step before the last crossed the threshold
+        if not above or not above[-1]:                     # not stopped by the rule: by the cap or the text's end
+            before = sum(len(x["emit"]) for x in r_mid["iterations"] if x["ctx"] < it["ctx"])
+            assert it["sl"] == min(6, n_new - before - 1)
