@@ -263,6 +263,26 @@ def main():
         log(f"[bench] trained classifier: validation F1 {f1:.3f} (tp {tp} fp {fp} fn {fn} tn {tn})")
         pols.append({"mode": "disco", "tau": args.tau, "sl_max": args.sl_max, "pos_mode": "absolute", "classifier": "trained",
                      "validation_f1": f1})
+        # the two rule-based baselines the paper compares with (Sec. 2 footnote; App. F).  The perplexity
+        # threshold is tuned, as App. F says, on validation text: a few candidate values (quantiles of
+        # 1 / largest probability over the labelling run of the other prompt), each timed on a short run
+        pols.append({"mode": "heuristic", "start": 5, "up": 2, "down": 1, "sl_max": args.sl_max})
+        inv_p = torch.sort(1.0 / f_tr[:n_lab, 0].float().cpu()).values
+        best_thr, best_rate = None, 0.0
+        for q in (0.2, 0.35, 0.5, 0.65, 0.8):
+            thr = float(inv_p[int(q * (n_lab - 1))]) * 1.001
+            eng.reset()
+            eng.prefill(prompt2[:-1])
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            r = eng.generate(prompt2, n_lab, {"mode": "ppl", "threshold": thr, "sl_max": args.sl_max},
+                             force={"mask": mask2, "tokens": greedy2}, do_prefill=False, max_iterations=12)
+            torch.cuda.synchronize()
+            rate = sum(len(it["emit"]) for it in r["iterations"]) / (time.perf_counter() - t1)
+            log(f"[bench] perplexity threshold {thr:.1f}: {rate:.1f} tokens/s on the validation prompt")
+            if rate > best_rate:
+                best_thr, best_rate = thr, rate
+        pols.append({"mode": "ppl", "threshold": best_thr, "sl_max": args.sl_max})
         for pol in pols:
             stamps = []
 

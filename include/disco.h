@@ -240,13 +240,20 @@ int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* cl
  *     from it, and that token is NOT part of the block: the "oracle" lookahead of Sec. 3 ("Finding the
  *     optimal SL per iteration"), an upper bound that needs the target's text in advance.  Then sl counts
  *     the matching tokens and sl + 1 draft steps have run (sl == cap: cap steps).
- *   dev_u_draft / dev_draft_probs / temperature: as in disco_draft_loop_sampled (not with the two above). */
+ *   dev_u_draft / dev_draft_probs / temperature: as in disco_draft_loop_sampled (not with the two above).
+ *   ppl_threshold: > 0 selects the perplexity rule, the rule-based baseline of App. F (the paper names
+ *     it and gives no formula; this is the usual definition): after draft token j of the block,
+ *     ppl_j = exp(-(1/j) sum_{i<=j} ln p_i) with p_i the draft's probability of its own token i, and
+ *     drafting stops after the first token with ppl_j > ppl_threshold (that token stays in the block)
+ *     or at cap.  The step records then carry ppl_j in their score field.  Needs clf == NULL and
+ *     static_sl == 0; not with dev_ref_tokens or sampling.  0 = off.                                    */
 typedef struct disco_loop_opts {
   const int32_t* dev_force_tokens;
   const int32_t* dev_ref_tokens;
   float temperature;
   const float* dev_u_draft;
   float* dev_draft_probs;
+  float ppl_threshold;
 } disco_loop_opts;
 
 int disco_draft_loop_ex(const disco_model* draft, disco_kv* kv, const disco_clf* clf,

@@ -56,7 +56,7 @@ class AcceptOut(C.Structure):
 
 class LoopOpts(C.Structure):
     _fields_ = [("dev_force_tokens", C.c_void_p), ("dev_ref_tokens", C.c_void_p), ("temperature", C.c_float),
-                ("dev_u_draft", C.c_void_p), ("dev_draft_probs", C.c_void_p)]
+                ("dev_u_draft", C.c_void_p), ("dev_draft_probs", C.c_void_p), ("ppl_threshold", C.c_float)]
 
 
 class LoopOut(C.Structure):
@@ -210,8 +210,9 @@ def disco_draft_loop(model, kv, clf, tokens_in, n_in, cap, static_sl, pos_featur
 
 def disco_draft_loop_ex(model, kv, clf, tokens_in, n_in, cap, static_sl, pos_feature0, tau, logits, steps, out,
                         host_out, ws, force_tokens=None, ref_tokens=None, temperature=0.0, u_draft=None,
-                        draft_probs=None, stream=None):
-    opts = LoopOpts(_ptr(force_tokens), _ptr(ref_tokens), temperature, _ptr(u_draft), _ptr(draft_probs))
+                        draft_probs=None, ppl_threshold=0.0, stream=None):
+    opts = LoopOpts(_ptr(force_tokens), _ptr(ref_tokens), temperature, _ptr(u_draft), _ptr(draft_probs),
+                    ppl_threshold)
     _check(lib().disco_draft_loop_ex(model.handle, kv.handle, C.byref(clf.c) if clf is not None else None,
                                      _ptr(tokens_in), n_in, cap, static_sl, pos_feature0, tau, C.byref(opts),
                                      _ptr(logits), _ptr(steps), _ptr(out), _ptr(host_out), _ptr(ws.buf), ws.nbytes,

@@ -436,11 +436,14 @@ int disco_kv_rollback(disco_kv* kv, int new_len) {
 static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in, int n_in,
                            int cap, int static_sl, float pos_feature0, float tau, const int32_t* dev_force_tokens,
                            const int32_t* dev_ref_tokens, float temperature, const float* dev_u_draft, float* dev_draft_probs,
-                           float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
+                           float ppl_threshold, float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
                            void* dev_ws, size_t ws_bytes, disco_stream s) {
   const bool sampled = dev_u_draft != nullptr;
   if (!aligned(dev_ref_tokens, 4)) return fail(DISCO_EINVAL, "misaligned pointer");
   if (sampled && (dev_ref_tokens || dev_force_tokens)) return fail(DISCO_EINVAL, "sampling excludes forced and reference tokens");
+  if (!(ppl_threshold >= 0.f)) return fail(DISCO_EINVAL, "perplexity threshold must be >= 0 (0 = off)");
+  if (ppl_threshold > 0.f && (sampled || dev_ref_tokens || clf || static_sl > 0))
+    return fail(DISCO_EINVAL, "the perplexity rule excludes sampling, reference tokens, a classifier and a static lookahead");
   if (sampled) {
     if (!(temperature > 0.f)) return fail(DISCO_EINVAL, "temperature must be positive");
     if (!dev_draft_probs || !aligned(dev_u_draft, 4) || !aligned(dev_draft_probs, 16)) return fail(DISCO_EINVAL, "sampling buffers null or misaligned");
@@ -484,6 +487,7 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
     a.block_slot = sampled ? nullptr : dev_out->block + j; a.gate = ws.gate;
     a.sl_count = ws.sl_count; a.force_token = dev_force_tokens ? dev_force_tokens + (j - 1) : nullptr;
     a.ref_token = dev_ref_tokens ? dev_ref_tokens + (j - 1) : nullptr;
+    a.ppl_threshold = ppl_threshold;
     a.scratch = ws.clf_scratch;
     HIP_TRY(launch_classify(a, st), "classify launch");
   }
@@ -496,7 +500,7 @@ int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* cl
                      float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
                      void* dev_ws, size_t ws_bytes, disco_stream s) {
   return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, dev_force_tokens, nullptr, 0.f,
-                         nullptr, nullptr, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
+                         nullptr, nullptr, 0.f, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
 }
 
 int disco_draft_loop_ex(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in, int n_in,
@@ -506,7 +510,7 @@ int disco_draft_loop_ex(const disco_model* draft, disco_kv* kv, const disco_clf*
   disco_loop_opts o{};
   if (opts) o = *opts;
   return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, o.dev_force_tokens,
-                         o.dev_ref_tokens, o.temperature, o.dev_u_draft, o.dev_draft_probs, dev_logits, dev_steps, dev_out,
+                         o.dev_ref_tokens, o.temperature, o.dev_u_draft, o.dev_draft_probs, o.ppl_threshold, dev_logits, dev_steps, dev_out,
                          host_out, dev_ws, ws_bytes, s);
 }
 
@@ -516,7 +520,7 @@ int disco_draft_loop_sampled(const disco_model* draft, disco_kv* kv, const disco
                              disco_loop_out* dev_out, disco_loop_out* host_out, void* dev_ws, size_t ws_bytes, disco_stream s) {
   if (!dev_u_draft) return fail(DISCO_EINVAL, "null argument");
   return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, nullptr, nullptr, temperature,
-                         dev_u_draft, dev_draft_probs, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
+                         dev_u_draft, dev_draft_probs, 0.f, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
 }
 
 int disco_sample(const float* dev_logits, int n_rows, int vocab, int64_t ld_logits, float temperature, const float* dev_u,

@@ -73,6 +73,7 @@ struct ClassifyArgs {
   int32_t* token_next; int32_t* block_slot; uint32_t* gate; int32_t* sl_count;
   const int32_t* force_token;
   const int32_t* ref_token;          // optional: known continuation; a different arg-max ends the block and stays out of it
+  float ppl_threshold;               // > 0: perplexity rule (needs sl_count; the float after it holds -sum ln p of the block)
   float* scratch;                    // optional: >= CLASSIFY_SCRATCH_BYTES, first word zero (ticket counter)
 };
 struct SampleArgs {

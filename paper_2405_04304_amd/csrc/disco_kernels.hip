@@ -1153,6 +1153,16 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
     bool mismatch = false;
     if (a.ref_token) { const int ref = *a.ref_token; mismatch = ref >= 0 && best.i != ref; }
     if (mismatch) halt = 3u;
+    // perplexity rule (App. F's rule-based baseline): the block's draft tokens so far have perplexity
+    // exp(-(1/j) sum ln p_i), p_i the draft's probability of its own token (the largest one); above the
+    // threshold this token is the block's last.  The running sum sits in the word after sl_count.
+    if (a.ppl_threshold > 0.f && a.sl_count) {
+      float* nll = reinterpret_cast<float*>(a.sl_count + 1);
+      const float sum = *nll - logf(feat_s[0]);
+      *nll = sum;
+      score = expf(sum / (float)(*a.sl_count + 1));
+      if (score > a.ppl_threshold) halt |= 1u;
+    }
     out->token = best.i;
 #pragma unroll
     for (int i = 0; i < 12; ++i) out->feats[i] = feat_s[i];
@@ -1346,6 +1356,16 @@ __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
     bool mismatch = false;
     if (a.ref_token) { const int ref = *a.ref_token; mismatch = ref >= 0 && gbest.i != ref; }
     if (mismatch) halt = 3u;
+    // perplexity rule (App. F's rule-based baseline): the block's draft tokens so far have perplexity
+    // exp(-(1/j) sum ln p_i), p_i the draft's probability of its own token (the largest one); above the
+    // threshold this token is the block's last.  The running sum sits in the word after sl_count.
+    if (a.ppl_threshold > 0.f && a.sl_count) {
+      float* nll = reinterpret_cast<float*>(a.sl_count + 1);
+      const float sum = *nll - logf(feat_s[0]);
+      *nll = sum;
+      score = expf(sum / (float)(*a.sl_count + 1));
+      if (score > a.ppl_threshold) halt |= 1u;
+    }
     out->token = gbest.i;
 #pragma unroll
     for (int i = 0; i < 12; ++i) out->feats[i] = feat_s[i];
@@ -1814,7 +1834,7 @@ struct LoopOut { int32_t sl; int32_t block[16]; };
 
 __global__ void k_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in, LoopOut* out) {
   if (threadIdx.x != 0) return;
-  *gate = 0u; *sl_count = 0;
+  *gate = 0u; sl_count[0] = 0; sl_count[1] = 0;     // second word: the perplexity rule's running sum (0.0f)
   out->sl = 0;
   out->block[0] = tokens_in[n_in - 1];
   for (int i = 1; i < 16; ++i) out->block[i] = 0;

@@ -109,11 +109,17 @@ class SpecEngine:
                  trace: bool = False, do_prefill: bool = True, on_iteration=None,
                  max_iterations: Optional[int] = None) -> Dict:
         mode = policy["mode"]
-        assert mode in ("static", "disco", "oracle")
+        assert mode in ("static", "disco", "oracle", "heuristic", "ppl")
         pos_mode = policy.get("pos_mode", "absolute")
         cap_policy = {"static": policy.get("gamma"), "disco": policy.get("sl_max"),
-                      "oracle": policy.get("sl_max", B.MAX_BLOCK - 1)}[mode]
+                      "oracle": policy.get("sl_max", B.MAX_BLOCK - 1), "heuristic": policy.get("sl_max"),
+                      "ppl": policy.get("sl_max")}[mode]
         tau = float(policy.get("tau", 0.0)) if mode == "disco" else -1.0e30
+        # the two rule-based baselines the paper compares with: a lookahead that follows the last
+        # iteration's outcome (host bookkeeping), and a perplexity threshold (decided on the device)
+        heur_sl = int(policy.get("start", 5)) if mode == "heuristic" else 0
+        clf = None if mode == "ppl" else self.clf
+        ppl_threshold = float(policy["threshold"]) if mode == "ppl" else 0.0
         if do_prefill:
             self.reset()
             self.prefill(prompt[:-1])
@@ -139,6 +145,8 @@ class SpecEngine:
             emitted = len(seq) - n_prompt
             remaining = max_new - emitted
             cap = min(cap_policy, remaining - 1)
+            if mode == "heuristic":
+                cap = min(cap, heur_sl)
             ctx_t = self.kv_t.len
             steps_rec = None
             if cap >= 1:
@@ -146,12 +154,13 @@ class SpecEngine:
                 pending = seq[len_d0:]
                 assert 1 <= len(pending) <= 2
                 self._put_tokens(pending)
-                B.disco_draft_loop_ex(self.draft, self.kv_d, self.clf, self.tok_in,
-                                      len(pending), cap, cap if mode == "static" else 0,
+                B.disco_draft_loop_ex(self.draft, self.kv_d, clf, self.tok_in,
+                                      len(pending), cap, cap if mode in ("static", "heuristic") else 0,
                                       float(emitted + 1) if pos_mode == "absolute" else 1.0, tau,
                                       self.logits_d, self.steps, self.loop_dev, self.loop_host, self.ws_d,
                                       force_tokens=(force_dev.data_ptr() + 4 * emitted) if force_dev is not None else None,
-                                      ref_tokens=(ref_dev.data_ptr() + 4 * emitted) if ref_dev is not None else None)
+                                      ref_tokens=(ref_dev.data_ptr() + 4 * emitted) if ref_dev is not None else None,
+                                      ppl_threshold=ppl_threshold)
                 torch.cuda.current_stream().synchronize()
                 lo = B.LoopOut.from_buffer_copy(self.loop_host.numpy().tobytes())
                 sl = lo.sl
@@ -181,6 +190,9 @@ class SpecEngine:
             B.disco_kv_rollback(self.kv_t, ctx_t + n + 1)
             if self.draft is not None and self.kv_d.len > ctx_t + n + 1:
                 B.disco_kv_rollback(self.kv_d, ctx_t + n + 1)
+            if mode == "heuristic" and sl > 0:
+                heur_sl = (min(heur_sl + int(policy.get("up", 2)), cap_policy) if n == sl
+                           else max(1, heur_sl - int(policy.get("down", 1))))
             it = {"sl": sl, "n": n, "block": block, "emit": emit, "ctx": ctx_t}
             if trace:
                 it["target_argmax"] = self.argmax[:sl + 1].tolist()

@@ -151,6 +151,17 @@ def test_sampling_and_loop_options_reject_bad_arguments_before_any_launch():
     o = B.LoopOpts(None, FAKE + 2, 0.0, None, None)
     assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.EINVAL
     assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 16, 0, 1.0, 0.5, None, *args_tail) == B.ECAP
+    # the perplexity rule: threshold >= 0, and not together with a static lookahead, reference tokens or sampling
+    o = B.LoopOpts(None, None, 0.0, None, None, -1.0)
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.EINVAL
+    o = B.LoopOpts(None, None, 0.0, None, None, float("nan"))
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.EINVAL
+    o = B.LoopOpts(None, None, 0.0, None, None, 20.0)
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 4, 4, 1.0, 0.5, C.byref(o), *args_tail) == B.EINVAL
+    o = B.LoopOpts(None, FAKE, 0.0, None, None, 20.0)
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.EINVAL
+    o = B.LoopOpts(None, None, 1.0, FAKE, FAKE, 20.0)
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.EINVAL
     assert lib.disco_kv_len(kv) == 0
     lib.disco_kv_destroy(kv)
     lib.disco_model_destroy(m)

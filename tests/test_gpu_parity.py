@@ -440,6 +440,52 @@ def test_loop_reference_lookahead_matches_oracle():
     assert st5["n_iterations"] >= orc15["n_iterations"]
 
 
+def test_loop_rule_based_baselines_match_oracle():
+    """The two rule-based lookahead baselines (Sec. 2 footnote: a lookahead that follows the previous
+    iteration's acceptance; App. F: a perplexity threshold).  Schedules, blocks and texts must equal the
+    oracle's up to a flagged position; under the perplexity rule a step whose value is within 1e-3
+    (relative) of the threshold is flagged too, and the per-step perplexities must agree."""
+    st = W.ModelShape("B", 2, 128, 2, 64, 2, 256, 512)
+    sd = W.ModelShape("B", 1, 128, 2, 64, 2, 256, 512)
+    tw, dw = W.make_weights(st, 0, "bf16", sigma=0.1), W.make_weights(sd, 10, "bf16", sigma=0.1)
+    ot, od = O.Model(st, tw, kv_bf16=True), O.Model(sd, dw, kv_bf16=True)
+    clf = W.make_classifier(100)
+    prompt = W.make_prompt(1, 40, st.vocab).tolist()
+    n_new = 96
+    ref, margins = O.greedy_target(ot, prompt, n_new)
+    force = {"mask": W.make_force_mask(5, n_new, 0.6), "tokens": ref}
+    d = dev()
+    eng = SpecEngine(B.DiscoModel(st, tw, d), B.DiscoModel(sd, dw, d), B.DiscoClf(clf, d), max_ctx=160, page_tokens=8)
+    heur = {"mode": "heuristic", "start": 5, "up": 2, "down": 1, "sl_max": 10}
+    orc = O.spec_decode(ot, od, clf, prompt, n_new, heur, force=force)
+    gpu = eng.generate(prompt, n_new, heur, force=force, trace=True)
+    if not _compare_runs(gpu, orc):
+        assert gpu["tokens"] == ref and gpu["sl_hist"] == orc["sl_hist"] and len(gpu["sl_hist"]) > 3
+    # thresholds from the oracle's own range of values: the median, and a high and a low quantile
+    probe = O.spec_decode(ot, od, clf, prompt, n_new, {"mode": "ppl", "threshold": 1e30, "sl_max": 10}, force=force)
+    vals = sorted(s["ppl"] for it in probe["iterations"] for s in it["steps"])
+    for q in (0.5, 0.85, 0.15):
+        thr = vals[int(q * (len(vals) - 1))] * 1.01
+        pol = {"mode": "ppl", "threshold": thr, "sl_max": 10}
+        orc = O.spec_decode(ot, od, clf, prompt, n_new, pol, force=force)
+        gpu = eng.generate(prompt, n_new, pol, force=force, trace=True)
+        diverged = False
+        for gi, oi in zip(gpu["iterations"], orc["iterations"]):
+            flagged = any(m < MARGIN for m in oi["target_margins"]) or any(
+                s["margin"] < MARGIN or abs(s["ppl"] - thr) <= 1e-3 * thr for s in oi["steps"])
+            if (gi["sl"], gi["n"], gi["block"], gi["emit"]) != (oi["sl"], oi["n"], oi["block"], oi["emit"]):
+                assert flagged, (gi["sl"], gi["n"], oi["sl"], oi["n"])
+                diverged = True
+                break
+            for gs, os_ in zip(gi["steps"], oi["steps"]):
+                assert abs(gs.score - os_["ppl"]) <= 2e-3 * os_["ppl"]          # the score field carries ppl_j
+                assert bool(gs.halt & 1) == os_["halt"] or flagged
+        if not diverged:
+            assert gpu["tokens"] == ref and gpu["sl_hist"] == orc["sl_hist"]
+        if q == 0.5:
+            assert len(gpu["sl_hist"]) > 2                                      # lookaheads do vary
+
+
 # ---- full-size verification block, fused draft loop, reproducibility -----------------------------------
 
 def test_verify_13b_full_depth_block_of_11():
