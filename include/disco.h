@@ -318,6 +318,24 @@ int disco_clf_train(const float* dev_feats, const int32_t* dev_labels, int n, in
 int disco_clf_eval(const disco_clf* clf, const float* dev_feats, const int32_t* dev_labels, int n,
                    float tau, float* dev_scores, int32_t* dev_counts, disco_stream s);
 
+/* ---- prompt pass (Sec. 2: both models are given the prompt before the first iteration) ----------- */
+
+/* Processes n_tokens prompt tokens in one dense pass instead of n_tokens / DISCO_MAX_BLOCK skinny
+ * forwards: the same arithmetic per token (bf16 weights, fp32-grade activations, bf16 KV entries) with
+ * the GEMMs tiled for the matrix unit.  Token i sits at position kv->len + i and attends to positions
+ * <= its own.  Appends n_tokens KV entries (kv->len += n_tokens).  dev_logits_last (may be NULL):
+ * fp32 [vocab], the logits after the last prompt token.  The pass works on groups of 16 tokens: the
+ * cache needs capacity for kv->len + 16 * ceil(n_tokens / 16) positions (entries beyond the new
+ * kv->len are scratch, as always).  Family B models only (DISCO_EINVAL otherwise: feed the prompt
+ * through disco_verify in blocks instead).  dev_ws: device buffer of at least
+ * disco_prefill_workspace_bytes(m, n_tokens, max_ctx >= kv->len + 16 * ceil(n_tokens / 16)) bytes,
+ * 256-byte aligned, initialised once with disco_workspace_init (which zeroes the ticket counters at
+ * its start; they sit at the offsets of an ordinary workspace).  Errors: EINVAL, ECAP, ESTATE, EHIP. */
+#define DISCO_PREFILL_MAX 8192
+size_t disco_prefill_workspace_bytes(const disco_model* m, int n_tokens, int max_ctx);
+int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens, int n_tokens,
+                  float* dev_logits_last, void* dev_ws, size_t ws_bytes, disco_stream s);
+
 /* ---- measurement probe ------------------------------------------------------------------------- */
 
 /* Brackets, with two HIP events on the launch stream, the MLP-input GEMM (gate/up + SwiGLU, or

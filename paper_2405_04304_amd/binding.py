@@ -78,6 +78,9 @@ _SIGNATURES = {
     "disco_kv_fill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]),
     "disco_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int, C.c_int]),
     "disco_workspace_init": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_void_p]),
+    "disco_prefill_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int, C.c_int]),
+    "disco_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t,
+                                C.c_void_p]),
     "disco_draft_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
                                    C.c_size_t, C.c_void_p, C.c_void_p]),
     "disco_classify": (C.c_int, [C.POINTER(Clf), C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_int,
@@ -190,6 +193,11 @@ def disco_verify(model, kv, block, n_block, argmax, logits, ws, stream=None):
                               _ptr(ws.buf), ws.nbytes, _stream() if stream is None else stream))
 
 
+def disco_prefill(model, kv, tokens, n_tokens, logits_last, ws, stream=None):
+    _check(lib().disco_prefill(model.handle, kv.handle, _ptr(tokens), n_tokens, _ptr(logits_last), _ptr(ws.buf),
+                               ws.nbytes, _stream() if stream is None else stream))
+
+
 def disco_accept(block, argmax, n_block, out, host_out=None, dev_n_block=None, stream=None):
     _check(lib().disco_accept(_ptr(block), _ptr(argmax), n_block, _ptr(dev_n_block), _ptr(out),
                               _ptr(host_out), _stream() if stream is None else stream))
@@ -241,6 +249,7 @@ def disco_draft_loop_sampled(model, kv, clf, tokens_in, n_in, cap, static_sl, po
 
 
 TRAIN_MAX_N = 2560
+PREFILL_MAX = 8192
 
 
 def disco_clf_train(feats, labels, n, hidden, epochs, lr, params, loss=None, stream=None):
@@ -334,6 +343,15 @@ class DiscoModel:
             raise DiscoError(EINVAL, "bad workspace request")
         ws = Workspace(n, self.device)
         _check(lib().disco_workspace_init(self.handle, ws.buf.data_ptr(), n, max_block, max_ctx, _stream()))
+        return ws
+
+    def prefill_workspace(self, n_tokens: int, max_ctx: int) -> "Workspace":
+        """Workspace of the dense prompt pass (holds the activations of every prompt token)."""
+        n = lib().disco_prefill_workspace_bytes(self.handle, n_tokens, max_ctx)
+        if n == 0:
+            raise DiscoError(EINVAL, "bad prefill workspace request")
+        ws = Workspace(n, self.device)
+        _check(lib().disco_workspace_init(self.handle, ws.buf.data_ptr(), n, MAX_BLOCK, max_ctx, _stream()))
         return ws
 
     def close(self):

@@ -219,9 +219,125 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   return DISCO_OK;
 }
 
+// ---- dense prompt pass -----------------------------------------------------------------------------
+
+// Workspace of the prompt pass: the ordinary workspace first (its ticket counters and split planes serve
+// the LM head of the last token), then the buffers of n_groups groups of 16 tokens.
+struct PfWs {
+  Ws base;
+  float* h; float* q; bf16_t* xn; bf16_t* xattn; bf16_t* xact; float* ssq; float* rstd;
+  size_t total;
+};
+
+PfWs carve_prefill(const disco_model* m, int n_groups, int max_ctx, void* base) {
+  const disco_model_desc& d = m->d;
+  PfWs w;
+  w.base = carve(m, DISCO_MAX_BLOCK, max_ctx, base);
+  char* p = static_cast<char*>(base);
+  size_t off = w.base.total;
+  auto take = [&](size_t bytes) { void* r = p ? p + off : nullptr; off += round_up(bytes, 256); return r; };
+  const size_t rows = (size_t)16 * n_groups;
+  w.h = static_cast<float*>(take(sizeof(float) * rows * d.d_model));
+  w.q = static_cast<float*>(take(sizeof(float) * rows * m->d_q));
+  w.xn = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * rows * d.d_model));
+  w.xattn = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * rows * m->d_q));
+  w.xact = static_cast<bf16_t*>(take(sizeof(bf16_t) * 2 * rows * d.d_ff));
+  w.ssq = static_cast<float*>(take(sizeof(float) * rows * (size_t)(d.d_model / 16)));
+  w.rstd = static_cast<float*>(take(sizeof(float) * rows));
+  w.total = off;
+  return w;
+}
+
 }  // namespace
 
 extern "C" {
+
+size_t disco_prefill_workspace_bytes(const disco_model* m, int n_tokens, int max_ctx) {
+  if (!m || n_tokens < 1 || n_tokens > DISCO_PREFILL_MAX || max_ctx < 0) return 0;
+  return carve_prefill(m, (n_tokens + 15) / 16, max_ctx, nullptr).total;
+}
+
+int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens, int n_tokens, float* dev_logits_last,
+                  void* dev_ws, size_t ws_bytes, disco_stream s) {
+  if (!m || !kv || !dev_tokens || !dev_ws) return fail(DISCO_EINVAL, "null argument");
+  if (kv->model != m) return fail(DISCO_ESTATE, "KV cache belongs to another model");
+  const disco_model_desc& d = m->d;
+  if (d.family != DISCO_FAMILY_B) return fail(DISCO_EINVAL, "the dense prompt pass supports family B models only");
+  if (n_tokens < 1 || n_tokens > DISCO_PREFILL_MAX) return fail(DISCO_ECAP, "prompt of %d tokens outside [1, %d]", n_tokens, DISCO_PREFILL_MAX);
+  const int G = (n_tokens + 15) / 16, pos0 = kv->len;
+  if (pos0 + 16 * G > kv->capacity)
+    return fail(DISCO_ECAP, "KV capacity %d below len %d + %d (the prompt rounded up to groups of 16)", kv->capacity, pos0, 16 * G);
+  if (!aligned(dev_tokens, 4) || !aligned(dev_ws, 256) || !aligned(dev_logits_last, 16)) return fail(DISCO_EINVAL, "misaligned pointer");
+  if (m->d_qkv % 64 || (2 * d.d_ff) % 64) return fail(DISCO_EINVAL, "projection widths must be multiples of 64");
+  const size_t need = carve_prefill(m, G, pos0 + 16 * G, nullptr).total;
+  if (ws_bytes < need) return fail(DISCO_EINVAL, "workspace of %zu bytes, %zu needed", ws_bytes, need);
+  const PfWs ws = carve_prefill(m, G, pos0 + 16 * G, dev_ws);
+  hipStream_t st = static_cast<hipStream_t>(s);
+  if (kv->dev_rope && !kv->rope_ready) {
+    HIP_TRY(launch_rope_fill(kv->dev_rope, kv->capacity, d.d_head, d.rope_base, st), "rotary table launch");
+    kv->rope_ready = true;
+  }
+  const int n_tiles = d.d_model / 16;
+  const size_t xs_d = (size_t)32 * d.d_model, xs_q = (size_t)32 * m->d_q, xs_ff = (size_t)32 * d.d_ff;
+
+  EmbedArgs ea{};
+  ea.tokens = dev_tokens; ea.n = n_tokens; ea.vocab = d.vocab; ea.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb);
+  ea.tok_stride = m->w.tok_emb_stride; ea.d = d.d_model; ea.gain = m->layers[0].norm1_g; ea.h = ws.h; ea.Xout = ws.xn;
+  ea.ssq_out = ws.ssq; ea.n_ssq_out = n_tiles;
+  HIP_TRY(launch_embed_groups(ea, G, st), "embedding launch");
+
+  auto dense = [&](const void* w, const bf16_t* x, size_t xs, int k, int n_rows) {
+    DenseArgs a{};
+    a.g.M = 16; a.g.W = static_cast<const bf16_t*>(w); a.g.X = x; a.g.KT = k / 32; a.g.n_rows = n_rows; a.g.grp = 1;
+    a.g.only_row = -1; a.n_groups = G; a.xs = xs;
+    return a;
+  };
+  for (int l = 0; l < d.n_layers; ++l) {
+    const disco_layer_weights& L = m->layers[l];
+    const bool last = (l + 1 == d.n_layers);
+    const float* next_g = last ? m->w.normf_g : m->layers[l + 1].norm1_g;
+    bf16_t* kv_layer = kv->pages + (size_t)l * kv->layer_stride;
+
+    HIP_TRY(launch_rstd_groups(ws.ssq, n_tiles, d.d_model, d.norm_eps, ws.rstd, G, st), "rstd launch");
+    DenseArgs qa = dense(L.wqkv, ws.xn, xs_d, d.d_model, m->d_qkv);
+    qa.rstd = ws.rstd; qa.g.grp = d.d_head / 32; qa.g.q = ws.q; qa.qs = (size_t)16 * m->d_q; qa.g.ldq = m->d_q;
+    qa.g.nq = d.n_heads; qa.g.nkv = d.n_kv_heads; qa.g.dh = d.d_head; qa.g.pos0 = pos0; qa.g.rope_tab = kv->dev_rope;
+    qa.g.kv_layer = kv_layer; qa.g.page_table = kv->dev_page_table; qa.g.page_tokens = kv->page_tokens;
+    HIP_TRY(launch_gemm_dense(qa, EPI_QKV, st), "qkv launch");
+
+    AttnArgs at{};
+    at.q = ws.q; at.ldq = m->d_q; at.kv_layer = kv_layer; at.page_table = kv->dev_page_table;
+    at.page_tokens = kv->page_tokens; at.nq = d.n_heads; at.nkv = d.n_kv_heads; at.dh = d.d_head; at.M = 16;
+    at.pos0 = pos0; at.scale = 1.0f / sqrtf((float)d.d_head); at.Xout = ws.xattn;
+    HIP_TRY(launch_attn_groups(at, G, xs_q, st), "attention launch");
+
+    DenseArgs oa = dense(L.wo, ws.xattn, xs_q, m->d_q, d.d_model);
+    oa.g.h = ws.h; oa.hs = (size_t)16 * d.d_model; oa.g.ld_out = d.d_model; oa.g.gain = L.norm2_g;
+    oa.g.Xout = ws.xn; oa.xouts = xs_d; oa.g.KT_out = d.d_model / 32; oa.g.ssq_out = ws.ssq; oa.ssq_outs = (size_t)n_tiles * 16;
+    HIP_TRY(launch_gemm_dense(oa, EPI_PARTIAL, st), "o-proj launch");
+
+    HIP_TRY(launch_rstd_groups(ws.ssq, n_tiles, d.d_model, d.norm_eps, ws.rstd, G, st), "rstd launch");
+    DenseArgs ua = dense(L.w_in, ws.xn, xs_d, d.d_model, 2 * d.d_ff);
+    ua.rstd = ws.rstd; ua.g.Xout = ws.xact; ua.xouts = xs_ff; ua.g.KT_out = d.d_ff / 32;
+    HIP_TRY(launch_gemm_dense(ua, EPI_SWIGLU, st), "mlp-in launch");
+
+    DenseArgs da = dense(L.w_out, ws.xact, xs_ff, d.d_ff, d.d_model);
+    da.g.h = ws.h; da.hs = (size_t)16 * d.d_model; da.g.ld_out = d.d_model; da.g.gain = next_g;
+    da.g.Xout = ws.xn; da.xouts = xs_d; da.g.KT_out = d.d_model / 32; da.g.ssq_out = ws.ssq; da.ssq_outs = (size_t)n_tiles * 16;
+    HIP_TRY(launch_gemm_dense(da, EPI_PARTIAL, st), "mlp-out launch");
+  }
+  if (dev_logits_last) {
+    // logits of the prompt's last token: the skinny LM head on the last group's panels
+    GemmArgs lm{};
+    lm.M = 16; lm.planes = ws.base.gpart; lm.counters = ws.base.gemm_counters;
+    lm.W = static_cast<const bf16_t*>(m->w.wlm); lm.X = ws.xn + (size_t)(G - 1) * xs_d; lm.KT = d.d_model / 32;
+    lm.ssq = ws.ssq + (size_t)(G - 1) * n_tiles * 16; lm.n_ssq = n_tiles; lm.d_in = d.d_model; lm.eps = d.norm_eps;
+    lm.n_rows = d.vocab; lm.out = dev_logits_last; lm.ld_out = d.vocab; lm.only_row = (n_tokens - 1) % 16;
+    HIP_TRY(launch_gemm(lm, EPI_STORE, st), "lm-head launch");
+  }
+  kv->len = pos0 + n_tokens;
+  return DISCO_OK;
+}
 
 const char* disco_last_error(void) { return g_err; }
 

@@ -45,6 +45,23 @@ struct GemmArgs {
   bf16_t* Xout; int KT_out;
 };
 
+// Dense prompt pass: the same GEMM over n_groups groups of 16 tokens in one launch.  g describes
+// group 0 (M = 16, two-panel layout); the strides give the distance to the next group's buffers.
+struct DenseArgs {
+  GemmArgs g;
+  int n_groups;
+  size_t xs, xouts;     // bf16 elements between the groups' input / output panels
+  size_t hs, qs;        // floats between the groups' residual rows / query rows
+  size_t ssq_outs;      // floats between the groups' sum-of-squares slots
+  const float* rstd;    // [group][16]: 1 / rms of the input rows (epilogues that read a normalised input)
+};
+
+// Embedding of n tokens into groups of 16 (family B): residual rows, gain * h panels, sums of squares.
+struct EmbedArgs {
+  const int32_t* tokens; int n; int vocab; const bf16_t* tok_emb; int64_t tok_stride;
+  int d; const float* gain; float* h; bf16_t* Xout; float* ssq_out; int n_ssq_out;
+};
+
 struct NormArgs {
   float* h; int d; int M; int layernorm; float eps;
   const float* g; const float* b;
@@ -114,6 +131,11 @@ hipError_t launch_gemm(const GemmArgs& a, int epi, hipStream_t s);
 int gemm_split_for(int n_rows, int KT, int M);   // K ranges the PARTIAL epilogue should be launched with
 hipError_t launch_norm(const NormArgs& a, hipStream_t s);
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
+// dense prompt pass (groups of 16 tokens; every group holds 16 rows, surplus rows are padding)
+hipError_t launch_gemm_dense(const DenseArgs& a, int epi, hipStream_t s);
+hipError_t launch_embed_groups(const EmbedArgs& a, int n_groups, hipStream_t s);
+hipError_t launch_rstd_groups(const float* ssq, int n_ssq, int d, float eps, float* rstd, int n_groups, hipStream_t s);
+hipError_t launch_attn_groups(const AttnArgs& a, int n_groups, size_t x_stride, hipStream_t s);
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s);
 hipError_t launch_sample_rows(const SampleArgs& a, int n_rows, hipStream_t s);
 hipError_t launch_accept_sample(const AcceptSampleArgs& a, hipStream_t s);

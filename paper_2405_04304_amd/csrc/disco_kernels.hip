@@ -223,6 +223,53 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
   union { u32x4 u; bf16x8 b; } c; c.u = v; return c.b;
 }
 
+// QKV epilogue of one lane: output features n0 .. n0+3 (lo4) and their rotary partners n0 + d_head/2 ..
+// (hi4) of token row m at position pos: rotation, then the query row or the paged K / V entry.
+__device__ __forceinline__ void qkv_store(const GemmArgs& a, float* q, const int n0, const int m, const int pos,
+                                          float (&lo4)[4], float (&hi4)[4]) {
+  const int head = n0 / a.dh, c = n0 % a.dh, half = a.dh >> 1;
+  const bool is_v = head >= a.nq + a.nkv;
+  if (a.rope_tab != nullptr && !is_v) {
+    // (cos, sin) of pos * base^(-2 (c + v) / d_head), tabulated per cached position
+    const float4* tab = reinterpret_cast<const float4*>(a.rope_tab + ((size_t)pos * half + c) * 2);
+    const float4 t0 = tab[0], t1 = tab[1];
+    const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float x0 = lo4[v], x1 = hi4[v];
+      lo4[v] = x0 * cs[v] - x1 * sn[v];
+      hi4[v] = x1 * cs[v] + x0 * sn[v];
+    }
+  }
+  if (head < a.nq) {
+    float* qp = q + (size_t)m * a.ldq + head * a.dh + c;
+    *reinterpret_cast<float4*>(qp) = make_float4(lo4[0], lo4[1], lo4[2], lo4[3]);
+    *reinterpret_cast<float4*>(qp + half) = make_float4(hi4[0], hi4[1], hi4[2], hi4[3]);
+  } else {
+    const int sel = is_v ? 1 : 0;
+    const int kvh = head - a.nq - sel * a.nkv;
+    const int lp = pos / a.page_tokens, off = pos % a.page_tokens;
+    const int pp = a.page_table ? a.page_table[lp] : lp;
+    bf16_t* blk = a.kv_layer + (((size_t)pp * 2 + sel) * a.nkv + kvh) * a.page_tokens * a.dh;
+    if (!is_v) {                 // K: [token][d_head]
+      bf16_t* dst = blk + (size_t)off * a.dh + c;
+      uint2 u0, u1;
+      u0.x = (uint32_t)f32_to_bf16(lo4[0]) | ((uint32_t)f32_to_bf16(lo4[1]) << 16);
+      u0.y = (uint32_t)f32_to_bf16(lo4[2]) | ((uint32_t)f32_to_bf16(lo4[3]) << 16);
+      u1.x = (uint32_t)f32_to_bf16(hi4[0]) | ((uint32_t)f32_to_bf16(hi4[1]) << 16);
+      u1.y = (uint32_t)f32_to_bf16(hi4[2]) | ((uint32_t)f32_to_bf16(hi4[3]) << 16);
+      *reinterpret_cast<uint2*>(dst) = u0;
+      *reinterpret_cast<uint2*>(dst + half) = u1;
+    } else {                     // V: transposed, [d_head][token]
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        blk[(size_t)(c + v) * a.page_tokens + off] = f32_to_bf16(lo4[v]);
+        blk[(size_t)(c + half + v) * a.page_tokens + off] = f32_to_bf16(hi4[v]);
+      }
+    }
+  }
+}
+
 template <int EPI> struct EpiTraits { static constexpr bool pair = (EPI == EPI_QKV || EPI == EPI_SWIGLU); };
 
 template <int P, int RT, int EPI, int NW, int U>
@@ -435,52 +482,10 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
     *reinterpret_cast<float4*>(a.out + row_off + urt[0] * 16 + 4 * g) = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
   } else if (EPI == EPI_QKV) {
     // two tiles: features c .. c+3 and their rotary partners c + dh/2 .. of one head
-    const int n0 = urt[0] * 16 + 4 * g;
-    const int head = n0 / a.dh, c = n0 % a.dh, half = a.dh >> 1;
     float lo4[4], hi4[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) { lo4[v] = y[0][v]; hi4[v] = y[TPU - 1][v]; }
-    const int pos = a.pos0 + m;
-    const bool is_v = head >= a.nq + a.nkv;
-    if (a.rope_tab != nullptr && !is_v) {
-      // (cos, sin) of pos * base^(-2 (c + v) / d_head), tabulated per cached position
-      const float4* tab = reinterpret_cast<const float4*>(a.rope_tab + ((size_t)pos * half + c) * 2);
-      const float4 t0 = tab[0], t1 = tab[1];
-      const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const float x0 = lo4[v], x1 = hi4[v];
-        lo4[v] = x0 * cs[v] - x1 * sn[v];
-        hi4[v] = x1 * cs[v] + x0 * sn[v];
-      }
-    }
-    if (head < a.nq) {
-      float* qp = a.q + (size_t)m * a.ldq + head * a.dh + c;
-      *reinterpret_cast<float4*>(qp) = make_float4(lo4[0], lo4[1], lo4[2], lo4[3]);
-      *reinterpret_cast<float4*>(qp + half) = make_float4(hi4[0], hi4[1], hi4[2], hi4[3]);
-    } else {
-      const int sel = is_v ? 1 : 0;
-      const int kvh = head - a.nq - sel * a.nkv;
-      const int lp = pos / a.page_tokens, off = pos % a.page_tokens;
-      const int pp = a.page_table ? a.page_table[lp] : lp;
-      bf16_t* blk = a.kv_layer + (((size_t)pp * 2 + sel) * a.nkv + kvh) * a.page_tokens * a.dh;
-      if (!is_v) {                 // K: [token][d_head]
-        bf16_t* dst = blk + (size_t)off * a.dh + c;
-        uint2 u0, u1;
-        u0.x = (uint32_t)f32_to_bf16(lo4[0]) | ((uint32_t)f32_to_bf16(lo4[1]) << 16);
-        u0.y = (uint32_t)f32_to_bf16(lo4[2]) | ((uint32_t)f32_to_bf16(lo4[3]) << 16);
-        u1.x = (uint32_t)f32_to_bf16(hi4[0]) | ((uint32_t)f32_to_bf16(hi4[1]) << 16);
-        u1.y = (uint32_t)f32_to_bf16(hi4[2]) | ((uint32_t)f32_to_bf16(hi4[3]) << 16);
-        *reinterpret_cast<uint2*>(dst) = u0;
-        *reinterpret_cast<uint2*>(dst + half) = u1;
-      } else {                     // V: transposed, [d_head][token]
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          blk[(size_t)(c + v) * a.page_tokens + off] = f32_to_bf16(lo4[v]);
-          blk[(size_t)(c + half + v) * a.page_tokens + off] = f32_to_bf16(hi4[v]);
-        }
-      }
-    }
+    qkv_store(a, a.q, urt[0] * 16 + 4 * g, m, a.pos0 + m, lo4, hi4);
   } else if (EPI == EPI_SWIGLU) {
     // tile 0 = gate rows, tile 1 = the matching up rows
     const int f = (urt[0] >> 1) * 16 + 4 * g;
@@ -925,12 +930,10 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
 // loads of step i + 1 in flight during the arithmetic of step i), merges its wavefronts through LDS
 // and writes the O-projection panels itself: no partial records, no hand-off between workgroups.
 template <int DH>
-__global__ __launch_bounds__(512) void k_attn_head(AttnArgs a) {
-  if (gated(a.gate)) return;
+__device__ __forceinline__ void attn_whole_head(const AttnArgs& a, const int head) {
   constexpr int CT = DH / 16, NWV = 8, WKEYS = 32, STEP = NWV * WKEYS;
   __shared__ f32x4 o_s[NWV][CT][64];
   __shared__ float m_s[NWV][16], l_s[NWV][16];
-  const int head = blockIdx.x;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int j = lane & 15, g = lane >> 4;
   const int total = a.pos0 + a.M;
@@ -969,6 +972,25 @@ __global__ __launch_bounds__(512) void k_attn_head(AttnArgs a) {
   xpack_store4(a.Xout, (a.nq * DH) >> 5, a.M, j, head * DH + w * 16 + 4 * g, out4);
 }
 
+template <int DH>
+__global__ __launch_bounds__(512) void k_attn_head(AttnArgs a) {
+  if (gated(a.gate)) return;
+  attn_whole_head<DH>(a, blockIdx.x);
+}
+
+// Prompt pass: workgroup = (query head, group of 16 prompt tokens).  Group r sits at positions
+// pos0 + 16 r .. and sees everything up to its own tokens, so every group runs the whole-head routine
+// on its own range; the longest ranges are scheduled first.
+template <int DH>
+__global__ __launch_bounds__(512) void k_attn_groups(AttnArgs a, int n_groups, size_t x_stride) {
+  const int r = n_groups - 1 - (int)blockIdx.y;
+  AttnArgs b = a;
+  b.pos0 = a.pos0 + 16 * r;
+  b.q = a.q + (size_t)r * 16 * a.ldq;
+  b.Xout = a.Xout + (size_t)r * x_stride;
+  attn_whole_head<DH>(b, blockIdx.x);
+}
+
 constexpr int ATTN_HEAD_MAX_CTX = 256;    // positions up to which the whole-head kernel is used (one step per wavefront);
                                           // beyond it the arithmetic of a head is worth spreading over several compute units
 
@@ -993,6 +1015,15 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t s) {
   const dim3 g1(a.nq, a.n_splits);
   if (a.dh == 128) hipLaunchKernelGGL(k_attn_partial<128>, g1, dim3(256), 0, s, a);
   else if (a.dh == 64) hipLaunchKernelGGL(k_attn_partial<64>, g1, dim3(256), 0, s, a);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_groups(const AttnArgs& a, int n_groups, size_t x_stride, hipStream_t s) {
+  if (a.M != 16 || n_groups < 1 || n_groups > 65535) return hipErrorInvalidValue;
+  const dim3 g1(a.nq, n_groups);
+  if (a.dh == 128) hipLaunchKernelGGL(k_attn_groups<128>, g1, dim3(512), 0, s, a, n_groups, x_stride);
+  else if (a.dh == 64) hipLaunchKernelGGL(k_attn_groups<64>, g1, dim3(512), 0, s, a, n_groups, x_stride);
   else return hipErrorInvalidValue;
   return hipGetLastError();
 }
@@ -1889,6 +1920,207 @@ hipError_t launch_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* to
 hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void* host_loop_out, hipStream_t s) {
   hipLaunchKernelGGL(k_loop_finish, dim3(1), dim3(64), 0, s, sl_count, reinterpret_cast<LoopOut*>(dev_loop_out),
                      reinterpret_cast<LoopOut*>(host_loop_out));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// dense prompt pass: the GEMMs of a forward over many groups of 16 tokens at once
+// ---------------------------------------------------------------------------------------------
+//
+// The prompt is processed before the first iteration (Sec. 2: the target model is given a prompt).
+// With hundreds of tokens per pass the GEMMs are bound by the matrix unit, not by the weight stream,
+// so the tiling differs from the skinny kernel: a wavefront owns 4 weight row tiles x 4 token groups
+// (sixteen 16 x 16 accumulators), walks the whole K range itself (no K split, no cross-wavefront
+// reduction) with NB register buffers of loads in flight, and every weight tile it fetches feeds 8
+// matrix instructions (hi and lo panel of 4 groups).  The four wavefronts of a workgroup take
+// neighbouring row tiles and the SAME token groups, so the activation tiles hit in the vector L1.
+// Workgroup ids are dealt round-robin to the 8 XCDs; the id -> (row block, token block) map gives all
+// token blocks of one row block to the same XCD, back to back, so that its L2 serves the weights to
+// every token block after the first.  Operand layouts, precision (bf16 hi + lo activations, fp32
+// accumulation) and epilogue arithmetic are those of the skinny kernel.
+
+template <int EPI, int NB>
+__global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
+  constexpr int RT = 4, CG = 4, NWV = 4;
+  constexpr bool PAIR = EpiTraits<EPI>::pair;
+  constexpr int UNITS = PAIR ? RT / 2 : RT, TPU = PAIR ? 2 : 1;
+  constexpr bool NORMED = (EPI != EPI_PARTIAL);
+  const GemmArgs& a = d.g;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int n_tiles = a.n_rows >> 4;
+  const int ncb = (d.n_groups + CG - 1) / CG;
+  const int nrb = (n_tiles + RT * NWV - 1) / (RT * NWV);
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int rb = (slot / ncb) * 8 + xcd, cb = slot % ncb;
+  if (rb >= nrb) return;
+  const int b = rb * NWV + w;                    // this wavefront's group of RT row tiles
+  if (b * RT >= n_tiles) return;                 // (no workgroup barrier below)
+  int rt[RT];
+  if (PAIR) {
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) {
+      const int bp = b * UNITS + u;
+      rt[2 * u] = (bp / a.grp) * (2 * a.grp) + (bp % a.grp);
+      rt[2 * u + 1] = rt[2 * u] + a.grp;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < RT; ++r) rt[r] = b * RT + r;
+  }
+  const int KT = a.KT;
+  const u32x4* Wp[RT];
+#pragma unroll
+  for (int r = 0; r < RT; ++r) Wp[r] = reinterpret_cast<const u32x4*>(a.W) + (size_t)rt[r] * KT * 64 + lane;
+  // token groups past the end are clamped to the last one: loaded and multiplied, never stored
+  const u32x4* Xp[CG];
+#pragma unroll
+  for (int c = 0; c < CG; ++c) {
+    const int ci = min(cb * CG + c, d.n_groups - 1);
+    Xp[c] = reinterpret_cast<const u32x4*>(a.X + (size_t)ci * d.xs) + lane;
+  }
+  f32x4 acc[RT][CG];
+#pragma unroll
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int c = 0; c < CG; ++c) acc[r][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  u32x4 A[NB][RT], Bh[NB][CG], Bl[NB][CG];
+  auto load = [&](u32x4 (&Ad)[RT], u32x4 (&Bhd)[CG], u32x4 (&Bld)[CG], const int kt) {
+    const size_t t = (size_t)(kt < KT ? kt : KT - 1) * 64;
+#pragma unroll
+    for (int r = 0; r < RT; ++r) Ad[r] = Wp[r][t];
+#pragma unroll
+    for (int c = 0; c < CG; ++c) { Bhd[c] = Xp[c][t]; Bld[c] = Xp[c][(size_t)KT * 64 + t]; }
+  };
+#pragma unroll
+  for (int i = 0; i < NB - 1; ++i) load(A[i], Bh[i], Bl[i], i);
+  for (int kt0 = 0; kt0 < KT; kt0 += NB) {
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int kt = kt0 + i;
+      if (kt < KT) {
+        load(A[(i + NB - 1) % NB], Bh[(i + NB - 1) % NB], Bl[(i + NB - 1) % NB], kt + NB - 1);
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+          for (int c = 0; c < CG; ++c) {
+            acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(Bh[i][c]), acc[r][c], 0, 0, 0);
+            acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(Bl[i][c]), acc[r][c], 0, 0, 0);
+          }
+      }
+    }
+  }
+
+  const int m = lane & 15, g = lane >> 4;         // token column, 4-row group of the 16 x 16 result
+#pragma unroll
+  for (int c = 0; c < CG; ++c) {
+    const int ci = cb * CG + c;
+    if (ci < d.n_groups) {
+    float rstd = 1.f;
+    if (NORMED && d.rstd != nullptr) rstd = d.rstd[ci * 16 + m];
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) {
+      f32x4 y0 = acc[u * TPU][c] * rstd, y1 = acc[u * TPU + TPU - 1][c] * rstd;
+      const int t0 = rt[u * TPU];
+      if (EPI == EPI_PARTIAL) {
+        // residual-stream update h += X.W^T, panels of gain * h and this tile's sums of squares for the next GEMM
+        const int col = t0 * 16 + 4 * g;
+        float4* hp = reinterpret_cast<float4*>(a.h + (size_t)ci * d.hs + (size_t)m * a.ld_out + col);
+        float4 h = *hp;
+        h.x += y0[0]; h.y += y0[1]; h.z += y0[2]; h.w += y0[3];
+        *hp = h;
+        const float4 gn = *reinterpret_cast<const float4*>(a.gain + col);
+        const float o[4] = {h.x * gn.x, h.y * gn.y, h.z * gn.z, h.w * gn.w};
+        xpack_store4(a.Xout + (size_t)ci * d.xouts, a.KT_out, 16, m, col, o);
+        const float sq = row4_sum((h.x * h.x + h.y * h.y) + (h.z * h.z + h.w * h.w));
+        if (g == 0) a.ssq_out[(size_t)ci * d.ssq_outs + t0 * 16 + m] = sq;      // [slot][token]
+      } else if (EPI == EPI_QKV) {
+        float lo4[4] = {y0[0], y0[1], y0[2], y0[3]}, hi4[4] = {y1[0], y1[1], y1[2], y1[3]};
+        qkv_store(a, a.q + (size_t)ci * d.qs, t0 * 16 + 4 * g, m, a.pos0 + 16 * ci + m, lo4, hi4);
+      } else if (EPI == EPI_SWIGLU) {
+        const int f = (t0 >> 1) * 16 + 4 * g;
+        float act[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) act[v] = y0[v] / (1.0f + expf(-y0[v])) * y1[v];
+        xpack_store4(a.Xout + (size_t)ci * d.xouts, a.KT_out, 16, m, f, act);
+      }
+    }
+    }
+  }
+}
+
+hipError_t launch_gemm_dense(const DenseArgs& d, int epi, hipStream_t s) {
+  const GemmArgs& a = d.g;
+  if (a.M != 16 || d.n_groups < 1 || a.KT < 1 || a.n_rows < 64 || (a.n_rows % 64) != 0) return hipErrorInvalidValue;
+  if ((epi == EPI_QKV || epi == EPI_SWIGLU) && (a.grp < 1 || (a.n_rows / 32) % a.grp != 0)) return hipErrorInvalidValue;
+  const int n_tiles = a.n_rows / 16;
+  const int ncb = (d.n_groups + 3) / 4, nrb = (n_tiles + 15) / 16;
+  const long long blocks = (long long)((nrb + 7) / 8) * 8 * ncb;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)blocks);
+  switch (epi) {
+    case EPI_QKV: hipLaunchKernelGGL((k_gemm_dense<EPI_QKV, 2>), grid, dim3(256), 0, s, d); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((k_gemm_dense<EPI_SWIGLU, 2>), grid, dim3(256), 0, s, d); break;
+    case EPI_PARTIAL: hipLaunchKernelGGL((k_gemm_dense<EPI_PARTIAL, 2>), grid, dim3(256), 0, s, d); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// Embedding rows of the prompt pass: one workgroup per token slot; slots past the prompt's end hold
+// token 0 (padding: computed, never used).  Writes the residual row, the gain * h panels of the first
+// RMSNorm'ed GEMM and the row's sum of squares (slot 0; the other slots are zeroed).
+__global__ __launch_bounds__(256) void k_embed_groups(EmbedArgs a) {
+  __shared__ float red[256 / 64 + 1];
+  const int idx = blockIdx.x, r = idx >> 4, m = idx & 15, t = threadIdx.x, d = a.d;
+  int tok = idx < a.n ? a.tokens[idx] : 0;
+  tok = tok < 0 ? 0 : (tok >= a.vocab ? a.vocab - 1 : tok);
+  const bf16_t* e = a.tok_emb + (size_t)tok * a.tok_stride;
+  float* h = a.h + (size_t)idx * d;
+  bf16_t* X = a.Xout + (size_t)r * (size_t)d * 32;             // two panels of d * 16 elements per group
+  const int KT = d >> 5;
+  float ss = 0.f;
+  for (int k = t * 4; k < d; k += 256 * 4) {
+    const uint2 u = *reinterpret_cast<const uint2*>(e + k);
+    const float4 v = make_float4(bf16_to_f32(u.x & 0xFFFF), bf16_to_f32(u.x >> 16), bf16_to_f32(u.y & 0xFFFF), bf16_to_f32(u.y >> 16));
+    *reinterpret_cast<float4*>(h + k) = v;
+    ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
+    const float4 gn = *reinterpret_cast<const float4*>(a.gain + k);
+    const float o[4] = {v.x * gn.x, v.y * gn.y, v.z * gn.z, v.w * gn.w};
+    xpack_store4(X, KT, 16, m, k, o);
+  }
+  ss = block_sum<256>(ss, red);
+  float* sq = a.ssq_out + (size_t)r * a.n_ssq_out * 16;
+  for (int i = t; i < a.n_ssq_out; i += 256) sq[i * 16 + m] = (i == 0) ? ss : 0.f;
+}
+
+hipError_t launch_embed_groups(const EmbedArgs& a, int n_groups, hipStream_t s) {
+  if (n_groups < 1 || (a.d & 31) || a.n < 1 || a.n > 16 * n_groups) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_embed_groups, dim3(16 * n_groups), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+// 1 / rms of every row of the prompt pass from its per-tile sums of squares, added in slot order.
+__global__ __launch_bounds__(256) void k_rstd_groups(const float* __restrict__ ssq, int n_ssq, int d, float eps,
+                                                     float* __restrict__ rstd) {
+  __shared__ float part[16][16];
+  const int r = blockIdx.x, m = threadIdx.x & 15, p = threadIdx.x >> 4;
+  const float* sq = ssq + (size_t)r * n_ssq * 16;
+  float s = 0.f;
+  for (int i = p; i < n_ssq; i += 16) s += sq[i * 16 + m];
+  part[p][m] = s;
+  __syncthreads();
+  if (p == 0) {
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tot += part[i][m];
+    rstd[r * 16 + m] = 1.0f / sqrtf(tot / (float)d + eps);
+  }
+}
+
+hipError_t launch_rstd_groups(const float* ssq, int n_ssq, int d, float eps, float* rstd, int n_groups, hipStream_t s) {
+  if (n_groups < 1 || n_ssq < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_rstd_groups, dim3(n_groups), dim3(256), 0, s, ssq, n_ssq, d, eps, rstd);
   return hipGetLastError();
 }
 

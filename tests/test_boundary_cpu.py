@@ -177,3 +177,28 @@ def test_kv_capacity_is_enforced_on_the_host():
     assert lib.disco_kv_len(kv) == 0
     lib.disco_kv_destroy(kv)
     lib.disco_model_destroy(m)
+
+
+def test_prefill_rejects_bad_arguments_before_any_launch():
+    lib = B.lib()
+    rc, m = _model()                                  # family B
+    rc, kv, _ = _kv(m, capacity=64, page=16)
+    assert lib.disco_prefill_workspace_bytes(m, 0, 64) == 0
+    assert lib.disco_prefill_workspace_bytes(m, B.PREFILL_MAX + 1, 64) == 0
+    assert lib.disco_prefill_workspace_bytes(None, 16, 64) == 0
+    need = lib.disco_prefill_workspace_bytes(m, 64, 64)
+    assert need > lib.disco_workspace_bytes(m, 16, 64)
+    assert lib.disco_prefill(m, kv, FAKE, 0, None, FAKE, need, None) == B.ECAP
+    assert lib.disco_prefill(m, kv, FAKE, 65, None, FAKE, need, None) == B.ECAP       # 80 positions > capacity 64
+    assert lib.disco_prefill(m, kv, None, 16, None, FAKE, need, None) == B.EINVAL
+    assert lib.disco_prefill(m, kv, FAKE, 64, None, FAKE, need - 256, None) == B.EINVAL
+    assert lib.disco_prefill(m, kv, FAKE + 2, 16, None, FAKE, need, None) == B.EINVAL
+    assert lib.disco_kv_len(kv) == 0
+    rc, ma = _model(family=0)
+    rc, kva, _ = _kv(ma, capacity=64, page=16)
+    assert lib.disco_prefill(ma, kva, FAKE, 16, None, FAKE, need, None) == B.EINVAL   # family A has no dense pass
+    assert lib.disco_prefill(m, kva, FAKE, 16, None, FAKE, need, None) == B.ESTATE     # cache of another model
+    for h in (kv, kva):
+        lib.disco_kv_destroy(h)
+    for h in (m, ma):
+        lib.disco_model_destroy(h)

@@ -1,0 +1,156 @@
+"""GPU parity of the dense prompt pass (disco_prefill) against the CPU oracle.
+
+The oracle has no separate prompt routine to mirror: a prompt pass is the model's forward over the
+prompt's tokens (Sec. 2: the models are given the prompt before the first iteration), and
+tests/test_oracle_blocks.py pins that the forward does not depend on how the tokens are cut into
+blocks.  So the expected values are the oracle's logits after the whole prompt, and, because the pass
+exists to fill the KV cache, the oracle's logits of LATER forwards that read those cache entries.
+Tolerances as in test_gpu_parity.py (2e-2 stated, 2e-3 held)."""
+import pytest
+import torch
+
+from paper_2405_04304_amd import binding as B
+from paper_2405_04304_amd.engine import SpecEngine
+from oracle import disco_oracle as O
+from workloads import synth as W
+
+from test_gpu_parity import MARGIN, check_logits, dev, setup_pair
+
+pytestmark = pytest.mark.gpu
+
+SMALL_B = W.ModelShape("B", 2, 128, 2, 64, 2, 256, 512)
+SMALL_B_GQA = W.ModelShape("B", 2, 256, 4, 64, 2, 288, 1008)
+SMALL_B_MQA128 = W.ModelShape("B", 2, 256, 2, 128, 1, 320, 512)
+SMALL_A = W.ModelShape("A", 2, 128, 2, 64, 2, 256, 512, max_pos=512)
+
+
+def _prefill_case(shape, seed, n, pre=0, page=16, permute=False, what=""):
+    """`pre` tokens go through a verification block first, so the pass starts at a position that is
+    not a multiple of 16; afterwards a 1-token and a 5-token forward read the cache the pass wrote."""
+    cap = pre + n + 48
+    om, gm, okv, gkv, ws = setup_pair(shape, seed, page_tokens=page, permute=permute, capacity=cap, gain_jitter=0.2, sigma=0.05)
+    d = dev()
+    toks = W.make_tokens(40 + n, pre + n + 6, shape.vocab).tolist()
+    tt = torch.tensor(toks, dtype=torch.int32, device=d)
+    am = torch.zeros(16, dtype=torch.int32, device=d)
+    if pre:
+        B.disco_verify(gm, gkv, tt, pre, am, None, ws)
+        om.forward(toks[:pre], okv)
+    pws = gm.prefill_workspace(n, cap)
+    last = torch.empty(shape.vocab, dtype=torch.float32, device=d)
+    print(f"[prefill] {what}: n {n} pre {pre} page {page} permute {permute}", flush=True)
+    B.disco_prefill(gm, gkv, tt.data_ptr() + 4 * pre, n, last, pws)
+    torch.cuda.synchronize()
+    ref = om.forward(toks[pre:pre + n], okv)
+    assert gkv.len == okv.len == pre + n
+    check_logits(last[None], ref[-1:], f"{what} prompt pass n={n} pre={pre}: last logits")
+    # later forwards read every cache entry the pass wrote
+    lg = torch.empty(5, shape.vocab, dtype=torch.float32, device=d)
+    B.disco_verify(gm, gkv, tt.data_ptr() + 4 * (pre + n), 1, am, lg, ws)
+    torch.cuda.synchronize()
+    check_logits(lg[:1], om.forward(toks[pre + n:pre + n + 1], okv), f"{what} 1-token forward after the pass")
+    B.disco_verify(gm, gkv, tt.data_ptr() + 4 * (pre + n + 1), 5, am, lg, ws)
+    torch.cuda.synchronize()
+    check_logits(lg, om.forward(toks[pre + n + 1:pre + n + 6], okv), f"{what} 5-token forward after the pass")
+    assert gkv.len == okv.len
+
+
+@pytest.mark.parametrize("n", [1, 15, 16, 17, 64, 100, 257])
+def test_prefill_small_model_lengths(n):
+    _prefill_case(SMALL_B, 11, n, what="B small")
+
+
+def test_prefill_offsets_pages_and_head_layouts():
+    _prefill_case(SMALL_B, 12, 50, pre=5, page=8, permute=True, what="B small, start 5, pages of 8 permuted")
+    _prefill_case(SMALL_B_GQA, 13, 70, pre=16, page=16, permute=True, what="B GQA")
+    _prefill_case(SMALL_B_GQA, 13, 33, pre=3, page=4, permute=True, what="B GQA pages of 4")
+    _prefill_case(SMALL_B_MQA128, 14, 130, pre=9, page=16, permute=False, what="B MQA d_head 128")
+
+
+def test_prefill_equals_blockwise_prompt_on_the_gpu():
+    """The dense pass and the prompt fed in blocks of 16 through the verification forward compute the
+    same function with different tilings and summation orders: the logits of a forward after either
+    must agree to fp32 rounding noise (far inside the parity bar)."""
+    shape = SMALL_B_GQA
+    n = 120
+    om, gm, okv, gkv, ws = setup_pair(shape, 15, page_tokens=8, permute=True, capacity=n + 40, gain_jitter=0.2, sigma=0.05)
+    gkv2 = B.DiscoKV(gm, n + 40, 16)                  # a second cache of the same model, other page size and order
+    d = dev()
+    toks = W.make_tokens(5, n + 4, shape.vocab).tolist()
+    tt = torch.tensor(toks, dtype=torch.int32, device=d)
+    am = torch.zeros(16, dtype=torch.int32, device=d)
+    B.disco_prefill(gm, gkv, tt, n, None, gm.prefill_workspace(n, n + 40))
+    for i in range(0, n, 16):
+        B.disco_verify(gm, gkv2, tt.data_ptr() + 4 * i, min(16, n - i), am, None, ws)
+    la = torch.empty(4, shape.vocab, dtype=torch.float32, device=d)
+    lb = torch.empty_like(la)
+    B.disco_verify(gm, gkv, tt.data_ptr() + 4 * n, 4, am, la, ws)
+    B.disco_verify(gm, gkv2, tt.data_ptr() + 4 * n, 4, am, lb, ws)
+    torch.cuda.synchronize()
+    scale = float(lb.abs().max())
+    assert float((la - lb).abs().max()) <= 1e-3 * scale
+    om.prefill(toks[:n], okv)
+    check_logits(la, om.forward(toks[n:n + 4], okv), "forward after the dense pass")
+
+
+def test_prefill_13b_shape_two_layers():
+    """The 13B-class layer shape at 512 prompt tokens (2 layers so that the oracle finishes in seconds),
+    in the launch configuration bench.py --prefill times; sampled check: the logits after the prompt and
+    of one later token."""
+    shape = W.scaled_shape(W.CFG2_TARGET, n_layers=2)
+    _prefill_case(shape, 0, 512, what="13B-shape x2 layers")
+
+
+def test_prefill_68m_shape():
+    _prefill_case(W.CFG1_DRAFT, 0, 300, pre=7, what="68M shape")
+
+
+def test_prefill_rejects_bad_arguments():
+    shape = SMALL_B
+    om, gm, okv, gkv, ws = setup_pair(shape, 11, capacity=64)
+    d = dev()
+    tt = torch.zeros(128, dtype=torch.int32, device=d)
+    pws = gm.prefill_workspace(64, 64)
+    with pytest.raises(B.DiscoError):                      # 70 tokens round up to 80 > capacity 64
+        B.disco_prefill(gm, gkv, tt, 70, None, pws)
+    with pytest.raises(B.DiscoError):
+        B.disco_prefill(gm, gkv, tt, 0, None, pws)
+    small = gm.workspace(16, 64)
+    with pytest.raises(B.DiscoError):                      # an ordinary workspace is too small
+        B.disco_prefill(gm, gkv, tt, 64, None, small)
+    assert gkv.len == 0
+    wa = W.make_weights(SMALL_A, 3, "bf16")
+    ga = B.DiscoModel(SMALL_A, wa, d)
+    kva = B.DiscoKV(ga, 64, 16)
+    with pytest.raises(B.DiscoError):                      # family A: no dense pass
+        B.disco_prefill(ga, kva, tt, 32, None, pws)
+
+
+def test_engine_uses_the_dense_pass_and_matches_the_oracle_loop():
+    st = W.ModelShape("B", 2, 128, 2, 64, 2, 256, 512)
+    sd = W.ModelShape("B", 1, 128, 2, 64, 2, 256, 512)
+    tw, dw = W.make_weights(st, 0, "bf16", sigma=0.1), W.make_weights(sd, 10, "bf16", sigma=0.1)
+    ot, od = O.Model(st, tw, kv_bf16=True), O.Model(sd, dw, kv_bf16=True)
+    clf = W.make_classifier(100)
+    prompt = W.make_prompt(3, 150, st.vocab).tolist()
+    n_new = 48
+    ref, margins = O.greedy_target(ot, prompt, n_new)
+    force = {"mask": W.make_force_mask(5, n_new, 0.6), "tokens": ref}
+    d = dev()
+    eng = SpecEngine(B.DiscoModel(st, tw, d), B.DiscoModel(sd, dw, d), B.DiscoClf(clf, d), max_ctx=220, page_tokens=16)
+    pol = {"mode": "disco", "tau": 0.55, "sl_max": 8, "pos_mode": "block"}
+    orc = O.spec_decode(ot, od, clf, prompt, n_new, pol, force=force)
+    runs = []
+    for dense in (True, False):
+        eng.reset()
+        eng.prefill(prompt[:-1], dense=dense)
+        runs.append(eng.generate(prompt, n_new, pol, force=force, do_prefill=False))
+    for gpu in runs:
+        for gi, oi in zip(gpu["iterations"], orc["iterations"]):
+            flagged = any(m < MARGIN for m in oi["target_margins"]) or any(
+                s["margin"] < MARGIN or abs(s["score"] - pol["tau"]) <= 1e-3 for s in oi["steps"])
+            if (gi["sl"], gi["n"], gi["block"], gi["emit"]) != (oi["sl"], oi["n"], oi["block"], oi["emit"]):
+                assert flagged
+                break
+        else:
+            assert gpu["tokens"] == orc["tokens"] == ref
