@@ -147,6 +147,64 @@ def micro(B, W, dev, reps):
     return out
 
 
+def prefill_bench(B, W, dev, reps):
+    """Prompt pass of both models at 512 / 1024 / 2048 tokens: the dense pass against the same prompt fed
+    in blocks of 16 through the verification forward.  Rates are ALGORITHMIC flops (2 per weight and
+    token in the projections and the LM head of the last token, 4 n ctx d_q / 2 causal attention flops
+    per layer; the bf16 hi + lo split of the activations is an implementation cost and not counted)
+    over wall time, against the dense bf16 matrix peak."""
+    MFMA_PEAK_TFLOPS = 2500.0
+
+    def flops(s, n):
+        mats = sum(int(torch.tensor(sh).prod()) for n_, sh, kind in W.weight_specs(s)
+                   if kind == "matrix" and n_ not in ("tok_emb", "pos_emb", "wlm"))
+        attn = s.n_layers * 4 * (n * (n + 1) // 2) * s.n_heads * s.d_head
+        return 2 * mats * n + attn + 2 * s.vocab * s.d_model
+
+    out = {"prefill": True, "reps": reps, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+           "mfma_peak_tflops": MFMA_PEAK_TFLOPS, "rows": []}
+    for name, shape, on_dev in (("68m_draft", W.CFG1_DRAFT, False), ("13b_target", W.CFG2_TARGET, True)):
+        gm = B.DiscoModel(shape, W.make_weights(shape, 0, "bf16", device=dev if on_dev else "cpu"), dev)
+        torch.cuda.empty_cache()
+        am = torch.zeros(B.MAX_BLOCK, dtype=torch.int32, device=dev)
+        for n in (512, 1024, 2048):
+            toks = W.make_prompt(1, n, shape.vocab).to(torch.int32).to(dev)
+            kv = B.DiscoKV(gm, n + 32, 16)
+            pws = gm.prefill_workspace(n, n + 32)
+            ws = gm.workspace(B.MAX_BLOCK, n + 32)
+
+            def dense():
+                B.disco_kv_rollback(kv, 0)
+                B.disco_prefill(gm, kv, toks, n, None, pws)
+
+            def blocks():
+                B.disco_kv_rollback(kv, 0)
+                for i in range(0, n, B.MAX_BLOCK):
+                    B.disco_verify(gm, kv, toks.data_ptr() + 4 * i, B.MAX_BLOCK, am, None, ws)
+
+            res = {}
+            for label, fn, r in (("dense", dense, reps), ("blocks", blocks, max(1, reps // 4))):
+                fn()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(r):
+                    fn()
+                torch.cuda.synchronize()
+                res[label] = (time.perf_counter() - t0) / r
+            fl = flops(shape, n)
+            row = {"model": name, "n_tokens": n, "dense_ms": 1e3 * res["dense"], "blocks_ms": 1e3 * res["blocks"],
+                   "speedup": res["blocks"] / res["dense"], "flops": fl, "dense_tflops": fl / res["dense"] / 1e12,
+                   "frac_of_mfma_peak": fl / res["dense"] / 1e12 / MFMA_PEAK_TFLOPS,
+                   "tokens_per_s": n / res["dense"]}
+            out["rows"].append(row)
+            log(f"[bench] prompt pass {name} n {n}: dense {row['dense_ms']:.2f} ms ({row['dense_tflops']:.0f} TFLOP/s), "
+                f"blocks of 16 {row['blocks_ms']:.2f} ms, x{row['speedup']:.2f}")
+            del kv, pws, ws
+        del gm
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -166,6 +224,10 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the single timed run: static lookahead 1..sl-max and DISCO halting on the same "
                          "prompt and forcing, one JSON line with a row per policy")
+    ap.add_argument("--prefill", action="store_true",
+                    help="instead of the loop: the prompt pass of the 68M-class and the 13B-class model at 512 / 1024 / 2048 "
+                         "tokens, dense pass against blocks of 16 through the verification forward; one JSON line "
+                         "(--steps = repetitions of the dense pass)")
     ap.add_argument("--micro", action="store_true",
                     help="instead of the loop: the draft-step micro-benchmark (68M-class shape, KV context 512 / 1024 / "
                          "2048) and the verification-block micro-benchmark (13B-class shape, context 1024, blocks of "
@@ -196,6 +258,9 @@ def main():
 
     if args.micro:
         print(json.dumps(micro(B, W, dev, args.steps)), flush=True)
+        return
+    if args.prefill:
+        print(json.dumps(prefill_bench(B, W, dev, args.steps)), flush=True)
         return
 
     target_shape = W.CFG2_TARGET if not args.layers else W.scaled_shape(W.CFG2_TARGET, n_layers=args.layers)

@@ -1929,88 +1929,23 @@ hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void*
 //
 // The prompt is processed before the first iteration (Sec. 2: the target model is given a prompt).
 // With hundreds of tokens per pass the GEMMs are bound by the matrix unit, not by the weight stream,
-// so the tiling differs from the skinny kernel: a wavefront owns 4 weight row tiles x 4 token groups
-// (sixteen 16 x 16 accumulators), walks the whole K range itself (no K split, no cross-wavefront
-// reduction) with NB register buffers of loads in flight, and every weight tile it fetches feeds 8
-// matrix instructions (hi and lo panel of 4 groups).  The four wavefronts of a workgroup take
-// neighbouring row tiles and the SAME token groups, so the activation tiles hit in the vector L1.
+// so the tiling differs from the skinny kernel: a wavefront owns RT weight row tiles x 4 token groups
+// (16 x 16 accumulators each), walks the whole K range itself (no K split, no cross-wavefront
+// reduction), and every weight tile it fetches feeds 8 matrix instructions (hi and lo panel of 4
+// groups).  The four wavefronts of a workgroup take neighbouring row tiles and the SAME token groups.
 // Workgroup ids are dealt round-robin to the 8 XCDs; the id -> (row block, token block) map gives all
 // token blocks of one row block to the same XCD, back to back, so that its L2 serves the weights to
 // every token block after the first.  Operand layouts, precision (bf16 hi + lo activations, fp32
 // accumulation) and epilogue arithmetic are those of the skinny kernel.
 
-template <int EPI, int NB>
-__global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
-  constexpr int RT = 4, CG = 4, NWV = 4;
+// Epilogues of the dense kernels for one wavefront: RT row tiles x CG token groups of accumulators.
+template <int EPI, int RT, int CG>
+__device__ __forceinline__ void dense_epilogue(const DenseArgs& d, const int cb, const int (&rt)[RT], f32x4 (&acc)[RT][CG]) {
   constexpr bool PAIR = EpiTraits<EPI>::pair;
   constexpr int UNITS = PAIR ? RT / 2 : RT, TPU = PAIR ? 2 : 1;
   constexpr bool NORMED = (EPI != EPI_PARTIAL);
   const GemmArgs& a = d.g;
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int n_tiles = a.n_rows >> 4;
-  const int ncb = (d.n_groups + CG - 1) / CG;
-  const int nrb = (n_tiles + RT * NWV - 1) / (RT * NWV);
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int rb = (slot / ncb) * 8 + xcd, cb = slot % ncb;
-  if (rb >= nrb) return;
-  const int b = rb * NWV + w;                    // this wavefront's group of RT row tiles
-  if (b * RT >= n_tiles) return;                 // (no workgroup barrier below)
-  int rt[RT];
-  if (PAIR) {
-#pragma unroll
-    for (int u = 0; u < UNITS; ++u) {
-      const int bp = b * UNITS + u;
-      rt[2 * u] = (bp / a.grp) * (2 * a.grp) + (bp % a.grp);
-      rt[2 * u + 1] = rt[2 * u] + a.grp;
-    }
-  } else {
-#pragma unroll
-    for (int r = 0; r < RT; ++r) rt[r] = b * RT + r;
-  }
-  const int KT = a.KT;
-  const u32x4* Wp[RT];
-#pragma unroll
-  for (int r = 0; r < RT; ++r) Wp[r] = reinterpret_cast<const u32x4*>(a.W) + (size_t)rt[r] * KT * 64 + lane;
-  // token groups past the end are clamped to the last one: loaded and multiplied, never stored
-  const u32x4* Xp[CG];
-#pragma unroll
-  for (int c = 0; c < CG; ++c) {
-    const int ci = min(cb * CG + c, d.n_groups - 1);
-    Xp[c] = reinterpret_cast<const u32x4*>(a.X + (size_t)ci * d.xs) + lane;
-  }
-  f32x4 acc[RT][CG];
-#pragma unroll
-  for (int r = 0; r < RT; ++r)
-#pragma unroll
-    for (int c = 0; c < CG; ++c) acc[r][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-  u32x4 A[NB][RT], Bh[NB][CG], Bl[NB][CG];
-  auto load = [&](u32x4 (&Ad)[RT], u32x4 (&Bhd)[CG], u32x4 (&Bld)[CG], const int kt) {
-    const size_t t = (size_t)(kt < KT ? kt : KT - 1) * 64;
-#pragma unroll
-    for (int r = 0; r < RT; ++r) Ad[r] = Wp[r][t];
-#pragma unroll
-    for (int c = 0; c < CG; ++c) { Bhd[c] = Xp[c][t]; Bld[c] = Xp[c][(size_t)KT * 64 + t]; }
-  };
-#pragma unroll
-  for (int i = 0; i < NB - 1; ++i) load(A[i], Bh[i], Bl[i], i);
-  for (int kt0 = 0; kt0 < KT; kt0 += NB) {
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int kt = kt0 + i;
-      if (kt < KT) {
-        load(A[(i + NB - 1) % NB], Bh[(i + NB - 1) % NB], Bl[(i + NB - 1) % NB], kt + NB - 1);
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-#pragma unroll
-          for (int c = 0; c < CG; ++c) {
-            acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(Bh[i][c]), acc[r][c], 0, 0, 0);
-            acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(Bl[i][c]), acc[r][c], 0, 0, 0);
-          }
-      }
-    }
-  }
-
+  const int lane = threadIdx.x & 63;
   const int m = lane & 15, g = lane >> 4;         // token column, 4-row group of the 16 x 16 result
 #pragma unroll
   for (int c = 0; c < CG; ++c) {
@@ -2049,22 +1984,116 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
   }
 }
 
+// The activation tiles are shared through LDS: wavefront w fetches the hi and lo tile
+// of token group w only (a quarter of the workgroup's activation tiles), a two-stage LDS ring hands
+// them to the other three, and the registers freed that way hold NB k-tiles of loads in flight.  One
+// workgroup barrier per k-tile; every wavefront runs the same trip count (idle ones compute on clamped
+// rows and store nothing).
+template <int EPI, int NB, int RT>
+__global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
+  constexpr int CG = 4, NWV = 4, NS = NB + 1;
+  constexpr bool PAIR = EpiTraits<EPI>::pair;
+  constexpr int UNITS = PAIR ? RT / 2 : RT;
+  __shared__ u32x4 bs[2][CG * 2][64];
+  const GemmArgs& a = d.g;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int n_tiles = a.n_rows >> 4;
+  const int ncb = (d.n_groups + CG - 1) / CG;
+  const int nrb = (n_tiles + RT * NWV - 1) / (RT * NWV);
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int rb = (slot / ncb) * 8 + xcd, cb = slot % ncb;
+  if (rb >= nrb) return;                          // whole workgroup
+  const bool live = (rb * NWV + w) * RT < n_tiles;
+  const int b = live ? rb * NWV + w : n_tiles / RT - 1;
+  int rt[RT];
+  if (PAIR) {
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) {
+      const int bp = b * UNITS + u;
+      rt[2 * u] = (bp / a.grp) * (2 * a.grp) + (bp % a.grp);
+      rt[2 * u + 1] = rt[2 * u] + a.grp;
+    }
+  } else {
+#pragma unroll
+    for (int r = 0; r < RT; ++r) rt[r] = b * RT + r;
+  }
+  const int KT = a.KT;
+  const u32x4* Wp[RT];
+#pragma unroll
+  for (int r = 0; r < RT; ++r) Wp[r] = reinterpret_cast<const u32x4*>(a.W) + (size_t)rt[r] * KT * 64 + lane;
+  const u32x4* Xw = reinterpret_cast<const u32x4*>(a.X + (size_t)min(cb * CG + w, d.n_groups - 1) * d.xs) + lane;
+  f32x4 acc[RT][CG];
+#pragma unroll
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int c = 0; c < CG; ++c) acc[r][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  u32x4 A[NS][RT], Bw[NS][2];
+  auto gload = [&](u32x4 (&Ad)[RT], u32x4 (&Bd)[2], const int kt) {
+    const size_t t = (size_t)(kt < KT ? kt : KT - 1) * 64;
+#pragma unroll
+    for (int r = 0; r < RT; ++r) Ad[r] = Wp[r][t];
+    Bd[0] = Xw[t]; Bd[1] = Xw[(size_t)KT * 64 + t];
+  };
+  static_assert(NB >= 2, "the slot refilled in an iteration must not be the one it hands to LDS");
+#pragma unroll
+  for (int i = 0; i < NB; ++i) gload(A[i], Bw[i], i);
+  bs[0][2 * w][lane] = Bw[0][0]; bs[0][2 * w + 1][lane] = Bw[0][1];
+  __syncthreads();
+  // Iteration kt: request k-tile kt + NB from memory, read the fragments of k-tile kt from LDS stage
+  // kt % 2, put this wavefront's share of k-tile kt + 1 into the other stage (its readers passed the
+  // barrier of the iteration before), run the matrix instructions of k-tile kt, barrier.
+  for (int kt0 = 0; kt0 < KT; kt0 += NS) {
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+      const int kt = kt0 + i;
+      if (kt < KT) {                              // uniform over the workgroup
+        gload(A[(i + NB) % NS], Bw[(i + NB) % NS], kt + NB);
+        u32x4 Bf[CG * 2];
+#pragma unroll
+        for (int t = 0; t < CG * 2; ++t) Bf[t] = bs[kt & 1][t][lane];
+        bs[(kt + 1) & 1][2 * w][lane] = Bw[(i + 1) % NS][0];
+        bs[(kt + 1) & 1][2 * w + 1][lane] = Bw[(i + 1) % NS][1];
+        // hi panels of all accumulators, then lo panels: no instruction reads the result of the one before it
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+#pragma unroll
+          for (int r = 0; r < RT; ++r)
+#pragma unroll
+            for (int c = 0; c < CG; ++c)
+              acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(Bf[2 * c + p]), acc[r][c], 0, 0, 0);
+        __syncthreads();
+      }
+    }
+  }
+  if (live) dense_epilogue<EPI, RT, CG>(d, cb, rt, acc);
+}
+
+template <int EPI>
+static hipError_t launch_gemm_dense_e(const DenseArgs& d, hipStream_t s) {
+  constexpr int NB = 5;                           // k-tiles of loads in flight per wavefront (measured best of 3..5)
+  const int n_tiles = d.g.n_rows / 16, ncb = (d.n_groups + 3) / 4;
+  // narrower row blocks when 64-row wavefront tiles would leave compute units without a workgroup
+  const bool wide = (long long)((n_tiles + 15) / 16) * ncb >= 256;
+  const int nrb = wide ? (n_tiles + 15) / 16 : (n_tiles + 7) / 8;
+  const long long blocks = (long long)((nrb + 7) / 8) * 8 * ncb;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)blocks);
+  if (wide) hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 4>), grid, dim3(256), 0, s, d);
+  else hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 2>), grid, dim3(256), 0, s, d);
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm_dense(const DenseArgs& d, int epi, hipStream_t s) {
   const GemmArgs& a = d.g;
   if (a.M != 16 || d.n_groups < 1 || a.KT < 1 || a.n_rows < 64 || (a.n_rows % 64) != 0) return hipErrorInvalidValue;
   if ((epi == EPI_QKV || epi == EPI_SWIGLU) && (a.grp < 1 || (a.n_rows / 32) % a.grp != 0)) return hipErrorInvalidValue;
-  const int n_tiles = a.n_rows / 16;
-  const int ncb = (d.n_groups + 3) / 4, nrb = (n_tiles + 15) / 16;
-  const long long blocks = (long long)((nrb + 7) / 8) * 8 * ncb;
-  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)blocks);
   switch (epi) {
-    case EPI_QKV: hipLaunchKernelGGL((k_gemm_dense<EPI_QKV, 2>), grid, dim3(256), 0, s, d); break;
-    case EPI_SWIGLU: hipLaunchKernelGGL((k_gemm_dense<EPI_SWIGLU, 2>), grid, dim3(256), 0, s, d); break;
-    case EPI_PARTIAL: hipLaunchKernelGGL((k_gemm_dense<EPI_PARTIAL, 2>), grid, dim3(256), 0, s, d); break;
+    case EPI_QKV: return launch_gemm_dense_e<EPI_QKV>(d, s);
+    case EPI_SWIGLU: return launch_gemm_dense_e<EPI_SWIGLU>(d, s);
+    case EPI_PARTIAL: return launch_gemm_dense_e<EPI_PARTIAL>(d, s);
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
 }
 
 // Embedding rows of the prompt pass: one workgroup per token slot; slots past the prompt's end hold
