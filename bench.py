@@ -147,7 +147,7 @@ def micro(B, W, dev, reps):
     return out
 
 
-def prefill_bench(B, W, dev, reps):
+def prefill_bench(B, W, dev, reps, models=("68m_draft", "13b_target"), lengths=(512, 1024, 2048)):
     """Prompt pass of both models at 512 / 1024 / 2048 tokens: the dense pass against the same prompt fed
     in blocks of 16 through the verification forward.  Rates are ALGORITHMIC flops (2 per weight and
     token in the projections and the LM head of the last token, 4 n ctx d_q / 2 causal attention flops
@@ -164,10 +164,12 @@ def prefill_bench(B, W, dev, reps):
     out = {"prefill": True, "reps": reps, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
            "mfma_peak_tflops": MFMA_PEAK_TFLOPS, "rows": []}
     for name, shape, on_dev in (("68m_draft", W.CFG1_DRAFT, False), ("13b_target", W.CFG2_TARGET, True)):
+        if name not in models:
+            continue
         gm = B.DiscoModel(shape, W.make_weights(shape, 0, "bf16", device=dev if on_dev else "cpu"), dev)
         torch.cuda.empty_cache()
         am = torch.zeros(B.MAX_BLOCK, dtype=torch.int32, device=dev)
-        for n in (512, 1024, 2048):
+        for n in lengths:
             toks = W.make_prompt(1, n, shape.vocab).to(torch.int32).to(dev)
             kv = B.DiscoKV(gm, n + 32, 16)
             pws = gm.prefill_workspace(n, n + 32)
@@ -228,6 +230,8 @@ def main():
                     help="instead of the loop: the prompt pass of the 68M-class and the 13B-class model at 512 / 1024 / 2048 "
                          "tokens, dense pass against blocks of 16 through the verification forward; one JSON line "
                          "(--steps = repetitions of the dense pass)")
+    ap.add_argument("--prefill-models", default="68m_draft,13b_target", help="models of --prefill (comma separated)")
+    ap.add_argument("--prefill-lengths", default="512,1024,2048", help="prompt lengths of --prefill (comma separated)")
     ap.add_argument("--micro", action="store_true",
                     help="instead of the loop: the draft-step micro-benchmark (68M-class shape, KV context 512 / 1024 / "
                          "2048) and the verification-block micro-benchmark (13B-class shape, context 1024, blocks of "
@@ -260,7 +264,8 @@ def main():
         print(json.dumps(micro(B, W, dev, args.steps)), flush=True)
         return
     if args.prefill:
-        print(json.dumps(prefill_bench(B, W, dev, args.steps)), flush=True)
+        print(json.dumps(prefill_bench(B, W, dev, args.steps, tuple(args.prefill_models.split(",")),
+                                       tuple(int(x) for x in args.prefill_lengths.split(",")))), flush=True)
         return
 
     target_shape = W.CFG2_TARGET if not args.layers else W.scaled_shape(W.CFG2_TARGET, n_layers=args.layers)
