@@ -163,7 +163,8 @@ def prefill_bench(B, W, dev, reps, models=("68m_draft", "13b_target"), lengths=(
 
     out = {"prefill": True, "reps": reps, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
            "mfma_peak_tflops": MFMA_PEAK_TFLOPS, "rows": []}
-    for name, shape, on_dev in (("68m_draft", W.CFG1_DRAFT, False), ("13b_target", W.CFG2_TARGET, True)):
+    for name, shape, on_dev in (("68m_draft", W.CFG1_DRAFT, False), ("13b_target", W.CFG2_TARGET, True),
+                                ("mqa_draft", W.CFG3_DRAFT, False), ("15b_mqa_target", W.CFG3_TARGET, True)):
         if name not in models:
             continue
         gm = B.DiscoModel(shape, W.make_weights(shape, 0, "bf16", device=dev if on_dev else "cpu"), dev)
@@ -230,7 +231,8 @@ def main():
                     help="instead of the loop: the prompt pass of the 68M-class and the 13B-class model at 512 / 1024 / 2048 "
                          "tokens, dense pass against blocks of 16 through the verification forward; one JSON line "
                          "(--steps = repetitions of the dense pass)")
-    ap.add_argument("--prefill-models", default="68m_draft,13b_target", help="models of --prefill (comma separated)")
+    ap.add_argument("--prefill-models", default="68m_draft,13b_target",
+                    help="models of --prefill, comma separated, of 68m_draft, 13b_target, mqa_draft, 15b_mqa_target")
     ap.add_argument("--prefill-lengths", default="512,1024,2048", help="prompt lengths of --prefill (comma separated)")
     ap.add_argument("--micro", action="store_true",
                     help="instead of the loop: the draft-step micro-benchmark (68M-class shape, KV context 512 / 1024 / "

@@ -326,8 +326,9 @@ int disco_clf_eval(const disco_clf* clf, const float* dev_feats, const int32_t* 
  * <= its own.  Appends n_tokens KV entries (kv->len += n_tokens).  dev_logits_last (may be NULL):
  * fp32 [vocab], the logits after the last prompt token.  The pass works on groups of 16 tokens: the
  * cache needs capacity for kv->len + 16 * ceil(n_tokens / 16) positions (entries beyond the new
- * kv->len are scratch, as always).  Family B models only (DISCO_EINVAL otherwise: feed the prompt
- * through disco_verify in blocks instead).  dev_ws: device buffer of at least
+ * kv->len are scratch, as always); the projection widths (d_q + 2 d_kv, and 2 d_ff or d_ff) must be
+ * multiples of 64 (DISCO_EINVAL otherwise: feed such a model's prompt through disco_verify in blocks
+ * instead).  dev_ws: device buffer of at least
  * disco_prefill_workspace_bytes(m, n_tokens, max_ctx >= kv->len + 16 * ceil(n_tokens / 16)) bytes,
  * 256-byte aligned, initialised once with disco_workspace_init (which zeroes the ticket counters at
  * its start; they sit at the offsets of an ordinary workspace).  Errors: EINVAL, ECAP, ESTATE, EHIP. */

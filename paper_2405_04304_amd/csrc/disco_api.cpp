@@ -262,13 +262,15 @@ int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   if (!m || !kv || !dev_tokens || !dev_ws) return fail(DISCO_EINVAL, "null argument");
   if (kv->model != m) return fail(DISCO_ESTATE, "KV cache belongs to another model");
   const disco_model_desc& d = m->d;
-  if (d.family != DISCO_FAMILY_B) return fail(DISCO_EINVAL, "the dense prompt pass supports family B models only");
+  const bool fam_a = d.family == DISCO_FAMILY_A;
   if (n_tokens < 1 || n_tokens > DISCO_PREFILL_MAX) return fail(DISCO_ECAP, "prompt of %d tokens outside [1, %d]", n_tokens, DISCO_PREFILL_MAX);
   const int G = (n_tokens + 15) / 16, pos0 = kv->len;
   if (pos0 + 16 * G > kv->capacity)
     return fail(DISCO_ECAP, "KV capacity %d below len %d + %d (the prompt rounded up to groups of 16)", kv->capacity, pos0, 16 * G);
+  if (fam_a && pos0 + n_tokens > d.max_pos) return fail(DISCO_ECAP, "position table of %d rows exceeded", d.max_pos);
   if (!aligned(dev_tokens, 4) || !aligned(dev_ws, 256) || !aligned(dev_logits_last, 16)) return fail(DISCO_EINVAL, "misaligned pointer");
-  if (m->d_qkv % 64 || (2 * d.d_ff) % 64) return fail(DISCO_EINVAL, "projection widths must be multiples of 64");
+  const int n_in = fam_a ? d.d_ff : 2 * d.d_ff;      // rows of the MLP input matrix
+  if (m->d_qkv % 64 || n_in % 64) return fail(DISCO_EINVAL, "projection widths must be multiples of 64 for the prompt pass");
   const size_t need = carve_prefill(m, G, pos0 + 16 * G, nullptr).total;
   if (ws_bytes < need) return fail(DISCO_EINVAL, "workspace of %zu bytes, %zu needed", ws_bytes, need);
   const PfWs ws = carve_prefill(m, G, pos0 + 16 * G, dev_ws);
@@ -280,27 +282,42 @@ int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   const int n_tiles = d.d_model / 16;
   const size_t xs_d = (size_t)32 * d.d_model, xs_q = (size_t)32 * m->d_q, xs_ff = (size_t)32 * d.d_ff;
 
-  EmbedArgs ea{};
-  ea.tokens = dev_tokens; ea.n = n_tokens; ea.vocab = d.vocab; ea.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb);
-  ea.tok_stride = m->w.tok_emb_stride; ea.d = d.d_model; ea.gain = m->layers[0].norm1_g; ea.h = ws.h; ea.Xout = ws.xn;
-  ea.ssq_out = ws.ssq; ea.n_ssq_out = n_tiles;
-  HIP_TRY(launch_embed_groups(ea, G, st), "embedding launch");
-
+  // Family B defers every RMSNorm into the consumer GEMM (gain * h panels and per-tile sums of squares
+  // from the producer, one 1 / rms per row from k_rstd_groups); family A runs LayerNorm launches.
+  NormArgs na{};
+  na.h = ws.h; na.d = d.d_model; na.M = 16; na.n_groups = G; na.layernorm = fam_a; na.eps = d.norm_eps;
+  na.Xout = ws.xn; na.pos0 = pos0; na.vocab = d.vocab; na.max_pos = d.max_pos;
+  if (!fam_a) { na.ssq_out = ws.ssq; na.n_ssq_out = n_tiles; }
+  {
+    NormArgs n0 = na;
+    n0.g = m->layers[0].norm1_g; n0.b = m->layers[0].norm1_b;
+    n0.tokens = dev_tokens; n0.n_tok = n_tokens; n0.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb);
+    n0.tok_stride = m->w.tok_emb_stride; n0.pos_emb = static_cast<const bf16_t*>(m->w.pos_emb);
+    HIP_TRY(launch_norm(n0, st), "embedding launch");
+  }
   auto dense = [&](const void* w, const bf16_t* x, size_t xs, int k, int n_rows) {
     DenseArgs a{};
     a.g.M = 16; a.g.W = static_cast<const bf16_t*>(w); a.g.X = x; a.g.KT = k / 32; a.g.n_rows = n_rows; a.g.grp = 1;
     a.g.only_row = -1; a.n_groups = G; a.xs = xs;
     return a;
   };
+  auto residual_update = [&](DenseArgs& a, const float* next_gain) {
+    a.g.h = ws.h; a.hs = (size_t)16 * d.d_model; a.g.ld_out = d.d_model;
+    if (!fam_a) {
+      a.g.gain = next_gain; a.g.Xout = ws.xn; a.xouts = xs_d; a.g.KT_out = d.d_model / 32;
+      a.g.ssq_out = ws.ssq; a.ssq_outs = (size_t)n_tiles * 16;
+    }
+  };
   for (int l = 0; l < d.n_layers; ++l) {
     const disco_layer_weights& L = m->layers[l];
     const bool last = (l + 1 == d.n_layers);
     const float* next_g = last ? m->w.normf_g : m->layers[l + 1].norm1_g;
+    const float* next_b = last ? m->w.normf_b : m->layers[l + 1].norm1_b;
     bf16_t* kv_layer = kv->pages + (size_t)l * kv->layer_stride;
 
-    HIP_TRY(launch_rstd_groups(ws.ssq, n_tiles, d.d_model, d.norm_eps, ws.rstd, G, st), "rstd launch");
+    if (!fam_a) HIP_TRY(launch_rstd_groups(ws.ssq, n_tiles, d.d_model, d.norm_eps, ws.rstd, G, st), "rstd launch");
     DenseArgs qa = dense(L.wqkv, ws.xn, xs_d, d.d_model, m->d_qkv);
-    qa.rstd = ws.rstd; qa.g.grp = d.d_head / 32; qa.g.q = ws.q; qa.qs = (size_t)16 * m->d_q; qa.g.ldq = m->d_q;
+    qa.rstd = fam_a ? nullptr : ws.rstd; qa.g.grp = d.d_head / 32; qa.g.q = ws.q; qa.qs = (size_t)16 * m->d_q; qa.g.ldq = m->d_q;
     qa.g.nq = d.n_heads; qa.g.nkv = d.n_kv_heads; qa.g.dh = d.d_head; qa.g.pos0 = pos0; qa.g.rope_tab = kv->dev_rope;
     qa.g.kv_layer = kv_layer; qa.g.page_table = kv->dev_page_table; qa.g.page_tokens = kv->page_tokens;
     HIP_TRY(launch_gemm_dense(qa, EPI_QKV, st), "qkv launch");
@@ -312,26 +329,36 @@ int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     HIP_TRY(launch_attn_groups(at, G, xs_q, st), "attention launch");
 
     DenseArgs oa = dense(L.wo, ws.xattn, xs_q, m->d_q, d.d_model);
-    oa.g.h = ws.h; oa.hs = (size_t)16 * d.d_model; oa.g.ld_out = d.d_model; oa.g.gain = L.norm2_g;
-    oa.g.Xout = ws.xn; oa.xouts = xs_d; oa.g.KT_out = d.d_model / 32; oa.g.ssq_out = ws.ssq; oa.ssq_outs = (size_t)n_tiles * 16;
+    residual_update(oa, L.norm2_g);
     HIP_TRY(launch_gemm_dense(oa, EPI_PARTIAL, st), "o-proj launch");
 
-    HIP_TRY(launch_rstd_groups(ws.ssq, n_tiles, d.d_model, d.norm_eps, ws.rstd, G, st), "rstd launch");
-    DenseArgs ua = dense(L.w_in, ws.xn, xs_d, d.d_model, 2 * d.d_ff);
-    ua.rstd = ws.rstd; ua.g.Xout = ws.xact; ua.xouts = xs_ff; ua.g.KT_out = d.d_ff / 32;
-    HIP_TRY(launch_gemm_dense(ua, EPI_SWIGLU, st), "mlp-in launch");
+    if (fam_a) {
+      NormArgs n2 = na;
+      n2.g = L.norm2_g; n2.b = L.norm2_b;
+      HIP_TRY(launch_norm(n2, st), "norm launch");
+    } else {
+      HIP_TRY(launch_rstd_groups(ws.ssq, n_tiles, d.d_model, d.norm_eps, ws.rstd, G, st), "rstd launch");
+    }
+    DenseArgs ua = dense(L.w_in, ws.xn, xs_d, d.d_model, n_in);
+    ua.rstd = fam_a ? nullptr : ws.rstd; ua.g.Xout = ws.xact; ua.xouts = xs_ff; ua.g.KT_out = d.d_ff / 32;
+    HIP_TRY(launch_gemm_dense(ua, fam_a ? EPI_GELU : EPI_SWIGLU, st), "mlp-in launch");
 
     DenseArgs da = dense(L.w_out, ws.xact, xs_ff, d.d_ff, d.d_model);
-    da.g.h = ws.h; da.hs = (size_t)16 * d.d_model; da.g.ld_out = d.d_model; da.g.gain = next_g;
-    da.g.Xout = ws.xn; da.xouts = xs_d; da.g.KT_out = d.d_model / 32; da.g.ssq_out = ws.ssq; da.ssq_outs = (size_t)n_tiles * 16;
+    residual_update(da, next_g);
     HIP_TRY(launch_gemm_dense(da, EPI_PARTIAL, st), "mlp-out launch");
+
+    if (fam_a && (!last || dev_logits_last)) {
+      NormArgs n3 = na;
+      n3.g = next_g; n3.b = next_b;
+      HIP_TRY(launch_norm(n3, st), "norm launch");
+    }
   }
   if (dev_logits_last) {
     // logits of the prompt's last token: the skinny LM head on the last group's panels
     GemmArgs lm{};
     lm.M = 16; lm.planes = ws.base.gpart; lm.counters = ws.base.gemm_counters;
     lm.W = static_cast<const bf16_t*>(m->w.wlm); lm.X = ws.xn + (size_t)(G - 1) * xs_d; lm.KT = d.d_model / 32;
-    lm.ssq = ws.ssq + (size_t)(G - 1) * n_tiles * 16; lm.n_ssq = n_tiles; lm.d_in = d.d_model; lm.eps = d.norm_eps;
+    if (!fam_a) { lm.ssq = ws.ssq + (size_t)(G - 1) * n_tiles * 16; lm.n_ssq = n_tiles; lm.d_in = d.d_model; lm.eps = d.norm_eps; }
     lm.n_rows = d.vocab; lm.out = dev_logits_last; lm.ld_out = d.vocab; lm.only_row = (n_tokens - 1) % 16;
     HIP_TRY(launch_gemm(lm, EPI_STORE, st), "lm-head launch");
   }

@@ -56,12 +56,6 @@ struct DenseArgs {
   const float* rstd;    // [group][16]: 1 / rms of the input rows (epilogues that read a normalised input)
 };
 
-// Embedding of n tokens into groups of 16 (family B): residual rows, gain * h panels, sums of squares.
-struct EmbedArgs {
-  const int32_t* tokens; int n; int vocab; const bf16_t* tok_emb; int64_t tok_stride;
-  int d; const float* gain; float* h; bf16_t* Xout; float* ssq_out; int n_ssq_out;
-};
-
 struct NormArgs {
   float* h; int d; int M; int layernorm; float eps;
   const float* g; const float* b;
@@ -71,6 +65,8 @@ struct NormArgs {
   const int32_t* tokens; const bf16_t* tok_emb; int64_t tok_stride; const bf16_t* pos_emb;
   int pos0; int vocab; int max_pos;
   const uint32_t* gate;
+  // prompt pass: n_groups > 0 launches 16 * n_groups token slots (M == 16); slots >= n_tok embed token 0
+  int n_groups; int n_tok;
 };
 
 struct AttnArgs {
@@ -133,7 +129,6 @@ hipError_t launch_norm(const NormArgs& a, hipStream_t s);
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
 // dense prompt pass (groups of 16 tokens; every group holds 16 rows, surplus rows are padding)
 hipError_t launch_gemm_dense(const DenseArgs& a, int epi, hipStream_t s);
-hipError_t launch_embed_groups(const EmbedArgs& a, int n_groups, hipStream_t s);
 hipError_t launch_rstd_groups(const float* ssq, int n_ssq, int d, float eps, float* rstd, int n_groups, hipStream_t s);
 hipError_t launch_attn_groups(const AttnArgs& a, int n_groups, size_t x_stride, hipStream_t s);
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s);

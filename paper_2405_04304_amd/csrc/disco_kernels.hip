@@ -594,14 +594,17 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
   if (gated(a.gate)) return;
   constexpr int VPT = 2;                       // float4 per thread: d <= NT * 8
   __shared__ float red[NT / 64 + 1];
-  const int m = blockIdx.x, t = threadIdx.x, d = a.d;
-  float* h = a.h + (size_t)m * d;
+  // row = token slot; slots beyond 16 belong to further groups of 16 (prompt pass), whose panels and
+  // sums of squares follow those of group 0
+  const int row = blockIdx.x, m = row & 15, grp = row >> 4, t = threadIdx.x, d = a.d;
+  float* h = a.h + (size_t)row * d;
+  bf16_t* Xout = a.Xout + (size_t)grp * d * 32;
   float4 v[VPT];
   const bf16_t* e = nullptr; const bf16_t* pe = nullptr;
   if (a.tokens) {
-    int tok = a.tokens[m];
+    int tok = (a.n_tok == 0 || row < a.n_tok) ? a.tokens[row] : 0;       // padding slots: token 0
     tok = tok < 0 ? 0 : (tok >= a.vocab ? a.vocab - 1 : tok);
-    int pos = a.pos0 + m;
+    int pos = a.pos0 + row;
     if (pos >= a.max_pos) pos = a.max_pos - 1;
     e = a.tok_emb + (size_t)tok * a.tok_stride;
     pe = a.pos_emb ? a.pos_emb + (size_t)pos * d : nullptr;
@@ -631,7 +634,8 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
 #pragma unroll
     for (int i = 0; i < VPT; ++i) ss += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
     ss = block_sum<NT>(ss, red);
-    for (int i = t; i < a.n_ssq_out; i += NT) a.ssq_out[i * 16 + m] = (i == 0) ? ss : 0.f;   // [slot][token]
+    float* sq = a.ssq_out + (size_t)grp * a.n_ssq_out * 16;
+    for (int i = t; i < a.n_ssq_out; i += NT) sq[i * 16 + m] = (i == 0) ? ss : 0.f;          // [slot][token]
     const int KT = d >> 5;
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
@@ -639,7 +643,7 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
       if (k < d) {
         const float4 g = *reinterpret_cast<const float4*>(a.g + k);
         const float o[4] = {v[i].x * g.x, v[i].y * g.y, v[i].z * g.z, v[i].w * g.w};
-        xpack_store4(a.Xout, KT, a.M, m, k, o);
+        xpack_store4(Xout, KT, a.M, m, k, o);
       }
     }
     return;
@@ -672,15 +676,18 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
         const float4 bb = *reinterpret_cast<const float4*>(a.b + k);
         o[0] += bb.x; o[1] += bb.y; o[2] += bb.z; o[3] += bb.w;
       }
-      xpack_store4(a.Xout, KT, a.M, m, k, o);
+      xpack_store4(Xout, KT, a.M, m, k, o);
     }
   }
 }
 
 hipError_t launch_norm(const NormArgs& a, hipStream_t s) {
   if (a.M < 1 || a.M > 16 || (a.d & 31) || a.d > 8192) return hipErrorInvalidValue;
-  if (a.d <= 2048) hipLaunchKernelGGL(k_norm<256>, dim3(a.M), dim3(256), 0, s, a);
-  else hipLaunchKernelGGL(k_norm<1024>, dim3(a.M), dim3(1024), 0, s, a);
+  // prompt pass: n_groups groups of 16 slots each (then M == 16: two-panel layout)
+  if (a.n_groups < 0 || (a.n_groups > 0 && a.M != 16)) return hipErrorInvalidValue;
+  const unsigned rows = a.n_groups > 0 ? 16u * (unsigned)a.n_groups : (unsigned)a.M;
+  if (a.d <= 2048) hipLaunchKernelGGL(k_norm<256>, dim3(rows), dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(k_norm<1024>, dim3(rows), dim3(1024), 0, s, a);
   return hipGetLastError();
 }
 
@@ -1964,11 +1971,18 @@ __device__ __forceinline__ void dense_epilogue(const DenseArgs& d, const int cb,
         float4 h = *hp;
         h.x += y0[0]; h.y += y0[1]; h.z += y0[2]; h.w += y0[3];
         *hp = h;
-        const float4 gn = *reinterpret_cast<const float4*>(a.gain + col);
-        const float o[4] = {h.x * gn.x, h.y * gn.y, h.z * gn.z, h.w * gn.w};
-        xpack_store4(a.Xout + (size_t)ci * d.xouts, a.KT_out, 16, m, col, o);
-        const float sq = row4_sum((h.x * h.x + h.y * h.y) + (h.z * h.z + h.w * h.w));
-        if (g == 0) a.ssq_out[(size_t)ci * d.ssq_outs + t0 * 16 + m] = sq;      // [slot][token]
+        if (a.Xout != nullptr) {                  // deferred RMSNorm of the next GEMM (LayerNorm models: a norm launch instead)
+          const float4 gn = *reinterpret_cast<const float4*>(a.gain + col);
+          const float o[4] = {h.x * gn.x, h.y * gn.y, h.z * gn.z, h.w * gn.w};
+          xpack_store4(a.Xout + (size_t)ci * d.xouts, a.KT_out, 16, m, col, o);
+          const float sq = row4_sum((h.x * h.x + h.y * h.y) + (h.z * h.z + h.w * h.w));
+          if (g == 0) a.ssq_out[(size_t)ci * d.ssq_outs + t0 * 16 + m] = sq;    // [slot][token]
+        }
+      } else if (EPI == EPI_GELU) {
+        float act[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) act[v] = 0.5f * y0[v] * (1.0f + erff(y0[v] * 0.70710678118654752f));
+        xpack_store4(a.Xout + (size_t)ci * d.xouts, a.KT_out, 16, m, t0 * 16 + 4 * g, act);
       } else if (EPI == EPI_QKV) {
         float lo4[4] = {y0[0], y0[1], y0[2], y0[3]}, hi4[4] = {y1[0], y1[1], y1[2], y1[3]};
         qkv_store(a, a.q + (size_t)ci * d.qs, t0 * 16 + 4 * g, m, a.pos0 + 16 * ci + m, lo4, hi4);
@@ -2092,41 +2106,9 @@ hipError_t launch_gemm_dense(const DenseArgs& d, int epi, hipStream_t s) {
     case EPI_QKV: return launch_gemm_dense_e<EPI_QKV>(d, s);
     case EPI_SWIGLU: return launch_gemm_dense_e<EPI_SWIGLU>(d, s);
     case EPI_PARTIAL: return launch_gemm_dense_e<EPI_PARTIAL>(d, s);
+    case EPI_GELU: return launch_gemm_dense_e<EPI_GELU>(d, s);
     default: return hipErrorInvalidValue;
   }
-}
-
-// Embedding rows of the prompt pass: one workgroup per token slot; slots past the prompt's end hold
-// token 0 (padding: computed, never used).  Writes the residual row, the gain * h panels of the first
-// RMSNorm'ed GEMM and the row's sum of squares (slot 0; the other slots are zeroed).
-__global__ __launch_bounds__(256) void k_embed_groups(EmbedArgs a) {
-  __shared__ float red[256 / 64 + 1];
-  const int idx = blockIdx.x, r = idx >> 4, m = idx & 15, t = threadIdx.x, d = a.d;
-  int tok = idx < a.n ? a.tokens[idx] : 0;
-  tok = tok < 0 ? 0 : (tok >= a.vocab ? a.vocab - 1 : tok);
-  const bf16_t* e = a.tok_emb + (size_t)tok * a.tok_stride;
-  float* h = a.h + (size_t)idx * d;
-  bf16_t* X = a.Xout + (size_t)r * (size_t)d * 32;             // two panels of d * 16 elements per group
-  const int KT = d >> 5;
-  float ss = 0.f;
-  for (int k = t * 4; k < d; k += 256 * 4) {
-    const uint2 u = *reinterpret_cast<const uint2*>(e + k);
-    const float4 v = make_float4(bf16_to_f32(u.x & 0xFFFF), bf16_to_f32(u.x >> 16), bf16_to_f32(u.y & 0xFFFF), bf16_to_f32(u.y >> 16));
-    *reinterpret_cast<float4*>(h + k) = v;
-    ss += (v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w);
-    const float4 gn = *reinterpret_cast<const float4*>(a.gain + k);
-    const float o[4] = {v.x * gn.x, v.y * gn.y, v.z * gn.z, v.w * gn.w};
-    xpack_store4(X, KT, 16, m, k, o);
-  }
-  ss = block_sum<256>(ss, red);
-  float* sq = a.ssq_out + (size_t)r * a.n_ssq_out * 16;
-  for (int i = t; i < a.n_ssq_out; i += 256) sq[i * 16 + m] = (i == 0) ? ss : 0.f;
-}
-
-hipError_t launch_embed_groups(const EmbedArgs& a, int n_groups, hipStream_t s) {
-  if (n_groups < 1 || (a.d & 31) || a.n < 1 || a.n > 16 * n_groups) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(k_embed_groups, dim3(16 * n_groups), dim3(256), 0, s, a);
-  return hipGetLastError();
 }
 
 // 1 / rms of every row of the prompt pass from its per-tile sums of squares, added in slot order.

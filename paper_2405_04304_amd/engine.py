@@ -49,14 +49,14 @@ class SpecEngine:
             B.disco_kv_rollback(self.kv_d, 0)
 
     def prefill(self, tokens: Sequence[int], dense: Optional[bool] = None) -> None:
-        """Feed the prompt through both models: one dense pass per model (family B, 32 tokens or more),
-        otherwise blocks of DISCO_MAX_BLOCK tokens through the verification forward.  dense=True / False
-        forces one of the two."""
+        """Feed the prompt through both models: one dense pass per model (32 tokens or more), otherwise
+        blocks of DISCO_MAX_BLOCK tokens through the verification forward.  dense=True / False forces one
+        of the two."""
         toks = torch.as_tensor(list(tokens), dtype=torch.int32).to(self.dev)
         n_all = len(tokens)
         for model, kv, ws in ((self.target, self.kv_t, self.ws_t),) + (
                 ((self.draft, self.kv_d, self.ws_d),) if self.draft is not None else ()):
-            use_dense = dense if dense is not None else (model.shape.family == "B" and n_all >= 32)
+            use_dense = dense if dense is not None else n_all >= 32
             if use_dense and n_all > 0:
                 for i in range(0, n_all, B.PREFILL_MAX):
                     n = min(B.PREFILL_MAX, n_all - i)

@@ -194,10 +194,17 @@ def test_prefill_rejects_bad_arguments_before_any_launch():
     assert lib.disco_prefill(m, kv, FAKE, 64, None, FAKE, need - 256, None) == B.EINVAL
     assert lib.disco_prefill(m, kv, FAKE + 2, 16, None, FAKE, need, None) == B.EINVAL
     assert lib.disco_kv_len(kv) == 0
-    rc, ma = _model(family=0)
+    rc, ma = _model(family=0, max_pos=48)
     rc, kva, _ = _kv(ma, capacity=64, page=16)
-    assert lib.disco_prefill(ma, kva, FAKE, 16, None, FAKE, need, None) == B.EINVAL   # family A has no dense pass
+    need_a = lib.disco_prefill_workspace_bytes(ma, 64, 64)
+    assert lib.disco_prefill(ma, kva, FAKE, 64, None, FAKE, need_a, None) == B.ECAP    # learned position table of 48 rows
+    assert "position" in B.last_error()
     assert lib.disco_prefill(m, kva, FAKE, 16, None, FAKE, need, None) == B.ESTATE     # cache of another model
+    rc, mo = _model(family=0, d_ff=96)                     # family A: d_ff itself must be a multiple of 64
+    rc, kvo, _ = _kv(mo, capacity=64, page=16)
+    assert lib.disco_prefill(mo, kvo, FAKE, 16, None, FAKE, lib.disco_prefill_workspace_bytes(mo, 16, 64), None) == B.EINVAL
+    lib.disco_kv_destroy(kvo)
+    lib.disco_model_destroy(mo)
     for h in (kv, kva):
         lib.disco_kv_destroy(h)
     for h in (m, ma):
