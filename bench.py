@@ -227,6 +227,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the single timed run: static lookahead 1..sl-max and DISCO halting on the same "
                          "prompt and forcing, one JSON line with a row per policy")
+    ap.add_argument("--grid", action="store_true",
+                    help="with --sweep: also the trained classifier over thresholds 0.3 / 0.5 / 0.7 x lookahead caps 5 / 10 / 15")
     ap.add_argument("--prefill", action="store_true",
                     help="instead of the loop: the prompt pass of the 68M-class and the 13B-class model at 512 / 1024 / 2048 "
                          "tokens, dense pass against blocks of 16 through the verification forward; one JSON line "
@@ -355,6 +357,10 @@ def main():
             if rate > best_rate:
                 best_thr, best_rate = thr, rate
         pols.append({"mode": "ppl", "threshold": best_thr, "sl_max": args.sl_max})
+        if args.grid:
+            # threshold x lookahead-cap grid for the trained classifier (the structure of the paper's Table 5)
+            pols += [{"mode": "disco", "tau": t, "sl_max": c, "pos_mode": "absolute", "classifier": "trained", "grid": True}
+                     for t in (0.3, 0.5, 0.7) for c in (5, 10, 15) if (t, c) != (args.tau, args.sl_max)]
         for pol in pols:
             stamps = []
 
