@@ -30,7 +30,7 @@ def dev():
     return torch.device("cuda:0")
 
 
-def check_logits(got: torch.Tensor, ref: torch.Tensor, what=""):
+def check_logits(got: torch.Tensor, ref: torch.Tensor, what="", tight=REL_TIGHT):
     got, ref = got.detach().cpu().double(), ref.double()
     assert got.shape == ref.shape
     assert torch.isfinite(got).all(), what
@@ -40,8 +40,8 @@ def check_logits(got: torch.Tensor, ref: torch.Tensor, what=""):
         scale = float(ref[r].abs().max())
         worst = max(worst, err / scale)
         assert err <= REL_TOL * scale, (what, r, err, scale)
-        assert err <= REL_TIGHT * scale, (what, "tight", r, err, scale)
-    print(f"[parity] {what}: max rel err {worst:.3e} (bar {REL_TOL}, tight {REL_TIGHT})", flush=True)
+        assert err <= tight * scale, (what, "tight", r, err, scale)
+    print(f"[parity] {what}: max rel err {worst:.3e} (bar {REL_TOL}, tight {tight})", flush=True)
     return worst
 
 
@@ -490,7 +490,8 @@ def test_loop_rule_based_baselines_match_oracle():
 
 def test_verify_13b_full_depth_block_of_11():
     """The verification forward exactly as bench.py launches it: 40 layers of the 13B shape, block of
-    11 tokens, ctx 512, weights drawn on the device; the oracle gets the same bytes."""
+    11 tokens, ctx 512, weights drawn on the device; the oracle gets the same bytes.  Then the dense prompt
+    pass on the same model (the weights take a while to draw: one test for both)."""
     shape = W.CFG2_TARGET
     d = dev()
     w = W.make_weights(shape, 0, "bf16", device=d)
@@ -523,6 +524,45 @@ def test_verify_13b_full_depth_block_of_11():
     check_argmax(am[:M].tolist(), ref, "13B full depth")
     n_flag = sum(1 for r in range(M) if O.top2_margin(ref[r]) < MARGIN)
     print(f"[parity] 13B full depth: {n_flag} of {M} rows flagged by the top-2 margin", flush=True)
+    # The prompt pass at full depth.  Against the oracle on a prompt it can walk in seconds (48 tokens, then a
+    # 4-token block that reads the cache the pass wrote), and, at the size bench.py --prefill times (512
+    # tokens), as a property: the dense pass and the same prompt in blocks of 16 through the forward verified
+    # above must leave caches that give the same logits for a later block.  With 40 layers of freshly
+    # computed bf16 keys and values (no exact pre-filled entries) every path sits at 3e-3 .. 4e-3 from
+    # the oracle and from the other path (neighbouring-bf16 roundings of K and V, amplified layer by layer):
+    # inside the stated bar of 2e-2, above the 2e-3 regression bar of the shallow cases; held to 8e-3 here.
+    deep_bar = 8e-3
+    n0 = 48
+    toks = W.make_prompt(1, 512 + 4, shape.vocab).to(torch.int32)
+    tt = toks.to(d)
+    kv0 = B.DiscoKV(gm, n0 + 32, 16)
+    ws0 = gm.workspace(16, n0 + 32)
+    print("[parity] 13B full depth: dense prompt pass of 48 tokens", flush=True)
+    last = torch.empty(shape.vocab, dtype=torch.float32, device=d)
+    B.disco_prefill(gm, kv0, tt, n0, last, gm.prefill_workspace(n0, n0 + 32))
+    l4 = torch.empty(4, shape.vocab, dtype=torch.float32, device=d)
+    B.disco_verify(gm, kv0, tt.data_ptr() + 4 * n0, 4, am, l4, ws0)
+    torch.cuda.synchronize()
+    okv0 = om.new_cache(n0 + 32)
+    ref0 = om.forward(toks[:n0].tolist(), okv0)
+    check_logits(last[None], ref0[-1:], "prompt pass 13B x40 layers n 48: last logits", tight=deep_bar)
+    check_logits(l4, om.forward(toks[n0:n0 + 4].tolist(), okv0), "13B x40 layers: block after the prompt pass", tight=deep_bar)
+    n = 512
+    kv_a, kv_b = B.DiscoKV(gm, n + 32, 16), B.DiscoKV(gm, n + 32, 16)
+    ws2 = gm.workspace(16, n + 32)
+    print("[parity] 13B full depth: dense prompt pass of 512 tokens", flush=True)
+    B.disco_prefill(gm, kv_a, tt, n, None, gm.prefill_workspace(n, n + 32))
+    for i in range(0, n, 16):
+        B.disco_verify(gm, kv_b, tt.data_ptr() + 4 * i, 16, am, None, ws2)
+    la = torch.empty(4, shape.vocab, dtype=torch.float32, device=d)
+    lb = torch.empty_like(la)
+    B.disco_verify(gm, kv_a, tt.data_ptr() + 4 * n, 4, am, la, ws2)
+    B.disco_verify(gm, kv_b, tt.data_ptr() + 4 * n, 4, am, lb, ws2)
+    torch.cuda.synchronize()
+    assert kv_a.len == kv_b.len == n + 4 and bool(torch.isfinite(la).all())
+    worst = float((la - lb).abs().max()) / float(lb.abs().max())
+    print(f"[parity] 13B full depth: dense vs block-wise prompt of 512, later block: max rel diff {worst:.3e}", flush=True)
+    assert worst <= deep_bar
 
 
 def test_draft_loop_equals_step_by_step_and_gates_after_halt():
