@@ -194,11 +194,30 @@ def prefill_bench(B, W, dev, reps, models=("68m_draft", "13b_target"), lengths=(
                     fn()
                 torch.cuda.synchronize()
                 res[label] = (time.perf_counter() - t0) / r
+            # the dominant kernel, the MLP-input GEMM (gate/up + SwiGLU, or W1 + GELU), bracketed by HIP events on
+            # the launch stream in the middle layer of `reps` further passes
+            B.disco_probe_enable(shape.n_layers // 2)
+            probe = []
+            for _ in range(reps):
+                dense()
+                torch.cuda.synchronize()
+                probe.append(B.disco_probe_read_ms())
+            B.disco_probe_enable(-1)
+            rows_in = shape.d_ff if shape.family == "A" else 2 * shape.d_ff
+            gemm_flops = 2 * n * shape.d_model * rows_in
+            probe_ms = sum(probe) / len(probe)
             fl = flops(shape, n)
             row = {"model": name, "n_tokens": n, "dense_ms": 1e3 * res["dense"], "blocks_ms": 1e3 * res["blocks"],
                    "speedup": res["blocks"] / res["dense"], "flops": fl, "dense_tflops": fl / res["dense"] / 1e12,
                    "frac_of_mfma_peak": fl / res["dense"] / 1e12 / MFMA_PEAK_TFLOPS,
-                   "tokens_per_s": n / res["dense"]}
+                   "tokens_per_s": n / res["dense"],
+                   "roofline": {"bound": "mfma", "achieved": gemm_flops / probe_ms / 1e9, "peak": MFMA_PEAK_TFLOPS,
+                                "unit": "TFLOP/s", "frac": gemm_flops / probe_ms / 1e9 / MFMA_PEAK_TFLOPS, "traffic": None,
+                                "kernel": "k_gemm_dense<%d, 5, %d> (MLP-input GEMM of the prompt pass)" % (
+                                    4 if shape.family == "A" else 3,
+                                    4 if -(-(rows_in // 16) // 16) * -(-((n + 15) // 16) // 4) >= 256 else 2),
+                                "flops_per_launch": gemm_flops, "avg_launch_ms": probe_ms, "launches_timed": len(probe),
+                                "note": "algorithmic flops; the bf16 hi + lo activation panels make the matrix unit do twice as many"}}
             out["rows"].append(row)
             log(f"[bench] prompt pass {name} n {n}: dense {row['dense_ms']:.2f} ms ({row['dense_tflops']:.0f} TFLOP/s), "
                 f"blocks of 16 {row['blocks_ms']:.2f} ms, x{row['speedup']:.2f}")

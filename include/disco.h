@@ -340,7 +340,7 @@ int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
 /* ---- measurement probe ------------------------------------------------------------------------- */
 
 /* Brackets, with two HIP events on the launch stream, the MLP-input GEMM (gate/up + SwiGLU, or
- * W1 + GELU) of layer `layer` in every forward of a model that has more than `layer` layers
+ * W1 + GELU) of layer `layer` in every forward or prompt pass of a model that has more than `layer` layers
  * (layer < 0 switches the probe off).  disco_probe_read_ms returns the elapsed time of the most
  * recent bracket (the caller has synchronised the stream) or a negative value if none was taken.
  * Process-wide state, for benchmarks; not thread-safe.                                             */

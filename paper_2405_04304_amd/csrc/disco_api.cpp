@@ -341,7 +341,10 @@ int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     }
     DenseArgs ua = dense(L.w_in, ws.xn, xs_d, d.d_model, n_in);
     ua.rstd = fam_a ? nullptr : ws.rstd; ua.g.Xout = ws.xact; ua.xouts = xs_ff; ua.g.KT_out = d.d_ff / 32;
+    const bool probe = (l == g_probe_layer) && g_probe_ev[0] != nullptr;
+    if (probe) HIP_TRY(hipEventRecord(g_probe_ev[0], st), "probe event");
     HIP_TRY(launch_gemm_dense(ua, fam_a ? EPI_GELU : EPI_SWIGLU, st), "mlp-in launch");
+    if (probe) { HIP_TRY(hipEventRecord(g_probe_ev[1], st), "probe event"); g_probe_taken = true; }
 
     DenseArgs da = dense(L.w_out, ws.xact, xs_ff, d.d_ff, d.d_model);
     residual_update(da, next_g);
