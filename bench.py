@@ -230,7 +230,8 @@ def prefill_bench(B, W, dev, reps, models=("68m_draft", "13b_target"), lengths=(
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=60)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed iterations (default: every prompt to its end for the full loop, 60 for the other modes)")
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--policy", default="disco", choices=["disco", "static"])
     ap.add_argument("--gamma", type=int, default=5)
@@ -259,9 +260,18 @@ def main():
                     help="instead of the loop: the draft-step micro-benchmark (68M-class shape, KV context 512 / 1024 / "
                          "2048) and the verification-block micro-benchmark (13B-class shape, context 1024, blocks of "
                          "1, 2, 4, 8, 11 tokens); one JSON line")
+    ap.add_argument("--prompts", type=int, default=16,
+                    help="number of prompts (seeds 1, 2, ..): the timed iterations run through them one after another, each "
+                         "prompt generating --new-tokens tokens; prompt pass and forcing set-up between prompts are untimed")
+    ap.add_argument("--new-tokens", type=int, default=256,
+                    help="tokens generated per prompt when --prompts > 1 (then --steps 0 runs every prompt to its end)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run plain device copies of known size and exit (reference for HBM byte counters)")
     args = ap.parse_args()
+    if args.sweep or args.temperature > 0 or args.micro or args.prefill:
+        args.prompts = 1                      # these modes run one prompt
+    if args.steps is None:
+        args.steps = 0 if args.prompts > 1 else 60
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process, one sequence); --gpus must be 1. "
               "The path shards by sequence across GPUs with no exchange; see DESIGN.md.", file=sys.stderr)
@@ -308,15 +318,19 @@ def main():
     gd = B.DiscoModel(draft_shape, dw, dev)
     log(f"[bench] weights ready in {time.time() - t0:.1f} s")
 
-    n_iter = args.warmup + args.steps
+    n_iter = args.warmup + args.steps if not (args.prompts > 1 and args.steps == 0) else 10 ** 9
     cap = args.gamma if args.policy == "static" else args.sl_max
-    max_new = n_iter * (cap + 1) + 2           # enough text for every iteration at full acceptance
+    max_new = min(n_iter, 10 ** 6) * (cap + 1) + 2   # enough text for every iteration at full acceptance
     prompt = W.make_prompt(1, args.prompt_len, target_shape.vocab).tolist()
+    multi = args.prompts > 1
+    if multi:
+        assert not args.sweep and args.temperature <= 0, "--prompts > 1 runs the greedy loop only"
+        max_new = args.new_tokens
     eng = SpecEngine(gt, gd, B.DiscoClf(clf, dev), max_ctx=args.prompt_len + max_new + 16, page_tokens=16)
 
     # untimed input shaping: the target's own greedy text decides which draft logits get forced
     t0 = time.time()
-    n_greedy = min(max_new, int(n_iter * 3.2) + 32)
+    n_greedy = max_new if multi else min(max_new, int(n_iter * 3.2) + 32)
     greedy = eng.greedy(prompt, n_greedy, progress=lambda i: log(f"[bench] greedy target token {i}/{n_greedy}"))
     greedy += [0] * (max_new - n_greedy)
     mask = W.make_force_mask(5, max_new, args.alpha)
@@ -423,28 +437,48 @@ def main():
         torch.cuda.synchronize()
         stamps.append(time.perf_counter())
         probe_ms.append(B.disco_probe_read_ms())
-        if len(stamps) % 10 == 1:
-            log(f"[bench] iteration {len(stamps) - 1}/{n_iter}")
+        if len(probe_ms) % 10 == 0:
+            log(f"[bench] iteration {len(probe_ms)}" + (f"/{n_iter}" if n_iter < 10 ** 9 else ""))
 
-    eng.reset()
-    eng.prefill(prompt[:-1])
-    torch.cuda.synchronize()
-    gc.collect()
-    gc.disable()                              # no collector pauses inside the timed iterations
-    stamps.append(time.perf_counter())
-    if args.temperature > 0:
-        uni = {k: W.make_uniforms(21, max_new + 16, k) for k in ("draft", "accept", "resample")}
-        res = eng.generate_sampling(prompt, max_new, policy, args.temperature, uni, do_prefill=False,
-                                    on_iteration=on_iter, max_iterations=n_iter)
-    else:
-        res = eng.generate(prompt, max_new, policy, force=force, do_prefill=False, on_iteration=on_iter,
-                           max_iterations=n_iter)
-    torch.cuda.synchronize()
-    gc.enable()
+    # Iterations run prompt after prompt until warmup + steps of them are done; the clock runs only inside
+    # iterations (each is bracketed by a device synchronisation), so the prompt pass and the forcing set-up
+    # of the later prompts are outside the timed region.
+    its, deltas, hist = [], [], {}
+    for p_idx in range(args.prompts):
+        if len(its) >= n_iter:
+            break
+        if p_idx > 0:
+            prompt = W.make_prompt(1 + p_idx, args.prompt_len, target_shape.vocab).tolist()
+            greedy = eng.greedy(prompt, n_greedy)
+            mask = W.make_force_mask(5 + p_idx, max_new, args.alpha)
+            force = {"mask": mask, "tokens": greedy}
+            log(f"[bench] prompt {p_idx + 1}/{args.prompts}: {len(its)} iterations so far")
+        eng.reset()
+        eng.prefill(prompt[:-1])
+        torch.cuda.synchronize()
+        gc.collect()
+        gc.disable()                          # no collector pauses inside the timed iterations
+        first = len(stamps)
+        stamps.append(time.perf_counter())
+        if args.temperature > 0:
+            uni = {k: W.make_uniforms(21, max_new + 16, k) for k in ("draft", "accept", "resample")}
+            res = eng.generate_sampling(prompt, max_new, policy, args.temperature, uni, do_prefill=False,
+                                        on_iteration=on_iter, max_iterations=n_iter - len(its))
+        else:
+            res = eng.generate(prompt, max_new, policy, force=force, do_prefill=False, on_iteration=on_iter,
+                               max_iterations=n_iter - len(its))
+        torch.cuda.synchronize()
+        gc.enable()
+        its += res["iterations"]
+        deltas += [stamps[i + 1] - stamps[i] for i in range(first, len(stamps) - 1)]
+        for k, v in res["sl_hist"].items():
+            hist[k] = hist.get(k, 0) + v
     B.disco_probe_enable(-1)
-    its = res["iterations"]
-    assert len(its) == n_iter, (len(its), n_iter)
-    t_timed = stamps[n_iter] - stamps[args.warmup]
+    if multi and args.steps == 0:             # --steps 0: every prompt to its end
+        n_iter = len(its)
+        args.steps = n_iter - args.warmup
+    assert len(its) == n_iter == len(deltas), (len(its), len(deltas), n_iter, "not enough text: raise --prompts or --new-tokens")
+    t_timed = sum(deltas[args.warmup:])
     timed = its[args.warmup:]
     emitted = sum(len(it["emit"]) for it in timed)
     drafted = sum(it["sl"] for it in timed)
@@ -452,7 +486,8 @@ def main():
     ms_per_step = 1e3 * t_timed / args.steps
     value = emitted / t_timed
 
-    ctx_mid = args.prompt_len + sum(len(it["emit"]) for it in its[:args.warmup]) + emitted // 2
+    ctx_mid = (args.prompt_len + args.new_tokens // 2 if multi else
+               args.prompt_len + sum(len(it["emit"]) for it in its[:args.warmup]) + emitted // 2)
     iter_bytes = fwd_bytes(target_shape, ctx_mid, 1 + drafted / args.steps) + (drafted / args.steps) * fwd_bytes(draft_shape, ctx_mid, 1)
     gemm_bytes = 2 * target_shape.d_ff * target_shape.d_model * 2          # gate + up matrices, bf16
     pm = [p for p in probe_ms[args.warmup:] if p > 0]
@@ -463,13 +498,14 @@ def main():
         "metric": "accepted tokens/s at 13B/68M bf16 (verify+draft achieved HBM GB/s in roofline)",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "ms_per_step_median": 1e3 * sorted(stamps[i + 1] - stamps[i] for i in range(args.warmup, n_iter))[args.steps // 2],
+        "ms_per_step_median": 1e3 * sorted(deltas[args.warmup:])[args.steps // 2],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {
             "workload": ("full DISCO loop, 13B-class target (40 layers, d 5120, 40x128 heads, SwiGLU 13824, vocab 32000) "
                          "+ 68M-class draft (2 layers, d 768), bf16 weights and KV, batch 1, "
-                         f"{args.prompt_len}-token random prompt, "
+                         + (f"{args.prompts} random prompts of {args.prompt_len} tokens, {args.new_tokens} new tokens each, " if multi
+                            else f"{args.prompt_len}-token random prompt, ")
                          + (f"greedy, forced acceptance {args.alpha}" if args.temperature <= 0 else
                             f"sampling at temperature {args.temperature} (speculative-sampling acceptance, caller-supplied uniforms)")),
             "policy": policy, "target_layers": target_shape.n_layers,
@@ -479,7 +515,7 @@ def main():
         "tokens_per_iteration": emitted / args.steps,
         "accepted_draft_tokens_per_iteration": accepted / args.steps,
         "drafted_tokens_per_iteration": drafted / args.steps,
-        "sl_hist": res["sl_hist"],
+        "sl_hist": dict(sorted(hist.items())),
         "iteration_hbm_gbs": iter_bytes / (t_timed / args.steps) / 1e9,
         "iteration_hbm_frac": iter_bytes / (t_timed / args.steps) / 1e9 / HBM_PEAK_GBS,
         "roofline": {
