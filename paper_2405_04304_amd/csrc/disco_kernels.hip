@@ -2014,9 +2014,15 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
   const int n_tiles = a.n_rows >> 4;
   const int ncb = (d.n_groups + CG - 1) / CG;
   const int nrb = (n_tiles + RT * NWV - 1) / (RT * NWV);
+  // Workgroup ids go round-robin to the 8 XCDs.  Within an XCD consecutive ids walk a tile of tile_r row
+  // blocks x tile_t token blocks (about as many workgroups as the XCD runs at once), so that what its L2
+  // must fetch for the workgroups in flight is tile_r weight slabs + tile_t activation slabs.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int rb = (slot / ncb) * 8 + xcd, cb = slot % ncb;
-  if (rb >= nrb) return;                          // whole workgroup
+  const int per_tile = d.tile_r * d.tile_t, n_tg = (ncb + d.tile_t - 1) / d.tile_t;
+  const int tile = slot / per_tile, in_tile = slot % per_tile;
+  const int rbl = (tile / n_tg) * d.tile_r + in_tile / d.tile_t;          // row block index within the XCD
+  const int rb = rbl * 8 + xcd, cb = (tile % n_tg) * d.tile_t + in_tile % d.tile_t;
+  if (rb >= nrb || cb >= ncb) return;             // whole workgroup
   const bool live = (rb * NWV + w) * RT < n_tiles;
   const int b = live ? rb * NWV + w : n_tiles / RT - 1;
   int rt[RT];
@@ -2090,11 +2096,16 @@ static hipError_t launch_gemm_dense_e(const DenseArgs& d, hipStream_t s) {
   // narrower row blocks when 64-row wavefront tiles would leave compute units without a workgroup
   const bool wide = (long long)((n_tiles + 15) / 16) * ncb >= 256;
   const int nrb = wide ? (n_tiles + 15) / 16 : (n_tiles + 7) / 8;
-  const long long blocks = (long long)((nrb + 7) / 8) * 8 * ncb;
+  DenseArgs a = d;
+  // about 64 workgroups run on an XCD at once: 8 x 8 for long prompts, 16 x 4 measured better at 8 token blocks
+  a.tile_t = ncb >= 16 ? 8 : (ncb < 4 ? ncb : 4);
+  const int nrbl = (nrb + 7) / 8;                 // row blocks per XCD
+  a.tile_r = 64 / a.tile_t < nrbl ? 64 / a.tile_t : nrbl;
+  const long long blocks = 8LL * ((nrbl + a.tile_r - 1) / a.tile_r) * ((ncb + a.tile_t - 1) / a.tile_t) * a.tile_r * a.tile_t;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)blocks);
-  if (wide) hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 4>), grid, dim3(256), 0, s, d);
-  else hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 2>), grid, dim3(256), 0, s, d);
+  if (wide) hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 4>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 2>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
 }
 
