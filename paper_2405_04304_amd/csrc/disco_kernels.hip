@@ -1940,9 +1940,9 @@ hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void*
 // (16 x 16 accumulators each), walks the whole K range itself (no K split, no cross-wavefront
 // reduction), and every weight tile it fetches feeds 8 matrix instructions (hi and lo panel of 4
 // groups).  The four wavefronts of a workgroup take neighbouring row tiles and the SAME token groups.
-// Workgroup ids are dealt round-robin to the 8 XCDs; the id -> (row block, token block) map gives all
-// token blocks of one row block to the same XCD, back to back, so that its L2 serves the weights to
-// every token block after the first.  Operand layouts, precision (bf16 hi + lo activations, fp32
+// Workgroup ids are dealt round-robin to the 8 XCDs; every row block belongs to one XCD, whose
+// workgroups walk tiles of several row blocks x several token blocks (see the kernel), so that its L2
+// serves each weight and activation slab to all workgroups of the tile.  Operand layouts, precision (bf16 hi + lo activations, fp32
 // accumulation) and epilogue arithmetic are those of the skinny kernel.
 
 // Epilogues of the dense kernels for one wavefront: RT row tiles x CG token groups of accumulators.
