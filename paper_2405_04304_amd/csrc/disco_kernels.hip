@@ -1049,6 +1049,87 @@ constexpr int FEAT_NT = 1024;
 // loads).  Arg-max, soft-max sums and entropy are DPP wave reductions merged across the 16
 // wavefronts in a fixed order.  Top-10: every wavefront finds the ten largest of the values its
 // lanes hold by ten cross-lane arg-max rounds, and one wavefront picks the ten largest of those 160.
+constexpr int CM_NT = 256;
+constexpr int CM_REC = 16;     // floats per record
+
+// Order-preserving map float -> uint32 (larger float <=> larger key; -inf maps above key 0, which marks
+// a dropped slot) and back.
+__device__ __forceinline__ uint32_t f32_key(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key_f32(uint32_t k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+// Wavefront maximum of unsigned keys: the cross-lane moves fold into the max instructions (one DPP
+// instruction per step; 0 is the identity, so lanes a step does not reach keep their value).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_max_u32(uint32_t v) {
+  const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xF, true);
+  return v > o ? v : o;
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+  v = dpp_max_u32<DPP_QUAD_XOR1, 0xF>(v);
+  v = dpp_max_u32<DPP_QUAD_XOR2, 0xF>(v);
+  v = dpp_max_u32<DPP_ROW_HALF_MIRROR, 0xF>(v);
+  v = dpp_max_u32<DPP_ROW_MIRROR, 0xF>(v);
+  v = dpp_max_u32<DPP_ROW_BCAST15, 0xA>(v);
+  v = dpp_max_u32<DPP_ROW_BCAST31, 0xC>(v);
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// The ten largest of the N values per lane held by one wavefront, descending, written by lane 0 to
+// out10: ten rounds of a cross-lane maximum over order-preserving integer keys; the first lane that
+// holds the maximum drops one instance of it (branch-free).  No LDS traffic and no workgroup barrier
+// inside; c is consumed.
+template <int N>
+__device__ __forceinline__ void wave_top10(float (&c)[N], float* out10) {
+  const int lane = threadIdx.x & 63;
+  uint32_t k[N];
+#pragma unroll
+  for (int e = 0; e < N; ++e) k[e] = f32_key(c[e]);
+#pragma unroll 1
+  for (int rnd = 0; rnd < 10; ++rnd) {
+    uint32_t cur = k[0];
+#pragma unroll
+    for (int e = 1; e < N; ++e) cur = cur > k[e] ? cur : k[e];
+    const uint32_t w = wave_max_u32(cur);
+    if (lane == 0) out10[rnd] = key_f32(w);
+    const unsigned long long owners = __ballot(cur == w);
+    bool drop = owners != 0ull && lane == __builtin_ctzll(owners);
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      const bool hit = drop && k[e] == w;
+      k[e] = hit ? 0u : k[e];
+      drop = drop && !hit;
+    }
+  }
+}
+
+// Ten largest of a workgroup's values: every wavefront's ten, then wavefront 0 ranks the candidates:
+// a candidate's rank is the number of candidates that beat it (larger, or equal with a lower slot), a
+// permutation of 0 .. n-1, and ranks below ten are the answer in order.  No dependent cross-lane chain.
+template <int N>
+__device__ __forceinline__ void block_top10(float (&c)[N], float (*wtop)[10], float* top_s) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  wave_top10<N>(c, wtop[wv]);
+  __syncthreads();
+  constexpr int NC = (CM_NT / 64) * 10;
+  static_assert(NC <= 64, "one candidate per lane");
+  if (wv == 0 && lane < NC) {
+    const float* cand = &wtop[0][0];
+    const float mine = cand[lane];
+    float o[NC];
+#pragma unroll
+    for (int j = 0; j < NC; ++j) o[j] = cand[j];          // all reads in flight at once (broadcasts)
+    int rank = 0;
+#pragma unroll
+    for (int j = 0; j < NC; ++j) rank += (o[j] > mine || (o[j] == mine && j < lane)) ? 1 : 0;
+    if (rank < 10) top_s[rank] = mine;
+  }
+  __syncthreads();
+}
+
 template <int V4>
 __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
   ClfOut* out = reinterpret_cast<ClfOut*>(a.out);
@@ -1120,25 +1201,26 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
   S = block_sum<FEAT_NT>(S, sv);
   T = block_sum<FEAT_NT>(T, sv);
 
-  // ten largest logits: every wavefront's ten by cross-lane arg-max rounds over the values its lanes
-  // hold (the winning lane drops the value it gave; the row is not needed afterwards), then
-  // wavefront 0 picks from the 160 candidates
+  // ten largest logits: every wavefront's ten by cross-lane maximum rounds over the values its lanes
+  // hold (the first lane that holds the maximum drops one instance; the row is not needed afterwards),
+  // then wavefront 0 picks from the 160 candidates
   {
 #pragma unroll 1
     for (int rnd = 0; rnd < 10; ++rnd) {
-      VI cur; cur.v = -INFINITY; cur.i = lane;
+      float cur = -INFINITY;
 #pragma unroll
-      for (int i = 0; i < V4; ++i) cur.v = fmaxf(cur.v, fmaxf(fmaxf(r[i].x, r[i].y), fmaxf(r[i].z, r[i].w)));
-      const VI wn = wave_argmax(cur);
-      if (lane == 0) wtop[wv][rnd] = wn.v;
-      if (wn.i == lane) {
+      for (int i = 0; i < V4; ++i) cur = fmaxf(cur, fmaxf(fmaxf(r[i].x, r[i].y), fmaxf(r[i].z, r[i].w)));
+      const float wn = wave_max(cur);
+      if (lane == 0) wtop[wv][rnd] = wn;
+      const unsigned long long owners = __ballot(cur == wn);
+      if (owners != 0ull && lane == __builtin_ctzll(owners)) {
         bool done = false;
 #pragma unroll
         for (int i = 0; i < V4; ++i) {
-          if (!done && r[i].x == wn.v) { r[i].x = -INFINITY; done = true; }
-          if (!done && r[i].y == wn.v) { r[i].y = -INFINITY; done = true; }
-          if (!done && r[i].z == wn.v) { r[i].z = -INFINITY; done = true; }
-          if (!done && r[i].w == wn.v) { r[i].w = -INFINITY; done = true; }
+          if (!done && r[i].x == wn) { r[i].x = -INFINITY; done = true; }
+          if (!done && r[i].y == wn) { r[i].y = -INFINITY; done = true; }
+          if (!done && r[i].z == wn) { r[i].z = -INFINITY; done = true; }
+          if (!done && r[i].w == wn) { r[i].w = -INFINITY; done = true; }
         }
       }
     }
@@ -1150,17 +1232,7 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
         const int ci = lane + 64 * k;
         c3[k] = ci < (FEAT_NT / 64) * 10 ? wtop[ci / 10][ci % 10] : -INFINITY;
       }
-#pragma unroll 1
-      for (int rnd = 0; rnd < 10; ++rnd) {
-        VI cur; cur.v = fmaxf(fmaxf(c3[0], c3[1]), c3[2]); cur.i = lane;
-        const VI wn = wave_argmax(cur);
-        if (lane == 0) top_s[rnd] = wn.v;
-        if (wn.i == lane) {
-          bool done = false;
-#pragma unroll
-          for (int k = 0; k < 3; ++k) if (!done && c3[k] == wn.v) { c3[k] = -INFINITY; done = true; }
-        }
-      }
+      wave_top10<3>(c3, top_s);
     }
   }
   __syncthreads();
@@ -1220,44 +1292,6 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
 // records in index order: S = sum S_b e^(m_b - M), T = sum e^(m_b - M) (T_b + (m_b - M) S_b), the ten
 // largest of the <= 640 candidates, then features, classifier and halt decision.  Forcing a token
 // to max + 4 is applied to the merged sums in closed form.
-constexpr int CM_NT = 256;
-constexpr int CM_REC = 16;     // floats per record
-
-// The ten largest of the N values per lane held by one wavefront, descending, written by lane 0 to
-// out10: ten cross-lane arg-max rounds, the winning lane drops the value it gave.  No LDS traffic and
-// no workgroup barrier inside.
-template <int N>
-__device__ __forceinline__ void wave_top10(float (&c)[N], float* out10) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll 1
-  for (int rnd = 0; rnd < 10; ++rnd) {
-    VI cur; cur.v = c[0]; cur.i = lane;
-#pragma unroll
-    for (int e = 1; e < N; ++e) cur.v = fmaxf(cur.v, c[e]);
-    const VI w = wave_argmax(cur);
-    if (lane == 0) out10[rnd] = w.v;
-    if (w.i == lane) {
-      bool done = false;
-#pragma unroll
-      for (int e = 0; e < N; ++e) if (!done && c[e] == w.v) { c[e] = -INFINITY; done = true; }
-    }
-  }
-}
-
-// Ten largest of a workgroup's values: every wavefront's ten, then wavefront 0 picks from those.
-template <int N>
-__device__ __forceinline__ void block_top10(float (&c)[N], float (*wtop)[10], float* top_s) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  wave_top10<N>(c, wtop[wv]);
-  __syncthreads();
-  if (wv == 0) {
-    float cand[1];
-    cand[0] = lane < (CM_NT / 64) * 10 ? wtop[lane / 10][lane % 10] : -INFINITY;
-    wave_top10<1>(cand, top_s);
-  }
-  __syncthreads();
-}
-
 __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
   ClfOut* out = reinterpret_cast<ClfOut*>(a.out);
   if (a.gate != nullptr && *a.gate != 0u) {
