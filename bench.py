@@ -1,14 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the DISCO speculative-decoding hot path on one MI355X.
 
-Workload (full-loop configuration: 13B-class target, 68M-class draft, bf16, batch 1): a 512-token
-random prompt is prefilled, then speculative iterations run with DISCO halting (cap 10) and 60 %
-seed-forced draft/target agreement.  One "step" is one whole iteration: draft steps with the fused
-feature/classifier kernel, the target's verification forward, greedy acceptance, KV rollback.
-`value` counts the tokens emitted per second (accepted draft tokens plus the target's own token of
-every iteration), inputs resident in HBM.
+Workload (full-loop configuration: 13B-class target, 68M-class draft, bf16, batch 1): 16 random prompts
+of 512 tokens, 256 new tokens each; every prompt goes through the dense prompt pass of both models,
+then speculative iterations run with DISCO halting (cap 10) and 60 % seed-forced draft/target
+agreement.  One "step" is one whole iteration: draft steps with the fused feature/classifier kernel,
+the target's verification forward, greedy acceptance, KV rollback.  The clock runs inside iterations
+only.  `value` counts the tokens emitted per second (accepted draft tokens plus the target's own
+token of every iteration), inputs resident in HBM.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric, value, unit, steps, ms_per_step, config (the workload in words), a
+`roofline` object for the dominant kernel and a `cpu_baseline` object (the CPU oracle timed on a
+bounded sample).  Other modes (--sweep, --micro, --prefill) print one JSON line of their own.
 """
 from __future__ import annotations
 
@@ -303,7 +306,7 @@ def main():
         args.steps = 0 if args.prompts > 1 else 60
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process, one sequence); --gpus must be 1. "
-              "The path shards by sequence across GPUs with no exchange; see DESIGN.md.", file=sys.stderr)
+              "The path shards by sequence across GPUs with no exchange: one process per GPU, each with its own prompts.", file=sys.stderr)
         sys.exit(2)
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     dev = torch.device("cuda:0")

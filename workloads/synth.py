@@ -73,13 +73,13 @@ class ClassifierShape:
 
 CLF_SHAPE = ClassifierShape()
 
-# benchmark configs[0]: tiny end-to-end pair (draft = first target layer + final LN + LM head)
+# tiny end-to-end pair (draft = first target layer + final LN + LM head)
 CFG0_TARGET = ModelShape("A", 4, 256, 4, 64, 4, 1024, 4096, max_pos=128)
 CFG0_DRAFT = dataclasses.replace(CFG0_TARGET, n_layers=1)
-# configs[1]: 68M-class draft;  configs[2]: 13B-class target
+# 68M-class draft;  13B-class target
 CFG1_DRAFT = ModelShape("B", 2, 768, 12, 64, 12, 3072, 32000)
 CFG2_TARGET = ModelShape("B", 40, 5120, 40, 128, 40, 13824, 32000)
-# configs[3]: multi-query code-model pair
+# multi-query code-model pair
 CFG3_TARGET = ModelShape("A", 40, 6144, 48, 128, 1, 24576, 49152, max_pos=4096)
 CFG3_DRAFT = ModelShape("A", 12, 768, 12, 64, 1, 3072, 49152, max_pos=4096)
 
