@@ -5,7 +5,7 @@ I2  static-SL text == DISCO text == oracle-SL text (corollary).
 I3  the iteration structure of every policy follows from the per-position match vector of the
     labelling run of App. D.1 (draft predicts one token from prompt + target prefix).
 I4  oracle SL == the maximum number of accepted draft tokens over all static lookaheads, and the
-    smallest lookahead that reaches it (Sec. 3, "optimal (maximum)"), by brute force.
+    smallest lookahead that reaches it (Sec. 3 defines it as the maximum), by brute force.
 I5  under i.i.d. acceptance alpha, mean tokens per iteration -> (1 - alpha^(g+1)) / (1 - alpha)
     (numerator of Eq. 1)."""
 import math
