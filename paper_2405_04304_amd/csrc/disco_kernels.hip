@@ -1106,25 +1106,25 @@ __device__ __forceinline__ void wave_top10(float (&c)[N], float* out10) {
   }
 }
 
-// Ten largest of a workgroup's values: every wavefront's ten, then wavefront 0 ranks the candidates:
+// Ten largest of a workgroup's values: every wavefront's ten, then one thread per candidate ranks it:
 // a candidate's rank is the number of candidates that beat it (larger, or equal with a lower slot), a
 // permutation of 0 .. n-1, and ranks below ten are the answer in order.  No dependent cross-lane chain.
-template <int N>
+template <int NT, int N>
 __device__ __forceinline__ void block_top10(float (&c)[N], float (*wtop)[10], float* top_s) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int wv = threadIdx.x >> 6;
   wave_top10<N>(c, wtop[wv]);
   __syncthreads();
-  constexpr int NC = (CM_NT / 64) * 10;
-  static_assert(NC <= 64, "one candidate per lane");
-  if (wv == 0 && lane < NC) {
+  constexpr int NC = (NT / 64) * 10;
+  if ((int)threadIdx.x < NC) {
+    const int me = threadIdx.x;
     const float* cand = &wtop[0][0];
-    const float mine = cand[lane];
+    const float mine = cand[me];
     float o[NC];
 #pragma unroll
     for (int j = 0; j < NC; ++j) o[j] = cand[j];          // all reads in flight at once (broadcasts)
     int rank = 0;
 #pragma unroll
-    for (int j = 0; j < NC; ++j) rank += (o[j] > mine || (o[j] == mine && j < lane)) ? 1 : 0;
+    for (int j = 0; j < NC; ++j) rank += (o[j] > mine || (o[j] == mine && j < me)) ? 1 : 0;
     if (rank < 10) top_s[rank] = mine;
   }
   __syncthreads();
@@ -1286,6 +1286,115 @@ __global__ __launch_bounds__(FEAT_NT) void k_classify(ClassifyArgs a) {
   }
 }
 
+// Classifier coefficients of one thread (hidden unit threadIdx.x), fetched early by the caller.
+struct ClfCoef { float w1[12]; float b1, w2, b2; };
+
+// Last stage of the feature / classifier computation, run by ONE workgroup of NT threads over nb
+// records {max, arg-max, S, T relative to the record's max, its ten largest values} (16 floats each,
+// written with agent-scope stores by the workgroups that reduced the logits): merged statistics in
+// record order, the ten largest of the nb * 10 candidates (CPT per thread), the forced logit in closed
+// form, features, classifier, halt decision and the loop's bookkeeping words.
+template <int NT, int CPT>
+__device__ __forceinline__ void classify_merge_finish(const ClassifyArgs& a, const float* recs, const int nb, const int force,
+                                                      const float xf, const ClfCoef& k, float* sv, int* si, float (*wtop)[10],
+                                                      float* top_s, float* feat_s) {
+  ClfOut* out = reinterpret_cast<ClfOut*>(a.out);
+  const int t = threadIdx.x;
+  VI bm; bm.v = -INFINITY; bm.i = 0x7fffffff;
+  float Sb = 0.f, Tb = 0.f, mb = 0.f;
+  if (t < nb) {
+    const float2 p0 = ld_agent2(recs + (size_t)t * CM_REC), p1 = ld_agent2(recs + (size_t)t * CM_REC + 2);
+    bm.v = p0.x; bm.i = __float_as_int(p0.y); mb = p0.x; Sb = p1.x; Tb = p1.y;
+  }
+  VI gbest = block_argmax<NT>(bm, sv, si);
+  float Sg = 0.f, Tg = 0.f;
+  if (t < nb) {
+    const float d = mb - gbest.v, f = expf(d);
+    Sg = Sb * f; Tg = f > 0.f ? f * (Tb + d * Sb) : 0.f;
+  }
+  Sg = block_sum<NT>(Sg, sv);
+  Tg = block_sum<NT>(Tg, sv);
+  // ten largest of the nb * 10 candidates (up to 3 per thread)
+  float cc[CPT];
+#pragma unroll
+  for (int q = 0; q < CPT; ++q) {
+    const int ci = t + q * NT;                               // candidate ci = record ci / 10, slot ci % 10
+    cc[q] = -INFINITY;
+    if (ci < nb * 10) {
+      const int rb = ci / 10, sl = ci % 10;
+      const float2 p = ld_agent2(recs + (size_t)rb * CM_REC + 4 + (sl & ~1));
+      cc[q] = (sl & 1) ? p.y : p.x;
+    }
+  }
+  block_top10<NT, CPT>(cc, wtop, top_s);
+  float mx = gbest.v;
+  if (force >= 0) {
+    // raise logit[force] from x_f to M + 4: shift every term to the new maximum, take the old
+    // contribution of x_f out and put the new one (e^0 = 1, with (x - max) = 0) in
+    const float mnew = gbest.v + 4.0f;
+    const float sh = expf(-4.0f), ef = expf(xf - mnew);
+    Tg = sh * (Tg - 4.0f * Sg) - (ef > 0.f ? ef * (xf - mnew) : 0.f);
+    Sg = sh * Sg - ef + 1.0f;
+    if (t == 0) {
+      // new top ten: M + 4 first, then the old ones without one instance of x_f (or without the last)
+      float old[10];
+      for (int i = 0; i < 10; ++i) old[i] = top_s[i];
+      int drop = 9;
+      for (int i = 9; i >= 0; --i) if (old[i] == xf) drop = i;
+      top_s[0] = mnew;
+      for (int i = 0, o = 1; i < 10 && o < 10; ++i) if (i != drop) top_s[o++] = old[i];
+      a.logits[force] = mnew;
+    }
+    mx = mnew; gbest.v = mnew; gbest.i = force;
+    __syncthreads();
+  }
+  if (t < 10) feat_s[t] = (top_s[t] == -INFINITY) ? 0.f : expf(top_s[t] - mx) / Sg;
+  if (t == 10) feat_s[10] = logf(Sg) - Tg / Sg;
+  if (t == 11) feat_s[11] = a.pos_feature;
+  __syncthreads();
+  float contrib = 0.f;
+  if (a.clf_params && t < a.hidden) {
+    float acc = k.b1;
+#pragma unroll
+    for (int i = 0; i < 12; ++i) acc += k.w1[i] * feat_s[i];
+    contrib = fmaxf(acc, 0.f) * k.w2;
+  }
+  const float z = block_sum<NT>(contrib, sv);
+  if (t == 0) {
+    float score = __builtin_nanf("");
+    uint32_t halt = a.force_halt ? 1u : 0u;
+    if (a.clf_params) {
+      score = 1.0f / (1.0f + expf(-(z + k.b2)));
+      if (score < a.tau) halt = 1u;
+    }
+    // reference lookahead: a token that differs from the known continuation ends the block and is
+    // not part of it (bit 1 of halt)
+    bool mismatch = false;
+    if (a.ref_token) { const int ref = *a.ref_token; mismatch = ref >= 0 && gbest.i != ref; }
+    if (mismatch) halt = 3u;
+    // perplexity rule (App. F's rule-based baseline): the block's draft tokens so far have perplexity
+    // exp(-(1/j) sum ln p_i), p_i the draft's probability of its own token (the largest one); above the
+    // threshold this token is the block's last.  The running sum sits in the word after sl_count.
+    if (a.ppl_threshold > 0.f && a.sl_count) {
+      float* nll = reinterpret_cast<float*>(a.sl_count + 1);
+      const float sum = *nll - logf(feat_s[0]);
+      *nll = sum;
+      score = expf(sum / (float)(*a.sl_count + 1));
+      if (score > a.ppl_threshold) halt |= 1u;
+    }
+    out->token = gbest.i;
+#pragma unroll
+    for (int i = 0; i < 12; ++i) out->feats[i] = feat_s[i];
+    out->score = score; out->halt = halt; out->executed = 1u;
+    if (!mismatch) {
+      if (a.token_next) *a.token_next = gbest.i;
+      if (a.block_slot) *a.block_slot = gbest.i;
+      if (a.sl_count) *a.sl_count += 1;
+    }
+    if (a.gate && halt) *a.gate = 1u;
+  }
+}
+
 // The same computation spread over ceil(V / 1024) workgroups (used when the caller gives scratch
 // memory).  Each workgroup reduces 1024 logits to a record {max, arg-max, S, T relative to its own
 // max, its ten largest values}; the last workgroup to finish (ticket, no waiting) merges the
@@ -1349,106 +1458,17 @@ __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
   // this workgroup's ten largest values
   {
     float c4[4] = {r4[0], r4[1], r4[2], r4[3]};
-    block_top10<4>(c4, wtop, top_s);
+    block_top10<CM_NT, 4>(c4, wtop, top_s);
   }
   if (t == 0) { st_agent2(rec, best.v, __int_as_float(best.i)); st_agent2(rec + 2, S, T); }
   if (t >= 2 && t < 7) st_agent2(rec + 2 * t, top_s[2 * t - 4], top_s[2 * t - 3]);
   if (!last_arrival(reinterpret_cast<int*>(a.scratch), nb, &s_last)) return;
 
-  // ---- merge (one workgroup) ----
-  VI bm; bm.v = -INFINITY; bm.i = 0x7fffffff;
-  float Sb = 0.f, Tb = 0.f, mb = 0.f;
-  if (t < nb) {
-    const float2 p0 = ld_agent2(a.scratch + 64 + (size_t)t * CM_REC), p1 = ld_agent2(a.scratch + 64 + (size_t)t * CM_REC + 2);
-    bm.v = p0.x; bm.i = __float_as_int(p0.y); mb = p0.x; Sb = p1.x; Tb = p1.y;
-  }
-  VI gbest = block_argmax<CM_NT>(bm, sv, si);
-  float Sg = 0.f, Tg = 0.f;
-  if (t < nb) {
-    const float d = mb - gbest.v, f = expf(d);
-    Sg = Sb * f; Tg = f > 0.f ? f * (Tb + d * Sb) : 0.f;
-  }
-  Sg = block_sum<CM_NT>(Sg, sv);
-  Tg = block_sum<CM_NT>(Tg, sv);
-  // ten largest of the nb * 10 candidates (up to 3 per thread)
-  float c3[3];
+  ClfCoef k;
 #pragma unroll
-  for (int k = 0; k < 3; ++k) {
-    const int ci = t + k * CM_NT;                              // candidate ci = record ci / 10, slot ci % 10
-    c3[k] = -INFINITY;
-    if (ci < nb * 10) {
-      const int rb = ci / 10, sl = ci % 10;
-      const float2 p = ld_agent2(a.scratch + 64 + (size_t)rb * CM_REC + 4 + (sl & ~1));
-      c3[k] = (sl & 1) ? p.y : p.x;
-    }
-  }
-  block_top10<3>(c3, wtop, top_s);
-  float mx = gbest.v;
-  if (force >= 0) {
-    // raise logit[force] from x_f to M + 4: shift every term to the new maximum, take the old
-    // contribution of x_f out and put the new one (e^0 = 1, with (x - max) = 0) in
-    const float mnew = gbest.v + 4.0f;
-    const float sh = expf(-4.0f), ef = expf(xf - mnew);
-    Tg = sh * (Tg - 4.0f * Sg) - (ef > 0.f ? ef * (xf - mnew) : 0.f);
-    Sg = sh * Sg - ef + 1.0f;
-    if (t == 0) {
-      // new top ten: M + 4 first, then the old ones without one instance of x_f (or without the last)
-      float old[10];
-      for (int i = 0; i < 10; ++i) old[i] = top_s[i];
-      int drop = 9;
-      for (int i = 9; i >= 0; --i) if (old[i] == xf) drop = i;
-      top_s[0] = mnew;
-      for (int i = 0, o = 1; i < 10 && o < 10; ++i) if (i != drop) top_s[o++] = old[i];
-      a.logits[force] = mnew;
-    }
-    mx = mnew; gbest.v = mnew; gbest.i = force;
-    __syncthreads();
-  }
-  if (t < 10) feat_s[t] = (top_s[t] == -INFINITY) ? 0.f : expf(top_s[t] - mx) / Sg;
-  if (t == 10) feat_s[10] = logf(Sg) - Tg / Sg;
-  if (t == 11) feat_s[11] = a.pos_feature;
-  __syncthreads();
-  float contrib = 0.f;
-  if (a.clf_params && t < a.hidden) {
-    float acc = cb1;
-#pragma unroll
-    for (int i = 0; i < 12; ++i) acc += w1[i] * feat_s[i];
-    contrib = fmaxf(acc, 0.f) * cw2;
-  }
-  const float z = block_sum<CM_NT>(contrib, sv);
-  if (t == 0) {
-    float score = __builtin_nanf("");
-    uint32_t halt = a.force_halt ? 1u : 0u;
-    if (a.clf_params) {
-      score = 1.0f / (1.0f + expf(-(z + cb2)));
-      if (score < a.tau) halt = 1u;
-    }
-    // reference lookahead: a token that differs from the known continuation ends the block and is
-    // not part of it (bit 1 of halt)
-    bool mismatch = false;
-    if (a.ref_token) { const int ref = *a.ref_token; mismatch = ref >= 0 && gbest.i != ref; }
-    if (mismatch) halt = 3u;
-    // perplexity rule (App. F's rule-based baseline): the block's draft tokens so far have perplexity
-    // exp(-(1/j) sum ln p_i), p_i the draft's probability of its own token (the largest one); above the
-    // threshold this token is the block's last.  The running sum sits in the word after sl_count.
-    if (a.ppl_threshold > 0.f && a.sl_count) {
-      float* nll = reinterpret_cast<float*>(a.sl_count + 1);
-      const float sum = *nll - logf(feat_s[0]);
-      *nll = sum;
-      score = expf(sum / (float)(*a.sl_count + 1));
-      if (score > a.ppl_threshold) halt |= 1u;
-    }
-    out->token = gbest.i;
-#pragma unroll
-    for (int i = 0; i < 12; ++i) out->feats[i] = feat_s[i];
-    out->score = score; out->halt = halt; out->executed = 1u;
-    if (!mismatch) {
-      if (a.token_next) *a.token_next = gbest.i;
-      if (a.block_slot) *a.block_slot = gbest.i;
-      if (a.sl_count) *a.sl_count += 1;
-    }
-    if (a.gate && halt) *a.gate = 1u;
-  }
+  for (int i = 0; i < 12; ++i) k.w1[i] = w1[i];
+  k.b1 = cb1; k.w2 = cw2; k.b2 = cb2;
+  classify_merge_finish<CM_NT, 3>(a, a.scratch + 64, nb, force, xf, k, sv, si, wtop, top_s, feat_s);
 }
 
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s) {
