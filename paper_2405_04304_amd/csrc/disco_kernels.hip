@@ -36,6 +36,12 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {  // round to nearest ev
 __device__ __forceinline__ bool gated(const uint32_t* gate) {
   return gate != nullptr && __builtin_nontemporal_load(gate) != 0u;
 }
+// The halt flag's value, requested but not waited for: kernels of the draft loop issue their first
+// operand loads behind it and test it just before they would wait for those, so that the flag's round
+// trip does not stand in front of every launch of the step (a halted step's launches still end there).
+__device__ __forceinline__ uint32_t gate_request(const uint32_t* gate) {
+  return gate != nullptr ? __builtin_nontemporal_load(gate) : 0u;
+}
 
 // Store 4 consecutive-k activations of token m into the packed panels as bf16 hi/lo.
 __device__ __forceinline__ void xpack_store4(bf16_t* X, int KT, int M, int m, int k, const float* v) {
@@ -280,6 +286,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
   static_assert(!PAIR || RT % 2 == 0, "pair epilogues need an even tile count");
   static_assert(UNITS <= NW, "one epilogue wavefront per unit");
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const uint32_t halted = gate_request(a.gate);
   int rt[RT];
   if (PAIR) {
 #pragma unroll
@@ -352,6 +359,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
     u32x4 A0[U][RT], B0[U][P], A1[U][RT], B1[U][P];
     int kt = kt_begin + w;
     if (kt < kt_end) load_step(A0, B0, kt);
+    if (halted != 0u) return;                     // uniform over the launch; nothing has been written yet
     while (kt < kt_end) {
       if (kt + STEP < kt_end) load_step(A1, B1, kt + STEP);
       mma_step(A0, B0, kt);
@@ -506,7 +514,6 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
 
 template <int P, int RT, int EPI, int NW, int U>
 __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
-  if (gated(a.gate)) return;
   const int split = blockIdx.y;
   const int kt_begin = (int)((int64_t)a.KT * split / a.n_split), kt_end = (int)((int64_t)a.KT * (split + 1) / a.n_split);
   gemm_unit<P, RT, EPI, NW, U>(a, blockIdx.x, kt_begin, kt_end, split, a.n_split);
@@ -591,7 +598,7 @@ hipError_t launch_gemm(const GemmArgs& a0, int epi, hipStream_t s) {
 // packed bf16 hi/lo panels -- or, for a deferred RMSNorm, gain * h panels plus the sum of squares.
 template <int NT>
 __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
-  if (gated(a.gate)) return;
+  const uint32_t halted = gate_request(a.gate);
   constexpr int VPT = 2;                       // float4 per thread: d <= NT * 8
   __shared__ float red[NT / 64 + 1];
   // row = token slot; slots beyond 16 belong to further groups of 16 (prompt pass), whose panels and
@@ -625,7 +632,14 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
       } else {
         v[i] = *reinterpret_cast<const float4*>(h + k);
       }
-      if (e) *reinterpret_cast<float4*>(h + k) = v[i];
+    }
+  }
+  if (halted != 0u) return;                       // uniform over the launch; nothing has been written yet
+  if (e) {
+#pragma unroll
+    for (int i = 0; i < VPT; ++i) {
+      const int k = (i * NT + t) * 4;
+      if (k < d) *reinterpret_cast<float4*>(h + k) = v[i];
     }
   }
   if (a.ssq_out != nullptr) {
@@ -844,7 +858,7 @@ struct AttnWave {
 
 template <int DH>
 __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
-  if (gated(a.gate)) return;
+  const uint32_t halted = gate_request(a.gate);
   constexpr int CT = DH / 16, NWV = 4, WKEYS = 32;
   __shared__ f32x4 o_s[NWV][CT][64];
   __shared__ float m_s[NWV][16], l_s[NWV][16];
@@ -861,6 +875,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
   int base = s0 + w * WKEYS;
   if (base < s1) aw.issue(r0, base);
   aw.load_q(head);
+  if (halted != 0u) return;                       // uniform over the launch; nothing has been written yet
   while (base < s1) {
     if (base + STEP < s1) aw.issue(r1, base + STEP);
     aw.step(r0, base);
@@ -937,7 +952,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
 // loads of step i + 1 in flight during the arithmetic of step i), merges its wavefronts through LDS
 // and writes the O-projection panels itself: no partial records, no hand-off between workgroups.
 template <int DH>
-__device__ __forceinline__ void attn_whole_head(const AttnArgs& a, const int head) {
+__device__ __forceinline__ void attn_whole_head(const AttnArgs& a, const int head, const uint32_t halted = 0u) {
   constexpr int CT = DH / 16, NWV = 8, WKEYS = 32, STEP = NWV * WKEYS;
   __shared__ f32x4 o_s[NWV][CT][64];
   __shared__ float m_s[NWV][16], l_s[NWV][16];
@@ -949,6 +964,7 @@ __device__ __forceinline__ void attn_whole_head(const AttnArgs& a, const int hea
   int base = w * WKEYS;
   if (base < total) aw.issue(r0, base);
   aw.load_q(head);
+  if (halted != 0u) return;                       // uniform over the launch; nothing has been written yet
   while (base < total) {
     if (base + STEP < total) aw.issue(r1, base + STEP);
     aw.step(r0, base);
@@ -981,8 +997,7 @@ __device__ __forceinline__ void attn_whole_head(const AttnArgs& a, const int hea
 
 template <int DH>
 __global__ __launch_bounds__(512) void k_attn_head(AttnArgs a) {
-  if (gated(a.gate)) return;
-  attn_whole_head<DH>(a, blockIdx.x);
+  attn_whole_head<DH>(a, blockIdx.x, gate_request(a.gate));
 }
 
 // Prompt pass: workgroup = (query head, group of 16 prompt tokens).  Group r sits at positions
@@ -1403,10 +1418,7 @@ __device__ __forceinline__ void classify_merge_finish(const ClassifyArgs& a, con
 // to max + 4 is applied to the merged sums in closed form.
 __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
   ClfOut* out = reinterpret_cast<ClfOut*>(a.out);
-  if (a.gate != nullptr && *a.gate != 0u) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) out->executed = 0u;
-    return;
-  }
+  const uint32_t halted = gate_request(const_cast<const uint32_t*>(a.gate));
   __shared__ float sv[CM_NT / 64 + 1];
   __shared__ int si[CM_NT / 64 + 1];
   __shared__ float top_s[10];
@@ -1442,6 +1454,10 @@ __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
       cb1 = a.clf_params[a.hidden * 12 + t];
       cw2 = a.clf_params[a.hidden * 13 + t];
     }
+  }
+  if (halted != 0u) {                             // uniform over the launch; the loads above are dropped
+    if (threadIdx.x == 0 && blockIdx.x == 0) out->executed = 0u;
+    return;
   }
   VI mine; mine.v = -INFINITY; mine.i = 0x7fffffff;
 #pragma unroll
