@@ -914,21 +914,25 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
   // feed the O-projection
   __shared__ int s_last;
   if (!last_arrival(a.counters + head, a.n_splits, &s_last)) return;
-  constexpr int TPQ = DH / 4;                                    // threads per query, 4 channels each
+  // 8 channels per thread: DH / 8 threads per query, so that all 16 queries of a block are merged in one
+  // pass (a second pass would put a second round trip to the records behind the first)
+  constexpr int TPQ = DH / 8;
   const int tq = threadIdx.x % TPQ;
   for (int qm = threadIdx.x / TPQ; qm < a.M; qm += 256 / TPQ) {
     const float* rbase = a.part + (((size_t)head * a.n_splits) * 16 + qm) * (DH + 2);
     const size_t stride = (size_t)16 * (DH + 2);
     // running (max, sum, o) over the ranges in range order; eight ranges' records are fetched at a
     // time so that their round trips overlap
-    float mx = NEG_BIG, L = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
+    float mx = NEG_BIG, L = 0.f, o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int sp0 = 0; sp0 < a.n_splits; sp0 += 8) {
-      float2 ml[8], v0[8], v1[8];
+      float2 ml[8], v[8][4];
 #pragma unroll
       for (int i = 0; i < 8; ++i)
         if (sp0 + i < a.n_splits) {
           const float* rc = rbase + (size_t)(sp0 + i) * stride;
-          ml[i] = ld_agent2(rc + DH); v0[i] = ld_agent2(rc + 4 * tq); v1[i] = ld_agent2(rc + 4 * tq + 2);
+          ml[i] = ld_agent2(rc + DH);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) v[i][c] = ld_agent2(rc + 8 * tq + 2 * c);
         }
 #pragma unroll
       for (int i = 0; i < 8; ++i)
@@ -936,15 +940,19 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
           const float m_new = fmaxf(mx, ml[i].x);
           const float f_old = expf(mx - m_new), f_new = expf(ml[i].x - m_new);
           L = L * f_old + ml[i].y * f_new;
-          o[0] = o[0] * f_old + v0[i].x * f_new; o[1] = o[1] * f_old + v0[i].y * f_new;
-          o[2] = o[2] * f_old + v1[i].x * f_new; o[3] = o[3] * f_old + v1[i].y * f_new;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            o[2 * c] = o[2 * c] * f_old + v[i][c].x * f_new;
+            o[2 * c + 1] = o[2 * c + 1] * f_old + v[i][c].y * f_new;
+          }
           mx = m_new;
         }
     }
     const float inv = 1.0f / L;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) o[i] *= inv;
-    xpack_store4(a.Xout, (a.nq * DH) >> 5, a.M, qm, head * DH + 4 * tq, o);
+    for (int i = 0; i < 8; ++i) o[i] *= inv;
+    xpack_store4(a.Xout, (a.nq * DH) >> 5, a.M, qm, head * DH + 8 * tq, o);
+    xpack_store4(a.Xout, (a.nq * DH) >> 5, a.M, qm, head * DH + 8 * tq + 4, o + 4);
   }
 }
 
