@@ -315,9 +315,16 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
   float sv[MAXS];
   if (NORMED) {
 #pragma unroll
+    for (int k = 0; k < MAXS; ++k) sv[k] = 0.f;
+    // rounds of 4 NW slots; the rounds past n_ssq are skipped by a uniform branch (a 768-wide model
+    // needs 2 of the 16 rounds: per-lane tests of all 16 cost more than the loads)
+    const int rounds = a.ssq != nullptr ? (a.n_ssq + 4 * NW - 1) / (4 * NW) : 0;
+#pragma unroll
     for (int k = 0; k < MAXS; ++k) {
-      const int idx = (lane >> 4) * NW + w + 4 * NW * k;
-      sv[k] = (a.ssq != nullptr && idx < a.n_ssq) ? a.ssq[idx * 16 + (lane & 15)] : 0.f;   // [slot][token]
+      if (k < rounds) {
+        const int idx = (lane >> 4) * NW + w + 4 * NW * k;
+        sv[k] = idx < a.n_ssq ? a.ssq[idx * 16 + (lane & 15)] : 0.f;   // [slot][token]
+      }
     }
     asm volatile("" ::: "memory");     // keep these loads ahead of the weight stream
   }
