@@ -233,7 +233,8 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
 // (hi4) of token row m at position pos: rotation, then the query row or the paged K / V entry.
 __device__ __forceinline__ void qkv_store(const GemmArgs& a, float* q, const int n0, const int m, const int pos,
                                           float (&lo4)[4], float (&hi4)[4]) {
-  const int head = n0 / a.dh, c = n0 % a.dh, half = a.dh >> 1;
+  const int dsh = a.dh == 128 ? 7 : 6;            // d_head is 64 or 128
+  const int head = n0 >> dsh, c = n0 & (a.dh - 1), half = a.dh >> 1;
   const bool is_v = head >= a.nq + a.nkv;
   if (a.rope_tab != nullptr && !is_v) {
     // (cos, sin) of pos * base^(-2 (c + v) / d_head), tabulated per cached position
@@ -254,7 +255,9 @@ __device__ __forceinline__ void qkv_store(const GemmArgs& a, float* q, const int
   } else {
     const int sel = is_v ? 1 : 0;
     const int kvh = head - a.nq - sel * a.nkv;
-    const int lp = pos / a.page_tokens, off = pos % a.page_tokens;
+    const int pt = a.page_tokens;
+    const bool pow2 = (pt & (pt - 1)) == 0;
+    const int lp = pow2 ? pos >> __builtin_ctz(pt) : pos / pt, off = pos - lp * pt;
     const int pp = a.page_table ? a.page_table[lp] : lp;
     bf16_t* blk = a.kv_layer + (((size_t)pp * 2 + sel) * a.nkv + kvh) * a.page_tokens * a.dh;
     if (!is_v) {                 // K: [token][d_head]
@@ -291,8 +294,8 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
   if (PAIR) {
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) {
-      const int bp = b * UNITS + u;
-      rt[2 * u] = (bp / a.grp) * (2 * a.grp) + (bp % a.grp);
+      const int bp = b * UNITS + u, gs = __builtin_ctz(a.grp);   // the pairing distance is a power of two
+      rt[2 * u] = ((bp >> gs) << (gs + 1)) + (bp & (a.grp - 1));
       rt[2 * u + 1] = rt[2 * u] + a.grp;
     }
   } else {
@@ -584,6 +587,7 @@ hipError_t launch_gemm(const GemmArgs& a0, int epi, hipStream_t s) {
   if (a.n_split > a.KT) return hipErrorInvalidValue;
   if (epi != EPI_QKV) a.grp = 1;
   if ((epi == EPI_QKV || epi == EPI_SWIGLU) && (a.n_rows % 32)) return hipErrorInvalidValue;
+  if (epi == EPI_QKV && (a.grp < 1 || (a.grp & (a.grp - 1)) != 0 || (a.dh != 64 && a.dh != 128))) return hipErrorInvalidValue;
   const bool p1 = a.M <= 8;
   switch (epi) {
     case EPI_PARTIAL: return p1 ? launch_gemm_p<1, EPI_PARTIAL>(a, s) : launch_gemm_p<2, EPI_PARTIAL>(a, s);
@@ -2114,8 +2118,8 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
   if (PAIR) {
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) {
-      const int bp = b * UNITS + u;
-      rt[2 * u] = (bp / a.grp) * (2 * a.grp) + (bp % a.grp);
+      const int bp = b * UNITS + u, gs = __builtin_ctz(a.grp);   // the pairing distance is a power of two
+      rt[2 * u] = ((bp >> gs) << (gs + 1)) + (bp & (a.grp - 1));
       rt[2 * u + 1] = rt[2 * u] + a.grp;
     }
   } else {
@@ -2197,7 +2201,8 @@ static hipError_t launch_gemm_dense_e(const DenseArgs& d, hipStream_t s) {
 hipError_t launch_gemm_dense(const DenseArgs& d, int epi, hipStream_t s) {
   const GemmArgs& a = d.g;
   if (a.M != 16 || d.n_groups < 1 || a.KT < 1 || a.n_rows < 64 || (a.n_rows % 64) != 0) return hipErrorInvalidValue;
-  if ((epi == EPI_QKV || epi == EPI_SWIGLU) && (a.grp < 1 || (a.n_rows / 32) % a.grp != 0)) return hipErrorInvalidValue;
+  if ((epi == EPI_QKV || epi == EPI_SWIGLU) && (a.grp < 1 || (a.grp & (a.grp - 1)) != 0 || (a.n_rows / 32) % a.grp != 0)) return hipErrorInvalidValue;
+  if (epi == EPI_QKV && a.dh != 64 && a.dh != 128) return hipErrorInvalidValue;
   switch (epi) {
     case EPI_QKV: return launch_gemm_dense_e<EPI_QKV>(d, s);
     case EPI_SWIGLU: return launch_gemm_dense_e<EPI_SWIGLU>(d, s);
