@@ -185,6 +185,21 @@ int disco_classify(const disco_clf* clf, float* dev_logits, int vocab, float pos
 /* Zeroes the ticket word of a classify scratch buffer (kernels leave it at zero afterwards).        */
 int disco_classify_scratch_init(void* dev_scratch, disco_stream s);
 
+/* disco_classify for callers that cannot allocate device memory or pass a scratch buffer of their own
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the many-
+ * workgroup reduction uses an array inside the library's code object instead of dev_scratch
+ * (DISCO_CLASSIFY_SCRATCH_BYTES per GPU, held until the process ends).  Same arguments, same results
+ * and the same kernels as disco_classify with a scratch buffer; the call allocates nothing, enqueues a
+ * small fill kernel that zeroes the array's ticket word and then the classify kernel.  vocab above
+ * DISCO_CLASSIFY_STATIC_MAX_VOCAB is refused with DISCO_ECAP.  Every call on one GPU shares that GPU's
+ * array: calls that overlap on one GPU (different streams, or replays of graphs that hold it) race;
+ * serialise them.  The first call on a device looks the array's address up (make it before a capture). */
+#define DISCO_CLASSIFY_STATIC_MAX_VOCAB 65536
+int disco_classify_static(const disco_clf* clf, float* dev_logits, int vocab, float pos_feature, float tau,
+                          int force_halt, disco_clf_out* dev_out, int32_t* dev_token_next,
+                          int32_t* dev_block_slot, uint32_t* dev_gate, int32_t* dev_sl_count,
+                          const int32_t* dev_force_token, disco_stream s);
+
 /* Target verification forward (Fig. 1: the target validates all draft tokens in parallel).
  * dev_block = [last emitted token, d_1 .. d_SL], n_block = SL + 1 in [1, DISCO_MAX_BLOCK]; token j
  * sits at position kv->len + j and attends to positions <= its own (causal inside the block).

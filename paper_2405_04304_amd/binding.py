@@ -87,6 +87,9 @@ _SIGNATURES = {
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                  C.c_void_p, C.c_void_p]),
     "disco_classify_scratch_init": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "disco_classify_static": (C.c_int, [C.POINTER(Clf), C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_int,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_void_p]),
     "disco_verify": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
                                C.c_void_p, C.c_size_t, C.c_void_p]),
     "disco_accept": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -176,6 +179,14 @@ def disco_classify(clf, logits, vocab, pos_feature, tau, force_halt, out, token_
                                 pos_feature, tau, int(force_halt), _ptr(out), _ptr(token_next),
                                 _ptr(block_slot), _ptr(gate), _ptr(sl_count), _ptr(force_token), _ptr(scratch),
                                 _stream() if stream is None else stream))
+
+
+def disco_classify_static(clf, logits, vocab, pos_feature, tau, force_halt, out, token_next=None,
+                          block_slot=None, gate=None, sl_count=None, force_token=None, stream=None):
+    _check(lib().disco_classify_static(C.byref(clf.c) if clf is not None else None, _ptr(logits), vocab,
+                                       pos_feature, tau, int(force_halt), _ptr(out), _ptr(token_next),
+                                       _ptr(block_slot), _ptr(gate), _ptr(sl_count), _ptr(force_token),
+                                       _stream() if stream is None else stream))
 
 
 CLASSIFY_SCRATCH_BYTES = 4352

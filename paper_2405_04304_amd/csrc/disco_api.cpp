@@ -526,13 +526,13 @@ int disco_draft_step(const disco_model* draft, disco_kv* kv, const int32_t* dev_
   return forward_block(draft, kv, dev_tokens_in, n_in, dev_logits, true, ws, dev_gate, static_cast<hipStream_t>(s));
 }
 
-int disco_classify(const disco_clf* clf, float* dev_logits, int vocab, float pos_feature, float tau, int force_halt,
-                   disco_clf_out* dev_out, int32_t* dev_token_next, int32_t* dev_block_slot, uint32_t* dev_gate,
-                   int32_t* dev_sl_count, const int32_t* dev_force_token, void* dev_scratch, disco_stream s) {
+static int classify_impl(const disco_clf* clf, float* dev_logits, int vocab, float pos_feature, float tau, int force_halt,
+                         disco_clf_out* dev_out, int32_t* dev_token_next, int32_t* dev_block_slot, uint32_t* dev_gate,
+                         int32_t* dev_sl_count, const int32_t* dev_force_token, float* scratch, hipStream_t st) {
   if (!dev_logits || !dev_out) return fail(DISCO_EINVAL, "null argument");
   if (vocab < 1 || vocab > 65536) return fail(DISCO_EINVAL, "vocab %d outside [1, 65536]", vocab);
   if (!aligned(dev_logits, 16) || !aligned(dev_out, 4) || !aligned(dev_token_next, 4) || !aligned(dev_block_slot, 4) ||
-      !aligned(dev_gate, 4) || !aligned(dev_sl_count, 4) || !aligned(dev_force_token, 4) || !aligned(dev_scratch, 256))
+      !aligned(dev_gate, 4) || !aligned(dev_sl_count, 4) || !aligned(dev_force_token, 4) || !aligned(scratch, 256))
     return fail(DISCO_EINVAL, "misaligned pointer");
   if (clf) {
     if (!clf->dev_params || !aligned(clf->dev_params, 4)) return fail(DISCO_EINVAL, "classifier parameters null or misaligned");
@@ -542,9 +542,32 @@ int disco_classify(const disco_clf* clf, float* dev_logits, int vocab, float pos
   a.logits = dev_logits; a.vocab = vocab; a.clf_params = clf ? clf->dev_params : nullptr; a.hidden = clf ? clf->hidden : 0;
   a.pos_feature = pos_feature; a.tau = tau; a.force_halt = force_halt; a.out = dev_out; a.token_next = dev_token_next;
   a.block_slot = dev_block_slot; a.gate = dev_gate; a.sl_count = dev_sl_count; a.force_token = dev_force_token;
-  a.scratch = static_cast<float*>(dev_scratch);
-  HIP_TRY(launch_classify(a, static_cast<hipStream_t>(s)), "classify launch");
+  a.scratch = scratch;
+  HIP_TRY(launch_classify(a, st), "classify launch");
   return DISCO_OK;
+}
+
+int disco_classify(const disco_clf* clf, float* dev_logits, int vocab, float pos_feature, float tau, int force_halt,
+                   disco_clf_out* dev_out, int32_t* dev_token_next, int32_t* dev_block_slot, uint32_t* dev_gate,
+                   int32_t* dev_sl_count, const int32_t* dev_force_token, void* dev_scratch, disco_stream s) {
+  return classify_impl(clf, dev_logits, vocab, pos_feature, tau, force_halt, dev_out, dev_token_next, dev_block_slot, dev_gate,
+                       dev_sl_count, dev_force_token, static_cast<float*>(dev_scratch), static_cast<hipStream_t>(s));
+}
+
+int disco_classify_static(const disco_clf* clf, float* dev_logits, int vocab, float pos_feature, float tau, int force_halt,
+                          disco_clf_out* dev_out, int32_t* dev_token_next, int32_t* dev_block_slot, uint32_t* dev_gate,
+                          int32_t* dev_sl_count, const int32_t* dev_force_token, disco_stream s) {
+  // the array holds one record per 1024 logits: 64 records
+  if (vocab > DISCO_CLASSIFY_STATIC_MAX_VOCAB)
+    return fail(DISCO_ECAP, "vocab %d above the %d logits that the library's own scratch array serves", vocab, DISCO_CLASSIFY_STATIC_MAX_VOCAB);
+  float* scratch = nullptr;
+  HIP_TRY(classify_static_scratch(&scratch), "address of the scratch array");
+  hipStream_t st = static_cast<hipStream_t>(s);
+  // the array keeps the last call's contents: the ticket word must start at zero (a fill kernel, which
+  // a captured graph replays correctly)
+  HIP_TRY(launch_zero(reinterpret_cast<int*>(scratch), 64, st), "scratch clear launch");
+  return classify_impl(clf, dev_logits, vocab, pos_feature, tau, force_halt, dev_out, dev_token_next, dev_block_slot, dev_gate,
+                       dev_sl_count, dev_force_token, scratch, st);
 }
 
 int disco_verify(const disco_model* target, disco_kv* kv, const int32_t* dev_block, int n_block, int32_t* dev_argmax,

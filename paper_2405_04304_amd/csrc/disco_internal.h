@@ -133,6 +133,8 @@ hipError_t launch_gemm_dense(const DenseArgs& a, int epi, hipStream_t s);
 hipError_t launch_rstd_groups(const float* ssq, int n_ssq, int d, float eps, float* rstd, int n_groups, hipStream_t s);
 hipError_t launch_attn_groups(const AttnArgs& a, int n_groups, size_t x_stride, hipStream_t s);
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s);
+// device address of the current GPU's file-scope classify scratch (CLASSIFY_SCRATCH_BYTES; no allocation)
+hipError_t classify_static_scratch(float** out);
 hipError_t launch_sample_rows(const SampleArgs& a, int n_rows, hipStream_t s);
 hipError_t launch_accept_sample(const AcceptSampleArgs& a, hipStream_t s);
 hipError_t launch_clf_train(const TrainArgs& a, hipStream_t s);

@@ -15,6 +15,8 @@
 //     is [token][d_head], a V block is transposed, [d_head][token] (see the attention kernel).
 #include "disco_internal.h"
 
+#include <mutex>
+
 namespace disco {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -1516,6 +1518,33 @@ hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s) {
   else if (a.vocab <= 32768) hipLaunchKernelGGL(k_classify<8>, dim3(1), dim3(FEAT_NT), 0, s, a);
   else hipLaunchKernelGGL(k_classify<16>, dim3(1), dim3(FEAT_NT), 0, s, a);
   return hipGetLastError();
+}
+
+// Scratch of the allocation-free form of the classify call (callers that cannot allocate): one copy of
+// this array per GPU, held from module load until the process ends.  In host code the name is only a
+// handle for hipGetSymbolAddress; kernels and clears get the device address looked up below.
+static __device__ __align__(256) unsigned char scratch[CLASSIFY_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mu;
+static float* g_scratch_ptr[MAX_DEVICES];        // device address of `scratch` on each GPU, once looked up
+
+// Device address of the current GPU's copy of `scratch` (looked up once per device, with that device current).
+hipError_t classify_static_scratch(float** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<float*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
 }
 
 // ---------------------------------------------------------------------------------------------

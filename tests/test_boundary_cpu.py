@@ -109,6 +109,9 @@ def test_forward_calls_reject_bad_arguments_before_any_launch():
     clf = B.Clf(FAKE, 300)
     assert lib.disco_classify(C.byref(clf), FAKE, 256, 1.0, 0.5, 0, FAKE, None, None, None, None, None, None, None) == B.EINVAL
     assert lib.disco_classify(None, FAKE, 256, 1.0, 0.5, 0, FAKE, None, None, None, None, None, FAKE + 16, None) == B.EINVAL
+    # the allocation-free form refuses a vocabulary beyond its array before any GPU call
+    assert lib.disco_classify_static(None, FAKE, 65537, 1.0, 0.5, 0, FAKE, None, None, None, None, None, None) == B.ECAP
+    assert b"scratch array" in lib.disco_last_error()
     assert lib.disco_draft_loop(m, kv, None, FAKE, 1, 16, 0, 1.0, 0.5, None, FAKE, FAKE, FAKE, None, FAKE, ws, None) == B.ECAP
     assert lib.disco_draft_loop(m, kv, None, FAKE, 3, 4, 0, 1.0, 0.5, None, FAKE, FAKE, FAKE, None, FAKE, ws, None) == B.EINVAL
     assert lib.disco_pack_weight(FAKE, 17, 32, FAKE, None) == B.EINVAL
