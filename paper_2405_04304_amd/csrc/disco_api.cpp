@@ -6,6 +6,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -43,6 +44,10 @@ struct disco_model {
   disco_model_weights w;
   std::vector<disco_layer_weights> layers;
   int d_q, d_kv, d_qkv;
+  // one launch per forward (RMSNorm / rotary / SwiGLU family with shapes the persistent kernel tiles)
+  bool persist_ok, persist_big;
+  std::vector<FwdLayer> fwd_layers;      // copied into every workspace by disco_workspace_init
+  int loop_steps;                        // draft-loop steps the workspace holds panel versions for (1: none beyond one forward)
 };
 
 struct disco_kv {
@@ -61,8 +66,18 @@ struct Ws {
   float* h; float* q; bf16_t* xn; bf16_t* xattn; bf16_t* xact; float* part; float* gpart; float* logits;
   float* ssq; int* gemm_counters; int* attn_counters; int n_counters; float* clf_scratch;
   uint32_t* gate; int32_t* sl_count; int32_t* tok_next;
+  // persistent forward: panel versions (a fresh address per phase and step), the layer table, barrier words
+  bf16_t* xn_v; bf16_t* xattn_v; bf16_t* xact_v; size_t xn_stride, xattn_stride, xact_stride;
+  FwdLayer* fwd_layers; unsigned* bar;
   size_t total;
 };
+
+// The persistent kernel can be switched off (DISCO_PERSISTENT=0 in the environment): every forward is then a
+// chain of launches, one per phase.
+bool persistent_enabled() {
+  static const bool on = [] { const char* e = getenv("DISCO_PERSISTENT"); return !(e && e[0] == '0'); }();
+  return on;
+}
 
 // Carve the workspace; with base == nullptr only the total is meaningful.
 Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
@@ -93,6 +108,16 @@ Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
   w.gate = static_cast<uint32_t*>(take(256));
   w.sl_count = reinterpret_cast<int32_t*>(w.gate ? w.gate + 16 : nullptr);
   w.tok_next = reinterpret_cast<int32_t*>(w.gate ? w.gate + 32 : nullptr);
+  w.xn_stride = (size_t)2 * 16 * d.d_model; w.xattn_stride = (size_t)2 * 16 * m->d_q; w.xact_stride = (size_t)2 * 16 * d.d_ff;
+  w.xn_v = w.xattn_v = w.xact_v = nullptr; w.fwd_layers = nullptr; w.bar = nullptr;
+  if (m->persist_ok) {
+    const size_t steps = (size_t)m->loop_steps, L = (size_t)d.n_layers;
+    w.xn_v = static_cast<bf16_t*>(take(sizeof(bf16_t) * w.xn_stride * (2 * L + 1) * steps));
+    w.xattn_v = static_cast<bf16_t*>(take(sizeof(bf16_t) * w.xattn_stride * L * steps));
+    w.xact_v = static_cast<bf16_t*>(take(sizeof(bf16_t) * w.xact_stride * L * steps));
+    w.fwd_layers = static_cast<FwdLayer*>(take(sizeof(FwdLayer) * L));
+    w.bar = static_cast<unsigned*>(take(sizeof(unsigned) * FWD_BAR_WORDS));
+  }
   // the only buffer whose size depends on max_ctx goes last, so that every other offset (the ticket
   // counters above all) is the same for every call on this workspace
   const int n_splits = (max_ctx + DISCO_MAX_BLOCK + ATTN_SPLIT_LEN - 1) / ATTN_SPLIT_LEN;
@@ -117,6 +142,23 @@ int check_forward_args(const disco_model* m, const disco_kv* kv, const int32_t* 
 
 #define HIP_TRY(expr, what) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return hip_fail(e__, what); } while (0)
 
+// The model / cache / workspace part of a persistent launch's arguments.
+FwdArgs forward_args(const disco_model* m, const disco_kv* kv, const Ws& ws) {
+  const disco_model_desc& d = m->d;
+  FwdArgs f{};
+  f.n_layers = d.n_layers; f.d = d.d_model; f.d_q = m->d_q; f.d_qkv = m->d_qkv; f.d_ff = d.d_ff; f.nq = d.n_heads;
+  f.nkv = d.n_kv_heads; f.dh = d.d_head; f.vocab = d.vocab; f.eps = d.norm_eps; f.attn_scale = 1.0f / sqrtf((float)d.d_head);
+  f.layers = ws.fwd_layers; f.normf_g = m->w.normf_g; f.wlm = static_cast<const bf16_t*>(m->w.wlm);
+  f.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb); f.tok_stride = m->w.tok_emb_stride;
+  f.h = ws.h; f.q = ws.q; f.ssq = ws.ssq; f.xn = ws.xn_v; f.xattn = ws.xattn_v; f.xact = ws.xact_v;
+  f.xn_stride = ws.xn_stride; f.xattn_stride = ws.xattn_stride; f.xact_stride = ws.xact_stride;
+  f.part = ws.part; f.planes = ws.gpart; f.gemm_counters = ws.gemm_counters; f.attn_counters = ws.attn_counters;
+  f.kv_pages = kv->pages; f.kv_layer_stride = kv->layer_stride; f.page_table = kv->dev_page_table;
+  f.page_tokens = kv->page_tokens; f.rope = kv->dev_rope;
+  f.bar = ws.bar; f.abort_word = ws.bar + 16 * 64; f.n_steps = 1;
+  return f;
+}
+
 // One forward of n tokens at positions kv->len ..: the shared body of draft step and verification.
 // logits_out: [vocab] of the last token (only_last) or [n x vocab].
 int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens, int n, float* logits_out,
@@ -130,6 +172,20 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   }
 
   const int n_tiles = d.d_model / 16;            // one sum-of-squares slot per 16 columns of h
+  if (m->persist_ok && ws.bar != nullptr && gate == nullptr && persistent_enabled()) {
+    // embedding launch (residual rows, first panel version, sums of squares), then the whole forward in one launch
+    NormArgs n0{};
+    n0.h = ws.h; n0.d = d.d_model; n0.M = n; n0.eps = d.norm_eps; n0.Xout = ws.xn_v; n0.pos0 = pos0; n0.vocab = d.vocab;
+    n0.max_pos = d.max_pos; n0.ssq_out = ws.ssq; n0.n_ssq_out = n_tiles; n0.g = m->layers[0].norm1_g;
+    n0.tokens = dev_tokens; n0.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb); n0.tok_stride = m->w.tok_emb_stride;
+    HIP_TRY(launch_norm(n0, s), "embedding launch");
+    HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.bar), FWD_BAR_WORDS, s), "barrier reset launch");
+    FwdArgs f = forward_args(m, kv, ws);
+    f.M = n; f.pos0 = pos0; f.logits = logits_out; f.only_last = only_last ? 1 : 0;
+    HIP_TRY(launch_forward(f, m->persist_big, false, s), "forward launch");
+    kv->len = pos0 + n;
+    return DISCO_OK;
+  }
   const int split_o = gemm_split_for(d.d_model, m->d_q / 32, n), split_dn = gemm_split_for(d.d_model, d.d_ff / 32, n);
 
   NormArgs na{};
@@ -420,6 +476,17 @@ int disco_model_create(const disco_model_desc* desc, const disco_model_weights* 
   m->w.layers = m->layers.data();
   if (d.family == DISCO_FAMILY_B) { m->w.pos_emb = nullptr; m->w.normf_b = nullptr; for (auto& L : m->layers) { L.norm1_b = nullptr; L.norm2_b = nullptr; } }
   m->d_q = d.n_heads * d.d_head; m->d_kv = d.n_kv_heads * d.d_head; m->d_qkv = m->d_q + 2 * m->d_kv;
+  m->persist_big = d.d_model >= 2048;
+  m->persist_ok = d.family == DISCO_FAMILY_B && forward_shape_ok(d.d_model, m->d_q, m->d_qkv, d.d_ff, d.d_head, d.vocab, m->persist_big);
+  m->loop_steps = 1;
+  if (m->persist_ok) {
+    for (const auto& L : m->layers)
+      m->fwd_layers.push_back(FwdLayer{static_cast<const bf16_t*>(L.wqkv), static_cast<const bf16_t*>(L.wo), static_cast<const bf16_t*>(L.w_in),
+                                       static_cast<const bf16_t*>(L.w_out), L.norm1_g, L.norm2_g});
+    // a draft loop in one launch needs panel versions for every step: kept for small models only
+    const size_t per_step = sizeof(bf16_t) * 32 * ((size_t)(2 * d.n_layers + 1) * d.d_model + (size_t)d.n_layers * (m->d_q + d.d_ff));
+    if (per_step <= ((size_t)4 << 20) && d.d_model <= 4096) m->loop_steps = DISCO_MAX_BLOCK;
+  }
   *out = m;
   return DISCO_OK;
 }
@@ -507,6 +574,11 @@ int disco_workspace_init(const disco_model* m, void* dev_ws, size_t ws_bytes, in
   const Ws ws = carve(m, max_block, max_ctx, dev_ws);
   HIP_TRY(launch_zero(ws.gemm_counters, ws.n_counters, static_cast<hipStream_t>(s)), "workspace init launch");
   HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.clf_scratch), 64, static_cast<hipStream_t>(s)), "workspace init launch");
+  if (ws.fwd_layers != nullptr) {
+    HIP_TRY(hipMemcpyAsync(ws.fwd_layers, m->fwd_layers.data(), sizeof(FwdLayer) * m->fwd_layers.size(), hipMemcpyHostToDevice,
+                           static_cast<hipStream_t>(s)), "layer table upload");
+    HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.bar), FWD_BAR_WORDS, static_cast<hipStream_t>(s)), "workspace init launch");
+  }
   return DISCO_OK;
 }
 
@@ -581,7 +653,7 @@ int disco_verify(const disco_model* target, disco_kv* kv, const int32_t* dev_blo
   hipStream_t st = static_cast<hipStream_t>(s);
   rc = forward_block(target, kv, dev_block, n_block, logits, false, ws, nullptr, st);
   if (rc) return rc;
-  HIP_TRY(launch_argmax_rows(logits, n_block, target->d.vocab, dev_argmax, st), "argmax launch");
+  HIP_TRY(launch_argmax_rows(logits, n_block, target->d.vocab, dev_argmax, ws.bar ? ws.bar + 16 * 64 : nullptr, st), "argmax launch");
   return DISCO_OK;
 }
 
@@ -636,6 +708,32 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
   const Ws ws = carve(draft, 2, kv->len + n_in + cap, dev_ws);
   HIP_TRY(launch_loop_init(ws.gate, ws.sl_count, dev_tokens_in, n_in, dev_out, st), "loop init launch");
   const int steps = static_sl > 0 ? static_sl : cap;
+  if (draft->persist_ok && ws.bar != nullptr && !sampled && steps <= draft->loop_steps && persistent_enabled()) {
+    // the whole loop in one launch: the kernel leaves at the first halting step
+    const disco_model_desc& d = draft->d;
+    const int pos0 = kv->len;
+    if (kv->dev_rope && !kv->rope_ready) {
+      HIP_TRY(launch_rope_fill(kv->dev_rope, kv->capacity, d.d_head, d.rope_base, st), "rotary table launch");
+      kv->rope_ready = true;
+    }
+    NormArgs n0{};
+    n0.h = ws.h; n0.d = d.d_model; n0.M = n_in; n0.eps = d.norm_eps; n0.Xout = ws.xn_v; n0.pos0 = pos0; n0.vocab = d.vocab;
+    n0.max_pos = d.max_pos; n0.ssq_out = ws.ssq; n0.n_ssq_out = d.d_model / 16; n0.g = draft->layers[0].norm1_g;
+    n0.tokens = dev_tokens_in; n0.tok_emb = static_cast<const bf16_t*>(draft->w.tok_emb); n0.tok_stride = draft->w.tok_emb_stride;
+    HIP_TRY(launch_norm(n0, st), "embedding launch");
+    HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.bar), FWD_BAR_WORDS, st), "barrier reset launch");
+    FwdArgs f = forward_args(draft, kv, ws);
+    f.M = n_in; f.pos0 = pos0; f.logits = dev_logits; f.only_last = 1; f.n_steps = steps;
+    ClassifyArgs& a = f.clf;
+    a.logits = dev_logits; a.vocab = d.vocab; a.clf_params = clf ? clf->dev_params : nullptr; a.hidden = clf ? clf->hidden : 0;
+    a.pos_feature = pos_feature0; a.tau = static_sl > 0 ? -1.0e30f : tau; a.out = dev_steps; a.token_next = ws.tok_next;
+    a.block_slot = dev_out->block + 1; a.gate = ws.gate; a.sl_count = ws.sl_count; a.force_token = dev_force_tokens;
+    a.ref_token = dev_ref_tokens; a.ppl_threshold = ppl_threshold; a.scratch = ws.clf_scratch;
+    HIP_TRY(launch_forward(f, draft->persist_big, true, st), "draft loop launch");
+    kv->len = pos0 + n_in + steps - 1;
+    HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, ws.bar + 16 * 64, st), "loop finish launch");
+    return DISCO_OK;
+  }
   for (int j = 1; j <= steps; ++j) {
     rc = forward_block(draft, kv, j == 1 ? dev_tokens_in : ws.tok_next, j == 1 ? n_in : 1, dev_logits, true, ws, ws.gate, st);
     if (rc) return rc;
@@ -660,7 +758,7 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
     a.scratch = ws.clf_scratch;
     HIP_TRY(launch_classify(a, st), "classify launch");
   }
-  HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, st), "loop finish launch");
+  HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, nullptr, st), "loop finish launch");
   return DISCO_OK;
 }
 

@@ -120,6 +120,32 @@ struct EvalArgs {
   float* scores; int* counts;
 };
 
+// One launch per forward (or per draft loop) for the RMSNorm / rotary / SwiGLU family: see k_forward.
+struct FwdLayer { const bf16_t* wqkv; const bf16_t* wo; const bf16_t* w_in; const bf16_t* w_out; const float* norm1_g; const float* norm2_g; };
+
+struct FwdArgs {
+  // model
+  int n_layers, d, d_q, d_qkv, d_ff, nq, nkv, dh, vocab; float eps; float attn_scale;
+  const FwdLayer* layers;            // DEVICE array of n_layers entries
+  const float* normf_g; const bf16_t* wlm;
+  const bf16_t* tok_emb; int64_t tok_stride;
+  // the forward: M tokens at positions pos0 ..; the residual rows h and the first panel version are already
+  // written (embedding launch)
+  int M, pos0;
+  float* h; float* q; float* ssq;
+  bf16_t* xn; bf16_t* xattn; bf16_t* xact;                 // panel versions: (2 L + 1), L and L per step
+  size_t xn_stride, xattn_stride, xact_stride;             // elements between versions
+  float* part; float* planes; int* gemm_counters; int* attn_counters;
+  bf16_t* kv_pages; size_t kv_layer_stride; const int32_t* page_table; int page_tokens; const float* rope;
+  float* logits; int only_last;
+  int split_o, split_dn, attn_split_len;                   // set by the launcher from the grid size
+  unsigned* bar; unsigned* abort_word;                     // BAR_GROUPS counters (zeroed before the launch), abort word
+  // draft loop: n_steps (forward, classify) pairs in one launch; step 0 feeds M tokens, later steps one;
+  // clf holds the first step's classify arguments (pos_feature, out, block_slot, force_token, ref_token advance per step)
+  int n_steps;
+  ClassifyArgs clf;
+};
+
 constexpr size_t CLASSIFY_SCRATCH_BYTES = 256 + 64 * 16 * sizeof(float);
 
 hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int64_t tile_mul,
@@ -127,6 +153,9 @@ hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int
 hipError_t launch_gemm(const GemmArgs& a, int epi, hipStream_t s);
 int gemm_split_for(int n_rows, int KT, int M);   // K ranges the PARTIAL epilogue should be launched with
 hipError_t launch_norm(const NormArgs& a, hipStream_t s);
+bool forward_shape_ok(int d, int d_q, int d_qkv, int d_ff, int dh, int vocab, bool big);
+hipError_t launch_forward(const FwdArgs& f, bool big, bool loop, hipStream_t s);
+constexpr int FWD_BAR_WORDS = 16 * 64 + 64;   // barrier counters + abort word, in 4-byte words
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
 // dense prompt pass (groups of 16 tokens; every group holds 16 rows, surplus rows are padding)
 hipError_t launch_gemm_dense(const DenseArgs& a, int epi, hipStream_t s);
@@ -139,7 +168,7 @@ hipError_t launch_sample_rows(const SampleArgs& a, int n_rows, hipStream_t s);
 hipError_t launch_accept_sample(const AcceptSampleArgs& a, hipStream_t s);
 hipError_t launch_clf_train(const TrainArgs& a, hipStream_t s);
 hipError_t launch_clf_eval(const EvalArgs& a, hipStream_t s);
-hipError_t launch_argmax_rows(const float* logits, int M, int vocab, int32_t* out, hipStream_t s);
+hipError_t launch_argmax_rows(const float* logits, int M, int vocab, int32_t* out, const unsigned* abort_word, hipStream_t s);
 hipError_t launch_accept(const int32_t* block, const int32_t* argmax, int n_block,
                          const int32_t* dev_n_block, void* dev_out, void* host_out, hipStream_t s);
 hipError_t launch_kv_fill(const bf16_t* src, bf16_t* pages, const int32_t* page_table, int n_layers,
@@ -149,7 +178,7 @@ hipError_t launch_rope_fill(float* tab, int n_pos, int dh, float base, hipStream
 hipError_t launch_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in,
                             void* dev_loop_out, hipStream_t s);
 hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void* host_loop_out,
-                              hipStream_t s);
+                              const unsigned* abort_word, hipStream_t s);
 
 constexpr int GEMM_MAX_SPLIT = 8;
 constexpr int ATTN_SPLIT_LEN = 128;  // fewest cached positions per attention workgroup

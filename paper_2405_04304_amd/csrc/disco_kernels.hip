@@ -45,7 +45,46 @@ __device__ __forceinline__ uint32_t gate_request(const uint32_t* gate) {
   return gate != nullptr ? __builtin_nontemporal_load(gate) : 0u;
 }
 
+// Stores and loads of data that another workgroup of the SAME launch reads or has written (COH): agent-scope
+// relaxed atomics, which on gfx950 are write-through stores and L2-bypassing loads, coherent across the
+// eight XCDs' separate L2s.  Without COH they are plain accesses (the consumer is a later launch).
+template <bool COH> __device__ __forceinline__ void st_f4(float* p, float a, float b, float c, float d) {
+  if (COH) {
+    const unsigned long long v0 = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+    const unsigned long long v1 = (unsigned long long)__float_as_uint(c) | ((unsigned long long)__float_as_uint(d) << 32);
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), v0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(reinterpret_cast<unsigned long long*>(p) + 1, v1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  } else {
+    *reinterpret_cast<float4*>(p) = make_float4(a, b, c, d);
+  }
+}
+template <bool COH> __device__ __forceinline__ float4 ld_f4(const float* p) {
+  if (COH) {
+    const unsigned long long v0 = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long v1 = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float4(__uint_as_float((uint32_t)v0), __uint_as_float((uint32_t)(v0 >> 32)), __uint_as_float((uint32_t)v1), __uint_as_float((uint32_t)(v1 >> 32)));
+  }
+  return *reinterpret_cast<const float4*>(p);
+}
+template <bool COH> __device__ __forceinline__ float ld_f1(const float* p) {
+  if (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return *p;
+}
+template <bool COH> __device__ __forceinline__ void st_f1(float* p, float v) {
+  if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+template <bool COH> __device__ __forceinline__ void st_u2(bf16_t* p, uint2 v) {
+  if (COH) __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), (unsigned long long)v.x | ((unsigned long long)v.y << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *reinterpret_cast<uint2*>(p) = v;
+}
+template <bool COH> __device__ __forceinline__ void st_h1(bf16_t* p, bf16_t v) {
+  if (COH) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+
 // Store 4 consecutive-k activations of token m into the packed panels as bf16 hi/lo.
+template <bool COH = false>
 __device__ __forceinline__ void xpack_store4(bf16_t* X, int KT, int M, int m, int k, const float* v) {
   const int kt = k >> 5, grp = (k & 31) >> 3, e = k & 7;
   uint32_t hi[2], lo[2];
@@ -60,8 +99,8 @@ __device__ __forceinline__ void xpack_store4(bf16_t* X, int KT, int M, int m, in
   size_t off_hi, off_lo;
   if (M <= 8) { off_hi = base + (size_t)m * 8; off_lo = base + (size_t)(m + 8) * 8; }
   else { off_hi = base + (size_t)m * 8; off_lo = (size_t)KT * 512 + base + (size_t)m * 8; }
-  *reinterpret_cast<uint2*>(X + off_hi) = make_uint2(hi[0], hi[1]);
-  *reinterpret_cast<uint2*>(X + off_lo) = make_uint2(lo[0], lo[1]);
+  st_u2<COH>(X + off_hi, make_uint2(hi[0], hi[1]));
+  st_u2<COH>(X + off_lo, make_uint2(lo[0], lo[1]));
 }
 
 // Wavefront reductions on the DPP cross-lane network (no LDS traffic): xor-1, xor-2 inside quads,
@@ -233,6 +272,7 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
 
 // QKV epilogue of one lane: output features n0 .. n0+3 (lo4) and their rotary partners n0 + d_head/2 ..
 // (hi4) of token row m at position pos: rotation, then the query row or the paged K / V entry.
+template <bool COH = false>
 __device__ __forceinline__ void qkv_store(const GemmArgs& a, float* q, const int n0, const int m, const int pos,
                                           float (&lo4)[4], float (&hi4)[4]) {
   const int dsh = a.dh == 128 ? 7 : 6;            // d_head is 64 or 128
@@ -252,8 +292,8 @@ __device__ __forceinline__ void qkv_store(const GemmArgs& a, float* q, const int
   }
   if (head < a.nq) {
     float* qp = q + (size_t)m * a.ldq + head * a.dh + c;
-    *reinterpret_cast<float4*>(qp) = make_float4(lo4[0], lo4[1], lo4[2], lo4[3]);
-    *reinterpret_cast<float4*>(qp + half) = make_float4(hi4[0], hi4[1], hi4[2], hi4[3]);
+    st_f4<COH>(qp, lo4[0], lo4[1], lo4[2], lo4[3]);
+    st_f4<COH>(qp + half, hi4[0], hi4[1], hi4[2], hi4[3]);
   } else {
     const int sel = is_v ? 1 : 0;
     const int kvh = head - a.nq - sel * a.nkv;
@@ -269,13 +309,13 @@ __device__ __forceinline__ void qkv_store(const GemmArgs& a, float* q, const int
       u0.y = (uint32_t)f32_to_bf16(lo4[2]) | ((uint32_t)f32_to_bf16(lo4[3]) << 16);
       u1.x = (uint32_t)f32_to_bf16(hi4[0]) | ((uint32_t)f32_to_bf16(hi4[1]) << 16);
       u1.y = (uint32_t)f32_to_bf16(hi4[2]) | ((uint32_t)f32_to_bf16(hi4[3]) << 16);
-      *reinterpret_cast<uint2*>(dst) = u0;
-      *reinterpret_cast<uint2*>(dst + half) = u1;
+      st_u2<COH>(dst, u0);
+      st_u2<COH>(dst + half, u1);
     } else {                     // V: transposed, [d_head][token]
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        blk[(size_t)(c + v) * a.page_tokens + off] = f32_to_bf16(lo4[v]);
-        blk[(size_t)(c + half + v) * a.page_tokens + off] = f32_to_bf16(hi4[v]);
+        st_h1<COH>(blk + (size_t)(c + v) * a.page_tokens + off, f32_to_bf16(lo4[v]));
+        st_h1<COH>(blk + (size_t)(c + half + v) * a.page_tokens + off, f32_to_bf16(hi4[v]));
       }
     }
   }
@@ -283,27 +323,67 @@ __device__ __forceinline__ void qkv_store(const GemmArgs& a, float* q, const int
 
 template <int EPI> struct EpiTraits { static constexpr bool pair = (EPI == EPI_QKV || EPI == EPI_SWIGLU); };
 
-template <int P, int RT, int EPI, int NW, int U>
-__device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const int kt_begin, const int kt_end,
-                                          const int seg, const int n_seg) {
+// LDS of one GEMM work unit.
+template <int RT, int NW>
+struct GemmSmem {
+  f32x4 red[NW][RT][64];
+  float red_ssq[NW][64];
+  int s_last;
+};
+
+// Row tiles of work unit b: RT consecutive tiles, or RT / 2 pairs (tile, tile + grp) for the two-tile epilogues.
+template <int RT, int EPI>
+__device__ __forceinline__ void gemm_unit_tiles(const GemmArgs& a, const int b, int (&rt)[RT]) {
   constexpr bool PAIR = EpiTraits<EPI>::pair;
-  constexpr int UNITS = PAIR ? RT / 2 : RT;       // output units handled by one wavefront each
-  static_assert(!PAIR || RT % 2 == 0, "pair epilogues need an even tile count");
-  static_assert(UNITS <= NW, "one epilogue wavefront per unit");
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const uint32_t halted = gate_request(a.gate);
-  int rt[RT];
+  constexpr int UNITS = PAIR ? RT / 2 : RT;
   if (PAIR) {
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) {
       const int bp = b * UNITS + u, gs = __builtin_ctz(a.grp);   // the pairing distance is a power of two
       rt[2 * u] = ((bp >> gs) << (gs + 1)) + (bp & (a.grp - 1));
-      rt[2 * u + 1] = rt[2 * u] + a.grp;
+      rt[(2 * u + 1) % RT] = rt[2 * u] + a.grp;
     }
   } else {
 #pragma unroll
     for (int r = 0; r < RT; ++r) rt[r] = b * RT + r;
   }
+}
+
+// The weight tiles of a unit's first two steps (k-tiles kt_begin + w and kt_begin + w + NW of wavefront w),
+// requested ahead of the unit itself: a persistent kernel issues them before it waits at the grid barrier in
+// front of the phase, since weights do not depend on the phase before.  gemm_unit<..., PRE = true> uses them.
+template <int RT, int EPI, int NW>
+__device__ __forceinline__ void gemm_prefetch(const GemmArgs& a, const int b, const int kt_begin, const int kt_end,
+                                              u32x4 (&pre)[2][8]) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int rt[RT];
+  gemm_unit_tiles<RT, EPI>(a, b, rt);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int k = kt_begin + w + i * NW;
+    if (k < kt_end) {
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+        pre[i][r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a.W) + ((size_t)rt[r] * a.KT + k) * 64 + lane);
+    }
+  }
+}
+
+// COH: the unit's inputs were written, and its outputs are read, by other workgroups of the same launch
+// (persistent kernel): hand-off accesses instead of plain ones; the activation panels are still plain loads
+// (the persistent kernel gives every phase panels at addresses that nobody has read before in the launch).
+template <int P, int RT, int EPI, int NW, int U, bool COH = false, bool PRE = false>
+__device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const int kt_begin, const int kt_end,
+                                          const int seg, const int n_seg, GemmSmem<RT, NW>& sm, u32x4 (&pre)[2][8]) {
+  constexpr bool PAIR = EpiTraits<EPI>::pair;
+  constexpr int UNITS = PAIR ? RT / 2 : RT;       // output units handled by one wavefront each
+  static_assert(!PAIR || RT % 2 == 0, "pair epilogues need an even tile count");
+  static_assert(UNITS <= NW, "one epilogue wavefront per unit");
+  static_assert(!PRE || U == 1, "preloaded steps are single k-tiles");
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const uint32_t halted = gate_request(a.gate);
+  int rt[RT];
+  gemm_unit_tiles<RT, EPI>(a, b, rt);
 
   f32x4 acc[RT][P];
 #pragma unroll
@@ -328,7 +408,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
     for (int k = 0; k < MAXS; ++k) {
       if (k < rounds) {
         const int idx = (lane >> 4) * NW + w + 4 * NW * k;
-        sv[k] = idx < a.n_ssq ? a.ssq[idx * 16 + (lane & 15)] : 0.f;   // [slot][token]
+        sv[k] = idx < a.n_ssq ? ld_f1<COH>(a.ssq + idx * 16 + (lane & 15)) : 0.f;   // [slot][token]
       }
     }
     asm volatile("" ::: "memory");     // keep these loads ahead of the weight stream
@@ -343,13 +423,20 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
   // Two register buffers: the loads of step i + 1 are issued before the matrix instructions of step
   // i, so the memory pipe stays full while the matrix unit works.  A step is U k-tiles per wavefront;
   // k-tiles past the end of the range are clamped to its last tile (loaded again, not used).
-  auto load_step = [&](u32x4 (&A)[U][RT], u32x4 (&B)[U][P], const int kt0) {
+  auto load_w = [&](u32x4 (&A)[U][RT], const int kt0) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int k = kt0 + u * NW;
       const size_t t = (size_t)(k < kt_end ? k : kt_end - 1) * 64;
 #pragma unroll
       for (int r = 0; r < RT; ++r) A[u][r] = __builtin_nontemporal_load(Wp[r] + t);
+    }
+  };
+  auto load_x = [&](u32x4 (&B)[U][P], const int kt0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int k = kt0 + u * NW;
+      const size_t t = (size_t)(k < kt_end ? k : kt_end - 1) * 64;
 #pragma unroll
       for (int p = 0; p < P; ++p) B[u][p] = Xp[(size_t)p * KT * 64 + t];
     }
@@ -370,23 +457,29 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
     constexpr int STEP = U * NW;
     u32x4 A0[U][RT], B0[U][P], A1[U][RT], B1[U][P];
     int kt = kt_begin + w;
-    if (kt < kt_end) load_step(A0, B0, kt);
+    if (PRE) {
+      // the weights of the first two steps are already on their way (gemm_prefetch)
+#pragma unroll
+      for (int r = 0; r < RT; ++r) { A0[0][r] = pre[0][r]; A1[0][r] = pre[1][r]; }
+      if (kt < kt_end) load_x(B0, kt);
+    } else {
+      if (kt < kt_end) { load_w(A0, kt); load_x(B0, kt); }
+    }
     if (halted != 0u) return;                     // uniform over the launch; nothing has been written yet
+    bool first = PRE;
     while (kt < kt_end) {
-      if (kt + STEP < kt_end) load_step(A1, B1, kt + STEP);
+      if (kt + STEP < kt_end) { if (!first) load_w(A1, kt + STEP); load_x(B1, kt + STEP); }
+      first = false;
       mma_step(A0, B0, kt);
       kt += STEP;
       if (kt >= kt_end) break;
-      if (kt + STEP < kt_end) load_step(A0, B0, kt + STEP);
+      if (kt + STEP < kt_end) { load_w(A0, kt + STEP); load_x(B0, kt + STEP); }
       mma_step(A1, B1, kt);
       kt += STEP;
     }
   }
 
   // hi + lo: same panel, columns n and n + 8 (P == 1), or two panels (P == 2)
-  __shared__ f32x4 red[NW][RT][64];
-  __shared__ float red_ssq[NORMED ? NW : 1][64];
-  __shared__ int s_last;
   __syncthreads();                                // a previous unit of this workgroup has left the buffers
 #pragma unroll
   for (int r = 0; r < RT; ++r) {
@@ -397,7 +490,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
     } else {
       y = acc[r][0] + acc[r][P - 1];
     }
-    red[w][r][lane] = y;
+    sm.red[w][r][lane] = y;
   }
   if (NORMED) {
     float part = 0.f;
@@ -406,7 +499,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
       asm volatile("" : "+v"(sv[k]));  // first use of the early loads is here, after the stream
       part += sv[k];
     }
-    red_ssq[w][lane] = part;
+    sm.red_ssq[w][lane] = part;
   }
   __syncthreads();
   constexpr int TPU = PAIR ? 2 : 1;               // tiles per unit
@@ -421,19 +514,19 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
     urt[i] = 0;
 #pragma unroll
     for (int rr = 0; rr < RT; ++rr) if (rr == r) urt[i] = rt[rr];
-    y[i] = red[0][r][lane];
+    y[i] = sm.red[0][r][lane];
 #pragma unroll
-    for (int ww = 1; ww < NW; ++ww) y[i] += red[ww][r][lane];   // fixed order: deterministic
+    for (int ww = 1; ww < NW; ++ww) y[i] += sm.red[ww][r][lane];   // fixed order: deterministic
   }
 
   // operands of the residual update that do not depend on other workgroups are fetched before the ticket
   float4 h = make_float4(0.f, 0.f, 0.f, 0.f), gn = h;
-  float4* hp = nullptr;
+  float* hp = nullptr;
   if (EPI == EPI_PARTIAL) {
     const int col = urt[0] * 16 + 4 * g;
-    hp = reinterpret_cast<float4*>(a.h + (size_t)m * a.ld_out + col);
+    hp = a.h + (size_t)m * a.ld_out + col;
     if (ep && m < a.M) {
-      h = *hp;
+      h = ld_f4<COH>(hp);
       if (a.Xout != nullptr) gn = *reinterpret_cast<const float4*>(a.gain + col);
     }
   }
@@ -451,7 +544,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
         st_agent2(dst + 2, y[i][2], y[i][3]);
       }
     }
-    if (!last_arrival(a.counters + b, n_seg, &s_last)) return;
+    if (!last_arrival(a.counters + b, n_seg, &sm.s_last)) return;
     if (ep) {
 #pragma unroll
       for (int i = 0; i < TPU; ++i) {
@@ -474,7 +567,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
 #pragma unroll
     for (int ww = 0; ww < NW; ++ww)
 #pragma unroll
-      for (int gg = 0; gg < 4; ++gg) ss += red_ssq[ww][gg * 16 + m];
+      for (int gg = 0; gg < 4; ++gg) ss += sm.red_ssq[ww][gg * 16 + m];
     const float rstd = 1.0f / sqrtf(ss / (float)a.d_in + a.eps);
 #pragma unroll
     for (int i = 0; i < TPU; ++i) y[i] *= rstd;
@@ -485,13 +578,13 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
     if (!ep || m >= a.M) return;
     const int col = urt[0] * 16 + 4 * g;
     h.x += y[0][0]; h.y += y[0][1]; h.z += y[0][2]; h.w += y[0][3];
-    *hp = h;
+    st_f4<COH>(hp, h.x, h.y, h.z, h.w);
     if (a.Xout != nullptr) {
       // feed the next RMSNorm'ed GEMM: panels of gain * h and this tile's sum of squares
       const float o[4] = {h.x * gn.x, h.y * gn.y, h.z * gn.z, h.w * gn.w};
-      xpack_store4(a.Xout, a.KT_out, a.M, m, col, o);
+      xpack_store4<COH>(a.Xout, a.KT_out, a.M, m, col, o);
       const float sq = row4_sum((h.x * h.x + h.y * h.y) + (h.z * h.z + h.w * h.w));
-      if (g == 0) a.ssq_out[urt[0] * 16 + m] = sq;                          // [slot][token]
+      if (g == 0) st_f1<COH>(a.ssq_out + urt[0] * 16 + m, sq);              // [slot][token]
     }
     return;
   }
@@ -499,13 +592,13 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
   if (EPI == EPI_STORE) {
     if (a.only_row >= 0 && m != a.only_row) return;
     const size_t row_off = a.only_row >= 0 ? 0 : (size_t)m * a.ld_out;
-    *reinterpret_cast<float4*>(a.out + row_off + urt[0] * 16 + 4 * g) = make_float4(y[0][0], y[0][1], y[0][2], y[0][3]);
+    st_f4<COH>(a.out + row_off + urt[0] * 16 + 4 * g, y[0][0], y[0][1], y[0][2], y[0][3]);
   } else if (EPI == EPI_QKV) {
     // two tiles: features c .. c+3 and their rotary partners c + dh/2 .. of one head
     float lo4[4], hi4[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) { lo4[v] = y[0][v]; hi4[v] = y[TPU - 1][v]; }
-    qkv_store(a, a.q, urt[0] * 16 + 4 * g, m, a.pos0 + m, lo4, hi4);
+    qkv_store<COH>(a, a.q, urt[0] * 16 + 4 * g, m, a.pos0 + m, lo4, hi4);
   } else if (EPI == EPI_SWIGLU) {
     // tile 0 = gate rows, tile 1 = the matching up rows
     const int f = (urt[0] >> 1) * 16 + 4 * g;
@@ -515,20 +608,22 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
       const float gt = y[0][v];
       act[v] = gt / (1.0f + expf(-gt)) * y[TPU - 1][v];
     }
-    xpack_store4(a.Xout, a.KT_out, a.M, m, f, act);
+    xpack_store4<COH>(a.Xout, a.KT_out, a.M, m, f, act);
   } else if (EPI == EPI_GELU) {
     float act[4];
 #pragma unroll
     for (int v = 0; v < 4; ++v) act[v] = 0.5f * y[0][v] * (1.0f + erff(y[0][v] * 0.70710678118654752f));
-    xpack_store4(a.Xout, a.KT_out, a.M, m, urt[0] * 16 + 4 * g, act);
+    xpack_store4<COH>(a.Xout, a.KT_out, a.M, m, urt[0] * 16 + 4 * g, act);
   }
 }
 
 template <int P, int RT, int EPI, int NW, int U>
 __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
+  __shared__ GemmSmem<RT, NW> sm;
+  u32x4 none[2][8];
   const int split = blockIdx.y;
   const int kt_begin = (int)((int64_t)a.KT * split / a.n_split), kt_end = (int)((int64_t)a.KT * (split + 1) / a.n_split);
-  gemm_unit<P, RT, EPI, NW, U>(a, blockIdx.x, kt_begin, kt_end, split, a.n_split);
+  gemm_unit<P, RT, EPI, NW, U>(a, blockIdx.x, kt_begin, kt_end, split, a.n_split, sm, none);
 }
 
 template <int P, int RT, int EPI, int NW, int U>
@@ -539,7 +634,6 @@ static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-#ifndef DISCO_GEMM_NO_DISPATCH
 // Launch shapes, from sweeps on MI355X at the 13B-class and 68M-class sizes.  Eight wavefronts per
 // workgroup and one k-tile per wavefront and step (two register buffers) were best everywhere.  The
 // activation panels are re-read from L2 by every workgroup, so wide outputs take 64 or 128 rows per
@@ -600,7 +694,6 @@ hipError_t launch_gemm(const GemmArgs& a0, int epi, hipStream_t s) {
     default: return hipErrorInvalidValue;
   }
 }
-#endif
 
 // ---------------------------------------------------------------------------------------------
 // (embedding +) LayerNorm / RMSNorm -> packed activation panels
@@ -609,20 +702,21 @@ hipError_t launch_gemm(const GemmArgs& a0, int epi, hipStream_t s) {
 // One workgroup per token row.  The row lives in registers: embedding gather (written to the
 // residual stream) or the residual stream itself, then the statistics, then the normalised row as
 // packed bf16 hi/lo panels -- or, for a deferred RMSNorm, gain * h panels plus the sum of squares.
-template <int NT>
-__global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
-  const uint32_t halted = gate_request(a.gate);
+// tok_override >= 0 replaces the token id read from a.tokens (embedding mode).  COH: the row is handed to other
+// workgroups of the same launch.
+template <int NT, bool COH = false>
+__device__ __forceinline__ void norm_row(const NormArgs& a, const int row, const int tok_override, float* red /* NT / 64 + 1 */,
+                                         const uint32_t halted) {
   constexpr int VPT = 2;                       // float4 per thread: d <= NT * 8
-  __shared__ float red[NT / 64 + 1];
   // row = token slot; slots beyond 16 belong to further groups of 16 (prompt pass), whose panels and
   // sums of squares follow those of group 0
-  const int row = blockIdx.x, m = row & 15, grp = row >> 4, t = threadIdx.x, d = a.d;
+  const int m = row & 15, grp = row >> 4, t = threadIdx.x, d = a.d;
   float* h = a.h + (size_t)row * d;
   bf16_t* Xout = a.Xout + (size_t)grp * d * 32;
   float4 v[VPT];
   const bf16_t* e = nullptr; const bf16_t* pe = nullptr;
-  if (a.tokens) {
-    int tok = (a.n_tok == 0 || row < a.n_tok) ? a.tokens[row] : 0;       // padding slots: token 0
+  if (a.tokens || tok_override >= 0) {
+    int tok = tok_override >= 0 ? tok_override : ((a.n_tok == 0 || row < a.n_tok) ? a.tokens[row] : 0);   // padding slots: token 0
     tok = tok < 0 ? 0 : (tok >= a.vocab ? a.vocab - 1 : tok);
     int pos = a.pos0 + row;
     if (pos >= a.max_pos) pos = a.max_pos - 1;
@@ -643,7 +737,7 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
           v[i].z += bf16_to_f32(p.y & 0xFFFF); v[i].w += bf16_to_f32(p.y >> 16);
         }
       } else {
-        v[i] = *reinterpret_cast<const float4*>(h + k);
+        v[i] = ld_f4<COH>(h + k);
       }
     }
   }
@@ -652,7 +746,7 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
       const int k = (i * NT + t) * 4;
-      if (k < d) *reinterpret_cast<float4*>(h + k) = v[i];
+      if (k < d) st_f4<COH>(h + k, v[i].x, v[i].y, v[i].z, v[i].w);
     }
   }
   if (a.ssq_out != nullptr) {
@@ -662,7 +756,7 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
     for (int i = 0; i < VPT; ++i) ss += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
     ss = block_sum<NT>(ss, red);
     float* sq = a.ssq_out + (size_t)grp * a.n_ssq_out * 16;
-    for (int i = t; i < a.n_ssq_out; i += NT) sq[i * 16 + m] = (i == 0) ? ss : 0.f;          // [slot][token]
+    for (int i = t; i < a.n_ssq_out; i += NT) st_f1<COH>(sq + i * 16 + m, (i == 0) ? ss : 0.f);   // [slot][token]
     const int KT = d >> 5;
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
@@ -670,7 +764,7 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
       if (k < d) {
         const float4 g = *reinterpret_cast<const float4*>(a.g + k);
         const float o[4] = {v[i].x * g.x, v[i].y * g.y, v[i].z * g.z, v[i].w * g.w};
-        xpack_store4(Xout, KT, a.M, m, k, o);
+        xpack_store4<COH>(Xout, KT, a.M, m, k, o);
       }
     }
     return;
@@ -703,9 +797,15 @@ __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
         const float4 bb = *reinterpret_cast<const float4*>(a.b + k);
         o[0] += bb.x; o[1] += bb.y; o[2] += bb.z; o[3] += bb.w;
       }
-      xpack_store4(Xout, KT, a.M, m, k, o);
+      xpack_store4<COH>(Xout, KT, a.M, m, k, o);
     }
   }
+}
+
+template <int NT>
+__global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
+  __shared__ float red[NT / 64 + 1];
+  norm_row<NT>(a, blockIdx.x, -1, red, gate_request(a.gate));
 }
 
 hipError_t launch_norm(const NormArgs& a, hipStream_t s) {
@@ -736,7 +836,10 @@ hipError_t launch_norm(const NormArgs& a, hipStream_t s) {
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 // One wavefront's share of the attention of one head: 32 cached positions per step.
-template <int DH>
+// QCOH: the queries were written by other workgroups of this launch (hand-off loads); VCOH: so were entries of
+// the transposed V blocks, in 128-byte lines that an earlier step of the same launch may have read (a draft loop
+// inside one launch), so V tiles are fetched with L2-bypassing loads.
+template <int DH, bool QCOH = false, bool VCOH = false>
 struct AttnWave {
   static constexpr int KS = DH / 32, CT = DH / 16;
   // raw operands of one step: K rows of two 16-position tiles, V^T tiles of the same positions
@@ -785,7 +888,14 @@ struct AttnWave {
         const int pp = a.page_table ? a.page_table[lp] : lp;
         const bf16_t* vp = a.kv_layer + (size_t)pp * page_elems + (size_t)(a.nkv + kvh) * kv_head_elems + (size_t)j * pt + off;
 #pragma unroll
-        for (int c = 0; c < CT; ++c) r.v[t][c] = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * pt);
+        for (int c = 0; c < CT; ++c) {
+          if (VCOH) {
+            const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(vp + (size_t)c * 16 * pt), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            r.v[t][c] = make_uint2((uint32_t)u, (uint32_t)(u >> 32));
+          } else {
+            r.v[t][c] = *reinterpret_cast<const uint2*>(vp + (size_t)c * 16 * pt);
+          }
+        }
       }
     }
   }
@@ -795,7 +905,7 @@ struct AttnWave {
     const float* qp = a.q + (size_t)min(j, a.M - 1) * a.ldq + head * DH + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
-      const float4 x0 = *reinterpret_cast<const float4*>(qp + ks * 32), x1 = *reinterpret_cast<const float4*>(qp + ks * 32 + 4);
+      const float4 x0 = ld_f4<QCOH>(qp + ks * 32), x1 = ld_f4<QCOH>(qp + ks * 32 + 4);
       const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
       union { bf16_t u[8]; bf16x8 v; } h, l;
 #pragma unroll
@@ -869,19 +979,26 @@ struct AttnWave {
   }
 };
 
-template <int DH>
-__global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
-  const uint32_t halted = gate_request(a.gate);
-  constexpr int CT = DH / 16, NWV = 4, WKEYS = 32;
-  __shared__ f32x4 o_s[NWV][CT][64];
-  __shared__ float m_s[NWV][16], l_s[NWV][16];
-  const int head = blockIdx.x, split = blockIdx.y;
+// LDS of one attention work unit of NWV wavefronts.
+template <int DH, int NWV>
+struct AttnSmem {
+  f32x4 o_s[NWV][DH / 16][64];
+  float m_s[NWV][16], l_s[NWV][16];
+  int s_last;
+};
+
+// Work unit (query head, range `split` of split_len cached positions) run by NWV wavefronts; the last range of
+// a head to finish merges all of the head's records and writes the O-projection panels.
+template <int DH, int NWV, bool COH = false, bool VCOH = false>
+__device__ __forceinline__ void attn_range(const AttnArgs& a, const int head, const int split, AttnSmem<DH, NWV>& sm,
+                                           const uint32_t halted) {
+  constexpr int CT = DH / 16, WKEYS = 32;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int j = lane & 15, g = lane >> 4;
   const int total = a.pos0 + a.M;
   const int s0 = split * a.split_len, s1 = min(s0 + a.split_len, total);
-  AttnWave<DH> aw(a, head, s1);
-  typename AttnWave<DH>::Raw r0, r1;
+  AttnWave<DH, COH, VCOH> aw(a, head, s1);
+  typename AttnWave<DH, COH, VCOH>::Raw r0, r1;
   // the first step's cache loads go out ahead of the q loads; later steps' loads are in flight during
   // the arithmetic of the step before
   constexpr int STEP = NWV * WKEYS;
@@ -899,39 +1016,42 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
     base += STEP;
   }
 
-  // merge the four wavefronts (fixed order), then one record per query: o[DH], max, sum
+  // merge the wavefronts (fixed order), then one record per query: o[DH], max, sum
+  __syncthreads();                                // a previous unit of this workgroup has left the buffers
 #pragma unroll
-  for (int c = 0; c < CT; ++c) o_s[w][c][lane] = aw.O[c];
-  if (g == 0) { m_s[w][j] = aw.m_run; l_s[w][j] = aw.l_run; }
+  for (int c = 0; c < CT; ++c) sm.o_s[w][c][lane] = aw.O[c];
+  if (g == 0) { sm.m_s[w][j] = aw.m_run; sm.l_s[w][j] = aw.l_run; }
   __syncthreads();
-  float mm = m_s[0][j];
+  float mm = sm.m_s[0][j];
 #pragma unroll
-  for (int ww = 1; ww < NWV; ++ww) mm = fmaxf(mm, m_s[ww][j]);
+  for (int ww = 1; ww < NWV; ++ww) mm = fmaxf(mm, sm.m_s[ww][j]);
   float f[NWV], ll = 0.f;
 #pragma unroll
-  for (int ww = 0; ww < NWV; ++ww) { f[ww] = expf(m_s[ww][j] - mm); ll += l_s[ww][j] * f[ww]; }
+  for (int ww = 0; ww < NWV; ++ww) { f[ww] = expf(sm.m_s[ww][j] - mm); ll += sm.l_s[ww][j] * f[ww]; }
   if (j < a.M) {
     float* rec = a.part + (((size_t)head * a.n_splits + split) * 16 + j) * (DH + 2);
+    // channel tiles are dealt to the wavefronts: tiles w, w + NWV, ..
 #pragma unroll
-    for (int ci = 0; ci < CT / NWV; ++ci) {
-      const int c = w * (CT / NWV) + ci;
-      f32x4 o = o_s[0][c][lane] * f[0];
+    for (int ci = 0; ci < (CT + NWV - 1) / NWV; ++ci) {
+      const int c = w + ci * NWV;
+      if (c < CT) {
+        f32x4 o = sm.o_s[0][c][lane] * f[0];
 #pragma unroll
-      for (int ww = 1; ww < NWV; ++ww) o += o_s[ww][c][lane] * f[ww];
-      st_agent2(rec + c * 16 + 4 * g, o[0], o[1]);
-      st_agent2(rec + c * 16 + 4 * g + 2, o[2], o[3]);
+        for (int ww = 1; ww < NWV; ++ww) o += sm.o_s[ww][c][lane] * f[ww];
+        st_agent2(rec + c * 16 + 4 * g, o[0], o[1]);
+        st_agent2(rec + c * 16 + 4 * g + 2, o[2], o[3]);
+      }
     }
     if (w == 0 && g == 0) st_agent2(rec + DH, mm, ll);
   }
   // the last range of this head to finish merges all ranges (in range order) into the panels that
   // feed the O-projection
-  __shared__ int s_last;
-  if (!last_arrival(a.counters + head, a.n_splits, &s_last)) return;
+  if (!last_arrival(a.counters + head, a.n_splits, &sm.s_last)) return;
   // 8 channels per thread: DH / 8 threads per query, so that all 16 queries of a block are merged in one
   // pass (a second pass would put a second round trip to the records behind the first)
   constexpr int TPQ = DH / 8;
   const int tq = threadIdx.x % TPQ;
-  for (int qm = threadIdx.x / TPQ; qm < a.M; qm += 256 / TPQ) {
+  for (int qm = threadIdx.x / TPQ; qm < a.M; qm += NWV * 64 / TPQ) {
     const float* rbase = a.part + (((size_t)head * a.n_splits) * 16 + qm) * (DH + 2);
     const size_t stride = (size_t)16 * (DH + 2);
     // running (max, sum, o) over the ranges in range order; eight ranges' records are fetched at a
@@ -964,9 +1084,15 @@ __global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
     const float inv = 1.0f / L;
 #pragma unroll
     for (int i = 0; i < 8; ++i) o[i] *= inv;
-    xpack_store4(a.Xout, (a.nq * DH) >> 5, a.M, qm, head * DH + 8 * tq, o);
-    xpack_store4(a.Xout, (a.nq * DH) >> 5, a.M, qm, head * DH + 8 * tq + 4, o + 4);
+    xpack_store4<COH>(a.Xout, (a.nq * DH) >> 5, a.M, qm, head * DH + 8 * tq, o);
+    xpack_store4<COH>(a.Xout, (a.nq * DH) >> 5, a.M, qm, head * DH + 8 * tq + 4, o + 4);
   }
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void k_attn_partial(AttnArgs a) {
+  __shared__ AttnSmem<DH, 4> sm;
+  attn_range<DH, 4>(a, blockIdx.x, blockIdx.y, sm, gate_request(a.gate));
 }
 
 // Short contexts: one workgroup of eight wavefronts takes a whole head (256 positions per step, the
@@ -1085,7 +1211,7 @@ constexpr int FEAT_NT = 1024;
 // loads).  Arg-max, soft-max sums and entropy are DPP wave reductions merged across the 16
 // wavefronts in a fixed order.  Top-10: every wavefront finds the ten largest of the values its
 // lanes hold by ten cross-lane arg-max rounds, and one wavefront picks the ten largest of those 160.
-constexpr int CM_NT = 256;
+constexpr int CM_NT = 512;     // threads per slice of the many-workgroup form: 2048 logits (the persistent draft loop uses the same slicing)
 constexpr int CM_REC = 16;     // floats per record
 
 // Order-preserving map float -> uint32 (larger float <=> larger key; -inf maps above key 0, which marks
@@ -1331,7 +1457,7 @@ struct ClfCoef { float w1[12]; float b1, w2, b2; };
 // record order, the ten largest of the nb * 10 candidates (CPT per thread), the forced logit in closed
 // form, features, classifier, halt decision and the loop's bookkeeping words.
 template <int NT, int CPT>
-__device__ __forceinline__ void classify_merge_finish(const ClassifyArgs& a, const float* recs, const int nb, const int force,
+__device__ __forceinline__ int classify_merge_finish(const ClassifyArgs& a, const float* recs, const int nb, const int force,
                                                       const float xf, const ClfCoef& k, float* sv, int* si, float (*wtop)[10],
                                                       float* top_s, float* feat_s) {
   ClfOut* out = reinterpret_cast<ClfOut*>(a.out);
@@ -1379,7 +1505,7 @@ __device__ __forceinline__ void classify_merge_finish(const ClassifyArgs& a, con
       for (int i = 9; i >= 0; --i) if (old[i] == xf) drop = i;
       top_s[0] = mnew;
       for (int i = 0, o = 1; i < 10 && o < 10; ++i) if (i != drop) top_s[o++] = old[i];
-      a.logits[force] = mnew;
+      st_f1<true>(a.logits + force, mnew);
     }
     mx = mnew; gbest.v = mnew; gbest.i = force;
     __syncthreads();
@@ -1411,11 +1537,13 @@ __device__ __forceinline__ void classify_merge_finish(const ClassifyArgs& a, con
     // perplexity rule (App. F's rule-based baseline): the block's draft tokens so far have perplexity
     // exp(-(1/j) sum ln p_i), p_i the draft's probability of its own token (the largest one); above the
     // threshold this token is the block's last.  The running sum sits in the word after sl_count.
+    // (the loop's words may have been written by another workgroup of the same launch: hand-off accesses)
+    const int sl_before = a.sl_count ? __hip_atomic_load(a.sl_count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
     if (a.ppl_threshold > 0.f && a.sl_count) {
       float* nll = reinterpret_cast<float*>(a.sl_count + 1);
-      const float sum = *nll - logf(feat_s[0]);
-      *nll = sum;
-      score = expf(sum / (float)(*a.sl_count + 1));
+      const float sum = ld_f1<true>(nll) - logf(feat_s[0]);
+      st_f1<true>(nll, sum);
+      score = expf(sum / (float)(sl_before + 1));
       if (score > a.ppl_threshold) halt |= 1u;
     }
     out->token = gbest.i;
@@ -1425,45 +1553,49 @@ __device__ __forceinline__ void classify_merge_finish(const ClassifyArgs& a, con
     if (!mismatch) {
       if (a.token_next) *a.token_next = gbest.i;
       if (a.block_slot) *a.block_slot = gbest.i;
-      if (a.sl_count) *a.sl_count += 1;
+      if (a.sl_count) __hip_atomic_store(a.sl_count, sl_before + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    if (a.gate && halt) *a.gate = 1u;
+    if (a.gate && halt) __hip_atomic_store(a.gate, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  return gbest.i;
 }
 
-// The same computation spread over ceil(V / 1024) workgroups (used when the caller gives scratch
-// memory).  Each workgroup reduces 1024 logits to a record {max, arg-max, S, T relative to its own
+// The same computation spread over ceil(V / 2048) workgroups (used when the caller gives scratch
+// memory).  Each workgroup reduces 2048 logits to a record {max, arg-max, S, T relative to its own
 // max, its ten largest values}; the last workgroup to finish (ticket, no waiting) merges the
 // records in index order: S = sum S_b e^(m_b - M), T = sum e^(m_b - M) (T_b + (m_b - M) S_b), the ten
-// largest of the <= 640 candidates, then features, classifier and halt decision.  Forcing a token
+// largest of the <= 320 candidates, then features, classifier and halt decision.  Forcing a token
 // to max + 4 is applied to the merged sums in closed form.
-__global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
+// b = index of this workgroup's slice of NT * 4 logits, nb = number of slices.  Returns the arg-max token in
+// every thread of the workgroup that finished the computation (the last to arrive), -1 in all others.
+// COH: the logits were written by other workgroups of the same launch.
+template <int NT, bool COH = false>
+__device__ __forceinline__ int classify_unit(const ClassifyArgs& a, const int b, const int nb, const uint32_t halted) {
   ClfOut* out = reinterpret_cast<ClfOut*>(a.out);
-  const uint32_t halted = gate_request(const_cast<const uint32_t*>(a.gate));
-  __shared__ float sv[CM_NT / 64 + 1];
-  __shared__ int si[CM_NT / 64 + 1];
+  __shared__ float sv[NT / 64 + 1];
+  __shared__ int si[NT / 64 + 1];
   __shared__ float top_s[10];
-  __shared__ float wtop[CM_NT / 64][10];
+  __shared__ float wtop[NT / 64][10];
   __shared__ float feat_s[12];
   __shared__ int s_last;
-  const int t = threadIdx.x, V = a.vocab, b = blockIdx.x, nb = gridDim.x;
+  const int t = threadIdx.x, V = a.vocab;
   const float* x = a.logits;
   float* rec = a.scratch + 64 + (size_t)b * CM_REC;          // scratch[0] is the ticket counter
-  const int idx = (b * CM_NT + t) * 4;
+  const int idx = (b * NT + t) * 4;
   float r4[4];
   if (idx + 3 < V) {
-    const float4 v = *reinterpret_cast<const float4*>(x + idx);
+    const float4 v = ld_f4<COH>(x + idx);
     r4[0] = v.x; r4[1] = v.y; r4[2] = v.z; r4[3] = v.w;
   } else {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) r4[e] = idx + e < V ? x[idx + e] : -INFINITY;
+    for (int e = 0; e < 4; ++e) r4[e] = idx + e < V ? ld_f1<COH>(x + idx + e) : -INFINITY;
   }
   // operands of the final stage that depend on no reduction are fetched now, so that the merging
   // workgroup does not pay their round trips one after another at the end
   int force = -1;
   float xf = 0.f;
   if (a.force_token) { force = *a.force_token; if (force >= V) force = -1; }
-  if (force >= 0) xf = x[force];
+  if (force >= 0) xf = ld_f1<COH>(x + force);
   float w1[12], cb1 = 0.f, cw2 = 0.f, cb2 = 0.f;
 #pragma unroll
   for (int i = 0; i < 12; ++i) w1[i] = 0.f;
@@ -1477,41 +1609,47 @@ __global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
     }
   }
   if (halted != 0u) {                             // uniform over the launch; the loads above are dropped
-    if (threadIdx.x == 0 && blockIdx.x == 0) out->executed = 0u;
-    return;
+    if (threadIdx.x == 0 && b == 0) out->executed = 0u;
+    return -1;
   }
   VI mine; mine.v = -INFINITY; mine.i = 0x7fffffff;
 #pragma unroll
   for (int e = 0; e < 4; ++e) { VI y; y.v = r4[e]; y.i = idx + e; mine = vi_best(mine, y); }
-  const VI best = block_argmax<CM_NT>(mine, sv, si);
+  const VI best = block_argmax<NT>(mine, sv, si);
   float S = 0.f, T = 0.f;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
     const float d = r4[e] - best.v, ex = expf(d);
     S += ex; T += ex > 0.f ? ex * d : 0.f;
   }
-  S = block_sum<CM_NT>(S, sv);
-  T = block_sum<CM_NT>(T, sv);
+  S = block_sum<NT>(S, sv);
+  T = block_sum<NT>(T, sv);
   // this workgroup's ten largest values
   {
     float c4[4] = {r4[0], r4[1], r4[2], r4[3]};
-    block_top10<CM_NT, 4>(c4, wtop, top_s);
+    block_top10<NT, 4>(c4, wtop, top_s);
   }
   if (t == 0) { st_agent2(rec, best.v, __int_as_float(best.i)); st_agent2(rec + 2, S, T); }
   if (t >= 2 && t < 7) st_agent2(rec + 2 * t, top_s[2 * t - 4], top_s[2 * t - 3]);
-  if (!last_arrival(reinterpret_cast<int*>(a.scratch), nb, &s_last)) return;
+  if (!last_arrival(reinterpret_cast<int*>(a.scratch), nb, &s_last)) return -1;
 
   ClfCoef k;
 #pragma unroll
   for (int i = 0; i < 12; ++i) k.w1[i] = w1[i];
   k.b1 = cb1; k.w2 = cw2; k.b2 = cb2;
-  classify_merge_finish<CM_NT, 3>(a, a.scratch + 64, nb, force, xf, k, sv, si, wtop, top_s, feat_s);
+  // at most 64 slices (65536 logits at NT = 256): 640 candidates
+  constexpr int CPT = (640 * 256 / NT + NT - 1) / NT;
+  return classify_merge_finish<NT, CPT>(a, a.scratch + 64, nb, force, xf, k, sv, si, wtop, top_s, feat_s);
+}
+
+__global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
+  classify_unit<CM_NT>(a, blockIdx.x, gridDim.x, gate_request(const_cast<const uint32_t*>(a.gate)));
 }
 
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s) {
   if (a.vocab < 1 || a.vocab > 65536) return hipErrorInvalidValue;
   if (a.scratch != nullptr && a.vocab >= 4096) {
-    hipLaunchKernelGGL(k_classify_multi, dim3((a.vocab + 1023) / 1024), dim3(CM_NT), 0, s, a);
+    hipLaunchKernelGGL(k_classify_multi, dim3((a.vocab + 4 * CM_NT - 1) / (4 * CM_NT)), dim3(CM_NT), 0, s, a);
     return hipGetLastError();
   }
   if (a.vocab <= 8192) hipLaunchKernelGGL(k_classify<2>, dim3(1), dim3(FEAT_NT), 0, s, a);
@@ -1551,18 +1689,20 @@ hipError_t classify_static_scratch(float** out) {
 // per-row arg-max of the verification logits; acceptance; KV fill; draft-loop bookkeeping
 // ---------------------------------------------------------------------------------------------
 
-__global__ __launch_bounds__(1024) void k_argmax_rows(const float* __restrict__ logits, int vocab, int32_t* __restrict__ out) {
+// abort_word (may be null): set by a persistent forward whose grid barrier gave up; the rows then get -1.
+__global__ __launch_bounds__(1024) void k_argmax_rows(const float* __restrict__ logits, int vocab, int32_t* __restrict__ out,
+                                                      const unsigned* abort_word) {
   __shared__ float sv[17];
   __shared__ int si[17];
   const float* x = logits + (size_t)blockIdx.x * vocab;
   VI mine; mine.v = -INFINITY; mine.i = 0x7fffffff;
   for (int i = threadIdx.x; i < vocab; i += 1024) { VI y; y.v = x[i]; y.i = i; mine = vi_best(mine, y); }
   const VI b = block_argmax<1024>(mine, sv, si);
-  if (threadIdx.x == 0) out[blockIdx.x] = b.i;
+  if (threadIdx.x == 0) out[blockIdx.x] = (abort_word != nullptr && *abort_word != 0u) ? -1 : b.i;
 }
 
-hipError_t launch_argmax_rows(const float* logits, int M, int vocab, int32_t* out, hipStream_t s) {
-  hipLaunchKernelGGL(k_argmax_rows, dim3(M), dim3(1024), 0, s, logits, vocab, out);
+hipError_t launch_argmax_rows(const float* logits, int M, int vocab, int32_t* out, const unsigned* abort_word, hipStream_t s) {
+  hipLaunchKernelGGL(k_argmax_rows, dim3(M), dim3(1024), 0, s, logits, vocab, out, abort_word);
   return hipGetLastError();
 }
 
@@ -1996,9 +2136,9 @@ __global__ void k_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* to
   for (int i = 1; i < 16; ++i) out->block[i] = 0;
 }
 
-__global__ void k_loop_finish(const int32_t* sl_count, LoopOut* out, LoopOut* host_out) {
+__global__ void k_loop_finish(const int32_t* sl_count, LoopOut* out, LoopOut* host_out, const unsigned* abort_word) {
   if (threadIdx.x != 0) return;
-  out->sl = *sl_count;
+  out->sl = (abort_word != nullptr && *abort_word != 0u) ? -1 : *sl_count;
   if (host_out) { *host_out = *out; __threadfence_system(); }
 }
 
@@ -2042,9 +2182,10 @@ hipError_t launch_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* to
   return hipGetLastError();
 }
 
-hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void* host_loop_out, hipStream_t s) {
+hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void* host_loop_out, const unsigned* abort_word,
+                              hipStream_t s) {
   hipLaunchKernelGGL(k_loop_finish, dim3(1), dim3(64), 0, s, sl_count, reinterpret_cast<LoopOut*>(dev_loop_out),
-                     reinterpret_cast<LoopOut*>(host_loop_out));
+                     reinterpret_cast<LoopOut*>(host_loop_out), abort_word);
   return hipGetLastError();
 }
 
@@ -2263,6 +2404,302 @@ hipError_t launch_rstd_groups(const float* ssq, int n_ssq, int d, float eps, flo
   if (n_groups < 1 || n_ssq < 1) return hipErrorInvalidValue;
   hipLaunchKernelGGL(k_rstd_groups, dim3(n_groups), dim3(256), 0, s, ssq, n_ssq, d, eps, rstd);
   return hipGetLastError();
+}
+
+
+
+// ---------------------------------------------------------------------------------------------
+// one launch per forward or per draft loop: persistent workgroups, phases separated by a grid barrier
+// ---------------------------------------------------------------------------------------------
+//
+// A forward of the RMSNorm / rotary / SwiGLU family is a chain of phases (per layer: QKV projection, attention,
+// O-projection, gate/up, down; then the LM head), each of which needs everything the phase before it wrote.
+// Launched one kernel per phase, every boundary costs a ramp (first weight bytes arrive 2 - 3 us after the
+// launch) on top of the phase's own tail.  Here one cooperative launch of one workgroup per compute unit runs
+// all phases; a workgroup's share of a phase is fixed by its index, so at the end of a phase it knows which
+// weight tiles it will need first in the next one and requests them BEFORE it waits at the grid barrier: the
+// weight stream of phase i + 1 is in flight while phase i drains and the barrier's round trips pass.
+//
+// Coherence inside the launch: the eight XCDs have separate L2s, and an L2-wide write-back / invalidate at
+// every barrier costs more than the barrier (measured: 8 - 13 us).  Instead (a) every store that another
+// workgroup will read is a write-through store and small hand-off data is read with L2-bypassing loads
+// (COH accesses above); (b) the large activation panels, which every workgroup of a phase reads, are given a
+// fresh address per phase ("versions"), so no L2 can hold an older copy and plain loads are safe and hit
+// in the reader's own L2 after the first touch.
+//
+// Grid barrier: 16 counters, workgroup i adds 1 to counter i % 16 (no return value needed), then 16 lanes of
+// its first wavefront poll the counters until all have reached epoch * (G / 16).  The host zeroes the
+// counters before the launch.  Every wait is bounded: after BAR_SPIN_LIMIT polls the workgroup sets the
+// abort word, every later barrier falls through at once, and the launch drains with unusable results (the
+// arg-max and loop-finish kernels turn a set abort word into -1 outputs).
+
+constexpr int BAR_GROUPS = 16;
+constexpr int BAR_SLOT = 64;                 // ints between two counters (256 bytes)
+constexpr int BAR_SPIN_LIMIT = 1 << 20;      // polls (each a memory round trip, about 1 us) before giving up
+
+__device__ __forceinline__ void bar_arrive(unsigned* cnt) {
+  __builtin_amdgcn_s_waitcnt(0);             // this wavefront's hand-off stores have completed
+  __builtin_amdgcn_s_barrier();              // ... and those of the whole workgroup
+  if (threadIdx.x == 0)
+    __hip_atomic_fetch_add(cnt + (blockIdx.x % BAR_GROUPS) * BAR_SLOT, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  asm volatile("" ::: "memory");
+}
+
+__device__ __forceinline__ void bar_wait(unsigned* cnt, unsigned* abort_word, const unsigned target) {
+  if (threadIdx.x < 64) {
+    int spins = 0;
+    for (;;) {
+      bool ok = true;
+      if ((int)threadIdx.x < BAR_GROUPS)
+        ok = (int)(__hip_atomic_load(cnt + threadIdx.x * BAR_SLOT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) >= 0;
+      if (__all(ok)) break;
+      ++spins;
+      if ((spins & 255) == 0 && __hip_atomic_load(abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+      if (spins > BAR_SPIN_LIMIT) {
+        if (threadIdx.x == 0) __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+  }
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+// Row tiles per work unit of the four GEMM kinds, by model class (chosen so that a phase has about one unit
+// per compute unit): wide models and narrow ones.
+struct FwdBig { static constexpr int QKV = 4, PART = 4, UP = 8, LM = 8; };
+struct FwdSmall { static constexpr int QKV = 2, PART = 1, UP = 2, LM = 8; };
+
+template <typename C>
+union FwdSmem {
+  GemmSmem<C::QKV, 8> qkv; GemmSmem<C::PART, 8> part; GemmSmem<C::UP, 8> up; GemmSmem<C::LM, 8> lm;
+  AttnSmem<128, 8> a128; AttnSmem<64, 8> a64;
+  float red[16];
+};
+
+// One GEMM phase: unit u = (row group u % groups, K range u / groups); workgroup i takes units i, i + G, ...
+// The weights of its first unit are already requested (pre) when have_pre.
+template <int P, int RT, int EPI>
+__device__ __forceinline__ void fwd_gemm_phase(const GemmArgs& ga, const int groups, GemmSmem<RT, 8>& sm, u32x4 (&pre)[2][8],
+                                               bool have_pre) {
+  const int n_units = groups * ga.n_split;
+  for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
+    const int b = u % groups, seg = u / groups;
+    const int kt_begin = (int)((int64_t)ga.KT * seg / ga.n_split), kt_end = (int)((int64_t)ga.KT * (seg + 1) / ga.n_split);
+    if (!have_pre) gemm_prefetch<RT, EPI, 8>(ga, b, kt_begin, kt_end, pre);
+    have_pre = false;
+    gemm_unit<P, RT, EPI, 8, 1, true, true>(ga, b, kt_begin, kt_end, seg, ga.n_split, sm, pre);
+  }
+}
+// The requests for the first unit of the phase (see above); false if this workgroup has no unit in it.
+template <int RT, int EPI>
+__device__ __forceinline__ bool fwd_gemm_prefetch(const GemmArgs& ga, const int groups, u32x4 (&pre)[2][8]) {
+  const int u = blockIdx.x;
+  if (u >= groups * ga.n_split) return false;
+  const int b = u % groups, seg = u / groups;
+  const int kt_begin = (int)((int64_t)ga.KT * seg / ga.n_split), kt_end = (int)((int64_t)ga.KT * (seg + 1) / ga.n_split);
+  gemm_prefetch<RT, EPI, 8>(ga, b, kt_begin, kt_end, pre);
+  return true;
+}
+
+template <int P, typename C, bool LOOP>
+__global__ __launch_bounds__(512) void k_forward(FwdArgs f) {
+  __shared__ __align__(16) FwdSmem<C> sm;
+  u32x4 pre[2][8];
+  unsigned epoch = 0;
+  const unsigned per_counter = gridDim.x / BAR_GROUPS;
+  const int KTd = f.d >> 5, n_tiles = f.d >> 4;
+  const int n_steps = LOOP ? f.n_steps : 1;
+  bool have_next = false;
+
+  // GEMM phase descriptions (uniform values: they live in scalar registers)
+  auto base_args = [&](const int M) {
+    GemmArgs g{};
+    g.M = M; g.n_split = 1; g.grp = 1; g.planes = f.planes; g.counters = f.gemm_counters; g.only_row = -1;
+    return g;
+  };
+  auto normed = [&](GemmArgs& g, const bf16_t* x) {
+    g.X = x; g.KT = KTd; g.ssq = f.ssq; g.n_ssq = n_tiles; g.d_in = f.d; g.eps = f.eps;
+  };
+  auto residual = [&](GemmArgs& g, const bf16_t* w, const bf16_t* x, const int k, const int split, const float* next_gain,
+                      bf16_t* xout) {
+    g.W = w; g.X = x; g.KT = k >> 5; g.n_rows = f.d; g.h = f.h; g.ld_out = f.d; g.n_split = split;
+    g.Xout = xout; g.KT_out = KTd; g.gain = next_gain; g.ssq_out = f.ssq; g.n_ssq_out = n_tiles;
+  };
+
+  for (int step = 0; step < n_steps; ++step) {
+    const int M = (LOOP && step > 0) ? 1 : f.M;
+    const int pos0 = (LOOP && step > 0) ? f.pos0 + f.M + (step - 1) : f.pos0;
+    // panel versions of this step
+    bf16_t* xn = f.xn + (size_t)step * (2 * f.n_layers + 1) * f.xn_stride;
+    bf16_t* xattn = f.xattn + (size_t)step * f.n_layers * f.xattn_stride;
+    bf16_t* xact = f.xact + (size_t)step * f.n_layers * f.xact_stride;
+
+    GemmArgs gq = base_args(M);
+    auto qkv_args = [&](const int l) {
+      GemmArgs g = base_args(M);
+      g.W = f.layers[l].wqkv; normed(g, xn + (size_t)(2 * l) * f.xn_stride); g.n_rows = f.d_qkv;
+      g.grp = f.dh >> 5; g.q = f.q; g.ldq = f.d_q; g.nq = f.nq; g.nkv = f.nkv; g.dh = f.dh; g.pos0 = pos0;
+      g.rope_tab = f.rope; g.kv_layer = f.kv_pages + (size_t)l * f.kv_layer_stride; g.page_table = f.page_table;
+      g.page_tokens = f.page_tokens;
+      return g;
+    };
+    gq = qkv_args(0);
+    bool have = false;
+    if (step == 0) have = fwd_gemm_prefetch<C::QKV, EPI_QKV>(gq, f.d_qkv / (16 * C::QKV), pre);
+    else have = have_next;               // (set below: the requests went out before the barrier that ended the step before)
+
+    for (int l = 0; l < f.n_layers; ++l) {
+      const FwdLayer L = f.layers[l];
+      const bool last = (l + 1 == f.n_layers);
+      // ---- QKV projection, rotary, KV append
+      fwd_gemm_phase<P, C::QKV, EPI_QKV>(gq, f.d_qkv / (16 * C::QKV), sm.qkv, pre, have);
+      bar_arrive(f.bar); ++epoch; bar_wait(f.bar, f.abort_word, epoch * per_counter);
+      // ---- attention
+      {
+        AttnArgs at{};
+        at.q = f.q; at.ldq = f.d_q; at.kv_layer = gq.kv_layer; at.page_table = f.page_table; at.page_tokens = f.page_tokens;
+        at.nq = f.nq; at.nkv = f.nkv; at.dh = f.dh; at.M = M; at.pos0 = pos0; at.scale = f.attn_scale; at.part = f.part;
+        at.split_len = f.attn_split_len; at.n_splits = (pos0 + M + f.attn_split_len - 1) / f.attn_split_len;
+        at.Xout = xattn + (size_t)l * f.xattn_stride; at.counters = f.attn_counters;
+        const int n_units = f.nq * at.n_splits;
+        for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
+          const int head = u % f.nq, split = u / f.nq;
+          if (f.dh == 128) attn_range<128, 8, true, LOOP>(at, head, split, sm.a128, 0u);
+          else attn_range<64, 8, true, LOOP>(at, head, split, sm.a64, 0u);
+        }
+      }
+      GemmArgs go = base_args(M);
+      residual(go, L.wo, xattn + (size_t)l * f.xattn_stride, f.d_q, f.split_o, L.norm2_g, xn + (size_t)(2 * l + 1) * f.xn_stride);
+      bar_arrive(f.bar); ++epoch;
+      have = fwd_gemm_prefetch<C::PART, EPI_PARTIAL>(go, f.d / (16 * C::PART), pre);
+      bar_wait(f.bar, f.abort_word, epoch * per_counter);
+      // ---- O-projection + residual
+      fwd_gemm_phase<P, C::PART, EPI_PARTIAL>(go, f.d / (16 * C::PART), sm.part, pre, have);
+      GemmArgs gu = base_args(M);
+      gu.W = L.w_in; normed(gu, xn + (size_t)(2 * l + 1) * f.xn_stride); gu.n_rows = 2 * f.d_ff;
+      gu.Xout = xact + (size_t)l * f.xact_stride; gu.KT_out = f.d_ff >> 5;
+      bar_arrive(f.bar); ++epoch;
+      have = fwd_gemm_prefetch<C::UP, EPI_SWIGLU>(gu, 2 * f.d_ff / (16 * C::UP), pre);
+      bar_wait(f.bar, f.abort_word, epoch * per_counter);
+      // ---- gate / up + SwiGLU
+      fwd_gemm_phase<P, C::UP, EPI_SWIGLU>(gu, 2 * f.d_ff / (16 * C::UP), sm.up, pre, have);
+      GemmArgs gd = base_args(M);
+      residual(gd, L.w_out, xact + (size_t)l * f.xact_stride, f.d_ff, f.split_dn, last ? f.normf_g : f.layers[l + 1].norm1_g,
+               xn + (size_t)(2 * l + 2) * f.xn_stride);
+      bar_arrive(f.bar); ++epoch;
+      have = fwd_gemm_prefetch<C::PART, EPI_PARTIAL>(gd, f.d / (16 * C::PART), pre);
+      bar_wait(f.bar, f.abort_word, epoch * per_counter);
+      // ---- down + residual
+      fwd_gemm_phase<P, C::PART, EPI_PARTIAL>(gd, f.d / (16 * C::PART), sm.part, pre, have);
+      bar_arrive(f.bar); ++epoch;
+      if (!last) {
+        gq = qkv_args(l + 1);
+        have = fwd_gemm_prefetch<C::QKV, EPI_QKV>(gq, f.d_qkv / (16 * C::QKV), pre);
+        bar_wait(f.bar, f.abort_word, epoch * per_counter);
+      }
+    }
+    // ---- LM head (the barrier after the last down projection is still open: arrive done, wait pending)
+    GemmArgs lm = base_args(M);
+    lm.W = f.wlm; normed(lm, xn + (size_t)(2 * f.n_layers) * f.xn_stride); lm.n_rows = f.vocab;
+    lm.out = f.logits; lm.ld_out = f.vocab; lm.only_row = f.only_last ? M - 1 : -1;
+    have = fwd_gemm_prefetch<C::LM, EPI_STORE>(lm, f.vocab / (16 * C::LM), pre);
+    bar_wait(f.bar, f.abort_word, epoch * per_counter);
+    fwd_gemm_phase<P, C::LM, EPI_STORE>(lm, f.vocab / (16 * C::LM), sm.lm, pre, have);
+    if (!LOOP) break;
+
+    // ---- draft loop: Eq. 2 features and classifier on the logits, the next token's embedding, halt test
+    bar_arrive(f.bar); ++epoch; bar_wait(f.bar, f.abort_word, epoch * per_counter);
+    {
+      ClassifyArgs ca = f.clf;
+      ca.pos_feature = f.clf.pos_feature + (float)step;
+      ca.force_halt = (step + 1 == n_steps) ? 1 : 0;
+      ca.out = reinterpret_cast<ClfOut*>(f.clf.out) + step;
+      ca.block_slot = f.clf.block_slot + step;
+      if (f.clf.force_token) ca.force_token = f.clf.force_token + step;
+      if (f.clf.ref_token) ca.ref_token = f.clf.ref_token + step;
+      const int nb = (f.vocab + 4 * CM_NT - 1) / (4 * CM_NT);
+      if ((int)blockIdx.x < nb) {
+        const int tok = classify_unit<CM_NT, true>(ca, blockIdx.x, nb, 0u);
+        if (tok >= 0 && step + 1 < n_steps) {
+          // this workgroup finished the step: it embeds the token for the next one (row 0 of the residual
+          // stream, the first panel version of the next step, the sum of squares)
+          NormArgs na{};
+          na.h = f.h; na.d = f.d; na.M = 1; na.layernorm = 0; na.eps = f.eps; na.g = f.layers[0].norm1_g;
+          na.Xout = f.xn + (size_t)(step + 1) * (2 * f.n_layers + 1) * f.xn_stride;
+          na.ssq_out = f.ssq; na.n_ssq_out = n_tiles; na.tok_emb = f.tok_emb; na.tok_stride = f.tok_stride;
+          na.vocab = f.vocab; na.max_pos = 1 << 30;
+          __syncthreads();
+          norm_row<512, true>(na, 0, tok, sm.red, 0u);
+        }
+      }
+    }
+    bar_arrive(f.bar); ++epoch;
+    if (step + 1 < n_steps) {
+      // the next step starts with layer 0's QKV projection of one token
+      GemmArgs gn = base_args(1);
+      gn.W = f.layers[0].wqkv; gn.KT = KTd; gn.grp = f.dh >> 5;
+      have_next = fwd_gemm_prefetch<C::QKV, EPI_QKV>(gn, f.d_qkv / (16 * C::QKV), pre);
+    }
+    bar_wait(f.bar, f.abort_word, epoch * per_counter);
+    if (__hip_atomic_load(f.clf.gate, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+  }
+}
+
+// Workgroups of the persistent launch: one per compute unit, a multiple of the barrier's counter count; 0 if
+// the device cannot hold them all at once (then there is no persistent launch).
+template <typename K>
+static int forward_grid_for(K kernel) {
+  int dev = 0, cus = 0, per_cu = 0, coop = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&coop, hipDeviceAttributeCooperativeLaunch, dev) != hipSuccess || !coop) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 512, 0) != hipSuccess || per_cu < 1) return 0;
+  return cus / BAR_GROUPS * BAR_GROUPS;
+}
+
+template <int P, typename C, bool LOOP>
+static hipError_t launch_forward_cfg(const FwdArgs& f0, hipStream_t s) {
+  static int grid = -1;                        // per process: the library serves the devices of one kind
+  if (grid < 0) grid = forward_grid_for(k_forward<P, C, LOOP>);
+  if (grid < BAR_GROUPS) return hipErrorCooperativeLaunchTooLarge;
+  FwdArgs f = f0;
+  // K ranges of the two residual-update GEMMs: about one work unit per workgroup, at least one k-tile per wavefront
+  auto split_for = [&](int k) {
+    const int groups = f.d / (16 * C::PART), kt = k >> 5;
+    int sp = grid / groups;
+    if (sp > kt / 8) sp = kt / 8;
+    return sp < 1 ? 1 : (sp > GEMM_MAX_SPLIT ? GEMM_MAX_SPLIT : sp);
+  };
+  f.split_o = split_for(f.d_q);
+  f.split_dn = split_for(f.d_ff);
+  // attention ranges: about one (head, range) unit per workgroup, never shorter than the records were sized for
+  const int total = f.pos0 + f.M + (LOOP ? f.n_steps - 1 : 0);
+  const int target = grid / f.nq < 1 ? 1 : grid / f.nq;
+  int len = ((total + target - 1) / target + 31) / 32 * 32;
+  f.attn_split_len = len < ATTN_SPLIT_LEN ? ATTN_SPLIT_LEN : len;
+  void* params[] = {&f};
+  return hipLaunchCooperativeKernel(reinterpret_cast<void*>(k_forward<P, C, LOOP>), dim3(grid), dim3(512), params, 0, s);
+}
+
+bool forward_shape_ok(int d, int d_q, int d_qkv, int d_ff, int dh, int vocab, bool big) {
+  const int rq = big ? FwdBig::QKV : FwdSmall::QKV, rp = big ? FwdBig::PART : FwdSmall::PART, ru = big ? FwdBig::UP : FwdSmall::UP;
+  if (d % (16 * rp) || d_qkv % (16 * rq) || (2 * d_ff) % (16 * ru) || vocab % 128) return false;
+  if (d % 32 || d_q % 32 || d_ff % 32) return false;
+  if (dh != 64 && dh != 128) return false;
+  return true;
+}
+
+hipError_t launch_forward(const FwdArgs& f, bool big, bool loop, hipStream_t s) {
+  if (f.M < 1 || f.M > 16 || !forward_shape_ok(f.d, f.d_q, f.d_qkv, f.d_ff, f.dh, f.vocab, big)) return hipErrorInvalidValue;
+  if (f.layers == nullptr || f.bar == nullptr || f.abort_word == nullptr) return hipErrorInvalidValue;
+  if (loop) {
+    if (f.M > 8 || f.n_steps < 1 || f.d > 4096 || f.clf.scratch == nullptr || f.clf.gate == nullptr) return hipErrorInvalidValue;
+    return big ? launch_forward_cfg<1, FwdBig, true>(f, s) : launch_forward_cfg<1, FwdSmall, true>(f, s);
+  }
+  if (f.M <= 8) return big ? launch_forward_cfg<1, FwdBig, false>(f, s) : launch_forward_cfg<1, FwdSmall, false>(f, s);
+  return big ? launch_forward_cfg<2, FwdBig, false>(f, s) : launch_forward_cfg<2, FwdSmall, false>(f, s);
 }
 
 }  // namespace disco
