@@ -297,6 +297,8 @@ def main():
                          "prompt generating --new-tokens tokens; prompt pass and forcing set-up between prompts are untimed")
     ap.add_argument("--new-tokens", type=int, default=256,
                     help="tokens generated per prompt when --prompts > 1 (then --steps 0 runs every prompt to its end)")
+    ap.add_argument("--launch-mode", type=int, default=0, choices=[0, 1],
+                    help="0: one launch per phase (default); 1: one cooperative launch per forward / draft loop (disco_set_launch_mode)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run plain device copies of known size and exit (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -325,8 +327,11 @@ def main():
     from paper_2405_04304_amd.engine import SpecEngine
     from workloads import synth as W
 
+    B.disco_set_launch_mode(args.launch_mode)
     if args.micro:
-        print(json.dumps(micro(B, W, dev, args.steps)), flush=True)
+        out = micro(B, W, dev, args.steps)
+        out["launch_mode"] = args.launch_mode
+        print(json.dumps(out), flush=True)
         return
     if args.prefill:
         print(json.dumps(prefill_bench(B, W, dev, args.steps, tuple(args.prefill_models.split(",")),

@@ -352,6 +352,18 @@ size_t disco_prefill_workspace_bytes(const disco_model* m, int n_tokens, int max
 int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens, int n_tokens,
                   float* dev_logits_last, void* dev_ws, size_t ws_bytes, disco_stream s);
 
+/* ---- launch structure ------------------------------------------------------------------------------ */
+
+/* A forward (and a whole draft loop) of the RMSNorm / rotary / SwiGLU family can run as ONE cooperative
+ * launch of persistent workgroups with a grid barrier between the phases (QKV projection, attention,
+ * O-projection, gate/up, down per layer; LM head; in a draft loop also the features / classifier and the
+ * next token's embedding, the kernel leaving at the first halting step) instead of one launch per phase.
+ * mode 0 (default): one launch per phase.  mode 1: one launch per forward where the model's shapes allow
+ * it (else mode 0 is used silently); results agree with mode 0 to fp32 summation order.  On MI355X mode 0
+ * is the faster one: see the measurements in the design notes.  Process-wide; returns the previous mode,
+ * or DISCO_EINVAL.  Not to be changed while calls are in flight on other threads.                      */
+int disco_set_launch_mode(int mode);
+
 /* ---- measurement probe ------------------------------------------------------------------------- */
 
 /* Brackets, with two HIP events on the launch stream, the MLP-input GEMM (gate/up + SwiGLU, or

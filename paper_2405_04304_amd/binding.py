@@ -113,6 +113,7 @@ _SIGNATURES = {
                                   C.c_void_p, C.c_void_p]),
     "disco_clf_eval": (C.c_int, [C.POINTER(Clf), C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                  C.c_void_p, C.c_void_p]),
+    "disco_set_launch_mode": (C.c_int, [C.c_int]),
     "disco_probe_enable": (C.c_int, [C.c_int]),
     "disco_probe_read_ms": (C.c_float, []),
 }
@@ -271,6 +272,13 @@ def disco_clf_train(feats, labels, n, hidden, epochs, lr, params, loss=None, str
 def disco_clf_eval(clf, feats, labels, n, tau, scores=None, counts=None, stream=None):
     _check(lib().disco_clf_eval(C.byref(clf.c), _ptr(feats), _ptr(labels), n, tau, _ptr(scores), _ptr(counts),
                                 _stream() if stream is None else stream))
+
+
+def disco_set_launch_mode(mode: int) -> int:
+    prev = lib().disco_set_launch_mode(mode)
+    if prev < 0:
+        raise DiscoError(prev, last_error())
+    return prev
 
 
 def disco_probe_enable(layer: int) -> None:

@@ -67,17 +67,15 @@ struct Ws {
   float* ssq; int* gemm_counters; int* attn_counters; int n_counters; float* clf_scratch;
   uint32_t* gate; int32_t* sl_count; int32_t* tok_next;
   // persistent forward: panel versions (a fresh address per phase and step), the layer table, barrier words
-  bf16_t* xn_v; bf16_t* xattn_v; bf16_t* xact_v; size_t xn_stride, xattn_stride, xact_stride;
+  bf16_t* xn_v; bf16_t* xattn_v; bf16_t* xact_v; float* q_v; size_t xn_stride, xattn_stride, xact_stride;
   FwdLayer* fwd_layers; unsigned* bar;
   size_t total;
 };
 
-// The persistent kernel can be switched off (DISCO_PERSISTENT=0 in the environment): every forward is then a
-// chain of launches, one per phase.
-bool persistent_enabled() {
-  static const bool on = [] { const char* e = getenv("DISCO_PERSISTENT"); return !(e && e[0] == '0'); }();
-  return on;
-}
+// Launch structure (disco_set_launch_mode): 0 = one launch per phase (default), 1 = one cooperative launch per
+// forward / draft loop.  DISCO_PERSISTENT=1 in the environment selects 1 at load time.
+int g_launch_mode = [] { const char* e = getenv("DISCO_PERSISTENT"); return (e && e[0] == '1') ? 1 : 0; }();
+bool persistent_enabled() { return g_launch_mode == 1; }
 
 // Carve the workspace; with base == nullptr only the total is meaningful.
 Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
@@ -108,13 +106,15 @@ Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
   w.gate = static_cast<uint32_t*>(take(256));
   w.sl_count = reinterpret_cast<int32_t*>(w.gate ? w.gate + 16 : nullptr);
   w.tok_next = reinterpret_cast<int32_t*>(w.gate ? w.gate + 32 : nullptr);
-  w.xn_stride = (size_t)2 * 16 * d.d_model; w.xattn_stride = (size_t)2 * 16 * m->d_q; w.xact_stride = (size_t)2 * 16 * d.d_ff;
-  w.xn_v = w.xattn_v = w.xact_v = nullptr; w.fwd_layers = nullptr; w.bar = nullptr;
+  w.xn_stride = (size_t)2 * 16 * d.d_model + 2 * (size_t)d.d_model;      // two panels + d floats of sums of squares
+  w.xattn_stride = (size_t)2 * 16 * m->d_q; w.xact_stride = (size_t)2 * 16 * d.d_ff;
+  w.xn_v = w.xattn_v = w.xact_v = nullptr; w.q_v = nullptr; w.fwd_layers = nullptr; w.bar = nullptr;
   if (m->persist_ok) {
     const size_t steps = (size_t)m->loop_steps, L = (size_t)d.n_layers;
     w.xn_v = static_cast<bf16_t*>(take(sizeof(bf16_t) * w.xn_stride * (2 * L + 1) * steps));
     w.xattn_v = static_cast<bf16_t*>(take(sizeof(bf16_t) * w.xattn_stride * L * steps));
     w.xact_v = static_cast<bf16_t*>(take(sizeof(bf16_t) * w.xact_stride * L * steps));
+    w.q_v = static_cast<float*>(take(sizeof(float) * 16 * m->d_q * L * steps));
     w.fwd_layers = static_cast<FwdLayer*>(take(sizeof(FwdLayer) * L));
     w.bar = static_cast<unsigned*>(take(sizeof(unsigned) * FWD_BAR_WORDS));
   }
@@ -150,12 +150,12 @@ FwdArgs forward_args(const disco_model* m, const disco_kv* kv, const Ws& ws) {
   f.nkv = d.n_kv_heads; f.dh = d.d_head; f.vocab = d.vocab; f.eps = d.norm_eps; f.attn_scale = 1.0f / sqrtf((float)d.d_head);
   f.layers = ws.fwd_layers; f.normf_g = m->w.normf_g; f.wlm = static_cast<const bf16_t*>(m->w.wlm);
   f.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb); f.tok_stride = m->w.tok_emb_stride;
-  f.h = ws.h; f.q = ws.q; f.ssq = ws.ssq; f.xn = ws.xn_v; f.xattn = ws.xattn_v; f.xact = ws.xact_v;
+  f.h = ws.h; f.q = ws.q_v; f.xn = ws.xn_v; f.xattn = ws.xattn_v; f.xact = ws.xact_v;
   f.xn_stride = ws.xn_stride; f.xattn_stride = ws.xattn_stride; f.xact_stride = ws.xact_stride;
   f.part = ws.part; f.planes = ws.gpart; f.gemm_counters = ws.gemm_counters; f.attn_counters = ws.attn_counters;
   f.kv_pages = kv->pages; f.kv_layer_stride = kv->layer_stride; f.page_table = kv->dev_page_table;
   f.page_tokens = kv->page_tokens; f.rope = kv->dev_rope;
-  f.bar = ws.bar; f.abort_word = ws.bar + 16 * 64; f.n_steps = 1;
+  f.bar = ws.bar; f.n_steps = 1;
   return f;
 }
 
@@ -176,7 +176,8 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     // embedding launch (residual rows, first panel version, sums of squares), then the whole forward in one launch
     NormArgs n0{};
     n0.h = ws.h; n0.d = d.d_model; n0.M = n; n0.eps = d.norm_eps; n0.Xout = ws.xn_v; n0.pos0 = pos0; n0.vocab = d.vocab;
-    n0.max_pos = d.max_pos; n0.ssq_out = ws.ssq; n0.n_ssq_out = n_tiles; n0.g = m->layers[0].norm1_g;
+    n0.max_pos = d.max_pos; n0.ssq_out = reinterpret_cast<float*>(ws.xn_v + (size_t)32 * d.d_model); n0.n_ssq_out = n_tiles;
+    n0.g = m->layers[0].norm1_g;
     n0.tokens = dev_tokens; n0.tok_emb = static_cast<const bf16_t*>(m->w.tok_emb); n0.tok_stride = m->w.tok_emb_stride;
     HIP_TRY(launch_norm(n0, s), "embedding launch");
     HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.bar), FWD_BAR_WORDS, s), "barrier reset launch");
@@ -484,7 +485,7 @@ int disco_model_create(const disco_model_desc* desc, const disco_model_weights* 
       m->fwd_layers.push_back(FwdLayer{static_cast<const bf16_t*>(L.wqkv), static_cast<const bf16_t*>(L.wo), static_cast<const bf16_t*>(L.w_in),
                                        static_cast<const bf16_t*>(L.w_out), L.norm1_g, L.norm2_g});
     // a draft loop in one launch needs panel versions for every step: kept for small models only
-    const size_t per_step = sizeof(bf16_t) * 32 * ((size_t)(2 * d.n_layers + 1) * d.d_model + (size_t)d.n_layers * (m->d_q + d.d_ff));
+    const size_t per_step = sizeof(bf16_t) * 34 * ((size_t)(2 * d.n_layers + 1) * d.d_model + (size_t)d.n_layers * (2 * m->d_q + d.d_ff));
     if (per_step <= ((size_t)4 << 20) && d.d_model <= 4096) m->loop_steps = DISCO_MAX_BLOCK;
   }
   *out = m;
@@ -653,7 +654,7 @@ int disco_verify(const disco_model* target, disco_kv* kv, const int32_t* dev_blo
   hipStream_t st = static_cast<hipStream_t>(s);
   rc = forward_block(target, kv, dev_block, n_block, logits, false, ws, nullptr, st);
   if (rc) return rc;
-  HIP_TRY(launch_argmax_rows(logits, n_block, target->d.vocab, dev_argmax, ws.bar ? ws.bar + 16 * 64 : nullptr, st), "argmax launch");
+  HIP_TRY(launch_argmax_rows(logits, n_block, target->d.vocab, dev_argmax, ws.bar ? ws.bar + FWD_BAR_ABORT_WORD : nullptr, st), "argmax launch");
   return DISCO_OK;
 }
 
@@ -718,7 +719,8 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
     }
     NormArgs n0{};
     n0.h = ws.h; n0.d = d.d_model; n0.M = n_in; n0.eps = d.norm_eps; n0.Xout = ws.xn_v; n0.pos0 = pos0; n0.vocab = d.vocab;
-    n0.max_pos = d.max_pos; n0.ssq_out = ws.ssq; n0.n_ssq_out = d.d_model / 16; n0.g = draft->layers[0].norm1_g;
+    n0.max_pos = d.max_pos; n0.ssq_out = reinterpret_cast<float*>(ws.xn_v + (size_t)32 * d.d_model); n0.n_ssq_out = d.d_model / 16;
+    n0.g = draft->layers[0].norm1_g;
     n0.tokens = dev_tokens_in; n0.tok_emb = static_cast<const bf16_t*>(draft->w.tok_emb); n0.tok_stride = draft->w.tok_emb_stride;
     HIP_TRY(launch_norm(n0, st), "embedding launch");
     HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.bar), FWD_BAR_WORDS, st), "barrier reset launch");
@@ -731,7 +733,7 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
     a.ref_token = dev_ref_tokens; a.ppl_threshold = ppl_threshold; a.scratch = ws.clf_scratch;
     HIP_TRY(launch_forward(f, draft->persist_big, true, st), "draft loop launch");
     kv->len = pos0 + n_in + steps - 1;
-    HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, ws.bar + 16 * 64, st), "loop finish launch");
+    HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, ws.bar + FWD_BAR_ABORT_WORD, st), "loop finish launch");
     return DISCO_OK;
   }
   for (int j = 1; j <= steps; ++j) {
@@ -851,6 +853,13 @@ int disco_clf_eval(const disco_clf* clf, const float* dev_feats, const int32_t* 
   a.scores = dev_scores; a.counts = dev_counts;
   HIP_TRY(launch_clf_eval(a, static_cast<hipStream_t>(s)), "eval launch");
   return DISCO_OK;
+}
+
+int disco_set_launch_mode(int mode) {
+  if (mode != 0 && mode != 1) return fail(DISCO_EINVAL, "launch mode %d: 0 (one launch per phase) or 1 (one launch per forward)", mode);
+  const int prev = g_launch_mode;
+  g_launch_mode = mode;
+  return prev;
 }
 
 int disco_probe_enable(int layer) {

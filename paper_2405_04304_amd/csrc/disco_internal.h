@@ -132,14 +132,16 @@ struct FwdArgs {
   // the forward: M tokens at positions pos0 ..; the residual rows h and the first panel version are already
   // written (embedding launch)
   int M, pos0;
-  float* h; float* q; float* ssq;
-  bf16_t* xn; bf16_t* xattn; bf16_t* xact;                 // panel versions: (2 L + 1), L and L per step
+  float* h;
+  float* q;                                                // query versions: L per step, 16 x d_q floats each
+  bf16_t* xn; bf16_t* xattn; bf16_t* xact;                 // panel versions: (2 L + 1), L and L per step; an xn version is
+                                                           // two panels followed by its sums of squares (d floats)
   size_t xn_stride, xattn_stride, xact_stride;             // elements between versions
   float* part; float* planes; int* gemm_counters; int* attn_counters;
   bf16_t* kv_pages; size_t kv_layer_stride; const int32_t* page_table; int page_tokens; const float* rope;
   float* logits; int only_last;
   int split_o, split_dn, attn_split_len;                   // set by the launcher from the grid size
-  unsigned* bar; unsigned* abort_word;                     // BAR_GROUPS counters (zeroed before the launch), abort word
+  unsigned* bar;                                           // FWD_BAR_WORDS words of the grid barrier, zeroed before the launch
   // draft loop: n_steps (forward, classify) pairs in one launch; step 0 feeds M tokens, later steps one;
   // clf holds the first step's classify arguments (pos_feature, out, block_slot, force_token, ref_token advance per step)
   int n_steps;
@@ -155,7 +157,8 @@ int gemm_split_for(int n_rows, int KT, int M);   // K ranges the PARTIAL epilogu
 hipError_t launch_norm(const NormArgs& a, hipStream_t s);
 bool forward_shape_ok(int d, int d_q, int d_qkv, int d_ff, int dh, int vocab, bool big);
 hipError_t launch_forward(const FwdArgs& f, bool big, bool loop, hipStream_t s);
-constexpr int FWD_BAR_WORDS = 16 * 64 + 64;   // barrier counters + abort word, in 4-byte words
+constexpr int FWD_BAR_WORDS = (2 * 16 + 2) * 64;   // group counters, top counter, release words, abort word: 256 bytes apart
+constexpr int FWD_BAR_ABORT_WORD = (2 * 16 + 1) * 64;
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
 // dense prompt pass (groups of 16 tokens; every group holds 16 rows, surplus rows are padding)
 hipError_t launch_gemm_dense(const DenseArgs& a, int epi, hipStream_t s);

@@ -323,6 +323,10 @@ __device__ __forceinline__ void qkv_store(const GemmArgs& a, float* q, const int
 
 template <int EPI> struct EpiTraits { static constexpr bool pair = (EPI == EPI_QKV || EPI == EPI_SWIGLU); };
 
+// Register buffers (k-tiles in flight per wavefront) by row tiles per unit: as many as the register file of a
+// workgroup of eight wavefronts holds next to the accumulators.
+constexpr int gemm_buffers(int rt, int panels) { return rt >= 8 ? (panels >= 2 ? 2 : 3) : 4; }
+
 // LDS of one GEMM work unit.
 template <int RT, int NW>
 struct GemmSmem {
@@ -349,47 +353,56 @@ __device__ __forceinline__ void gemm_unit_tiles(const GemmArgs& a, const int b, 
   }
 }
 
-// The weight tiles of a unit's first two steps (k-tiles kt_begin + w and kt_begin + w + NW of wavefront w),
-// requested ahead of the unit itself: a persistent kernel issues them before it waits at the grid barrier in
-// front of the phase, since weights do not depend on the phase before.  gemm_unit<..., PRE = true> uses them.
-template <int RT, int EPI, int NW>
-__device__ __forceinline__ void gemm_prefetch(const GemmArgs& a, const int b, const int kt_begin, const int kt_end,
-                                              u32x4 (&pre)[2][8]) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  int rt[RT];
-  gemm_unit_tiles<RT, EPI>(a, b, rt);
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int k = kt_begin + w + i * NW;
-    if (k < kt_end) {
-#pragma unroll
-      for (int r = 0; r < RT; ++r)
-        pre[i][r] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(a.W) + ((size_t)rt[r] * a.KT + k) * 64 + lane);
-    }
-  }
-}
-
 // COH: the unit's inputs were written, and its outputs are read, by other workgroups of the same launch
 // (persistent kernel): hand-off accesses instead of plain ones; the activation panels are still plain loads
 // (the persistent kernel gives every phase panels at addresses that nobody has read before in the launch).
-template <int P, int RT, int EPI, int NW, int U, bool COH = false, bool PRE = false>
+// `hook` runs once, right after the unit's first weight tiles (two steps per wavefront) have been requested and
+// before anything that depends on the unit's inputs is touched: a persistent kernel waits there for the grid
+// barrier that ends the phase before, so the weight stream is in flight while that phase drains.
+struct NoHook { __device__ __forceinline__ void operator()() const {} };
+
+template <int P, int RT, int EPI, int NW, int U, bool COH = false, typename Hook = NoHook>
 __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const int kt_begin, const int kt_end,
-                                          const int seg, const int n_seg, GemmSmem<RT, NW>& sm, u32x4 (&pre)[2][8]) {
+                                          const int seg, const int n_seg, GemmSmem<RT, NW>& sm, const Hook hook = Hook()) {
   constexpr bool PAIR = EpiTraits<EPI>::pair;
   constexpr int UNITS = PAIR ? RT / 2 : RT;       // output units handled by one wavefront each
   static_assert(!PAIR || RT % 2 == 0, "pair epilogues need an even tile count");
   static_assert(UNITS <= NW, "one epilogue wavefront per unit");
-  static_assert(!PRE || U == 1, "preloaded steps are single k-tiles");
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const uint32_t halted = gate_request(a.gate);
   int rt[RT];
   gemm_unit_tiles<RT, EPI>(a, b, rt);
 
-  f32x4 acc[RT][P];
+  // one accumulator per row tile: with two panels (hi, lo) both products are added into it
+  f32x4 acc[RT];
 #pragma unroll
-  for (int r = 0; r < RT; ++r)
+  for (int r = 0; r < RT; ++r) acc[r] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int KT = a.KT;
+  const u32x4* Wp[RT];
 #pragma unroll
-    for (int p = 0; p < P; ++p) acc[r][p] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int r = 0; r < RT; ++r) Wp[r] = reinterpret_cast<const u32x4*>(a.W) + (size_t)rt[r] * KT * 64 + lane;
+  const u32x4* Xp = reinterpret_cast<const u32x4*>(a.X) + lane;
+
+  // U register buffers, one k-tile each: wavefront w takes k-tiles kt_begin + w, + NW, ...; the loads of the next
+  // U - 1 steps are in flight while the matrix unit works on a step (U * RT KiB of weights per wavefront: the
+  // stream is bound by the bytes in flight, see the launch shapes below).
+  auto load_w = [&](u32x4 (&A)[RT], const int k) {
+#pragma unroll
+    for (int r = 0; r < RT; ++r) A[r] = __builtin_nontemporal_load(Wp[r] + (size_t)k * 64);
+  };
+  auto load_x = [&](u32x4 (&B)[P], const int k) {
+#pragma unroll
+    for (int p = 0; p < P; ++p) B[p] = Xp[((size_t)p * KT + k) * 64];
+  };
+  u32x4 A[U][RT], B[U][P];
+  const int kt0 = kt_begin + w;
+  // the weights of the first U steps depend on nothing: they go out first
+#pragma unroll
+  for (int i = 0; i < U; ++i)
+    if (kt0 + i * NW < kt_end) load_w(A[i], kt0 + i * NW);
+  asm volatile("" ::: "memory");
+  hook();
 
   // deferred RMSNorm: the panels hold g * h (not normalised).  The producer left one sum of squares
   // per token and 16-column tile; every lane fetches a few of them now (lane = token lane % 16,
@@ -408,74 +421,28 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
     for (int k = 0; k < MAXS; ++k) {
       if (k < rounds) {
         const int idx = (lane >> 4) * NW + w + 4 * NW * k;
-        sv[k] = idx < a.n_ssq ? ld_f1<COH>(a.ssq + idx * 16 + (lane & 15)) : 0.f;   // [slot][token]
+        sv[k] = idx < a.n_ssq ? a.ssq[idx * 16 + (lane & 15)] : 0.f;   // [slot][token]; plain loads: see k_forward
       }
     }
-    asm volatile("" ::: "memory");     // keep these loads ahead of the weight stream
+    asm volatile("" ::: "memory");     // keep these loads ahead of the rest of the stream
   }
-
-  const int KT = a.KT;
-  const u32x4* Wp[RT];
 #pragma unroll
-  for (int r = 0; r < RT; ++r) Wp[r] = reinterpret_cast<const u32x4*>(a.W) + (size_t)rt[r] * KT * 64 + lane;
-  const u32x4* Xp = reinterpret_cast<const u32x4*>(a.X) + lane;
-
-  // Two register buffers: the loads of step i + 1 are issued before the matrix instructions of step
-  // i, so the memory pipe stays full while the matrix unit works.  A step is U k-tiles per wavefront;
-  // k-tiles past the end of the range are clamped to its last tile (loaded again, not used).
-  auto load_w = [&](u32x4 (&A)[U][RT], const int kt0) {
+  for (int i = 0; i < U; ++i)
+    if (kt0 + i * NW < kt_end) load_x(B[i], kt0 + i * NW);
+  if (halted != 0u) return;                       // uniform over the launch; nothing has been written yet
+  for (int kt = kt0; kt < kt_end; kt += U * NW) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int k = kt0 + u * NW;
-      const size_t t = (size_t)(k < kt_end ? k : kt_end - 1) * 64;
+    for (int i = 0; i < U; ++i) {
+      const int k = kt + i * NW;
+      if (k < kt_end) {
 #pragma unroll
-      for (int r = 0; r < RT; ++r) A[u][r] = __builtin_nontemporal_load(Wp[r] + t);
-    }
-  };
-  auto load_x = [&](u32x4 (&B)[U][P], const int kt0) {
+        for (int p = 0; p < P; ++p)                // panel outside: RT independent instructions between two on one accumulator
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int k = kt0 + u * NW;
-      const size_t t = (size_t)(k < kt_end ? k : kt_end - 1) * 64;
-#pragma unroll
-      for (int p = 0; p < P; ++p) B[u][p] = Xp[(size_t)p * KT * 64 + t];
-    }
-  };
-  auto mma_step = [&](const u32x4 (&A)[U][RT], const u32x4 (&B)[U][P], const int kt0) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (U == 1 || kt0 + u * NW < kt_end) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-#pragma unroll
-          for (int p = 0; p < P; ++p)
-            acc[r][p] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[u][r]), as_bf16x8(B[u][p]), acc[r][p], 0, 0, 0);
+          for (int r = 0; r < RT; ++r)
+            acc[r] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(B[i][p]), acc[r], 0, 0, 0);
+        const int kn = k + U * NW;                 // the buffer's next k-tile
+        if (kn < kt_end) { load_w(A[i], kn); load_x(B[i], kn); }
       }
-    }
-  };
-  {
-    constexpr int STEP = U * NW;
-    u32x4 A0[U][RT], B0[U][P], A1[U][RT], B1[U][P];
-    int kt = kt_begin + w;
-    if (PRE) {
-      // the weights of the first two steps are already on their way (gemm_prefetch)
-#pragma unroll
-      for (int r = 0; r < RT; ++r) { A0[0][r] = pre[0][r]; A1[0][r] = pre[1][r]; }
-      if (kt < kt_end) load_x(B0, kt);
-    } else {
-      if (kt < kt_end) { load_w(A0, kt); load_x(B0, kt); }
-    }
-    if (halted != 0u) return;                     // uniform over the launch; nothing has been written yet
-    bool first = PRE;
-    while (kt < kt_end) {
-      if (kt + STEP < kt_end) { if (!first) load_w(A1, kt + STEP); load_x(B1, kt + STEP); }
-      first = false;
-      mma_step(A0, B0, kt);
-      kt += STEP;
-      if (kt >= kt_end) break;
-      if (kt + STEP < kt_end) { load_w(A0, kt + STEP); load_x(B0, kt + STEP); }
-      mma_step(A1, B1, kt);
-      kt += STEP;
     }
   }
 
@@ -483,12 +450,10 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
   __syncthreads();                                // a previous unit of this workgroup has left the buffers
 #pragma unroll
   for (int r = 0; r < RT; ++r) {
-    f32x4 y;
+    f32x4 y = acc[r];
     if (P == 1) {
 #pragma unroll
-      for (int v = 0; v < 4; ++v) y[v] = acc[r][0][v] + __shfl_xor(acc[r][0][v], 8);
-    } else {
-      y = acc[r][0] + acc[r][P - 1];
+      for (int v = 0; v < 4; ++v) y[v] = acc[r][v] + __shfl_xor(acc[r][v], 8);
     }
     sm.red[w][r][lane] = y;
   }
@@ -620,10 +585,9 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
 template <int P, int RT, int EPI, int NW, int U>
 __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
   __shared__ GemmSmem<RT, NW> sm;
-  u32x4 none[2][8];
   const int split = blockIdx.y;
   const int kt_begin = (int)((int64_t)a.KT * split / a.n_split), kt_end = (int)((int64_t)a.KT * (split + 1) / a.n_split);
-  gemm_unit<P, RT, EPI, NW, U>(a, blockIdx.x, kt_begin, kt_end, split, a.n_split, sm, none);
+  gemm_unit<P, RT, EPI, NW, U>(a, blockIdx.x, kt_begin, kt_end, split, a.n_split, sm);
 }
 
 template <int P, int RT, int EPI, int NW, int U>
@@ -658,17 +622,17 @@ static hipError_t launch_gemm_p(const GemmArgs& a, hipStream_t s) {
   constexpr bool PAIR = EpiTraits<EPI>::pair;
   const int n = a.n_rows;
   if constexpr (EPI == EPI_PARTIAL) {
-    if (n % 64 == 0 && n >= 2048) return launch_gemm_cfg<P, 4, EPI, 8, 1>(a, s);
-    if (n % 32 == 0 && (int64_t)(n / 32) * a.n_split >= 200) return launch_gemm_cfg<P, 2, EPI, 8, 1>(a, s);
-    return launch_gemm_cfg<P, 1, EPI, 8, 1>(a, s);
+    if (n % 64 == 0 && n >= 2048) return launch_gemm_cfg<P, 4, EPI, 8, gemm_buffers(4, P)>(a, s);
+    if (n % 32 == 0 && (int64_t)(n / 32) * a.n_split >= 200) return launch_gemm_cfg<P, 2, EPI, 8, gemm_buffers(2, P)>(a, s);
+    return launch_gemm_cfg<P, 1, EPI, 8, gemm_buffers(1, P)>(a, s);
   } else {
-    if (EPI != EPI_QKV && a.KT >= 64 && n % 128 == 0 && n / 128 >= 200) return launch_gemm_cfg<P, 8, EPI, 8, 1>(a, s);
-    if (n % 64 == 0 && n / 64 >= 200) return launch_gemm_cfg<P, 4, EPI, 8, 1>(a, s);
+    if (EPI != EPI_QKV && a.KT >= 64 && n % 128 == 0 && n / 128 >= 200) return launch_gemm_cfg<P, 8, EPI, 8, gemm_buffers(8, P)>(a, s);
+    if (n % 64 == 0 && n / 64 >= 200) return launch_gemm_cfg<P, 4, EPI, 8, gemm_buffers(4, P)>(a, s);
     if constexpr (PAIR) {
-      return launch_gemm_cfg<P, 2, EPI, 8, 1>(a, s);
+      return launch_gemm_cfg<P, 2, EPI, 8, gemm_buffers(2, P)>(a, s);
     } else {
-      if (n % 32 == 0 && n / 32 >= 200) return launch_gemm_cfg<P, 2, EPI, 8, 1>(a, s);
-      return launch_gemm_cfg<P, 1, EPI, 8, 1>(a, s);
+      if (n % 32 == 0 && n / 32 >= 200) return launch_gemm_cfg<P, 2, EPI, 8, gemm_buffers(2, P)>(a, s);
+      return launch_gemm_cfg<P, 1, EPI, 8, gemm_buffers(1, P)>(a, s);
     }
   }
 }
@@ -997,8 +961,8 @@ __device__ __forceinline__ void attn_range(const AttnArgs& a, const int head, co
   const int j = lane & 15, g = lane >> 4;
   const int total = a.pos0 + a.M;
   const int s0 = split * a.split_len, s1 = min(s0 + a.split_len, total);
-  AttnWave<DH, COH, VCOH> aw(a, head, s1);
-  typename AttnWave<DH, COH, VCOH>::Raw r0, r1;
+  AttnWave<DH, false, VCOH> aw(a, head, s1);     // (a persistent kernel gives the queries a fresh address per layer)
+  typename AttnWave<DH, false, VCOH>::Raw r0, r1;
   // the first step's cache loads go out ahead of the q loads; later steps' loads are in flight during
   // the arithmetic of the step before
   constexpr int STEP = NWV * WKEYS;
@@ -2423,40 +2387,55 @@ hipError_t launch_rstd_groups(const float* ssq, int n_ssq, int d, float eps, flo
 // Coherence inside the launch: the eight XCDs have separate L2s, and an L2-wide write-back / invalidate at
 // every barrier costs more than the barrier (measured: 8 - 13 us).  Instead (a) every store that another
 // workgroup will read is a write-through store and small hand-off data is read with L2-bypassing loads
-// (COH accesses above); (b) the large activation panels, which every workgroup of a phase reads, are given a
-// fresh address per phase ("versions"), so no L2 can hold an older copy and plain loads are safe and hit
-// in the reader's own L2 after the first touch.
+// (COH accesses above); (b) what MANY workgroups of a phase read (the activation panels with their sums of
+// squares, the queries) is given a fresh address per phase ("versions"), so no L2 can hold an older copy
+// and plain loads are safe and hit in the reader's own L2 after the first touch: L2-bypassing loads of the
+// same few lines from every workgroup queue up on a few memory channels.
 //
-// Grid barrier: 16 counters, workgroup i adds 1 to counter i % 16 (no return value needed), then 16 lanes of
-// its first wavefront poll the counters until all have reached epoch * (G / 16).  The host zeroes the
-// counters before the launch.  Every wait is bounded: after BAR_SPIN_LIMIT polls the workgroup sets the
-// abort word, every later barrier falls through at once, and the launch drains with unusable results (the
-// arg-max and loop-finish kernels turn a set abort word into -1 outputs).
+// Grid barrier, two levels: workgroup i adds 1 to the counter of its group i % 16; the workgroup that completes
+// a group adds 1 to the top counter; the one that completes the top counter writes the barrier's number into
+// the 16 release words, and every workgroup polls only the release word of its own group (16 pollers per
+// word: with every workgroup polling every counter, the polls of 256 workgroups queue up on a few memory
+// channels and the workgroups leave the barrier microseconds apart).  All words are 256 bytes apart.  The
+// host zeroes them before the launch.  Every wait is bounded: after BAR_SPIN_LIMIT polls the workgroup
+// sets the abort word, every later barrier falls through at once, and the launch drains with unusable
+// results (the arg-max and loop-finish kernels turn a set abort word into -1 outputs).
 
 constexpr int BAR_GROUPS = 16;
-constexpr int BAR_SLOT = 64;                 // ints between two counters (256 bytes)
+constexpr int BAR_SLOT = 64;                 // ints between two words (256 bytes)
+constexpr int BAR_TOP = BAR_GROUPS;          // word index (in slots) of the top counter
+constexpr int BAR_RELEASE = BAR_GROUPS + 1;  // first release word
+constexpr int BAR_ABORT = 2 * BAR_GROUPS + 1;
 constexpr int BAR_SPIN_LIMIT = 1 << 20;      // polls (each a memory round trip, about 1 us) before giving up
 
-__device__ __forceinline__ void bar_arrive(unsigned* cnt) {
+// n = number of this barrier (1, 2, ..), per_group = workgroups per group
+__device__ __forceinline__ void bar_arrive(unsigned* bar, const unsigned n, const unsigned per_group) {
   __builtin_amdgcn_s_waitcnt(0);             // this wavefront's hand-off stores have completed
   __builtin_amdgcn_s_barrier();              // ... and those of the whole workgroup
-  if (threadIdx.x == 0)
-    __hip_atomic_fetch_add(cnt + (blockIdx.x % BAR_GROUPS) * BAR_SLOT, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (threadIdx.x == 0) {
+    const unsigned old = __hip_atomic_fetch_add(bar + (blockIdx.x % BAR_GROUPS) * BAR_SLOT, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old + 1 == n * per_group) {
+      const unsigned old_top = __hip_atomic_fetch_add(bar + BAR_TOP * BAR_SLOT, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (old_top + 1 == n * BAR_GROUPS) {
+#pragma unroll
+        for (int g = 0; g < BAR_GROUPS; ++g)
+          __hip_atomic_store(bar + (BAR_RELEASE + g) * BAR_SLOT, n, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
   asm volatile("" ::: "memory");
 }
 
-__device__ __forceinline__ void bar_wait(unsigned* cnt, unsigned* abort_word, const unsigned target) {
-  if (threadIdx.x < 64) {
+__device__ __forceinline__ void bar_wait(unsigned* bar, const unsigned n) {
+  if (threadIdx.x == 0) {
+    unsigned* rel = bar + (BAR_RELEASE + blockIdx.x % BAR_GROUPS) * BAR_SLOT;
+    unsigned* abort_word = bar + BAR_ABORT * BAR_SLOT;
     int spins = 0;
-    for (;;) {
-      bool ok = true;
-      if ((int)threadIdx.x < BAR_GROUPS)
-        ok = (int)(__hip_atomic_load(cnt + threadIdx.x * BAR_SLOT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) >= 0;
-      if (__all(ok)) break;
+    while ((int)(__hip_atomic_load(rel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - n) < 0) {
       ++spins;
       if ((spins & 255) == 0 && __hip_atomic_load(abort_word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
       if (spins > BAR_SPIN_LIMIT) {
-        if (threadIdx.x == 0) __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         break;
       }
       __builtin_amdgcn_s_sleep(1);
@@ -2471,179 +2450,208 @@ __device__ __forceinline__ void bar_wait(unsigned* cnt, unsigned* abort_word, co
 struct FwdBig { static constexpr int QKV = 4, PART = 4, UP = 8, LM = 8; };
 struct FwdSmall { static constexpr int QKV = 2, PART = 1, UP = 2, LM = 8; };
 
-template <typename C>
-union FwdSmem {
-  GemmSmem<C::QKV, 8> qkv; GemmSmem<C::PART, 8> part; GemmSmem<C::UP, 8> up; GemmSmem<C::LM, 8> lm;
-  AttnSmem<128, 8> a128; AttnSmem<64, 8> a64;
-  float red[16];
+// LDS of the persistent kernel: one arena, every phase lays its own structure over it (the phases are
+// separate functions, so that each gets its own register allocation).
+constexpr int FWD_SMEM_BYTES = 68 * 1024;
+__shared__ __align__(16) unsigned char g_fwd_smem[FWD_SMEM_BYTES];
+template <typename T> __device__ __forceinline__ T& fwd_smem() {
+  static_assert(sizeof(T) <= FWD_SMEM_BYTES, "phase structure larger than the arena");
+  return *reinterpret_cast<T*>(g_fwd_smem);
+}
+
+// The launch's arguments stay in the kernel-argument segment; the phase functions read them through this
+// pointer (scalar loads).
+typedef const FwdArgs __attribute__((address_space(4)))* FwdArgsPtr;
+
+// What a phase function needs beyond the launch's arguments.
+struct FwdCtx { FwdArgsPtr f; int step, l, M, pos0; unsigned bar_n; };   // bar_n: number of the barrier that ends the phase before (0: none)
+
+struct FwdWaitHook {
+  unsigned* bar; unsigned n;
+  __device__ __forceinline__ void operator()() const { if (n != 0u) bar_wait(bar, n); }
 };
 
-// One GEMM phase: unit u = (row group u % groups, K range u / groups); workgroup i takes units i, i + G, ...
-// The weights of its first unit are already requested (pre) when have_pre.
-template <int P, int RT, int EPI>
-__device__ __forceinline__ void fwd_gemm_phase(const GemmArgs& ga, const int groups, GemmSmem<RT, 8>& sm, u32x4 (&pre)[2][8],
-                                               bool have_pre) {
-  const int n_units = groups * ga.n_split;
-  for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
-    const int b = u % groups, seg = u / groups;
-    const int kt_begin = (int)((int64_t)ga.KT * seg / ga.n_split), kt_end = (int)((int64_t)ga.KT * (seg + 1) / ga.n_split);
-    if (!have_pre) gemm_prefetch<RT, EPI, 8>(ga, b, kt_begin, kt_end, pre);
-    have_pre = false;
-    gemm_unit<P, RT, EPI, 8, 1, true, true>(ga, b, kt_begin, kt_end, seg, ga.n_split, sm, pre);
-  }
+__device__ __forceinline__ GemmArgs fwd_base_args(FwdArgsPtr f, const int M) {
+  GemmArgs g{};
+  g.M = M; g.n_split = 1; g.grp = 1; g.planes = f->planes; g.counters = f->gemm_counters; g.only_row = -1;
+  return g;
 }
-// The requests for the first unit of the phase (see above); false if this workgroup has no unit in it.
-template <int RT, int EPI>
-__device__ __forceinline__ bool fwd_gemm_prefetch(const GemmArgs& ga, const int groups, u32x4 (&pre)[2][8]) {
-  const int u = blockIdx.x;
-  if (u >= groups * ga.n_split) return false;
-  const int b = u % groups, seg = u / groups;
-  const int kt_begin = (int)((int64_t)ga.KT * seg / ga.n_split), kt_end = (int)((int64_t)ga.KT * (seg + 1) / ga.n_split);
-  gemm_prefetch<RT, EPI, 8>(ga, b, kt_begin, kt_end, pre);
-  return true;
+// the sums of squares of a panel version follow its two panels
+__device__ __forceinline__ float* fwd_ssq_of(FwdArgsPtr f, const bf16_t* xn_version) {
+  return reinterpret_cast<float*>(const_cast<bf16_t*>(xn_version) + (size_t)32 * f->d);
+}
+__device__ __forceinline__ void fwd_normed_input(FwdArgsPtr f, GemmArgs& g, const bf16_t* x) {
+  g.X = x; g.KT = f->d >> 5; g.ssq = fwd_ssq_of(f, x); g.n_ssq = f->d >> 4; g.d_in = f->d; g.eps = f->eps;
+}
+__device__ __forceinline__ void fwd_residual(FwdArgsPtr f, GemmArgs& g, const bf16_t* w, const bf16_t* x, const int k, const int split,
+                                             const float* next_gain, bf16_t* xout) {
+  g.W = w; g.X = x; g.KT = k >> 5; g.n_rows = f->d; g.h = f->h; g.ld_out = f->d; g.n_split = split;
+  g.Xout = xout; g.KT_out = f->d >> 5; g.gain = next_gain; g.ssq_out = fwd_ssq_of(f, xout); g.n_ssq_out = f->d >> 4;
+}
+// panel versions of a step: xn has 2 L + 1 per step, xattn and xact L each
+__device__ __forceinline__ bf16_t* fwd_xn(FwdArgsPtr f, const int step, const int v) {
+  return f->xn + ((size_t)step * (2 * f->n_layers + 1) + v) * f->xn_stride;
+}
+__device__ __forceinline__ float* fwd_q(FwdArgsPtr f, const int step, const int l) {
+  return f->q + ((size_t)step * f->n_layers + l) * 16 * f->d_q;
+}
+__device__ __forceinline__ bf16_t* fwd_xattn(FwdArgsPtr f, const int step, const int l) {
+  return f->xattn + ((size_t)step * f->n_layers + l) * f->xattn_stride;
+}
+__device__ __forceinline__ bf16_t* fwd_xact(FwdArgsPtr f, const int step, const int l) {
+  return f->xact + ((size_t)step * f->n_layers + l) * f->xact_stride;
+}
+
+// One GEMM phase: unit u = (row group u % groups, K range u / groups); workgroup i takes units i, i + G, ...
+// Its first unit waits for the phase before (after requesting its first weight tiles); a workgroup without a
+// unit just waits.  Ends with the arrival at the phase's own barrier.
+template <int P, int RT, int EPI>
+__device__ __forceinline__ void fwd_gemm_phase(const FwdCtx& c, const GemmArgs& ga, const int groups) {
+  GemmSmem<RT, 8>& sm = fwd_smem<GemmSmem<RT, 8>>();
+  const FwdWaitHook hook{c.f->bar, c.bar_n};
+  const int n_units = groups * ga.n_split;
+  int u = blockIdx.x;
+  if (u >= n_units) {
+    hook();
+  } else {
+    bool first = true;
+    for (; u < n_units; u += gridDim.x) {
+      const int b = u % groups, seg = u / groups;
+      const int kt_begin = (int)((int64_t)ga.KT * seg / ga.n_split), kt_end = (int)((int64_t)ga.KT * (seg + 1) / ga.n_split);
+      if (first) gemm_unit<P, RT, EPI, 8, gemm_buffers(RT, P), true, FwdWaitHook>(ga, b, kt_begin, kt_end, seg, ga.n_split, sm, hook);
+      else gemm_unit<P, RT, EPI, 8, gemm_buffers(RT, P), true, FwdWaitHook>(ga, b, kt_begin, kt_end, seg, ga.n_split, sm, FwdWaitHook{nullptr, 0u});
+      first = false;
+    }
+  }
+  bar_arrive(c.f->bar, c.bar_n + 1, gridDim.x / BAR_GROUPS);
+}
+
+#define FWD_PHASE_FN __forceinline__
+
+template <int P, typename C>
+__device__ FWD_PHASE_FN void fwd_qkv(const FwdCtx c) {
+  FwdArgsPtr f = c.f;
+  GemmArgs g = fwd_base_args(f, c.M);
+  g.W = f->layers[c.l].wqkv; fwd_normed_input(f, g, fwd_xn(f, c.step, 2 * c.l)); g.n_rows = f->d_qkv;
+  g.grp = f->dh >> 5; g.q = fwd_q(f, c.step, c.l); g.ldq = f->d_q; g.nq = f->nq; g.nkv = f->nkv; g.dh = f->dh; g.pos0 = c.pos0;
+  g.rope_tab = f->rope; g.kv_layer = f->kv_pages + (size_t)c.l * f->kv_layer_stride; g.page_table = f->page_table;
+  g.page_tokens = f->page_tokens;
+  fwd_gemm_phase<P, C::QKV, EPI_QKV>(c, g, f->d_qkv / (16 * C::QKV));
+}
+
+template <bool LOOP>
+__device__ FWD_PHASE_FN void fwd_attn(const FwdCtx c) {
+  FwdArgsPtr f = c.f;
+  AttnArgs at{};
+  at.q = fwd_q(f, c.step, c.l); at.ldq = f->d_q; at.kv_layer = f->kv_pages + (size_t)c.l * f->kv_layer_stride; at.page_table = f->page_table;
+  at.page_tokens = f->page_tokens; at.nq = f->nq; at.nkv = f->nkv; at.dh = f->dh; at.M = c.M; at.pos0 = c.pos0;
+  at.scale = f->attn_scale; at.part = f->part; at.split_len = f->attn_split_len;
+  at.n_splits = (c.pos0 + c.M + f->attn_split_len - 1) / f->attn_split_len;
+  at.Xout = fwd_xattn(f, c.step, c.l); at.counters = f->attn_counters;
+  FwdWaitHook{f->bar, c.bar_n}();
+  const int n_units = f->nq * at.n_splits;
+  for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
+    const int head = u % f->nq, split = u / f->nq;
+    if (f->dh == 128) attn_range<128, 8, true, LOOP>(at, head, split, fwd_smem<AttnSmem<128, 8>>(), 0u);
+    else attn_range<64, 8, true, LOOP>(at, head, split, fwd_smem<AttnSmem<64, 8>>(), 0u);
+  }
+  bar_arrive(f->bar, c.bar_n + 1, gridDim.x / BAR_GROUPS);
+}
+
+template <int P, typename C>
+__device__ FWD_PHASE_FN void fwd_o(const FwdCtx c) {
+  FwdArgsPtr f = c.f;
+  GemmArgs g = fwd_base_args(f, c.M);
+  fwd_residual(f, g, f->layers[c.l].wo, fwd_xattn(f, c.step, c.l), f->d_q, f->split_o, f->layers[c.l].norm2_g,
+               fwd_xn(f, c.step, 2 * c.l + 1));
+  fwd_gemm_phase<P, C::PART, EPI_PARTIAL>(c, g, f->d / (16 * C::PART));
+}
+
+template <int P, typename C>
+__device__ FWD_PHASE_FN void fwd_up(const FwdCtx c) {
+  FwdArgsPtr f = c.f;
+  GemmArgs g = fwd_base_args(f, c.M);
+  g.W = f->layers[c.l].w_in; fwd_normed_input(f, g, fwd_xn(f, c.step, 2 * c.l + 1)); g.n_rows = 2 * f->d_ff;
+  g.Xout = fwd_xact(f, c.step, c.l); g.KT_out = f->d_ff >> 5;
+  fwd_gemm_phase<P, C::UP, EPI_SWIGLU>(c, g, 2 * f->d_ff / (16 * C::UP));
+}
+
+template <int P, typename C>
+__device__ FWD_PHASE_FN void fwd_down(const FwdCtx c) {
+  FwdArgsPtr f = c.f;
+  GemmArgs g = fwd_base_args(f, c.M);
+  const bool last = (c.l + 1 == f->n_layers);
+  fwd_residual(f, g, f->layers[c.l].w_out, fwd_xact(f, c.step, c.l), f->d_ff, f->split_dn,
+               last ? f->normf_g : f->layers[last ? c.l : c.l + 1].norm1_g, fwd_xn(f, c.step, 2 * c.l + 2));
+  fwd_gemm_phase<P, C::PART, EPI_PARTIAL>(c, g, f->d / (16 * C::PART));
+}
+
+template <int P, typename C>
+__device__ FWD_PHASE_FN void fwd_lm(const FwdCtx c) {
+  FwdArgsPtr f = c.f;
+  GemmArgs g = fwd_base_args(f, c.M);
+  g.W = f->wlm; fwd_normed_input(f, g, fwd_xn(f, c.step, 2 * f->n_layers)); g.n_rows = f->vocab;
+  g.out = f->logits; g.ld_out = f->vocab; g.only_row = f->only_last ? c.M - 1 : -1;
+  fwd_gemm_phase<P, C::LM, EPI_STORE>(c, g, f->vocab / (16 * C::LM));
+}
+
+// Draft loop: Eq. 2 features and classifier on the step's logits; the workgroup that finishes them embeds the
+// next step's token (row 0 of the residual stream, the first panel version of that step, the sums of squares).
+__device__ FWD_PHASE_FN void fwd_classify(const FwdCtx c) {
+  FwdArgsPtr f = c.f;
+  FwdWaitHook{f->bar, c.bar_n}();
+  ClassifyArgs ca{};
+  ca.logits = f->clf.logits; ca.vocab = f->clf.vocab; ca.clf_params = f->clf.clf_params; ca.hidden = f->clf.hidden;
+  ca.tau = f->clf.tau; ca.token_next = f->clf.token_next; ca.gate = f->clf.gate; ca.sl_count = f->clf.sl_count;
+  ca.ppl_threshold = f->clf.ppl_threshold; ca.scratch = f->clf.scratch;
+  ca.pos_feature = f->clf.pos_feature + (float)c.step;
+  ca.force_halt = (c.step + 1 == f->n_steps) ? 1 : 0;
+  ca.out = reinterpret_cast<ClfOut*>(f->clf.out) + c.step;
+  ca.block_slot = f->clf.block_slot + c.step;
+  ca.force_token = f->clf.force_token ? f->clf.force_token + c.step : nullptr;
+  ca.ref_token = f->clf.ref_token ? f->clf.ref_token + c.step : nullptr;
+  const int nb = (f->vocab + 4 * CM_NT - 1) / (4 * CM_NT);
+  if ((int)blockIdx.x < nb) {
+    const int tok = classify_unit<CM_NT, true>(ca, blockIdx.x, nb, 0u);
+    if (tok >= 0 && c.step + 1 < f->n_steps) {
+      NormArgs na{};
+      na.h = f->h; na.d = f->d; na.M = 1; na.layernorm = 0; na.eps = f->eps; na.g = f->layers[0].norm1_g;
+      na.Xout = fwd_xn(f, c.step + 1, 0);
+      na.ssq_out = fwd_ssq_of(f, na.Xout); na.n_ssq_out = f->d >> 4; na.tok_emb = f->tok_emb; na.tok_stride = f->tok_stride;
+      na.vocab = f->vocab; na.max_pos = 1 << 30;
+      __syncthreads();
+      norm_row<CM_NT, true>(na, 0, tok, reinterpret_cast<float*>(g_fwd_smem), 0u);
+    }
+  }
+  bar_arrive(f->bar, c.bar_n + 1, gridDim.x / BAR_GROUPS);
 }
 
 template <int P, typename C, bool LOOP>
-__global__ __launch_bounds__(512) void k_forward(FwdArgs f) {
-  __shared__ __align__(16) FwdSmem<C> sm;
-  u32x4 pre[2][8];
-  unsigned epoch = 0;
-  const unsigned per_counter = gridDim.x / BAR_GROUPS;
-  const int KTd = f.d >> 5, n_tiles = f.d >> 4;
-  const int n_steps = LOOP ? f.n_steps : 1;
-  bool have_next = false;
-
-  // GEMM phase descriptions (uniform values: they live in scalar registers)
-  auto base_args = [&](const int M) {
-    GemmArgs g{};
-    g.M = M; g.n_split = 1; g.grp = 1; g.planes = f.planes; g.counters = f.gemm_counters; g.only_row = -1;
-    return g;
-  };
-  auto normed = [&](GemmArgs& g, const bf16_t* x) {
-    g.X = x; g.KT = KTd; g.ssq = f.ssq; g.n_ssq = n_tiles; g.d_in = f.d; g.eps = f.eps;
-  };
-  auto residual = [&](GemmArgs& g, const bf16_t* w, const bf16_t* x, const int k, const int split, const float* next_gain,
-                      bf16_t* xout) {
-    g.W = w; g.X = x; g.KT = k >> 5; g.n_rows = f.d; g.h = f.h; g.ld_out = f.d; g.n_split = split;
-    g.Xout = xout; g.KT_out = KTd; g.gain = next_gain; g.ssq_out = f.ssq; g.n_ssq_out = n_tiles;
-  };
-
+__global__ __launch_bounds__(512) void k_forward(FwdArgs f_by_value) {
+  (void)f_by_value;                           // read through the kernel-argument segment (first argument, offset 0)
+  FwdArgsPtr f = (FwdArgsPtr)__builtin_amdgcn_kernarg_segment_ptr();
+  unsigned epoch = 0;                         // barriers this workgroup has arrived at
+  const int n_steps = LOOP ? f->n_steps : 1, n_layers = f->n_layers;
   for (int step = 0; step < n_steps; ++step) {
-    const int M = (LOOP && step > 0) ? 1 : f.M;
-    const int pos0 = (LOOP && step > 0) ? f.pos0 + f.M + (step - 1) : f.pos0;
-    // panel versions of this step
-    bf16_t* xn = f.xn + (size_t)step * (2 * f.n_layers + 1) * f.xn_stride;
-    bf16_t* xattn = f.xattn + (size_t)step * f.n_layers * f.xattn_stride;
-    bf16_t* xact = f.xact + (size_t)step * f.n_layers * f.xact_stride;
-
-    GemmArgs gq = base_args(M);
-    auto qkv_args = [&](const int l) {
-      GemmArgs g = base_args(M);
-      g.W = f.layers[l].wqkv; normed(g, xn + (size_t)(2 * l) * f.xn_stride); g.n_rows = f.d_qkv;
-      g.grp = f.dh >> 5; g.q = f.q; g.ldq = f.d_q; g.nq = f.nq; g.nkv = f.nkv; g.dh = f.dh; g.pos0 = pos0;
-      g.rope_tab = f.rope; g.kv_layer = f.kv_pages + (size_t)l * f.kv_layer_stride; g.page_table = f.page_table;
-      g.page_tokens = f.page_tokens;
-      return g;
-    };
-    gq = qkv_args(0);
-    bool have = false;
-    if (step == 0) have = fwd_gemm_prefetch<C::QKV, EPI_QKV>(gq, f.d_qkv / (16 * C::QKV), pre);
-    else have = have_next;               // (set below: the requests went out before the barrier that ended the step before)
-
-    for (int l = 0; l < f.n_layers; ++l) {
-      const FwdLayer L = f.layers[l];
-      const bool last = (l + 1 == f.n_layers);
-      // ---- QKV projection, rotary, KV append
-      fwd_gemm_phase<P, C::QKV, EPI_QKV>(gq, f.d_qkv / (16 * C::QKV), sm.qkv, pre, have);
-      bar_arrive(f.bar); ++epoch; bar_wait(f.bar, f.abort_word, epoch * per_counter);
-      // ---- attention
-      {
-        AttnArgs at{};
-        at.q = f.q; at.ldq = f.d_q; at.kv_layer = gq.kv_layer; at.page_table = f.page_table; at.page_tokens = f.page_tokens;
-        at.nq = f.nq; at.nkv = f.nkv; at.dh = f.dh; at.M = M; at.pos0 = pos0; at.scale = f.attn_scale; at.part = f.part;
-        at.split_len = f.attn_split_len; at.n_splits = (pos0 + M + f.attn_split_len - 1) / f.attn_split_len;
-        at.Xout = xattn + (size_t)l * f.xattn_stride; at.counters = f.attn_counters;
-        const int n_units = f.nq * at.n_splits;
-        for (int u = blockIdx.x; u < n_units; u += gridDim.x) {
-          const int head = u % f.nq, split = u / f.nq;
-          if (f.dh == 128) attn_range<128, 8, true, LOOP>(at, head, split, sm.a128, 0u);
-          else attn_range<64, 8, true, LOOP>(at, head, split, sm.a64, 0u);
-        }
-      }
-      GemmArgs go = base_args(M);
-      residual(go, L.wo, xattn + (size_t)l * f.xattn_stride, f.d_q, f.split_o, L.norm2_g, xn + (size_t)(2 * l + 1) * f.xn_stride);
-      bar_arrive(f.bar); ++epoch;
-      have = fwd_gemm_prefetch<C::PART, EPI_PARTIAL>(go, f.d / (16 * C::PART), pre);
-      bar_wait(f.bar, f.abort_word, epoch * per_counter);
-      // ---- O-projection + residual
-      fwd_gemm_phase<P, C::PART, EPI_PARTIAL>(go, f.d / (16 * C::PART), sm.part, pre, have);
-      GemmArgs gu = base_args(M);
-      gu.W = L.w_in; normed(gu, xn + (size_t)(2 * l + 1) * f.xn_stride); gu.n_rows = 2 * f.d_ff;
-      gu.Xout = xact + (size_t)l * f.xact_stride; gu.KT_out = f.d_ff >> 5;
-      bar_arrive(f.bar); ++epoch;
-      have = fwd_gemm_prefetch<C::UP, EPI_SWIGLU>(gu, 2 * f.d_ff / (16 * C::UP), pre);
-      bar_wait(f.bar, f.abort_word, epoch * per_counter);
-      // ---- gate / up + SwiGLU
-      fwd_gemm_phase<P, C::UP, EPI_SWIGLU>(gu, 2 * f.d_ff / (16 * C::UP), sm.up, pre, have);
-      GemmArgs gd = base_args(M);
-      residual(gd, L.w_out, xact + (size_t)l * f.xact_stride, f.d_ff, f.split_dn, last ? f.normf_g : f.layers[l + 1].norm1_g,
-               xn + (size_t)(2 * l + 2) * f.xn_stride);
-      bar_arrive(f.bar); ++epoch;
-      have = fwd_gemm_prefetch<C::PART, EPI_PARTIAL>(gd, f.d / (16 * C::PART), pre);
-      bar_wait(f.bar, f.abort_word, epoch * per_counter);
-      // ---- down + residual
-      fwd_gemm_phase<P, C::PART, EPI_PARTIAL>(gd, f.d / (16 * C::PART), sm.part, pre, have);
-      bar_arrive(f.bar); ++epoch;
-      if (!last) {
-        gq = qkv_args(l + 1);
-        have = fwd_gemm_prefetch<C::QKV, EPI_QKV>(gq, f.d_qkv / (16 * C::QKV), pre);
-        bar_wait(f.bar, f.abort_word, epoch * per_counter);
-      }
+    FwdCtx c;
+    c.f = f; c.step = step;
+    c.M = (LOOP && step > 0) ? 1 : f->M;
+    c.pos0 = (LOOP && step > 0) ? f->pos0 + f->M + (step - 1) : f->pos0;
+    for (int l = 0; l < n_layers; ++l) {
+      c.l = l;
+      c.bar_n = epoch++; fwd_qkv<P, C>(c);
+      c.bar_n = epoch++; fwd_attn<LOOP>(c);
+      c.bar_n = epoch++; fwd_o<P, C>(c);
+      c.bar_n = epoch++; fwd_up<P, C>(c);
+      c.bar_n = epoch++; fwd_down<P, C>(c);
     }
-    // ---- LM head (the barrier after the last down projection is still open: arrive done, wait pending)
-    GemmArgs lm = base_args(M);
-    lm.W = f.wlm; normed(lm, xn + (size_t)(2 * f.n_layers) * f.xn_stride); lm.n_rows = f.vocab;
-    lm.out = f.logits; lm.ld_out = f.vocab; lm.only_row = f.only_last ? M - 1 : -1;
-    have = fwd_gemm_prefetch<C::LM, EPI_STORE>(lm, f.vocab / (16 * C::LM), pre);
-    bar_wait(f.bar, f.abort_word, epoch * per_counter);
-    fwd_gemm_phase<P, C::LM, EPI_STORE>(lm, f.vocab / (16 * C::LM), sm.lm, pre, have);
+    c.l = 0;
+    c.bar_n = epoch++; fwd_lm<P, C>(c);
     if (!LOOP) break;
-
-    // ---- draft loop: Eq. 2 features and classifier on the logits, the next token's embedding, halt test
-    bar_arrive(f.bar); ++epoch; bar_wait(f.bar, f.abort_word, epoch * per_counter);
-    {
-      ClassifyArgs ca = f.clf;
-      ca.pos_feature = f.clf.pos_feature + (float)step;
-      ca.force_halt = (step + 1 == n_steps) ? 1 : 0;
-      ca.out = reinterpret_cast<ClfOut*>(f.clf.out) + step;
-      ca.block_slot = f.clf.block_slot + step;
-      if (f.clf.force_token) ca.force_token = f.clf.force_token + step;
-      if (f.clf.ref_token) ca.ref_token = f.clf.ref_token + step;
-      const int nb = (f.vocab + 4 * CM_NT - 1) / (4 * CM_NT);
-      if ((int)blockIdx.x < nb) {
-        const int tok = classify_unit<CM_NT, true>(ca, blockIdx.x, nb, 0u);
-        if (tok >= 0 && step + 1 < n_steps) {
-          // this workgroup finished the step: it embeds the token for the next one (row 0 of the residual
-          // stream, the first panel version of the next step, the sum of squares)
-          NormArgs na{};
-          na.h = f.h; na.d = f.d; na.M = 1; na.layernorm = 0; na.eps = f.eps; na.g = f.layers[0].norm1_g;
-          na.Xout = f.xn + (size_t)(step + 1) * (2 * f.n_layers + 1) * f.xn_stride;
-          na.ssq_out = f.ssq; na.n_ssq_out = n_tiles; na.tok_emb = f.tok_emb; na.tok_stride = f.tok_stride;
-          na.vocab = f.vocab; na.max_pos = 1 << 30;
-          __syncthreads();
-          norm_row<512, true>(na, 0, tok, sm.red, 0u);
-        }
-      }
-    }
-    bar_arrive(f.bar); ++epoch;
-    if (step + 1 < n_steps) {
-      // the next step starts with layer 0's QKV projection of one token
-      GemmArgs gn = base_args(1);
-      gn.W = f.layers[0].wqkv; gn.KT = KTd; gn.grp = f.dh >> 5;
-      have_next = fwd_gemm_prefetch<C::QKV, EPI_QKV>(gn, f.d_qkv / (16 * C::QKV), pre);
-    }
-    bar_wait(f.bar, f.abort_word, epoch * per_counter);
-    if (__hip_atomic_load(f.clf.gate, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
+    c.bar_n = epoch++; fwd_classify(c);
+    // every workgroup learns the verdict of the step (the wait also orders the next step behind the embedding)
+    bar_wait(f->bar, epoch);
+    if (__hip_atomic_load(f->clf.gate, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) break;
   }
 }
 
@@ -2693,7 +2701,7 @@ bool forward_shape_ok(int d, int d_q, int d_qkv, int d_ff, int dh, int vocab, bo
 
 hipError_t launch_forward(const FwdArgs& f, bool big, bool loop, hipStream_t s) {
   if (f.M < 1 || f.M > 16 || !forward_shape_ok(f.d, f.d_q, f.d_qkv, f.d_ff, f.dh, f.vocab, big)) return hipErrorInvalidValue;
-  if (f.layers == nullptr || f.bar == nullptr || f.abort_word == nullptr) return hipErrorInvalidValue;
+  if (f.layers == nullptr || f.bar == nullptr) return hipErrorInvalidValue;
   if (loop) {
     if (f.M > 8 || f.n_steps < 1 || f.d > 4096 || f.clf.scratch == nullptr || f.clf.gate == nullptr) return hipErrorInvalidValue;
     return big ? launch_forward_cfg<1, FwdBig, true>(f, s) : launch_forward_cfg<1, FwdSmall, true>(f, s);
