@@ -28,9 +28,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE counters
-# (profiles/gemm_gateup_13b_hbm_traffic.txt; counters cannot be read from inside this process)
-GATEUP_TRAFFIC_BYTES = 280147 * 1024
+TRAFFIC_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "gemm_gateup_13b_hbm_traffic.txt")
+
+
+def gateup_traffic_bytes(panels: int):
+    """HBM bytes per launch of the dominant kernel (target gate/up GEMM) from the rocprofv3 FETCH_SIZE +
+    WRITE_SIZE counter summary under profiles/ (counters cannot be read from inside this process): the line
+    'traffic_bytes_per_launch panels=<1|2> <bytes>'.  None if the summary is missing or has no such line."""
+    try:
+        for ln in open(TRAFFIC_FILE):
+            w = ln.split()
+            if len(w) == 3 and w[0] == "traffic_bytes_per_launch" and w[1] == f"panels={panels}":
+                return int(w[2])
+    except OSError:
+        pass
+    return None
 
 
 def log(*a):
@@ -265,7 +277,10 @@ def main():
     ap.add_argument("--steps", type=int, default=None,
                     help="timed iterations (default: every prompt to its end for the full loop, 60 for the other modes)")
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--policy", default="disco", choices=["disco", "static"])
+    ap.add_argument("--policy", default="disco", choices=["disco", "disco-seeded", "static"],
+                    help="disco: DISCO halting with the classifier TRAINED before the clock starts (labelling run on a further "
+                         "prompt, disco_clf_train); disco-seeded: the untrained seeded classifier; static: fixed lookahead --gamma")
+    ap.add_argument("--train-tokens", type=int, default=200, help="labelled positions of the classifier's training run")
     ap.add_argument("--gamma", type=int, default=5)
     ap.add_argument("--tau", type=float, default=0.5)
     ap.add_argument("--sl-max", type=int, default=10)
@@ -465,6 +480,31 @@ def main():
                           "prompt_len": args.prompt_len, "n_gpus": 1, "data": "synthetic", "dtype": "bf16"}), flush=True)
         return
 
+    # DISCO's classifier is TRAINED before the clock starts (Sec. 4 "SL classifier training", App. D.1): labelling
+    # run of the draft over the target's greedy text of a FURTHER prompt under the same forcing recipe, full-batch
+    # training on the GPU, F1 on the first timed prompt's labelling run.  (With noise weights the seeded classifier
+    # never halts: DISCO would be static lookahead at the cap.)
+    clf_info = {"trained": False}
+    if args.policy == "disco" and args.temperature <= 0:
+        t0 = time.time()
+        n_lab = min(args.train_tokens, max_new, B.TRAIN_MAX_N)
+        seed_tr = 1000 + args.prompts
+        prompt_tr = W.make_prompt(seed_tr, args.prompt_len, target_shape.vocab).tolist()
+        greedy_tr = eng.greedy(prompt_tr, n_lab)
+        mask_tr = W.make_force_mask(seed_tr, n_lab, args.alpha)
+        f_tr, y_tr, _ = eng.label_run(prompt_tr, greedy_tr, {"mask": mask_tr, "tokens": greedy_tr})
+        trained = B.DiscoClf(clf, dev)
+        B.disco_clf_train(f_tr, y_tr, n_lab, trained.hidden, 400, 0.5, trained.dev, None)
+        n_val = min(n_lab, n_greedy)
+        f_va, y_va, _ = eng.label_run(prompt, greedy[:n_val], {"mask": mask[:n_val], "tokens": greedy})
+        counts = torch.zeros(4, dtype=torch.int32, device=dev)
+        B.disco_clf_eval(trained, f_va, y_va, n_val, args.tau, None, counts)
+        tp, fp, fn, tn = counts.cpu().tolist()
+        eng.clf = trained
+        clf_info = {"trained": True, "train_positions": n_lab, "train_prompt_seed": seed_tr, "epochs": 400, "lr": 0.5,
+                    "validation_f1": 2 * tp / max(2 * tp + fp + fn, 1), "validation_positions": n_val}
+        log(f"[bench] classifier trained on {n_lab} positions in {time.time() - t0:.1f} s, validation F1 {clf_info['validation_f1']:.3f}")
+
     # the timed region: a hand-rolled loop over engine iterations so that exactly K are timed
     probe_layer = target_shape.n_layers // 2
     B.disco_probe_enable(probe_layer)
@@ -481,9 +521,11 @@ def main():
     # iterations (each is bracketed by a device synchronisation), so the prompt pass and the forcing set-up
     # of the later prompts are outside the timed region.
     its, deltas, hist = [], [], {}
+    prompts_run, tokens_generated = 0, 0
     for p_idx in range(args.prompts):
         if len(its) >= n_iter:
             break
+        prompts_run += 1
         if p_idx > 0:
             prompt = W.make_prompt(1 + p_idx, args.prompt_len, target_shape.vocab).tolist()
             greedy = eng.greedy(prompt, n_greedy)
@@ -507,6 +549,7 @@ def main():
         torch.cuda.synchronize()
         gc.enable()
         its += res["iterations"]
+        tokens_generated += len(res["tokens"])
         deltas += [stamps[i + 1] - stamps[i] for i in range(first, len(stamps) - 1)]
         for k, v in res["sl_hist"].items():
             hist[k] = hist.get(k, 0) + v
@@ -523,14 +566,16 @@ def main():
     ms_per_step = 1e3 * t_timed / args.steps
     value = emitted / t_timed
 
-    ctx_mid = (args.prompt_len + args.new_tokens // 2 if multi else
-               args.prompt_len + sum(len(it["emit"]) for it in its[:args.warmup]) + emitted // 2)
+    # context of the timed iterations as they ran (KV length before the verification block)
+    ctx_mid = sum(it["ctx"] for it in timed) / len(timed)
     iter_bytes = fwd_bytes(target_shape, ctx_mid, 1 + drafted / args.steps) + (drafted / args.steps) * fwd_bytes(draft_shape, ctx_mid, 1)
     gemm_bytes = 2 * target_shape.d_ff * target_shape.d_model * 2          # gate + up matrices, bf16
     pm = [p for p in probe_ms[args.warmup:] if p > 0]
     gemm_ms = sum(pm) / len(pm)
     achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9
-
+    # which form of the dominant kernel the timed blocks ran: one activation panel (blocks of <= 8 tokens) or two
+    n_two = sum(1 for it in timed if it["sl"] + 1 > 8)
+    panels = 2 if n_two * 2 > len(timed) else 1
     out = {
         "metric": "accepted tokens/s at 13B/68M bf16 (verify+draft achieved HBM GB/s in roofline)",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -540,11 +585,16 @@ def main():
         "dtype": "bf16", "data": "synthetic",
         "config": {
             "workload": ("full DISCO loop, 13B-class target (40 layers, d 5120, 40x128 heads, SwiGLU 13824, vocab 32000) "
-                         "+ 68M-class draft (2 layers, d 768), bf16 weights and KV, batch 1, "
-                         + (f"{args.prompts} random prompts of {args.prompt_len} tokens, {args.new_tokens} new tokens each, " if multi
-                            else f"{args.prompt_len}-token random prompt, ")
+                         "+ 68M-class draft (2 layers, d 768), bf16 weights and KV, batch 1; "
+                         + (f"{prompts_run} random prompt(s) of {args.prompt_len} tokens (seeds 1..{prompts_run})"
+                            + (f", {args.new_tokens} new tokens each" if multi else "")
+                            + f": {len(its)} speculative iterations ran ({tokens_generated} tokens generated), the last "
+                            + f"{args.steps} of them timed after {args.warmup} warm-up iterations; mean KV context of the timed "
+                            + f"iterations {ctx_mid:.0f}; ")
                          + (f"greedy, forced acceptance {args.alpha}" if args.temperature <= 0 else
                             f"sampling at temperature {args.temperature} (speculative-sampling acceptance, caller-supplied uniforms)")),
+            "prompts_run": prompts_run, "iterations_run": len(its), "tokens_generated": tokens_generated,
+            "classifier": clf_info,
             "policy": policy, "target_layers": target_shape.n_layers,
             "tokens_counted": "accepted draft tokens + the target's token of each iteration",
         },
@@ -557,8 +607,10 @@ def main():
         "iteration_hbm_frac": iter_bytes / (t_timed / args.steps) / 1e9 / HBM_PEAK_GBS,
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": GATEUP_TRAFFIC_BYTES if not args.layers else None,
-            "kernel": "k_gemm<2, 8, 3, 8, 1> (target gate/up GEMM + SwiGLU at M = 9..16)",
+            "traffic": gateup_traffic_bytes(panels) if not args.layers else None,
+            "traffic_source": "profiles/gemm_gateup_13b_hbm_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch, scaled by a plain copy)",
+            "kernel": ("k_gemm<%d, 8, 3, 8, %d> (target gate/up GEMM + SwiGLU; %d of the %d timed blocks had more than 8 tokens and ran the "
+                       "two-panel form)" % (panels, 2 if panels == 2 else 3, n_two, len(timed))),
             "bytes_per_launch": gemm_bytes, "avg_launch_ms": gemm_ms, "launches_timed": len(pm),
             "timing": f"HIP events around the launch of layer {probe_layer} in every timed verification forward",
         },

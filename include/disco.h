@@ -158,7 +158,9 @@ int disco_workspace_init(const disco_model* m, void* dev_ws, size_t ws_bytes, in
  * token) from dev_tokens_in at positions kv->len .., appends their keys/values, and writes the fp32
  * logits [vocab] of the LAST fed token to dev_logits.  kv->len += n_in.
  * dev_gate (may be NULL): if *dev_gate != 0 when the kernels run, the step does nothing on the
- * device (the host still advances kv->len; roll it back with disco_kv_rollback).
+ * device (the host still advances kv->len; roll it back with disco_kv_rollback).  The word must not
+ * change while the step's launches are in flight (a step that is gated off half way leaves the
+ * workspace's ticket counters non-zero: initialise the workspace again).
  * Errors: EINVAL (null/misaligned, n_in not in [1, DISCO_MAX_BLOCK]), ECAP (KV capacity).          */
 int disco_draft_step(const disco_model* draft, disco_kv* kv, const int32_t* dev_tokens_in, int n_in,
                      float* dev_logits, void* dev_ws, size_t ws_bytes, const uint32_t* dev_gate,
@@ -241,7 +243,9 @@ typedef struct disco_loop_out {
  * On return the host's kv->len has advanced by n_in + steps - 1 (steps = static_sl if > 0, else
  * cap); after synchronising, the caller reads sl from host_out (pinned) or dev_out and calls
  * disco_kv_rollback(kv, len0 + n_in + sl - 1).
- * dev_logits: fp32 [vocab] scratch for the draft logits.  cap in [1, DISCO_MAX_BLOCK - 1].          */
+ * dev_logits: fp32 [vocab] scratch for the draft logits.  cap in [1, DISCO_MAX_BLOCK - 1].
+ * If a launch fails (DISCO_EHIP) the host's kv->len is what it was on entry; the device-side loop state
+ * (gate, counters, dev_out) is undefined and the workspace must be initialised again before its next use. */
 int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* clf,
                      const int32_t* dev_tokens_in, int n_in, int cap, int static_sl,
                      float pos_feature0, float tau, const int32_t* dev_force_tokens,
@@ -363,16 +367,6 @@ int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
  * is the faster one: see the measurements in the design notes.  Process-wide; returns the previous mode,
  * or DISCO_EINVAL.  Not to be changed while calls are in flight on other threads.                      */
 int disco_set_launch_mode(int mode);
-
-/* ---- measurement probe ------------------------------------------------------------------------- */
-
-/* Brackets, with two HIP events on the launch stream, the MLP-input GEMM (gate/up + SwiGLU, or
- * W1 + GELU) of layer `layer` in every forward or prompt pass of a model that has more than `layer` layers
- * (layer < 0 switches the probe off).  disco_probe_read_ms returns the elapsed time of the most
- * recent bracket (the caller has synchronised the stream) or a negative value if none was taken.
- * Process-wide state, for benchmarks; not thread-safe.                                             */
-int disco_probe_enable(int layer);
-float disco_probe_read_ms(void);
 
 #ifdef __cplusplus
 }

@@ -2,12 +2,14 @@
 // sequences of a draft step, a verification forward and the fused draft loop.  Every check runs on
 // the host before the first launch, so argument errors are reported without touching the GPU.
 #include "../../include/disco.h"
+#include "../../include/disco_bench.h"
 #include "disco_internal.h"
 
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -17,10 +19,20 @@ namespace {
 
 thread_local char g_err[512] = "";
 
-// measurement probe (see disco_probe_enable)
+// measurement probe (disco_bench.h)
+std::mutex g_probe_mu;
 int g_probe_layer = -1;
 bool g_probe_taken = false;
 hipEvent_t g_probe_ev[2] = {nullptr, nullptr};
+
+// Records event `which` (0 before, 1 after the bracketed launch) if the probe is set on `layer`.
+hipError_t probe_record(int layer, int which, hipStream_t s) {
+  std::lock_guard<std::mutex> lock(g_probe_mu);
+  if (layer != g_probe_layer || g_probe_ev[which] == nullptr) return hipSuccess;
+  const hipError_t e = hipEventRecord(g_probe_ev[which], s);
+  if (e == hipSuccess && which == 1) g_probe_taken = true;
+  return e;
+}
 
 int fail(int code, const char* fmt, ...) {
   va_list ap;
@@ -252,10 +264,9 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     u.M = n; u.gate = gate; u.planes = ws.gpart; u.counters = ws.gemm_counters;
     u.W = static_cast<const bf16_t*>(L.w_in); normed_input(u);
     u.n_rows = fam_a ? d.d_ff : 2 * d.d_ff; u.grp = 1; u.Xout = ws.xact; u.KT_out = d.d_ff / 32;
-    const bool probe = (l == g_probe_layer) && g_probe_ev[0] != nullptr;
-    if (probe) HIP_TRY(hipEventRecord(g_probe_ev[0], s), "probe event");
+    HIP_TRY(probe_record(l, 0, s), "probe event");
     HIP_TRY(launch_gemm(u, fam_a ? EPI_GELU : EPI_SWIGLU, s), "mlp-in launch");
-    if (probe) { HIP_TRY(hipEventRecord(g_probe_ev[1], s), "probe event"); g_probe_taken = true; }
+    HIP_TRY(probe_record(l, 1, s), "probe event");
 
     GemmArgs dn{};
     residual_update(dn, L.w_out, ws.xact, d.d_ff, split_dn, next_g);
@@ -398,10 +409,9 @@ int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     }
     DenseArgs ua = dense(L.w_in, ws.xn, xs_d, d.d_model, n_in);
     ua.rstd = fam_a ? nullptr : ws.rstd; ua.g.Xout = ws.xact; ua.xouts = xs_ff; ua.g.KT_out = d.d_ff / 32;
-    const bool probe = (l == g_probe_layer) && g_probe_ev[0] != nullptr;
-    if (probe) HIP_TRY(hipEventRecord(g_probe_ev[0], st), "probe event");
+    HIP_TRY(probe_record(l, 0, st), "probe event");
     HIP_TRY(launch_gemm_dense(ua, fam_a ? EPI_GELU : EPI_SWIGLU, st), "mlp-in launch");
-    if (probe) { HIP_TRY(hipEventRecord(g_probe_ev[1], st), "probe event"); g_probe_taken = true; }
+    HIP_TRY(probe_record(l, 1, st), "probe event");
 
     DenseArgs da = dense(L.w_out, ws.xact, xs_ff, d.d_ff, d.d_model);
     residual_update(da, next_g);
@@ -736,16 +746,17 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
     HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, ws.bar + FWD_BAR_ABORT_WORD, st), "loop finish launch");
     return DISCO_OK;
   }
+  const int len_entry = kv->len;
   for (int j = 1; j <= steps; ++j) {
     rc = forward_block(draft, kv, j == 1 ? dev_tokens_in : ws.tok_next, j == 1 ? n_in : 1, dev_logits, true, ws, ws.gate, st);
-    if (rc) return rc;
+    if (rc) { kv->len = len_entry; return rc; }   // a launch failed: the cache length is as on entry (see disco.h)
     if (sampled) {
       // the draft token of this step is drawn before the classifier may close the gate on it
       SampleArgs sa{};
       sa.logits = dev_logits; sa.ld = draft->d.vocab; sa.vocab = draft->d.vocab; sa.inv_t = 1.0f / temperature;
       sa.u = dev_u_draft + (j - 1); sa.probs = dev_draft_probs + (size_t)(j - 1) * draft->d.vocab;
       sa.tokens = ws.tok_next; sa.block_slot = dev_out->block + j; sa.gate = ws.gate;
-      HIP_TRY(launch_sample_rows(sa, 1, st), "sample launch");
+      { const hipError_t e = launch_sample_rows(sa, 1, st); if (e != hipSuccess) { kv->len = len_entry; return hip_fail(e, "sample launch"); } }
     }
     ClassifyArgs a{};
     a.logits = dev_logits; a.vocab = draft->d.vocab; a.clf_params = clf ? clf->dev_params : nullptr; a.hidden = clf ? clf->hidden : 0;
@@ -758,7 +769,7 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
     a.ref_token = dev_ref_tokens ? dev_ref_tokens + (j - 1) : nullptr;
     a.ppl_threshold = ppl_threshold;
     a.scratch = ws.clf_scratch;
-    HIP_TRY(launch_classify(a, st), "classify launch");
+    { const hipError_t e = launch_classify(a, st); if (e != hipSuccess) { kv->len = len_entry; return hip_fail(e, "classify launch"); } }
   }
   HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, nullptr, st), "loop finish launch");
   return DISCO_OK;
@@ -863,6 +874,7 @@ int disco_set_launch_mode(int mode) {
 }
 
 int disco_probe_enable(int layer) {
+  std::lock_guard<std::mutex> lock(g_probe_mu);
   g_probe_taken = false;
   if (layer < 0) { g_probe_layer = -1; return DISCO_OK; }
   for (int i = 0; i < 2; ++i)
@@ -872,6 +884,7 @@ int disco_probe_enable(int layer) {
 }
 
 float disco_probe_read_ms(void) {
+  std::lock_guard<std::mutex> lock(g_probe_mu);
   if (!g_probe_taken) return -1.0f;
   float ms = -1.0f;
   if (hipEventElapsedTime(&ms, g_probe_ev[0], g_probe_ev[1]) != hipSuccess) return -1.0f;

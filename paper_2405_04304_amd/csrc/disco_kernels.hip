@@ -155,7 +155,13 @@ __device__ __forceinline__ float2 ld_agent2(const float* p) {
   return make_float2(__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32)));
 }
 // Ticket of a split reduction: true in every thread of the workgroup that arrives last.
+// Ordering: the hand-off data moves with write-through stores and L2-bypassing loads (above), so no cache
+// maintenance is needed, and an agent-scope release / acquire on the ticket would add exactly that (an
+// L2-wide write-back and invalidate, measured at 8 - 13 us per use on MI355X).  What IS needed is that the
+// stores have completed before the ticket is taken (the explicit wait) and that the compiler keeps the
+// hand-off accesses on their side of the ticket: the two signal fences are compiler-only barriers.
 __device__ __forceinline__ bool last_arrival(int* counter, int n, int* s_flag) {
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   __builtin_amdgcn_s_waitcnt(0);                 // this wavefront's hand-off stores have completed
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -164,6 +170,7 @@ __device__ __forceinline__ bool last_arrival(int* counter, int n, int* s_flag) {
     if (t == n - 1) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
   }
   __syncthreads();
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
   return *s_flag != 0;
 }
 

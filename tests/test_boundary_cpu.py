@@ -14,8 +14,11 @@ FAKE = 0x7F0000000000  # 256-byte aligned address that is never touched
 
 
 def _declared():
-    text = open(os.path.join(ROOT, "include", "disco.h")).read()
-    return sorted(set(re.findall(r"\b(disco_[a-z_]+)\s*\(", text)))
+    names = set()
+    for h in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if h.endswith(".h"):
+            names |= set(re.findall(r"\b(disco_[a-z_]+)\s*\(", open(os.path.join(ROOT, "include", h)).read()))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():

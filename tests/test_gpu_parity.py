@@ -18,6 +18,8 @@ from paper_2405_04304_amd.engine import SpecEngine
 from oracle import disco_oracle as O
 from workloads import synth as W
 
+from loop_compare import compare_runs
+
 pytestmark = pytest.mark.gpu
 
 REL_TOL = 2e-2      # the stated bar
@@ -30,7 +32,7 @@ def dev():
     return torch.device("cuda:0")
 
 
-def check_logits(got: torch.Tensor, ref: torch.Tensor, what="", tight=REL_TIGHT):
+def check_logits(got: torch.Tensor, ref: torch.Tensor, what="", tight=REL_TIGHT, quiet=False):
     got, ref = got.detach().cpu().double(), ref.double()
     assert got.shape == ref.shape
     assert torch.isfinite(got).all(), what
@@ -41,7 +43,8 @@ def check_logits(got: torch.Tensor, ref: torch.Tensor, what="", tight=REL_TIGHT)
         worst = max(worst, err / scale)
         assert err <= REL_TOL * scale, (what, r, err, scale)
         assert err <= tight * scale, (what, "tight", r, err, scale)
-    print(f"[parity] {what}: max rel err {worst:.3e} (bar {REL_TOL}, tight {tight})", flush=True)
+    if not quiet:
+        print(f"[parity] {what}: max rel err {worst:.3e} (bar {REL_TOL}, tight {tight})", flush=True)
     return worst
 
 
@@ -209,7 +212,7 @@ def test_draft_step_small_models(shape, ctx, page, permute):
         assert gkv.len == okv.len
 
 
-@pytest.mark.parametrize("ctx", [512, 2048])
+@pytest.mark.parametrize("ctx", [512, 1024, 2048])
 def test_draft_step_68m_shape(ctx):
     shape = W.CFG1_DRAFT
     om, gm, okv, gkv, ws = setup_pair(shape, 0, kv_ctx=ctx, capacity=ctx + 32)
@@ -330,20 +333,16 @@ def test_verify_rollback_causality_and_m1_equals_draft_step():
 # ---- the loop ----------------------------------------------------------------------------------------
 
 def _compare_runs(gpu, orc, tau=None):
-    """Token streams and schedules must agree up to the first flagged position."""
-    diverged = False
-    for gi, oi in zip(gpu["iterations"], orc["iterations"]):
-        flagged = any(m < MARGIN for m in oi["target_margins"]) or any(
-            s["margin"] < MARGIN or (tau is not None and abs(s["score"] - tau) <= 1e-3) for s in oi["steps"])
-        if (gi["sl"], gi["n"], gi["block"], gi["emit"]) != (oi["sl"], oi["n"], oi["block"], oi["emit"]):
-            assert flagged, (gi, {k: oi[k] for k in ("sl", "n", "block", "emit")})
-            diverged = True
-            break
-        if "steps" in gi and gi["steps"] is not None:
+    """Token streams and schedules must agree up to the first position where the oracle flags the very
+    decision that differs (loop_compare); returns whether the runs diverged there."""
+    def feats_agree(gi, oi):
+        if gi.get("steps") is not None:
             for gs, os_ in zip(gi["steps"], oi["steps"]):
                 assert torch.allclose(torch.tensor(list(gs.feats)), os_["feats"], rtol=2e-3, atol=1e-5)
                 assert abs(gs.score - os_["score"]) < 1e-3
-    return diverged
+
+    near = (lambda s: abs(s["score"] - tau) <= 1e-3) if tau is not None else None
+    return compare_runs(gpu, orc, near, feats_agree) is not None
 
 
 def test_loop_cfg0_matches_oracle_and_greedy():
@@ -379,6 +378,47 @@ def test_loop_cfg0_matches_oracle_and_greedy():
     print(f"[parity] cfg0 loop: {n_div} of 12 policy runs diverged at a flagged position", flush=True)
 
 
+def test_cfg0_fp32_statement_against_bf16_storage():
+    """The tiny pair is stated with fp32 weights; the library stores matrices and KV entries as bf16 (the
+    reading recorded in the design notes).  The oracle on the fp32 weights with an fp32 cache, against the
+    GPU on the bf16-rounded weights with a bf16 cache, teacher-forced along the oracle's own greedy text:
+    every row of logits within the stated 2e-2 relative, every arg-max equal except where the oracle flags a
+    top-2 margin below 2e-2."""
+    shape = W.CFG0_TARGET
+    w32 = W.make_weights(shape, 0, "f32")
+    o32 = O.Model(shape, w32, kv_bf16=False)
+    prompt = W.make_prompt(1, 32, shape.vocab).tolist()
+    ref_tokens, _ = O.greedy_target(o32, prompt, 64)
+    seq = prompt + ref_tokens
+    okv = o32.new_cache(len(seq) + 1)
+    ref = torch.cat([o32.forward(seq[i:i + 16], okv) for i in range(0, len(seq), 16)])
+    d = dev()
+    gm = B.DiscoModel(shape, {k: (v.to(torch.bfloat16) if v.dim() == 2 else v) for k, v in w32.items()}, d)
+    gkv = B.DiscoKV(gm, len(seq) + 16, 16)
+    ws = gm.workspace(16, len(seq) + 16)
+    am = torch.zeros(16, dtype=torch.int32, device=d)
+    tt = torch.tensor(seq, dtype=torch.int32, device=d)
+    rows, toks = [], []
+    for i in range(0, len(seq), 16):
+        lg = torch.empty(16, shape.vocab, dtype=torch.float32, device=d)
+        B.disco_verify(gm, gkv, tt.data_ptr() + 4 * i, 16, am, lg, ws)
+        torch.cuda.synchronize()
+        rows.append(lg.cpu())
+        toks += am.tolist()
+    got = torch.cat(rows)
+    worst, n_flag = 0.0, 0
+    for r in range(len(seq)):
+        err = float((got[r].double() - ref[r].double()).abs().max())
+        scale = float(ref[r].abs().max())
+        worst = max(worst, err / scale)
+        assert err <= REL_TOL * scale, (r, err, scale)
+        if toks[r] != O.argmax_lowest(ref[r]):
+            assert O.top2_margin(ref[r]) < MARGIN, (r, toks[r])
+            n_flag += 1
+    print(f"[parity] cfg0 fp32 statement vs bf16 storage: max rel err {worst:.3e} (bar {REL_TOL}), "
+          f"{n_flag} arg-max differences, all at flagged rows", flush=True)
+
+
 def test_loop_forced_acceptance_small_pair():
     """Independent draft, 60 % forced agreement (the full-loop workload's recipe), small shapes."""
     st = W.ModelShape("B", 2, 128, 2, 64, 2, 256, 512)
@@ -402,6 +442,109 @@ def test_loop_forced_acceptance_small_pair():
             assert gpu["tokens"] == ref and gpu["sl_hist"] == orc["sl_hist"]
             assert gpu["n_draft_forwards"] == sum(it["sl"] for it in orc["iterations"])
         assert sum(it["n"] for it in gpu["iterations"]) > n_new // 4      # forcing does produce acceptance
+
+
+def _teacher_forced(st, sd, tw, dw, clf_p, prompt, n_new, pol, force=None):
+    """Every call of every iteration of the oracle's run is repeated on the GPU with the ORACLE's inputs
+    (its pending tokens, its draft tokens, its block), and every output is compared: draft logits, Eq. 2
+    features, score, token and halt bit of every draft step; the target's arg-max of every block row; the
+    acceptance result.  A flagged decision is skipped, and since the next call is fed the oracle's tokens
+    again the comparison goes on to the end of the run instead of stopping there."""
+    d = dev()
+    ot, od = O.Model(st, tw, kv_bf16=True), O.Model(sd, dw, kv_bf16=True)
+    orc = O.spec_decode(ot, od, clf_p, prompt, n_new, pol, force=force)
+    gt, gd = B.DiscoModel(st, tw, d), B.DiscoModel(sd, dw, d)
+    clf = B.DiscoClf(clf_p, d)
+    cap_ctx = len(prompt) + n_new + 32
+    kv_t, kv_d = B.DiscoKV(gt, cap_ctx, 16), B.DiscoKV(gd, cap_ctx, 16)
+    ws_t, ws_d = gt.workspace(16, cap_ctx), gd.workspace(16, cap_ctx)
+    am = torch.zeros(16, dtype=torch.int32, device=d)
+    pre = torch.tensor(prompt[:-1], dtype=torch.int32, device=d)
+    for model, kv, ws in ((gt, kv_t, ws_t), (gd, kv_d, ws_d)):
+        for i in range(0, len(prompt) - 1, 16):
+            B.disco_verify(model, kv, pre.data_ptr() + 4 * i, min(16, len(prompt) - 1 - i), am, None, ws)
+    # the oracle's draft model replays its own run so that its logits are at hand for every step
+    okv_d = od.new_cache(cap_ctx)
+    od.prefill(list(prompt[:-1]), okv_d, 64)
+    logits = torch.empty(sd.vocab, dtype=torch.float32, device=d)
+    out = B.struct_tensor(B.ClfOut, 1, d)
+    acc = B.struct_tensor(B.AcceptOut, 1, d)
+    seq = list(prompt)
+    tau = pol.get("tau")
+    n_steps = n_skipped = 0
+    for it in orc["iterations"]:
+        emitted = len(seq) - len(prompt)
+        sl, block = it["sl"], it["block"]
+        assert kv_d.len == okv_d.len
+        feed = seq[kv_d.len:]                                # pending tokens of the first draft call (1 or 2)
+        for j, stp in enumerate(it["steps"], start=1):
+            tin = torch.tensor(feed, dtype=torch.int32, device=d)
+            B.disco_draft_step(gd, kv_d, tin, len(feed), logits, ws_d)
+            ref = od.forward(feed, okv_d)[-1:]
+            ft = None
+            if force is not None and bool(force["mask"][emitted + j - 1]):
+                ft = torch.tensor([int(force["tokens"][emitted + j - 1])], dtype=torch.int32, device=d)
+            pos = float(emitted + j) if pol.get("pos_mode", "absolute") == "absolute" else float(j)
+            B.disco_classify(clf, logits, sd.vocab, pos, tau if tau is not None else 0.0, 0, out, force_token=ft)
+            torch.cuda.synchronize()
+            if ft is None:
+                check_logits(logits[None], ref, f"teacher-forced draft step, iteration ctx {it['ctx']} step {j}", quiet=True)
+            r = B.read_struct(B.ClfOut, out)
+            n_steps += 1
+            if stp["margin"] >= MARGIN:
+                assert r.token == stp["token"], (it["ctx"], j, r.token, stp["token"])
+            else:
+                n_skipped += 1
+            assert torch.allclose(torch.tensor(list(r.feats)), stp["feats"], rtol=2e-3, atol=1e-5)
+            if tau is not None and stp["score"] is not None:
+                assert abs(r.score - stp["score"]) < 1e-3
+                if abs(stp["score"] - tau) > 1e-3:
+                    assert bool(r.halt & 1) == (stp["score"] < tau)
+            feed = [stp["token"]]                            # the ORACLE's token goes in next
+        tb = torch.tensor(block, dtype=torch.int32, device=d)
+        assert kv_t.len == it["ctx"]
+        B.disco_verify(gt, kv_t, tb, sl + 1, am, None, ws_t)
+        # acceptance on the oracle's block and the oracle's arg-max: bit-exact; on the GPU's arg-max: equal
+        # rows except flagged ones
+        got = am[:sl + 1].tolist()
+        for r_, (g_, o_) in enumerate(zip(got, it["target_argmax"])):
+            if g_ != o_:
+                assert it["target_margins"][r_] < MARGIN, (it["ctx"], r_, g_, o_)
+        ta = torch.tensor(it["target_argmax"], dtype=torch.int32, device=d)
+        B.disco_accept(tb, ta, sl + 1, acc)
+        a = B.read_struct(B.AcceptOut, acc)
+        assert a.n == it["n"] and list(a.emit[:a.n + 1])[:len(it["emit"])] == it["emit"]
+        seq += it["emit"]
+        len_t = it["ctx"] + it["n"] + 1
+        B.disco_kv_rollback(kv_t, len_t)
+        if kv_d.len > len_t:                                 # the draft keeps what the target kept
+            B.disco_kv_rollback(kv_d, len_t)
+            okv_d.rollback(len_t)
+    assert seq[len(prompt):] == orc["tokens"]
+    return len(orc["iterations"]), n_steps, n_skipped
+
+
+def test_loop_teacher_forced_every_iteration_compared():
+    # the tiny LayerNorm / GELU pair with the early-exit draft, DISCO halting in both position modes
+    st, sd = W.CFG0_TARGET, W.CFG0_DRAFT
+    tw = W.make_weights(st, 0, "bf16")
+    dw = W.early_exit_draft(tw, 1)
+    clf = W.make_classifier(100)
+    prompt = W.make_prompt(1, 32, st.vocab).tolist()
+    for pol in ({"mode": "disco", "tau": 0.6, "sl_max": 8, "pos_mode": "block"},
+                {"mode": "disco", "tau": 0.55, "sl_max": 8, "pos_mode": "absolute"}, {"mode": "static", "gamma": 5}):
+        n_it, n_st, n_sk = _teacher_forced(st, sd, tw, dw, clf, prompt, 64, pol)
+        print(f"[parity] teacher-forced cfg0 {pol}: {n_it} iterations, {n_st} draft steps compared, {n_sk} tokens at flagged margins", flush=True)
+    # RMSNorm / rotary / SwiGLU pair with an independent draft and 60 % forced agreement
+    st = W.ModelShape("B", 2, 128, 2, 64, 2, 256, 512)
+    sd = W.ModelShape("B", 1, 128, 2, 64, 2, 256, 512)
+    tw, dw = W.make_weights(st, 0, "bf16", sigma=0.1), W.make_weights(sd, 10, "bf16", sigma=0.1)
+    prompt = W.make_prompt(1, 40, st.vocab).tolist()
+    ref, _ = O.greedy_target(O.Model(st, tw, kv_bf16=True), prompt, 96)
+    force = {"mask": W.make_force_mask(5, 96, 0.6), "tokens": ref}
+    n_it, n_st, n_sk = _teacher_forced(st, sd, tw, dw, clf, prompt, 96, {"mode": "disco", "tau": 0.7, "sl_max": 10, "pos_mode": "block"},
+                                       force=force)
+    print(f"[parity] teacher-forced forced-acceptance pair: {n_it} iterations, {n_st} draft steps compared, {n_sk} at flagged margins", flush=True)
 
 
 def test_loop_reference_lookahead_matches_oracle():
@@ -469,17 +612,12 @@ def test_loop_rule_based_baselines_match_oracle():
         pol = {"mode": "ppl", "threshold": thr, "sl_max": 10}
         orc = O.spec_decode(ot, od, clf, prompt, n_new, pol, force=force)
         gpu = eng.generate(prompt, n_new, pol, force=force, trace=True)
-        diverged = False
-        for gi, oi in zip(gpu["iterations"], orc["iterations"]):
-            flagged = any(m < MARGIN for m in oi["target_margins"]) or any(
-                s["margin"] < MARGIN or abs(s["ppl"] - thr) <= 1e-3 * thr for s in oi["steps"])
-            if (gi["sl"], gi["n"], gi["block"], gi["emit"]) != (oi["sl"], oi["n"], oi["block"], oi["emit"]):
-                assert flagged, (gi["sl"], gi["n"], oi["sl"], oi["n"])
-                diverged = True
-                break
+        def ppl_agree(gi, oi):
             for gs, os_ in zip(gi["steps"], oi["steps"]):
                 assert abs(gs.score - os_["ppl"]) <= 2e-3 * os_["ppl"]          # the score field carries ppl_j
-                assert bool(gs.halt & 1) == os_["halt"] or flagged
+                assert bool(gs.halt & 1) == os_["halt"]
+
+        diverged = compare_runs(gpu, orc, lambda s: abs(s["ppl"] - thr) <= 1e-3 * thr, ppl_agree) is not None
         if not diverged:
             assert gpu["tokens"] == ref and gpu["sl_hist"] == orc["sl_hist"]
         if q == 0.5:
@@ -490,7 +628,8 @@ def test_loop_rule_based_baselines_match_oracle():
 
 def test_verify_13b_full_depth_block_of_11():
     """The verification forward exactly as bench.py launches it: 40 layers of the 13B shape, block of
-    11 tokens, ctx 512, weights drawn on the device; the oracle gets the same bytes.  Then the dense prompt
+    11 tokens at ctx 512 and blocks of 1 and 8 tokens at ctx 1024 (the micro-benchmark's context), weights
+    drawn on the device; the oracle gets the same bytes.  Then the dense prompt
     pass on the same model (the weights take a while to draw: one test for both)."""
     shape = W.CFG2_TARGET
     d = dev()
@@ -500,30 +639,32 @@ def test_verify_13b_full_depth_block_of_11():
     del w
     torch.cuda.empty_cache()
     print("[parity] 13B full depth: weights on host", flush=True)
-    ctx, M = 512, 11
-    fill = W.make_kv_fill(shape, ctx, 2)
-    gkv = B.DiscoKV(gm, ctx + 32, 16)
-    gkv.fill(fill.to(d))
-    ws = gm.workspace(16, ctx + 32)
-    blk = W.make_tokens(41, M, shape.vocab).tolist()
-    tb = torch.tensor(blk, dtype=torch.int32, device=d)
-    am = torch.zeros(16, dtype=torch.int32, device=d)
-    lg = torch.empty(M, shape.vocab, dtype=torch.float32, device=d)
-    B.disco_verify(gm, gkv, tb, M, am, lg, ws)
-    torch.cuda.synchronize()
-    lg2 = torch.empty_like(lg)
-    B.disco_kv_rollback(gkv, ctx)
-    B.disco_verify(gm, gkv, tb, M, am, lg2, ws)
-    torch.cuda.synchronize()
-    assert torch.equal(lg, lg2)                      # split reductions add in a fixed order
     om = O.Model(shape, w_host, kv_bf16=True, cache_upcast=False)
-    okv = om.new_cache(ctx + 32)
-    okv.fill(fill)
-    ref = om.forward(blk, okv)
-    check_logits(lg, ref, "verify 13B x40 layers ctx 512 M 11")
-    check_argmax(am[:M].tolist(), ref, "13B full depth")
-    n_flag = sum(1 for r in range(M) if O.top2_margin(ref[r]) < MARGIN)
-    print(f"[parity] 13B full depth: {n_flag} of {M} rows flagged by the top-2 margin", flush=True)
+    am = torch.zeros(16, dtype=torch.int32, device=d)
+    # block of 11 at ctx 512, and the verification micro-benchmark's context (1024) with blocks of 1 and 8
+    for ctx, M in ((512, 11), (1024, 1), (1024, 8)):
+        fill = W.make_kv_fill(shape, ctx, 2)
+        gkv = B.DiscoKV(gm, ctx + 32, 16)
+        gkv.fill(fill.to(d))
+        ws = gm.workspace(16, ctx + 32)
+        blk = W.make_tokens(41, M, shape.vocab).tolist()
+        tb = torch.tensor(blk, dtype=torch.int32, device=d)
+        lg = torch.empty(M, shape.vocab, dtype=torch.float32, device=d)
+        B.disco_verify(gm, gkv, tb, M, am, lg, ws)
+        torch.cuda.synchronize()
+        lg2 = torch.empty_like(lg)
+        B.disco_kv_rollback(gkv, ctx)
+        B.disco_verify(gm, gkv, tb, M, am, lg2, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(lg, lg2)                      # split reductions add in a fixed order
+        okv = om.new_cache(ctx + 32)
+        okv.fill(fill)
+        ref = om.forward(blk, okv)
+        check_logits(lg, ref, f"verify 13B x40 layers ctx {ctx} M {M}")
+        check_argmax(am[:M].tolist(), ref, "13B full depth")
+        n_flag = sum(1 for r in range(M) if O.top2_margin(ref[r]) < MARGIN)
+        print(f"[parity] 13B full depth ctx {ctx}: {n_flag} of {M} rows flagged by the top-2 margin", flush=True)
+        del gkv, ws, okv
     # The prompt pass at full depth.  Against the oracle on a prompt it can walk in seconds (48 tokens, then a
     # 4-token block that reads the cache the pass wrote), and, at the size bench.py --prefill times (512
     # tokens), as a property: the dense pass and the same prompt in blocks of 16 through the forward verified
