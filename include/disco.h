@@ -337,6 +337,23 @@ int disco_clf_train(const float* dev_feats, const int32_t* dev_labels, int n, in
 int disco_clf_eval(const disco_clf* clf, const float* dev_feats, const int32_t* dev_labels, int n,
                    float tau, float* dev_scores, int32_t* dev_counts, disco_stream s);
 
+/* Training examples from a labelling run (App. D.1: at every generated position the draft predicts one token
+ * from the prompt plus the target's own continuation; the example is the Eq. 2 feature vector of the draft's
+ * distribution, labelled by whether the draft's token equals the target's).  dev_records: the n records that
+ * disco_classify wrote, one per position; dev_ref_tokens: the target's n tokens.  Writes dev_feats [n x 12],
+ * dev_labels [n] (1 = equal) and, if dev_tokens != NULL, the draft's tokens [n].                          */
+int disco_clf_examples(const disco_clf_out* dev_records, int n, const int32_t* dev_ref_tokens, float* dev_feats,
+                       int32_t* dev_labels, int32_t* dev_tokens, disco_stream s);
+
+/* ---- rule-based lookahead baseline (Sec. 2 footnote, Table 1 "dynHeur") ------------------------------ */
+
+/* The heuristic the paper compares with changes the lookahead "according to the acceptance of the previous
+ * iterations" and gives no constants; this is the usual rule: after an iteration whose `drafted` tokens were
+ * all accepted the next lookahead is lookahead + up, otherwise lookahead - down, kept inside [1, cap]; an
+ * iteration that drafted nothing leaves it unchanged.  Host arithmetic only.  Returns the next lookahead, or
+ * DISCO_EINVAL (lookahead < 1, cap < 1, accepted outside [0, drafted], negative steps).                   */
+int disco_heuristic_next(int lookahead, int drafted, int accepted, int up, int down, int cap);
+
 /* ---- prompt pass (Sec. 2: both models are given the prompt before the first iteration) ----------- */
 
 /* Processes n_tokens prompt tokens in one dense pass instead of n_tokens / DISCO_MAX_BLOCK skinny

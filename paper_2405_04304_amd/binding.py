@@ -114,6 +114,8 @@ _SIGNATURES = {
     "disco_clf_eval": (C.c_int, [C.POINTER(Clf), C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                  C.c_void_p, C.c_void_p]),
     "disco_set_launch_mode": (C.c_int, [C.c_int]),
+    "disco_clf_examples": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "disco_heuristic_next": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "disco_probe_enable": (C.c_int, [C.c_int]),
     "disco_probe_read_ms": (C.c_float, []),
 }
@@ -272,6 +274,18 @@ def disco_clf_train(feats, labels, n, hidden, epochs, lr, params, loss=None, str
 def disco_clf_eval(clf, feats, labels, n, tau, scores=None, counts=None, stream=None):
     _check(lib().disco_clf_eval(C.byref(clf.c), _ptr(feats), _ptr(labels), n, tau, _ptr(scores), _ptr(counts),
                                 _stream() if stream is None else stream))
+
+
+def disco_clf_examples(records, n, ref_tokens, feats, labels, tokens=None, stream=None):
+    _check(lib().disco_clf_examples(_ptr(records), n, _ptr(ref_tokens), _ptr(feats), _ptr(labels), _ptr(tokens),
+                                    _stream() if stream is None else stream))
+
+
+def disco_heuristic_next(lookahead: int, drafted: int, accepted: int, up: int, down: int, cap: int) -> int:
+    r = lib().disco_heuristic_next(lookahead, drafted, accepted, up, down, cap)
+    if r < 0:
+        raise DiscoError(r, last_error())
+    return r
 
 
 def disco_set_launch_mode(mode: int) -> int:

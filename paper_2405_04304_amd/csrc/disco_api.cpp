@@ -866,6 +866,26 @@ int disco_clf_eval(const disco_clf* clf, const float* dev_feats, const int32_t* 
   return DISCO_OK;
 }
 
+int disco_clf_examples(const disco_clf_out* dev_records, int n, const int32_t* dev_ref_tokens, float* dev_feats,
+                       int32_t* dev_labels, int32_t* dev_tokens, disco_stream s) {
+  if (!dev_records || !dev_ref_tokens || !dev_feats || !dev_labels) return fail(DISCO_EINVAL, "null argument");
+  if (n < 1) return fail(DISCO_EINVAL, "n must be positive");
+  if (!aligned(dev_records, 4) || !aligned(dev_ref_tokens, 4) || !aligned(dev_feats, 4) || !aligned(dev_labels, 4) || !aligned(dev_tokens, 4))
+    return fail(DISCO_EINVAL, "misaligned pointer");
+  HIP_TRY(launch_clf_examples(dev_records, n, dev_ref_tokens, dev_feats, dev_labels, dev_tokens, static_cast<hipStream_t>(s)), "examples launch");
+  return DISCO_OK;
+}
+
+int disco_heuristic_next(int lookahead, int drafted, int accepted, int up, int down, int cap) {
+  if (lookahead < 1 || drafted < 0 || accepted < 0 || accepted > drafted || up < 0 || down < 0 || cap < 1)
+    return fail(DISCO_EINVAL, "heuristic: lookahead and cap must be >= 1, 0 <= accepted <= drafted, steps >= 0");
+  if (drafted == 0) return lookahead > cap ? cap : lookahead;          // nothing was drafted: nothing was learnt
+  int next = (accepted == drafted) ? lookahead + up : lookahead - down;
+  if (next > cap) next = cap;
+  if (next < 1) next = 1;
+  return next;
+}
+
 int disco_set_launch_mode(int mode) {
   if (mode != 0 && mode != 1) return fail(DISCO_EINVAL, "launch mode %d: 0 (one launch per phase) or 1 (one launch per forward)", mode);
   const int prev = g_launch_mode;

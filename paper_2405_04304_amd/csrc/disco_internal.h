@@ -171,6 +171,8 @@ hipError_t launch_sample_rows(const SampleArgs& a, int n_rows, hipStream_t s);
 hipError_t launch_accept_sample(const AcceptSampleArgs& a, hipStream_t s);
 hipError_t launch_clf_train(const TrainArgs& a, hipStream_t s);
 hipError_t launch_clf_eval(const EvalArgs& a, hipStream_t s);
+hipError_t launch_clf_examples(const void* rec, int n, const int32_t* ref_tokens, float* feats, int32_t* labels, int32_t* tokens,
+                               hipStream_t s);
 hipError_t launch_argmax_rows(const float* logits, int M, int vocab, int32_t* out, const unsigned* abort_word, hipStream_t s);
 hipError_t launch_accept(const int32_t* block, const int32_t* argmax, int n_block,
                          const int32_t* dev_n_block, void* dev_out, void* host_out, hipStream_t s);

@@ -2097,6 +2097,26 @@ hipError_t launch_clf_eval(const EvalArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Training examples of the labelling run (App. D.1): from the classify record of every position, the twelve
+// features, the draft's token and the label "the draft's token equals the target's token there".
+__global__ __launch_bounds__(256) void k_clf_examples(const ClfOut* __restrict__ rec, int n, const int32_t* __restrict__ ref_tokens,
+                                                      float* __restrict__ feats, int32_t* __restrict__ labels, int32_t* __restrict__ tokens) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const ClfOut r = rec[i];
+#pragma unroll
+  for (int k = 0; k < 12; ++k) feats[(size_t)i * 12 + k] = r.feats[k];
+  labels[i] = (r.token == ref_tokens[i]) ? 1 : 0;
+  if (tokens != nullptr) tokens[i] = r.token;
+}
+
+hipError_t launch_clf_examples(const void* rec, int n, const int32_t* ref_tokens, float* feats, int32_t* labels, int32_t* tokens,
+                               hipStream_t s) {
+  hipLaunchKernelGGL(k_clf_examples, dim3((n + 255) / 256), dim3(256), 0, s, reinterpret_cast<const ClfOut*>(rec), n, ref_tokens,
+                     feats, labels, tokens);
+  return hipGetLastError();
+}
+
 struct LoopOut { int32_t sl; int32_t block[16]; };
 
 __global__ void k_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in, LoopOut* out) {

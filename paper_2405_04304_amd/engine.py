@@ -109,11 +109,11 @@ class SpecEngine:
                              rec.data_ptr() + sz * p,
                              force_token=(force_dev.data_ptr() + 4 * p) if force_dev is not None else None,
                              scratch=scratch)
+        feats = torch.empty(n, B.N_FEAT, dtype=torch.float32, device=self.dev)
+        labels = torch.empty(n, dtype=torch.int32, device=self.dev)
+        tokens = torch.empty(n, dtype=torch.int32, device=self.dev)
+        B.disco_clf_examples(rec, n, ref_dev, feats, labels, tokens)
         torch.cuda.synchronize(self.dev)
-        words = rec.view(torch.int32).view(n, sz // 4)
-        tokens = words[:, 0].contiguous()
-        feats = words[:, 1:13].contiguous().view(torch.float32)
-        labels = (tokens == ref_dev).to(torch.int32)
         return feats, labels, tokens
 
 
@@ -128,7 +128,7 @@ class SpecEngine:
                       "ppl": policy.get("sl_max")}[mode]
         tau = float(policy.get("tau", 0.0)) if mode == "disco" else -1.0e30
         # the two rule-based baselines the paper compares with: a lookahead that follows the last
-        # iteration's outcome (host bookkeeping), and a perplexity threshold (decided on the device)
+        # iteration's outcome (disco_heuristic_next), and a perplexity threshold (decided on the device)
         heur_sl = int(policy.get("start", 5)) if mode == "heuristic" else 0
         clf = None if mode == "ppl" else self.clf
         ppl_threshold = float(policy["threshold"]) if mode == "ppl" else 0.0
@@ -202,9 +202,8 @@ class SpecEngine:
             B.disco_kv_rollback(self.kv_t, ctx_t + n + 1)
             if self.draft is not None and self.kv_d.len > ctx_t + n + 1:
                 B.disco_kv_rollback(self.kv_d, ctx_t + n + 1)
-            if mode == "heuristic" and sl > 0:
-                heur_sl = (min(heur_sl + int(policy.get("up", 2)), cap_policy) if n == sl
-                           else max(1, heur_sl - int(policy.get("down", 1))))
+            if mode == "heuristic":
+                heur_sl = B.disco_heuristic_next(heur_sl, sl, n, int(policy.get("up", 2)), int(policy.get("down", 1)), cap_policy)
             it = {"sl": sl, "n": n, "block": block, "emit": emit, "ctx": ctx_t}
             if trace:
                 it["target_argmax"] = self.argmax[:sl + 1].tolist()

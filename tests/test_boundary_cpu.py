@@ -215,3 +215,26 @@ def test_prefill_rejects_bad_arguments_before_any_launch():
         lib.disco_kv_destroy(h)
     for h in (m, ma):
         lib.disco_model_destroy(h)
+
+
+def test_heuristic_lookahead_rule_by_hand():
+    """The acceptance-following lookahead rule (the reading of the paper's unnamed heuristic: +up after a fully
+    accepted block, -down otherwise, inside [1, cap]; nothing drafted: unchanged), on hand cases and on the
+    hand sequence that pins the oracle's heuristic policy."""
+    f = B.disco_heuristic_next
+    assert f(5, 5, 5, 2, 1, 10) == 7 and f(9, 9, 9, 2, 1, 10) == 10 and f(10, 10, 10, 2, 1, 10) == 10
+    assert f(5, 5, 4, 2, 1, 10) == 4 and f(1, 1, 0, 2, 1, 10) == 1 and f(2, 2, 0, 2, 3, 10) == 1
+    assert f(5, 0, 0, 2, 1, 10) == 5 and f(12, 0, 0, 2, 1, 10) == 10
+    # start 5: full, full, full (cap 10), reject, reject, full
+    sl, seen = 5, []
+    for drafted_all in (True, True, True, False, False, True):
+        seen.append(sl)
+        sl = f(sl, sl, sl if drafted_all else 0, 2, 1, 10)
+    assert seen == [5, 7, 9, 10, 9, 8] and sl == 10
+    for bad in ((0, 1, 1, 2, 1, 10), (5, 2, 3, 2, 1, 10), (5, 2, 1, -1, 1, 10), (5, 2, 1, 2, 1, 0)):
+        with pytest.raises(B.DiscoError) as e:
+            f(*bad)
+        assert e.value.code == B.EINVAL
+    lib = B.lib()
+    assert lib.disco_clf_examples(None, 4, FAKE, FAKE, FAKE, None, None) == B.EINVAL
+    assert lib.disco_clf_examples(FAKE, 0, FAKE, FAKE, FAKE, None, None) == B.EINVAL
