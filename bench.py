@@ -285,7 +285,7 @@ def main():
     ap.add_argument("--tau", type=float, default=0.5)
     ap.add_argument("--sl-max", type=int, default=10)
     ap.add_argument("--alpha", type=float, default=0.6)
-    ap.add_argument("--prompt-len", type=int, default=512)
+    ap.add_argument("--prompt-len", type=int, default=None, help="prompt tokens (default 512; 2048 for --config cfg3)")
     ap.add_argument("--layers", type=int, default=0, help="debug: truncate the target (invalidates the number)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--temperature", type=float, default=0.0,
@@ -307,20 +307,32 @@ def main():
                     help="instead of the loop: the draft-step micro-benchmark (68M-class shape, KV context 512 / 1024 / "
                          "2048) and the verification-block micro-benchmark (13B-class shape, context 1024, blocks of "
                          "1, 2, 4, 8, 11 tokens); one JSON line")
-    ap.add_argument("--prompts", type=int, default=16,
+    ap.add_argument("--prompts", type=int, default=None,
                     help="number of prompts (seeds 1, 2, ..): the timed iterations run through them one after another, each "
                          "prompt generating --new-tokens tokens; prompt pass and forcing set-up between prompts are untimed")
-    ap.add_argument("--new-tokens", type=int, default=256,
+    ap.add_argument("--new-tokens", type=int, default=None,
                     help="tokens generated per prompt when --prompts > 1 (then --steps 0 runs every prompt to its end)")
+    ap.add_argument("--config", default="cfg4", choices=["cfg4", "cfg3"],
+                    help="cfg4 (default, the headline): 13B-class target + 68M-class draft, 16 prompts of 512 tokens, 256 new "
+                         "tokens each; cfg3: the multi-query code-model pair (15B-class LayerNorm / GELU target with one KV head, "
+                         "12-layer draft that reuses the target's embedding table), one prompt of 2048 tokens, 128 new tokens")
     ap.add_argument("--launch-mode", type=int, default=0, choices=[0, 1],
                     help="0: one launch per phase (default); 1: one cooperative launch per forward / draft loop (disco_set_launch_mode)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run plain device copies of known size and exit (reference for HBM byte counters)")
     args = ap.parse_args()
+    cfg3 = args.config == "cfg3"
+    if args.prompt_len is None:
+        args.prompt_len = 2048 if cfg3 else 512
+    if args.prompts is None:
+        args.prompts = 1 if cfg3 else 16
+    if args.new_tokens is None:
+        args.new_tokens = 128 if cfg3 else 256
     if args.sweep or args.temperature > 0 or args.micro or args.prefill:
         args.prompts = 1                      # these modes run one prompt
+    run_to_end = args.steps is None and (args.prompts > 1 or cfg3) and not (args.sweep or args.temperature > 0)
     if args.steps is None:
-        args.steps = 0 if args.prompts > 1 else 60
+        args.steps = 0 if run_to_end else 60
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one process, one sequence); --gpus must be 1. "
               "The path shards by sequence across GPUs with no exchange: one process per GPU, each with its own prompts.", file=sys.stderr)
@@ -353,11 +365,15 @@ def main():
                                        tuple(int(x) for x in args.prefill_lengths.split(",")))), flush=True)
         return
 
-    target_shape = W.CFG2_TARGET if not args.layers else W.scaled_shape(W.CFG2_TARGET, n_layers=args.layers)
-    draft_shape = W.CFG1_DRAFT
+    full_target = W.CFG3_TARGET if cfg3 else W.CFG2_TARGET
+    target_shape = full_target if not args.layers else W.scaled_shape(full_target, n_layers=args.layers)
+    draft_shape = W.CFG3_DRAFT if cfg3 else W.CFG1_DRAFT
     t0 = time.time()
     tw = W.make_weights(target_shape, 0, "bf16", device=dev)
     dw = W.make_weights(draft_shape, 10, "bf16", device="cpu")
+    if cfg3:
+        # the draft reuses the target's token embeddings: the first d_draft columns of the target's table
+        dw["tok_emb"] = tw["tok_emb"][:, :draft_shape.d_model].cpu()
     clf = W.make_classifier(100)
     layers_sampled = target_shape.n_layers        # the oracle walks the whole target once (about 10 s of CPU work)
     tw_host = None
@@ -367,16 +383,17 @@ def main():
     gt = B.DiscoModel(target_shape, tw, dev)
     del tw
     torch.cuda.empty_cache()
-    gd = B.DiscoModel(draft_shape, dw, dev)
+    gd = (B.DiscoModel(draft_shape, dw, dev, tok_emb=gt.tok_emb, tok_emb_stride=target_shape.d_model) if cfg3
+          else B.DiscoModel(draft_shape, dw, dev))
     log(f"[bench] weights ready in {time.time() - t0:.1f} s")
 
-    n_iter = args.warmup + args.steps if not (args.prompts > 1 and args.steps == 0) else 10 ** 9
+    n_iter = args.warmup + args.steps if not run_to_end else 10 ** 9
     cap = args.gamma if args.policy == "static" else args.sl_max
     max_new = min(n_iter, 10 ** 6) * (cap + 1) + 2   # enough text for every iteration at full acceptance
     prompt = W.make_prompt(1, args.prompt_len, target_shape.vocab).tolist()
-    multi = args.prompts > 1
+    multi = args.prompts > 1 or run_to_end
     if multi:
-        assert not args.sweep and args.temperature <= 0, "--prompts > 1 runs the greedy loop only"
+        assert not args.sweep and args.temperature <= 0, "--prompts > 1 and --config cfg3 run the greedy loop only"
         max_new = args.new_tokens
     eng = SpecEngine(gt, gd, B.DiscoClf(clf, dev), max_ctx=args.prompt_len + max_new + 16, page_tokens=16)
 
@@ -554,7 +571,7 @@ def main():
         for k, v in res["sl_hist"].items():
             hist[k] = hist.get(k, 0) + v
     B.disco_probe_enable(-1)
-    if multi and args.steps == 0:             # --steps 0: every prompt to its end
+    if run_to_end or (multi and args.steps == 0):   # every prompt to its end
         n_iter = len(its)
         args.steps = n_iter - args.warmup
     assert len(its) == n_iter == len(deltas), (len(its), len(deltas), n_iter, "not enough text: raise --prompts or --new-tokens")
@@ -569,7 +586,8 @@ def main():
     # context of the timed iterations as they ran (KV length before the verification block)
     ctx_mid = sum(it["ctx"] for it in timed) / len(timed)
     iter_bytes = fwd_bytes(target_shape, ctx_mid, 1 + drafted / args.steps) + (drafted / args.steps) * fwd_bytes(draft_shape, ctx_mid, 1)
-    gemm_bytes = 2 * target_shape.d_ff * target_shape.d_model * 2          # gate + up matrices, bf16
+    # the MLP-input matrix: gate + up (SwiGLU family) or W1 (GELU family), bf16
+    gemm_bytes = (1 if target_shape.family == "A" else 2) * target_shape.d_ff * target_shape.d_model * 2
     pm = [p for p in probe_ms[args.warmup:] if p > 0]
     gemm_ms = sum(pm) / len(pm)
     achieved = gemm_bytes / (gemm_ms * 1e-3) / 1e9
@@ -577,15 +595,20 @@ def main():
     n_two = sum(1 for it in timed if it["sl"] + 1 > 8)
     panels = 2 if n_two * 2 > len(timed) else 1
     out = {
-        "metric": "accepted tokens/s at 13B/68M bf16 (verify+draft achieved HBM GB/s in roofline)",
+        "metric": ("accepted tokens/s at the 15B multi-query code-model pair, bf16 (verify+draft achieved HBM GB/s in roofline)" if cfg3 else
+                   "accepted tokens/s at 13B/68M bf16 (verify+draft achieved HBM GB/s in roofline)"),
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "ms_per_step_median": 1e3 * sorted(deltas[args.warmup:])[args.steps // 2],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {
-            "workload": ("full DISCO loop, 13B-class target (40 layers, d 5120, 40x128 heads, SwiGLU 13824, vocab 32000) "
-                         "+ 68M-class draft (2 layers, d 768), bf16 weights and KV, batch 1; "
+            "workload": (("full DISCO loop, multi-query code-model pair: 15B-class target (40 layers, d 6144, 48 query heads x 128 with "
+                          "one KV head, GELU 24576, LayerNorm, learned positions, vocab 49152) + 12-layer draft (d 768, 12 query heads "
+                          "x 64 with one KV head, GELU 3072) that reads the first 768 columns of the target's embedding table, "
+                          "bf16 weights and KV, batch 1; " if cfg3 else
+                          "full DISCO loop, 13B-class target (40 layers, d 5120, 40x128 heads, SwiGLU 13824, vocab 32000) "
+                          "+ 68M-class draft (2 layers, d 768), bf16 weights and KV, batch 1; ")
                          + (f"{prompts_run} random prompt(s) of {args.prompt_len} tokens (seeds 1..{prompts_run})"
                             + (f", {args.new_tokens} new tokens each" if multi else "")
                             + f": {len(its)} speculative iterations ran ({tokens_generated} tokens generated), the last "
@@ -607,10 +630,11 @@ def main():
         "iteration_hbm_frac": iter_bytes / (t_timed / args.steps) / 1e9 / HBM_PEAK_GBS,
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": gateup_traffic_bytes(panels) if not args.layers else None,
+            "traffic": gateup_traffic_bytes(panels) if not (args.layers or cfg3) else None,
             "traffic_source": "profiles/gemm_gateup_13b_hbm_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch, scaled by a plain copy)",
-            "kernel": ("k_gemm<%d, 8, 3, 8, %d> (target gate/up GEMM + SwiGLU; %d of the %d timed blocks had more than 8 tokens and ran the "
-                       "two-panel form)" % (panels, 2 if panels == 2 else 3, n_two, len(timed))),
+            "kernel": ("k_gemm<%d, 8, %d, 8, %d> (target %s; %d of the %d timed blocks had more than 8 tokens and ran the "
+                       "two-panel form)" % (panels, 4 if cfg3 else 3, 2 if panels == 2 else 3,
+                                            "W1 GEMM + GELU" if cfg3 else "gate/up GEMM + SwiGLU", n_two, len(timed))),
             "bytes_per_launch": gemm_bytes, "avg_launch_ms": gemm_ms, "launches_timed": len(pm),
             "timing": f"HIP events around the launch of layer {probe_layer} in every timed verification forward",
         },
