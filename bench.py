@@ -316,6 +316,8 @@ def main():
                     help="cfg4 (default, the headline): 13B-class target + 68M-class draft, 16 prompts of 512 tokens, 256 new "
                          "tokens each; cfg3: the multi-query code-model pair (15B-class LayerNorm / GELU target with one KV head, "
                          "12-layer draft that reuses the target's embedding table), one prompt of 2048 tokens, 128 new tokens")
+    ap.add_argument("--chunk", type=int, default=0,
+                    help="draft steps enqueued between two looks at the halt flag (0 = library default, >= sl-max: whole loop at once)")
     ap.add_argument("--launch-mode", type=int, default=0, choices=[0, 1],
                     help="0: one launch per phase (default); 1: one cooperative launch per forward / draft loop (disco_set_launch_mode)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -409,6 +411,7 @@ def main():
 
     policy = ({"mode": "static", "gamma": args.gamma} if args.policy == "static" else
               {"mode": "disco", "tau": args.tau, "sl_max": args.sl_max, "pos_mode": "absolute"})
+    policy["chunk"] = args.chunk
 
     # algorithmic bytes (bf16 weights once per forward, live KV once per forward, fp32 logits)
     def fwd_bytes(s, ctx, m):

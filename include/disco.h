@@ -232,6 +232,7 @@ int disco_kv_rollback(disco_kv* kv, int new_len);
 typedef struct disco_loop_out {
   int32_t sl;                         /* number of drafted tokens                                   */
   int32_t block[DISCO_MAX_BLOCK];     /* block[0] = last emitted token, block[1..sl] = draft tokens */
+  int32_t halted;                     /* 1 if a step's decision (or the forced halt of the last step) ended the drafting */
 } disco_loop_out;
 
 /* Enqueues up to `cap` (draft step, classify) pairs with no host round trip: a device flag set by
@@ -273,6 +274,14 @@ typedef struct disco_loop_opts {
   const float* dev_u_draft;
   float* dev_draft_probs;
   float ppl_threshold;
+  /* A block drafted in several calls (the host looks at `halted` between them and enqueues more steps only
+   * if drafting goes on: steps enqueued after a halt are empty launches that still cost time).
+   * block_offset = k > 0: dev_out already holds k draft tokens of this block from the calls before, on the same
+   * workspace; nothing is reset, step j writes block[k + j] and dev_steps[k + j - 1], dev_tokens_in points at
+   * block[k] (n_in = 1), pos_feature0 and the per-step option arrays are those of step k + 1.
+   * open_end != 0: the call's last step does not force a halt.  k + cap <= DISCO_MAX_BLOCK - 1.                  */
+  int32_t block_offset;
+  int32_t open_end;
 } disco_loop_opts;
 
 int disco_draft_loop_ex(const disco_model* draft, disco_kv* kv, const disco_clf* clf,
@@ -280,6 +289,51 @@ int disco_draft_loop_ex(const disco_model* draft, disco_kv* kv, const disco_clf*
                         float pos_feature0, float tau, const disco_loop_opts* opts, float* dev_logits,
                         disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
                         void* dev_ws, size_t ws_bytes, disco_stream s);
+
+/* ---- one speculative iteration driven from the host side of the library (Fig. 1) ------------- */
+
+/* Device and pinned buffers one iteration works in; the caller owns them all and may reuse them for
+ * every iteration of a sequence.                                                                     */
+typedef struct disco_iter_buffers {
+  int32_t* dev_tokens_in;          /* 2 entries: the tokens the draft model has not seen yet           */
+  float* dev_logits_draft;         /* [draft vocab] fp32                                               */
+  disco_clf_out* dev_steps;        /* DISCO_MAX_BLOCK - 1 step records                                 */
+  disco_loop_out* dev_loop_out;
+  disco_loop_out* host_loop_out;   /* pinned, device-accessible                                        */
+  int32_t* dev_argmax;             /* DISCO_MAX_BLOCK entries                                          */
+  disco_accept_out* dev_accept_out;
+  disco_accept_out* host_accept_out;  /* pinned, device-accessible                                     */
+} disco_iter_buffers;
+
+typedef struct disco_iter_result {
+  int32_t sl;                      /* draft tokens in the block                                        */
+  int32_t n;                       /* accepted ones                                                    */
+  int32_t draft_forwards;          /* draft steps whose result was used (sl, plus the leaving step of a reference run) */
+  int32_t draft_steps_enqueued;    /* steps launched, empty ones after a halt included                 */
+  int32_t block[DISCO_MAX_BLOCK];  /* block[0..sl]                                                     */
+  int32_t emit[DISCO_MAX_BLOCK];   /* emit[0..n]: accepted draft tokens, then the target's token       */
+} disco_iter_result;
+
+/* One iteration of Fig. 1: draft until the policy halts or `cap` tokens are drafted, verify the block
+ * with the target, accept greedily, drop the rejected suffix from both caches.  The call blocks: it
+ * synchronises stream s after each chunk of draft steps and after the acceptance, and returns the
+ * outcome in *host_result (ordinary host memory).
+ * host_pending[n_pending] (1 or 2 host values): the tokens of the sequence that the draft cache does not
+ * hold yet; the last one is the last emitted token, block[0].  cap = 0 (or draft == NULL): no drafting,
+ * the target decodes one token.  static_sl, pos_feature0, tau, opts (sampling excluded; block_offset and
+ * open_end are set by this call and must be 0) as in disco_draft_loop_ex.
+ * chunk: draft steps enqueued between two looks at the halt flag (0 = library default; >= cap: the whole
+ * loop at once, as disco_draft_loop does).  Steps enqueued after a halt are empty launches, a look at the
+ * flag is a stream synchronisation: the chunk trades one for the other and does not change the result.
+ * A static lookahead (static_sl > 0) is enqueued whole.
+ * On return kv_target holds len0_t + n + 1 entries and kv_draft at most as many (it lacks the tokens the
+ * next call passes as pending).  Errors as the calls it is made of; after an error the cache lengths are
+ * those of the failing call's contract and the iteration must not be resumed.                          */
+int disco_iterate(const disco_model* target, disco_kv* kv_target, void* dev_ws_target, size_t ws_target_bytes,
+                  const disco_model* draft, disco_kv* kv_draft, void* dev_ws_draft, size_t ws_draft_bytes,
+                  const disco_clf* clf, const int32_t* host_pending, int n_pending, int cap, int static_sl,
+                  int chunk, float pos_feature0, float tau, const disco_loop_opts* opts,
+                  const disco_iter_buffers* buf, disco_iter_result* host_result, disco_stream s);
 
 /* ---- sampling at temperature > 0 (Sec. 3, last sentence; App. F) ----------------------------- */
 /* The method keeps the rejection-sampling scheme of speculative decoding, which preserves the target

@@ -56,11 +56,23 @@ class AcceptOut(C.Structure):
 
 class LoopOpts(C.Structure):
     _fields_ = [("dev_force_tokens", C.c_void_p), ("dev_ref_tokens", C.c_void_p), ("temperature", C.c_float),
-                ("dev_u_draft", C.c_void_p), ("dev_draft_probs", C.c_void_p), ("ppl_threshold", C.c_float)]
+                ("dev_u_draft", C.c_void_p), ("dev_draft_probs", C.c_void_p), ("ppl_threshold", C.c_float),
+                ("block_offset", C.c_int32), ("open_end", C.c_int32)]
 
 
 class LoopOut(C.Structure):
-    _fields_ = [("sl", C.c_int32), ("block", C.c_int32 * MAX_BLOCK)]
+    _fields_ = [("sl", C.c_int32), ("block", C.c_int32 * MAX_BLOCK), ("halted", C.c_int32)]
+
+
+class IterBuffers(C.Structure):
+    _fields_ = [("dev_tokens_in", C.c_void_p), ("dev_logits_draft", C.c_void_p), ("dev_steps", C.c_void_p),
+                ("dev_loop_out", C.c_void_p), ("host_loop_out", C.c_void_p), ("dev_argmax", C.c_void_p),
+                ("dev_accept_out", C.c_void_p), ("host_accept_out", C.c_void_p)]
+
+
+class IterResult(C.Structure):
+    _fields_ = [("sl", C.c_int32), ("n", C.c_int32), ("draft_forwards", C.c_int32),
+                ("draft_steps_enqueued", C.c_int32), ("block", C.c_int32 * MAX_BLOCK), ("emit", C.c_int32 * MAX_BLOCK)]
 
 
 _SIGNATURES = {
@@ -109,6 +121,10 @@ _SIGNATURES = {
     "disco_draft_loop_ex": (C.c_int, [C.c_void_p, C.c_void_p, C.POINTER(Clf), C.c_void_p, C.c_int, C.c_int,
                                       C.c_int, C.c_float, C.c_float, C.POINTER(LoopOpts), C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "disco_iterate": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.c_size_t, C.POINTER(Clf), C.POINTER(C.c_int32), C.c_int, C.c_int, C.c_int, C.c_int,
+                                C.c_float, C.c_float, C.POINTER(LoopOpts), C.POINTER(IterBuffers),
+                                C.POINTER(IterResult), C.c_void_p]),
     "disco_clf_train": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float, C.c_void_p,
                                   C.c_void_p, C.c_void_p]),
     "disco_clf_eval": (C.c_int, [C.POINTER(Clf), C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_void_p,
@@ -232,13 +248,31 @@ def disco_draft_loop(model, kv, clf, tokens_in, n_in, cap, static_sl, pos_featur
 
 def disco_draft_loop_ex(model, kv, clf, tokens_in, n_in, cap, static_sl, pos_feature0, tau, logits, steps, out,
                         host_out, ws, force_tokens=None, ref_tokens=None, temperature=0.0, u_draft=None,
-                        draft_probs=None, ppl_threshold=0.0, stream=None):
+                        draft_probs=None, ppl_threshold=0.0, block_offset=0, open_end=0, stream=None):
     opts = LoopOpts(_ptr(force_tokens), _ptr(ref_tokens), temperature, _ptr(u_draft), _ptr(draft_probs),
-                    ppl_threshold)
+                    ppl_threshold, block_offset, open_end)
     _check(lib().disco_draft_loop_ex(model.handle, kv.handle, C.byref(clf.c) if clf is not None else None,
                                      _ptr(tokens_in), n_in, cap, static_sl, pos_feature0, tau, C.byref(opts),
                                      _ptr(logits), _ptr(steps), _ptr(out), _ptr(host_out), _ptr(ws.buf), ws.nbytes,
                                      _stream() if stream is None else stream))
+
+
+def iter_buffers(tokens_in, logits_draft, steps, loop_out, host_loop_out, argmax, accept_out, host_accept_out):
+    return IterBuffers(_ptr(tokens_in), _ptr(logits_draft), _ptr(steps), _ptr(loop_out), _ptr(host_loop_out),
+                       _ptr(argmax), _ptr(accept_out), _ptr(host_accept_out))
+
+
+def disco_iterate(target, kv_t, ws_t, draft, kv_d, ws_d, clf, pending, cap, static_sl, chunk, pos_feature0, tau,
+                  buffers, result, force_tokens=None, ref_tokens=None, ppl_threshold=0.0, stream=None):
+    """One speculative iteration in the library; `result` (IterResult) is filled on return."""
+    opts = LoopOpts(_ptr(force_tokens), _ptr(ref_tokens), 0.0, None, None, ppl_threshold, 0, 0)
+    pend = (C.c_int32 * len(pending))(*pending)
+    _check(lib().disco_iterate(target.handle, kv_t.handle, _ptr(ws_t.buf), ws_t.nbytes,
+                               draft.handle if draft is not None else None, kv_d.handle if kv_d is not None else None,
+                               _ptr(ws_d.buf) if ws_d is not None else None, ws_d.nbytes if ws_d is not None else 0,
+                               C.byref(clf.c) if clf is not None else None, pend, len(pending), cap, static_sl, chunk,
+                               pos_feature0, tau, C.byref(opts), C.byref(buffers), C.byref(result),
+                               _stream() if stream is None else stream))
 
 
 def disco_sample(logits, n_rows, vocab, ld_logits, temperature, u, probs, tokens, stream=None):

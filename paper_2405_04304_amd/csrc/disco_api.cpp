@@ -686,11 +686,16 @@ int disco_kv_rollback(disco_kv* kv, int new_len) {
 }
 
 static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in, int n_in,
-                           int cap, int static_sl, float pos_feature0, float tau, const int32_t* dev_force_tokens,
-                           const int32_t* dev_ref_tokens, float temperature, const float* dev_u_draft, float* dev_draft_probs,
-                           float ppl_threshold, float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
+                           int cap, int static_sl, float pos_feature0, float tau, const disco_loop_opts& o, float* dev_logits,
+                           disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
                            void* dev_ws, size_t ws_bytes, disco_stream s) {
+  const int32_t* dev_force_tokens = o.dev_force_tokens; const int32_t* dev_ref_tokens = o.dev_ref_tokens;
+  const float temperature = o.temperature; const float* dev_u_draft = o.dev_u_draft; float* dev_draft_probs = o.dev_draft_probs;
+  const float ppl_threshold = o.ppl_threshold;
+  const int k0 = o.block_offset;
   const bool sampled = dev_u_draft != nullptr;
+  if (k0 < 0 || k0 + cap > DISCO_MAX_BLOCK - 1) return fail(DISCO_ECAP, "block offset %d + cap %d outside [0, %d]", k0, cap, DISCO_MAX_BLOCK - 1);
+  if (k0 > 0 && (sampled || n_in != 1)) return fail(DISCO_EINVAL, "a continued block feeds one token and is not sampled");
   if (!aligned(dev_ref_tokens, 4)) return fail(DISCO_EINVAL, "misaligned pointer");
   if (sampled && (dev_ref_tokens || dev_force_tokens)) return fail(DISCO_EINVAL, "sampling excludes forced and reference tokens");
   if (!(ppl_threshold >= 0.f)) return fail(DISCO_EINVAL, "perplexity threshold must be >= 0 (0 = off)");
@@ -717,8 +722,10 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
   if (carve(draft, 2, kv->len + n_in + cap, nullptr).total > ws_bytes) return fail(DISCO_EINVAL, "workspace too small for the draft loop");
   hipStream_t st = static_cast<hipStream_t>(s);
   const Ws ws = carve(draft, 2, kv->len + n_in + cap, dev_ws);
-  HIP_TRY(launch_loop_init(ws.gate, ws.sl_count, dev_tokens_in, n_in, dev_out, st), "loop init launch");
+  if (k0 == 0) HIP_TRY(launch_loop_init(ws.gate, ws.sl_count, dev_tokens_in, n_in, dev_out, st), "loop init launch");
   const int steps = static_sl > 0 ? static_sl : cap;
+  dev_steps += k0;                                 // records and block slots of this call's steps
+  int32_t* block_base = dev_out->block + k0;
   if (draft->persist_ok && ws.bar != nullptr && !sampled && steps <= draft->loop_steps && persistent_enabled()) {
     // the whole loop in one launch: the kernel leaves at the first halting step
     const disco_model_desc& d = draft->d;
@@ -735,15 +742,15 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
     HIP_TRY(launch_norm(n0, st), "embedding launch");
     HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.bar), FWD_BAR_WORDS, st), "barrier reset launch");
     FwdArgs f = forward_args(draft, kv, ws);
-    f.M = n_in; f.pos0 = pos0; f.logits = dev_logits; f.only_last = 1; f.n_steps = steps;
+    f.M = n_in; f.pos0 = pos0; f.logits = dev_logits; f.only_last = 1; f.n_steps = steps; f.open_end = o.open_end ? 1 : 0;
     ClassifyArgs& a = f.clf;
     a.logits = dev_logits; a.vocab = d.vocab; a.clf_params = clf ? clf->dev_params : nullptr; a.hidden = clf ? clf->hidden : 0;
     a.pos_feature = pos_feature0; a.tau = static_sl > 0 ? -1.0e30f : tau; a.out = dev_steps; a.token_next = ws.tok_next;
-    a.block_slot = dev_out->block + 1; a.gate = ws.gate; a.sl_count = ws.sl_count; a.force_token = dev_force_tokens;
+    a.block_slot = block_base + 1; a.gate = ws.gate; a.sl_count = ws.sl_count; a.force_token = dev_force_tokens;
     a.ref_token = dev_ref_tokens; a.ppl_threshold = ppl_threshold; a.scratch = ws.clf_scratch;
     HIP_TRY(launch_forward(f, draft->persist_big, true, st), "draft loop launch");
     kv->len = pos0 + n_in + steps - 1;
-    HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, ws.bar + FWD_BAR_ABORT_WORD, st), "loop finish launch");
+    HIP_TRY(launch_loop_finish(ws.sl_count, ws.gate, dev_out, host_out, ws.bar + FWD_BAR_ABORT_WORD, st), "loop finish launch");
     return DISCO_OK;
   }
   const int len_entry = kv->len;
@@ -755,23 +762,23 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
       SampleArgs sa{};
       sa.logits = dev_logits; sa.ld = draft->d.vocab; sa.vocab = draft->d.vocab; sa.inv_t = 1.0f / temperature;
       sa.u = dev_u_draft + (j - 1); sa.probs = dev_draft_probs + (size_t)(j - 1) * draft->d.vocab;
-      sa.tokens = ws.tok_next; sa.block_slot = dev_out->block + j; sa.gate = ws.gate;
+      sa.tokens = ws.tok_next; sa.block_slot = block_base + j; sa.gate = ws.gate;
       { const hipError_t e = launch_sample_rows(sa, 1, st); if (e != hipSuccess) { kv->len = len_entry; return hip_fail(e, "sample launch"); } }
     }
     ClassifyArgs a{};
     a.logits = dev_logits; a.vocab = draft->d.vocab; a.clf_params = clf ? clf->dev_params : nullptr; a.hidden = clf ? clf->hidden : 0;
     a.pos_feature = pos_feature0 + (float)(j - 1);
     a.tau = static_sl > 0 ? -1.0e30f : tau;
-    a.force_halt = (j == steps) ? 1 : 0;
+    a.force_halt = (j == steps && !o.open_end) ? 1 : 0;
     a.out = dev_steps + (j - 1); a.token_next = sampled ? nullptr : ws.tok_next;
-    a.block_slot = sampled ? nullptr : dev_out->block + j; a.gate = ws.gate;
+    a.block_slot = sampled ? nullptr : block_base + j; a.gate = ws.gate;
     a.sl_count = ws.sl_count; a.force_token = dev_force_tokens ? dev_force_tokens + (j - 1) : nullptr;
     a.ref_token = dev_ref_tokens ? dev_ref_tokens + (j - 1) : nullptr;
     a.ppl_threshold = ppl_threshold;
     a.scratch = ws.clf_scratch;
     { const hipError_t e = launch_classify(a, st); if (e != hipSuccess) { kv->len = len_entry; return hip_fail(e, "classify launch"); } }
   }
-  HIP_TRY(launch_loop_finish(ws.sl_count, dev_out, host_out, nullptr, st), "loop finish launch");
+  HIP_TRY(launch_loop_finish(ws.sl_count, ws.gate, dev_out, host_out, nullptr, st), "loop finish launch");
   return DISCO_OK;
 }
 
@@ -779,8 +786,10 @@ int disco_draft_loop(const disco_model* draft, disco_kv* kv, const disco_clf* cl
                      int cap, int static_sl, float pos_feature0, float tau, const int32_t* dev_force_tokens,
                      float* dev_logits, disco_clf_out* dev_steps, disco_loop_out* dev_out, disco_loop_out* host_out,
                      void* dev_ws, size_t ws_bytes, disco_stream s) {
-  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, dev_force_tokens, nullptr, 0.f,
-                         nullptr, nullptr, 0.f, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
+  disco_loop_opts o{};
+  o.dev_force_tokens = dev_force_tokens;
+  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, o, dev_logits, dev_steps, dev_out,
+                         host_out, dev_ws, ws_bytes, s);
 }
 
 int disco_draft_loop_ex(const disco_model* draft, disco_kv* kv, const disco_clf* clf, const int32_t* dev_tokens_in, int n_in,
@@ -789,8 +798,7 @@ int disco_draft_loop_ex(const disco_model* draft, disco_kv* kv, const disco_clf*
                         size_t ws_bytes, disco_stream s) {
   disco_loop_opts o{};
   if (opts) o = *opts;
-  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, o.dev_force_tokens,
-                         o.dev_ref_tokens, o.temperature, o.dev_u_draft, o.dev_draft_probs, o.ppl_threshold, dev_logits, dev_steps, dev_out,
+  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, o, dev_logits, dev_steps, dev_out,
                          host_out, dev_ws, ws_bytes, s);
 }
 
@@ -799,8 +807,81 @@ int disco_draft_loop_sampled(const disco_model* draft, disco_kv* kv, const disco
                              const float* dev_u_draft, float* dev_draft_probs, float* dev_logits, disco_clf_out* dev_steps,
                              disco_loop_out* dev_out, disco_loop_out* host_out, void* dev_ws, size_t ws_bytes, disco_stream s) {
   if (!dev_u_draft) return fail(DISCO_EINVAL, "null argument");
-  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, nullptr, nullptr, temperature,
-                         dev_u_draft, dev_draft_probs, 0.f, dev_logits, dev_steps, dev_out, host_out, dev_ws, ws_bytes, s);
+  disco_loop_opts o{};
+  o.temperature = temperature; o.dev_u_draft = dev_u_draft; o.dev_draft_probs = dev_draft_probs;
+  return draft_loop_impl(draft, kv, clf, dev_tokens_in, n_in, cap, static_sl, pos_feature0, tau, o, dev_logits, dev_steps, dev_out,
+                         host_out, dev_ws, ws_bytes, s);
+}
+
+int disco_iterate(const disco_model* target, disco_kv* kv_t, void* dev_ws_t, size_t ws_t_bytes, const disco_model* draft,
+                  disco_kv* kv_d, void* dev_ws_d, size_t ws_d_bytes, const disco_clf* clf, const int32_t* host_pending,
+                  int n_pending, int cap, int static_sl, int chunk, float pos_feature0, float tau, const disco_loop_opts* opts,
+                  const disco_iter_buffers* buf, disco_iter_result* res, disco_stream s) {
+  if (!target || !kv_t || !buf || !res || !host_pending) return fail(DISCO_EINVAL, "null argument");
+  if (n_pending < 1 || n_pending > 2) return fail(DISCO_EINVAL, "n_pending must be 1 or 2");
+  if (cap < 0 || cap > DISCO_MAX_BLOCK - 1) return fail(DISCO_ECAP, "cap %d outside [0, %d]", cap, DISCO_MAX_BLOCK - 1);
+  if (chunk < 0) return fail(DISCO_EINVAL, "chunk must be >= 0");
+  if (!buf->dev_loop_out || !buf->host_loop_out || !buf->dev_argmax || !buf->dev_accept_out || !buf->host_accept_out)
+    return fail(DISCO_EINVAL, "null iteration buffer");
+  disco_loop_opts o{};
+  if (opts) o = *opts;
+  if (o.dev_u_draft || o.block_offset || o.open_end) return fail(DISCO_EINVAL, "sampling and block continuation are not options of an iteration");
+  if (!draft) cap = 0;
+  if (cap > 0 && (!kv_d || !dev_ws_d || !buf->dev_tokens_in || !buf->dev_logits_draft || !buf->dev_steps)) return fail(DISCO_EINVAL, "null draft-side argument");
+  hipStream_t st = static_cast<hipStream_t>(s);
+  const int len_t0 = kv_t->len;
+  int sl = 0, enq = 0, ran = 0;
+  if (cap >= 1) {
+    const int len_d0 = kv_d->len;
+    HIP_TRY(launch_put_tokens(buf->dev_tokens_in, host_pending[0], n_pending > 1 ? host_pending[1] : 0, n_pending, nullptr, nullptr, st),
+            "token upload launch");
+    const int total = static_sl > 0 ? static_sl : cap;          // steps the block may take
+    int c = chunk > 0 ? chunk : 3;                              // default: a look at the flag every third step
+    if (static_sl > 0 || c > total) c = total;
+    bool halted = false;
+    while (!halted && enq < total) {
+      const int todo = total - enq < c ? total - enq : c;
+      disco_loop_opts oc = o;
+      oc.block_offset = enq; oc.open_end = (enq + todo < total) ? 1 : 0;
+      if (oc.dev_force_tokens) oc.dev_force_tokens += enq;
+      if (oc.dev_ref_tokens) oc.dev_ref_tokens += enq;
+      const int rc = draft_loop_impl(draft, kv_d, clf, enq == 0 ? buf->dev_tokens_in : buf->dev_loop_out->block + enq, enq == 0 ? n_pending : 1,
+                                     todo, static_sl > 0 ? todo : 0, pos_feature0 + (float)enq, tau, oc, buf->dev_logits_draft,
+                                     buf->dev_steps, buf->dev_loop_out, buf->host_loop_out, dev_ws_d, ws_d_bytes, s);
+      if (rc) return rc;
+      enq += todo;
+      HIP_TRY(hipStreamSynchronize(st), "stream synchronisation");
+      sl = buf->host_loop_out->sl;
+      if (sl < 0) return fail(DISCO_EHIP, "the draft loop's grid barrier timed out");
+      halted = buf->host_loop_out->halted != 0;
+    }
+    if (sl > DISCO_MAX_BLOCK - 1) return fail(DISCO_ESTATE, "draft loop reported %d tokens", sl);
+    // with a reference the step whose token left it ran too
+    ran = sl + ((o.dev_ref_tokens && sl < cap) ? 1 : 0);
+    const int rc = disco_kv_rollback(kv_d, len_d0 + n_pending + ran - 1);
+    if (rc) return rc;
+  } else {
+    HIP_TRY(launch_put_tokens(nullptr, host_pending[0], n_pending > 1 ? host_pending[1] : 0, n_pending, buf->dev_loop_out, nullptr, st),
+            "block launch");
+  }
+  int rc = disco_verify(target, kv_t, buf->dev_loop_out->block, sl + 1, buf->dev_argmax, nullptr, dev_ws_t, ws_t_bytes, s);
+  if (rc) return rc;
+  rc = disco_accept(buf->dev_loop_out->block, buf->dev_argmax, sl + 1, nullptr, buf->dev_accept_out, buf->host_accept_out, s);
+  if (rc) return rc;
+  HIP_TRY(hipStreamSynchronize(st), "stream synchronisation");
+  const disco_accept_out& acc = *buf->host_accept_out;
+  if (acc.n < 0 || acc.n > sl) return fail(DISCO_ESTATE, "acceptance reported %d of %d tokens", acc.n, sl);
+  if (acc.emit[acc.n] < 0) return fail(DISCO_EHIP, "the verification forward's grid barrier timed out");
+  rc = disco_kv_rollback(kv_t, len_t0 + acc.n + 1);
+  if (rc) return rc;
+  if (kv_d && kv_d->len > len_t0 + acc.n + 1) { rc = disco_kv_rollback(kv_d, len_t0 + acc.n + 1); if (rc) return rc; }
+  res->sl = sl; res->n = acc.n; res->draft_forwards = ran; res->draft_steps_enqueued = enq;
+  for (int i = 0; i < DISCO_MAX_BLOCK; ++i) {
+    res->block[i] = (cap >= 1 && i <= sl) ? buf->host_loop_out->block[i] : 0;
+    res->emit[i] = i <= acc.n ? acc.emit[i] : 0;
+  }
+  if (cap < 1) res->block[0] = host_pending[n_pending - 1];
+  return DISCO_OK;
 }
 
 int disco_sample(const float* dev_logits, int n_rows, int vocab, int64_t ld_logits, float temperature, const float* dev_u,

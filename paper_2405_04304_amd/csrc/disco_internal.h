@@ -145,6 +145,7 @@ struct FwdArgs {
   // draft loop: n_steps (forward, classify) pairs in one launch; step 0 feeds M tokens, later steps one;
   // clf holds the first step's classify arguments (pos_feature, out, block_slot, force_token, ref_token advance per step)
   int n_steps;
+  int open_end;                      // the last step does not force a halt (the block goes on in a further launch)
   ClassifyArgs clf;
 };
 
@@ -182,7 +183,8 @@ hipError_t launch_zero(int* p, int n, hipStream_t s);
 hipError_t launch_rope_fill(float* tab, int n_pos, int dh, float base, hipStream_t s);
 hipError_t launch_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in,
                             void* dev_loop_out, hipStream_t s);
-hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void* host_loop_out,
+hipError_t launch_put_tokens(int32_t* tokens, int t0, int t1, int n, void* dev_loop_out, void* host_loop_out, hipStream_t s);
+hipError_t launch_loop_finish(const int32_t* sl_count, const uint32_t* gate, void* dev_loop_out, void* host_loop_out,
                               const unsigned* abort_word, hipStream_t s);
 
 constexpr int GEMM_MAX_SPLIT = 8;

@@ -2117,19 +2117,20 @@ hipError_t launch_clf_examples(const void* rec, int n, const int32_t* ref_tokens
   return hipGetLastError();
 }
 
-struct LoopOut { int32_t sl; int32_t block[16]; };
+struct LoopOut { int32_t sl; int32_t block[16]; int32_t halted; };   // mirrors disco_loop_out
 
 __global__ void k_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* tokens_in, int n_in, LoopOut* out) {
   if (threadIdx.x != 0) return;
   *gate = 0u; sl_count[0] = 0; sl_count[1] = 0;     // second word: the perplexity rule's running sum (0.0f)
-  out->sl = 0;
+  out->sl = 0; out->halted = 0;
   out->block[0] = tokens_in[n_in - 1];
   for (int i = 1; i < 16; ++i) out->block[i] = 0;
 }
 
-__global__ void k_loop_finish(const int32_t* sl_count, LoopOut* out, LoopOut* host_out, const unsigned* abort_word) {
+__global__ void k_loop_finish(const int32_t* sl_count, const uint32_t* gate, LoopOut* out, LoopOut* host_out, const unsigned* abort_word) {
   if (threadIdx.x != 0) return;
   out->sl = (abort_word != nullptr && *abort_word != 0u) ? -1 : *sl_count;
+  out->halted = (int32_t)*gate;
   if (host_out) { *host_out = *out; __threadfence_system(); }
 }
 
@@ -2173,9 +2174,27 @@ hipError_t launch_loop_init(uint32_t* gate, int32_t* sl_count, const int32_t* to
   return hipGetLastError();
 }
 
-hipError_t launch_loop_finish(const int32_t* sl_count, void* dev_loop_out, void* host_loop_out, const unsigned* abort_word,
-                              hipStream_t s) {
-  hipLaunchKernelGGL(k_loop_finish, dim3(1), dim3(64), 0, s, sl_count, reinterpret_cast<LoopOut*>(dev_loop_out),
+// Host values into device slots: the pending tokens of an iteration (n <= 2) and, for an iteration that
+// drafts nothing, the one-token block.
+__global__ void k_put_tokens(int32_t* tokens, int t0, int t1, int n, LoopOut* out, LoopOut* host_out) {
+  if (threadIdx.x != 0) return;
+  if (tokens) { tokens[0] = t0; if (n > 1) tokens[1] = t1; }
+  if (out) {
+    out->sl = 0; out->halted = 1; out->block[0] = n > 1 ? t1 : t0;
+    for (int i = 1; i < 16; ++i) out->block[i] = 0;
+    if (host_out) *host_out = *out;
+  }
+}
+
+hipError_t launch_put_tokens(int32_t* tokens, int t0, int t1, int n, void* dev_loop_out, void* host_loop_out, hipStream_t s) {
+  hipLaunchKernelGGL(k_put_tokens, dim3(1), dim3(64), 0, s, tokens, t0, t1, n, reinterpret_cast<LoopOut*>(dev_loop_out),
+                     reinterpret_cast<LoopOut*>(host_loop_out));
+  return hipGetLastError();
+}
+
+hipError_t launch_loop_finish(const int32_t* sl_count, const uint32_t* gate, void* dev_loop_out, void* host_loop_out,
+                              const unsigned* abort_word, hipStream_t s) {
+  hipLaunchKernelGGL(k_loop_finish, dim3(1), dim3(64), 0, s, sl_count, gate, reinterpret_cast<LoopOut*>(dev_loop_out),
                      reinterpret_cast<LoopOut*>(host_loop_out), abort_word);
   return hipGetLastError();
 }
@@ -2632,7 +2651,7 @@ __device__ FWD_PHASE_FN void fwd_classify(const FwdCtx c) {
   ca.tau = f->clf.tau; ca.token_next = f->clf.token_next; ca.gate = f->clf.gate; ca.sl_count = f->clf.sl_count;
   ca.ppl_threshold = f->clf.ppl_threshold; ca.scratch = f->clf.scratch;
   ca.pos_feature = f->clf.pos_feature + (float)c.step;
-  ca.force_halt = (c.step + 1 == f->n_steps) ? 1 : 0;
+  ca.force_halt = (c.step + 1 == f->n_steps && !f->open_end) ? 1 : 0;
   ca.out = reinterpret_cast<ClfOut*>(f->clf.out) + c.step;
   ca.block_slot = f->clf.block_slot + c.step;
   ca.force_token = f->clf.force_token ? f->clf.force_token + c.step : nullptr;

@@ -150,58 +150,41 @@ class SpecEngine:
         n_prompt = len(seq)
         iters: List[Dict] = []
         n_draft_fwd = n_target_fwd = 0
-        loop_block_ptr = self.loop_dev.data_ptr() + 4
+        bufs = B.iter_buffers(self.tok_in, self.logits_d if self.draft is not None else None, self.steps, self.loop_dev,
+                              self.loop_host, self.argmax, self.acc_dev, self.acc_host)
+        res = B.IterResult()
+        chunk = int(policy.get("chunk", 0))
+        kv_d, ws_d = (self.kv_d, self.ws_d) if self.draft is not None else (None, None)
         while len(seq) - n_prompt < max_new:
             if max_iterations is not None and len(iters) >= max_iterations:
                 break
             emitted = len(seq) - n_prompt
             remaining = max_new - emitted
-            cap = min(cap_policy, remaining - 1)
+            cap = min(cap_policy, remaining - 1) if self.draft is not None else 0
             if mode == "heuristic":
                 cap = min(cap, heur_sl)
+            cap = max(cap, 0)
             ctx_t = self.kv_t.len
-            steps_rec = None
-            if cap >= 1:
-                len_d0 = self.kv_d.len
-                pending = seq[len_d0:]
-                assert 1 <= len(pending) <= 2
-                self._put_tokens(pending)
-                B.disco_draft_loop_ex(self.draft, self.kv_d, clf, self.tok_in,
-                                      len(pending), cap, cap if mode in ("static", "heuristic") else 0,
-                                      float(emitted + 1) if pos_mode == "absolute" else 1.0, tau,
-                                      self.logits_d, self.steps, self.loop_dev, self.loop_host, self.ws_d,
-                                      force_tokens=(force_dev.data_ptr() + 4 * emitted) if force_dev is not None else None,
-                                      ref_tokens=(ref_dev.data_ptr() + 4 * emitted) if ref_dev is not None else None,
-                                      ppl_threshold=ppl_threshold)
-                torch.cuda.current_stream().synchronize()
-                lo = B.LoopOut.from_buffer_copy(self.loop_host.numpy().tobytes())
-                sl = lo.sl
-                block = list(lo.block[:sl + 1])
-                # draft steps that ran: with a reference, the step whose token left it ran too
-                ran = sl + (1 if (mode == "oracle" and sl < cap) else 0)
-                B.disco_kv_rollback(self.kv_d, len_d0 + len(pending) + ran - 1)
-                n_draft_fwd += ran
-                if trace:
-                    raw = self.steps.cpu().numpy().tobytes()
-                    sz = C.sizeof(B.ClfOut)
-                    steps_rec = [B.ClfOut.from_buffer_copy(raw[i * sz:(i + 1) * sz]) for i in range(ran)]
-            else:
-                sl, block = 0, [seq[-1]]
-                lo = B.LoopOut()
-                lo.sl = 0
-                lo.block[0] = seq[-1]
-                self.loop_dev.copy_(torch.frombuffer(bytearray(bytes(lo)), dtype=torch.uint8))
-            B.disco_verify(self.target, self.kv_t, loop_block_ptr, sl + 1, self.argmax, None, self.ws_t)
-            B.disco_accept(loop_block_ptr, self.argmax, sl + 1, self.acc_dev, self.acc_host)
-            torch.cuda.current_stream().synchronize()
+            pending = seq[self.kv_d.len:] if cap >= 1 else seq[-1:]
+            assert 1 <= len(pending) <= 2
+            # the whole iteration (chunks of draft steps, verification, acceptance, both rollbacks) runs in the library
+            B.disco_iterate(self.target, self.kv_t, self.ws_t, self.draft, kv_d, ws_d, clf, pending, cap,
+                            cap if mode in ("static", "heuristic") else 0, chunk,
+                            float(emitted + 1) if pos_mode == "absolute" else 1.0, tau, bufs, res,
+                            force_tokens=(force_dev.data_ptr() + 4 * emitted) if force_dev is not None else None,
+                            ref_tokens=(ref_dev.data_ptr() + 4 * emitted) if ref_dev is not None else None,
+                            ppl_threshold=ppl_threshold)
+            sl, n = res.sl, res.n
+            block = list(res.block[:sl + 1])
+            n_draft_fwd += res.draft_forwards
             n_target_fwd += 1
-            acc = B.AcceptOut.from_buffer_copy(self.acc_host.numpy().tobytes())
-            n = acc.n
-            emit = list(acc.emit[:n + 1])[:remaining]
+            steps_rec = None
+            if trace and cap >= 1:
+                raw = self.steps.cpu().numpy().tobytes()
+                sz = C.sizeof(B.ClfOut)
+                steps_rec = [B.ClfOut.from_buffer_copy(raw[i * sz:(i + 1) * sz]) for i in range(res.draft_forwards)]
+            emit = list(res.emit[:n + 1])[:remaining]
             seq.extend(emit)
-            B.disco_kv_rollback(self.kv_t, ctx_t + n + 1)
-            if self.draft is not None and self.kv_d.len > ctx_t + n + 1:
-                B.disco_kv_rollback(self.kv_d, ctx_t + n + 1)
             if mode == "heuristic":
                 heur_sl = B.disco_heuristic_next(heur_sl, sl, n, int(policy.get("up", 2)), int(policy.get("down", 1)), cap_policy)
             it = {"sl": sl, "n": n, "block": block, "emit": emit, "ctx": ctx_t}
