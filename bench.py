@@ -191,7 +191,17 @@ def micro(B, W, dev, reps):
     return out
 
 
-def prefill_bench(B, W, dev, reps, models=("68m_draft", "13b_target"), lengths=(512, 1024, 2048)):
+def dense_kernel_args(epi, n_tiles, n_groups, bf16_act):
+    """Template arguments the library's launch rule picks for a dense GEMM of n_tiles 16-row tiles over n_groups
+    token groups: <epilogue, k-tiles in flight, row tiles per wavefront, bf16 activations>."""
+    ncb = -(-n_groups // (8 if bf16_act else 4))
+    if bf16_act and n_tiles % 8 == 0 and -(-n_tiles // 32) * ncb >= 256:
+        return "%d, 3, 8, true" % epi
+    rt = 4 if -(-n_tiles // 16) * ncb >= 256 else 2
+    return "%d, %d, %d, %s" % (epi, 4 if bf16_act else 5, rt, "true" if bf16_act else "false")
+
+
+def prefill_bench(B, W, dev, reps, models=("68m_draft", "13b_target"), lengths=(512, 1024, 2048), bf16_act=False):
     """Prompt pass of both models at 512 / 1024 / 2048 tokens: the dense pass against the same prompt fed
     in blocks of 16 through the verification forward.  Rates are ALGORITHMIC flops (2 per weight and
     token in the projections and the LM head of the last token, 4 n ctx d_q / 2 causal attention flops
@@ -205,7 +215,9 @@ def prefill_bench(B, W, dev, reps, models=("68m_draft", "13b_target"), lengths=(
         attn = s.n_layers * 4 * (n * (n + 1) // 2) * s.n_heads * s.d_head
         return 2 * mats * n + attn + 2 * s.vocab * s.d_model
 
+    flags = B.PREFILL_BF16_ACTIVATIONS if bf16_act else 0
     out = {"prefill": True, "reps": reps, "n_gpus": 1, "dtype": "bf16", "data": "synthetic",
+           "activations": "bf16 (hi panel only)" if bf16_act else "fp32 grade (bf16 hi + lo panels)",
            "mfma_peak_tflops": MFMA_PEAK_TFLOPS, "rows": []}
     for name, shape, on_dev in (("68m_draft", W.CFG1_DRAFT, False), ("13b_target", W.CFG2_TARGET, True),
                                 ("mqa_draft", W.CFG3_DRAFT, False), ("15b_mqa_target", W.CFG3_TARGET, True)):
@@ -222,7 +234,7 @@ def prefill_bench(B, W, dev, reps, models=("68m_draft", "13b_target"), lengths=(
 
             def dense():
                 B.disco_kv_rollback(kv, 0)
-                B.disco_prefill(gm, kv, toks, n, None, pws)
+                B.disco_prefill(gm, kv, toks, n, None, pws, flags=flags)
 
             def blocks():
                 B.disco_kv_rollback(kv, 0)
@@ -257,11 +269,11 @@ def prefill_bench(B, W, dev, reps, models=("68m_draft", "13b_target"), lengths=(
                    "tokens_per_s": n / res["dense"],
                    "roofline": {"bound": "mfma", "achieved": gemm_flops / probe_ms / 1e9, "peak": MFMA_PEAK_TFLOPS,
                                 "unit": "TFLOP/s", "frac": gemm_flops / probe_ms / 1e9 / MFMA_PEAK_TFLOPS, "traffic": None,
-                                "kernel": "k_gemm_dense<%d, 5, %d> (MLP-input GEMM of the prompt pass)" % (
-                                    4 if shape.family == "A" else 3,
-                                    4 if -(-(rows_in // 16) // 16) * -(-((n + 15) // 16) // 4) >= 256 else 2),
+                                "kernel": "k_gemm_dense<%s> (MLP-input GEMM of the prompt pass)" % dense_kernel_args(
+                                    4 if shape.family == "A" else 3, rows_in // 16, (n + 15) // 16, bf16_act),
                                 "flops_per_launch": gemm_flops, "avg_launch_ms": probe_ms, "launches_timed": len(probe),
-                                "note": "algorithmic flops; the bf16 hi + lo activation panels make the matrix unit do twice as many"}}
+                                "note": ("algorithmic flops = matrix-unit flops (bf16 activations)" if bf16_act else
+                                         "algorithmic flops; the bf16 hi + lo activation panels make the matrix unit do twice as many")}}
             out["rows"].append(row)
             log(f"[bench] prompt pass {name} n {n}: dense {row['dense_ms']:.2f} ms ({row['dense_tflops']:.0f} TFLOP/s), "
                 f"blocks of 16 {row['blocks_ms']:.2f} ms, x{row['speedup']:.2f}")
@@ -302,6 +314,8 @@ def main():
                          "(--steps = repetitions of the dense pass)")
     ap.add_argument("--prefill-models", default="68m_draft,13b_target",
                     help="models of --prefill, comma separated, of 68m_draft, 13b_target, mqa_draft, 15b_mqa_target")
+    ap.add_argument("--prefill-bf16-act", action="store_true",
+                    help="--prefill with DISCO_PREFILL_BF16_ACTIVATIONS (activations rounded to bf16: half the matrix work)")
     ap.add_argument("--prefill-lengths", default="512,1024,2048", help="prompt lengths of --prefill (comma separated)")
     ap.add_argument("--micro", action="store_true",
                     help="instead of the loop: the draft-step micro-benchmark (68M-class shape, KV context 512 / 1024 / "
@@ -364,7 +378,7 @@ def main():
         return
     if args.prefill:
         print(json.dumps(prefill_bench(B, W, dev, args.steps, tuple(args.prefill_models.split(",")),
-                                       tuple(int(x) for x in args.prefill_lengths.split(",")))), flush=True)
+                                       tuple(int(x) for x in args.prefill_lengths.split(",")), args.prefill_bf16_act)), flush=True)
         return
 
     full_target = W.CFG3_TARGET if cfg3 else W.CFG2_TARGET

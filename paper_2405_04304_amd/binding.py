@@ -93,6 +93,8 @@ _SIGNATURES = {
     "disco_prefill_workspace_bytes": (C.c_size_t, [C.c_void_p, C.c_int, C.c_int]),
     "disco_prefill": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_size_t,
                                 C.c_void_p]),
+    "disco_prefill_ex": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_uint, C.c_void_p,
+                                   C.c_size_t, C.c_void_p]),
     "disco_draft_step": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
                                    C.c_size_t, C.c_void_p, C.c_void_p]),
     "disco_classify": (C.c_int, [C.POINTER(Clf), C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_int,
@@ -223,7 +225,14 @@ def disco_verify(model, kv, block, n_block, argmax, logits, ws, stream=None):
                               _ptr(ws.buf), ws.nbytes, _stream() if stream is None else stream))
 
 
-def disco_prefill(model, kv, tokens, n_tokens, logits_last, ws, stream=None):
+PREFILL_BF16_ACTIVATIONS = 1
+
+
+def disco_prefill(model, kv, tokens, n_tokens, logits_last, ws, stream=None, flags=0):
+    if flags:
+        _check(lib().disco_prefill_ex(model.handle, kv.handle, _ptr(tokens), n_tokens, _ptr(logits_last), flags,
+                                      _ptr(ws.buf), ws.nbytes, _stream() if stream is None else stream))
+        return
     _check(lib().disco_prefill(model.handle, kv.handle, _ptr(tokens), n_tokens, _ptr(logits_last), _ptr(ws.buf),
                                ws.nbytes, _stream() if stream is None else stream))
 

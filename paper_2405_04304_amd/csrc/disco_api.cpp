@@ -327,7 +327,14 @@ size_t disco_prefill_workspace_bytes(const disco_model* m, int n_tokens, int max
 
 int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens, int n_tokens, float* dev_logits_last,
                   void* dev_ws, size_t ws_bytes, disco_stream s) {
+  return disco_prefill_ex(m, kv, dev_tokens, n_tokens, dev_logits_last, 0u, dev_ws, ws_bytes, s);
+}
+
+int disco_prefill_ex(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens, int n_tokens, float* dev_logits_last,
+                     unsigned flags, void* dev_ws, size_t ws_bytes, disco_stream s) {
   if (!m || !kv || !dev_tokens || !dev_ws) return fail(DISCO_EINVAL, "null argument");
+  if (flags & ~(unsigned)DISCO_PREFILL_BF16_ACTIVATIONS) return fail(DISCO_EINVAL, "unknown prompt-pass flag 0x%x", flags);
+  const int hi_only = (flags & DISCO_PREFILL_BF16_ACTIVATIONS) ? 1 : 0;
   if (kv->model != m) return fail(DISCO_ESTATE, "KV cache belongs to another model");
   const disco_model_desc& d = m->d;
   const bool fam_a = d.family == DISCO_FAMILY_A;
@@ -366,7 +373,7 @@ int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   auto dense = [&](const void* w, const bf16_t* x, size_t xs, int k, int n_rows) {
     DenseArgs a{};
     a.g.M = 16; a.g.W = static_cast<const bf16_t*>(w); a.g.X = x; a.g.KT = k / 32; a.g.n_rows = n_rows; a.g.grp = 1;
-    a.g.only_row = -1; a.n_groups = G; a.xs = xs;
+    a.g.only_row = -1; a.n_groups = G; a.xs = xs; a.hi_only = hi_only;
     return a;
   };
   auto residual_update = [&](DenseArgs& a, const float* next_gain) {

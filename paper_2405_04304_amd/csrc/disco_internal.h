@@ -54,6 +54,7 @@ struct DenseArgs {
   size_t hs, qs;        // floats between the groups' residual rows / query rows
   size_t ssq_outs;      // floats between the groups' sum-of-squares slots
   const float* rstd;    // [group][16]: 1 / rms of the input rows (epilogues that read a normalised input)
+  int hi_only;          // bf16 activations: the lo panels are not read
   int tile_r, tile_t;   // set by the launcher: row blocks x token blocks walked by consecutive workgroups of an XCD
 };
 

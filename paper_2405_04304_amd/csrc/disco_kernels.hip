@@ -2272,12 +2272,15 @@ __device__ __forceinline__ void dense_epilogue(const DenseArgs& d, const int cb,
 // them to the other three, and the registers freed that way hold NB k-tiles of loads in flight.  One
 // workgroup barrier per k-tile; every wavefront runs the same trip count (idle ones compute on clamped
 // rows and store nothing).
-template <int EPI, int NB, int RT>
+// HI: bf16 activations.  Only the hi panels are read, and the LDS slots and matrix instructions that the lo
+// panels took serve four more token groups instead: a workgroup then covers 8 token groups, the work per weight
+// tile is unchanged and the weights are fetched half as often.
+template <int EPI, int NB, int RT, bool HI>
 __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
-  constexpr int CG = 4, NWV = 4, NS = NB + 1;
+  constexpr int CG = HI ? 8 : 4, NWV = 4, NS = NB + 1;
   constexpr bool PAIR = EpiTraits<EPI>::pair;
   constexpr int UNITS = PAIR ? RT / 2 : RT;
-  __shared__ u32x4 bs[2][CG * 2][64];
+  __shared__ u32x4 bs[2][8][64];
   const GemmArgs& a = d.g;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int n_tiles = a.n_rows >> 4;
@@ -2310,7 +2313,11 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
   const u32x4* Wp[RT];
 #pragma unroll
   for (int r = 0; r < RT; ++r) Wp[r] = reinterpret_cast<const u32x4*>(a.W) + (size_t)rt[r] * KT * 64 + lane;
-  const u32x4* Xw = reinterpret_cast<const u32x4*>(a.X + (size_t)min(cb * CG + w, d.n_groups - 1) * d.xs) + lane;
+  // the two activation tiles this wavefront hands to the workgroup per k-tile: hi and lo panel of token group w, or
+  // (HI) the hi panels of token groups 2w and 2w + 1
+  const u32x4* Xw = reinterpret_cast<const u32x4*>(a.X + (size_t)min(cb * CG + (HI ? 2 * w : w), d.n_groups - 1) * d.xs) + lane;
+  const u32x4* Xw1 = HI ? reinterpret_cast<const u32x4*>(a.X + (size_t)min(cb * CG + 2 * w + 1, d.n_groups - 1) * d.xs) + lane
+                        : Xw + (size_t)a.KT * 64;
   f32x4 acc[RT][CG];
 #pragma unroll
   for (int r = 0; r < RT; ++r)
@@ -2322,7 +2329,7 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
     const size_t t = (size_t)(kt < KT ? kt : KT - 1) * 64;
 #pragma unroll
     for (int r = 0; r < RT; ++r) Ad[r] = Wp[r][t];
-    Bd[0] = Xw[t]; Bd[1] = Xw[(size_t)KT * 64 + t];
+    Bd[0] = Xw[t]; Bd[1] = Xw1[t];
   };
   static_assert(NB >= 2, "the slot refilled in an iteration must not be the one it hands to LDS");
 #pragma unroll
@@ -2338,19 +2345,27 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
       const int kt = kt0 + i;
       if (kt < KT) {                              // uniform over the workgroup
         gload(A[(i + NB) % NS], Bw[(i + NB) % NS], kt + NB);
-        u32x4 Bf[CG * 2];
+        u32x4 Bf[8];
 #pragma unroll
-        for (int t = 0; t < CG * 2; ++t) Bf[t] = bs[kt & 1][t][lane];
+        for (int t = 0; t < 8; ++t) Bf[t] = bs[kt & 1][t][lane];
         bs[(kt + 1) & 1][2 * w][lane] = Bw[(i + 1) % NS][0];
         bs[(kt + 1) & 1][2 * w + 1][lane] = Bw[(i + 1) % NS][1];
         // hi panels of all accumulators, then lo panels: no instruction reads the result of the one before it
-#pragma unroll
-        for (int p = 0; p < 2; ++p)
+        if constexpr (HI) {
 #pragma unroll
           for (int r = 0; r < RT; ++r)
 #pragma unroll
-            for (int c = 0; c < CG; ++c)
-              acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(Bf[2 * c + p]), acc[r][c], 0, 0, 0);
+            for (int c = 0; c < 8; ++c)
+              acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(Bf[c]), acc[r][c], 0, 0, 0);
+        } else {
+#pragma unroll
+          for (int p = 0; p < 2; ++p)
+#pragma unroll
+            for (int r = 0; r < RT; ++r)
+#pragma unroll
+              for (int c = 0; c < CG; ++c)
+                acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(Bf[2 * c + p]), acc[r][c], 0, 0, 0);
+        }
         __syncthreads();
       }
     }
@@ -2358,13 +2373,16 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
   if (live) dense_epilogue<EPI, RT, CG>(d, cb, rt, acc);
 }
 
-template <int EPI>
+template <int EPI, bool HI>
 static hipError_t launch_gemm_dense_e(const DenseArgs& d, hipStream_t s) {
-  constexpr int NB = 5;                           // k-tiles of loads in flight per wavefront (measured best of 3..5)
-  const int n_tiles = d.g.n_rows / 16, ncb = (d.n_groups + 3) / 4;
-  // narrower row blocks when 64-row wavefront tiles would leave compute units without a workgroup
+  constexpr int NB = HI ? 4 : 5;                  // k-tiles of loads in flight per wavefront (measured best of 3..5 with two panels)
+  constexpr int CG = HI ? 8 : 4;
+  const int n_tiles = d.g.n_rows / 16, ncb = (d.n_groups + CG - 1) / CG;
+  // 128-row wavefront tiles (bf16 activations only: 128 x 128 accumulators fill the accumulation registers) where they
+  // still give every compute unit a workgroup; narrower row blocks when 64-row tiles would not
+  const bool wide8 = HI && (n_tiles % 8) == 0 && (long long)((n_tiles + 31) / 32) * ncb >= 256;
   const bool wide = (long long)((n_tiles + 15) / 16) * ncb >= 256;
-  const int nrb = wide ? (n_tiles + 15) / 16 : (n_tiles + 7) / 8;
+  const int nrb = wide8 ? (n_tiles + 31) / 32 : (wide ? (n_tiles + 15) / 16 : (n_tiles + 7) / 8);
   DenseArgs a = d;
   // about 64 workgroups run on an XCD at once: 8 x 8 for long prompts, 16 x 4 measured better at 8 token blocks
   a.tile_t = ncb >= 16 ? 8 : (ncb < 4 ? ncb : 4);
@@ -2373,9 +2391,17 @@ static hipError_t launch_gemm_dense_e(const DenseArgs& d, hipStream_t s) {
   const long long blocks = 8LL * ((nrbl + a.tile_r - 1) / a.tile_r) * ((ncb + a.tile_t - 1) / a.tile_t) * a.tile_r * a.tile_t;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
   const dim3 grid((unsigned)blocks);
-  if (wide) hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 4>), grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 2>), grid, dim3(256), 0, s, a);
+  if constexpr (HI) {
+    if (wide8) { hipLaunchKernelGGL((k_gemm_dense<EPI, 3, 8, true>), grid, dim3(256), 0, s, a); return hipGetLastError(); }
+  }
+  if (wide) hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 4, HI>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 2, HI>), grid, dim3(256), 0, s, a);
   return hipGetLastError();
+}
+
+template <int EPI>
+static hipError_t launch_gemm_dense_h(const DenseArgs& d, hipStream_t s) {
+  return d.hi_only ? launch_gemm_dense_e<EPI, true>(d, s) : launch_gemm_dense_e<EPI, false>(d, s);
 }
 
 hipError_t launch_gemm_dense(const DenseArgs& d, int epi, hipStream_t s) {
@@ -2384,10 +2410,10 @@ hipError_t launch_gemm_dense(const DenseArgs& d, int epi, hipStream_t s) {
   if ((epi == EPI_QKV || epi == EPI_SWIGLU) && (a.grp < 1 || (a.grp & (a.grp - 1)) != 0 || (a.n_rows / 32) % a.grp != 0)) return hipErrorInvalidValue;
   if (epi == EPI_QKV && a.dh != 64 && a.dh != 128) return hipErrorInvalidValue;
   switch (epi) {
-    case EPI_QKV: return launch_gemm_dense_e<EPI_QKV>(d, s);
-    case EPI_SWIGLU: return launch_gemm_dense_e<EPI_SWIGLU>(d, s);
-    case EPI_PARTIAL: return launch_gemm_dense_e<EPI_PARTIAL>(d, s);
-    case EPI_GELU: return launch_gemm_dense_e<EPI_GELU>(d, s);
+    case EPI_QKV: return launch_gemm_dense_h<EPI_QKV>(d, s);
+    case EPI_SWIGLU: return launch_gemm_dense_h<EPI_SWIGLU>(d, s);
+    case EPI_PARTIAL: return launch_gemm_dense_h<EPI_PARTIAL>(d, s);
+    case EPI_GELU: return launch_gemm_dense_h<EPI_GELU>(d, s);
     default: return hipErrorInvalidValue;
   }
 }
