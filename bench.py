@@ -648,9 +648,14 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": gateup_traffic_bytes(panels) if not (args.layers or cfg3) else None,
-            "traffic_source": "profiles/gemm_gateup_13b_hbm_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch, scaled by a plain copy)",
-            "kernel": ("k_gemm<%d, 8, %d, 8, %d> (target %s; %d of the %d timed blocks had more than 8 tokens and ran the "
-                       "two-panel form)" % (panels, 4 if cfg3 else 3, 2 if panels == 2 else 3,
+            "traffic_source": (None if (args.layers or cfg3) else
+                               "profiles/gemm_gateup_13b_hbm_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch, "
+                               "scaled by a plain copy)"),
+            # template arguments: panels, row tiles per workgroup (24576 rows run 96-row workgroups, 27648 rows 128-row
+            # ones), epilogue, wavefronts, register buffers
+            "kernel": ("k_gemm<%d, %d, %d, 8, %d> (target %s; %d of the %d timed blocks had more than 8 tokens and ran the "
+                       "two-panel form)" % (panels, 6 if cfg3 else 8, 4 if cfg3 else 3,
+                                            4 if cfg3 else (2 if panels == 2 else 3),
                                             "W1 GEMM + GELU" if cfg3 else "gate/up GEMM + SwiGLU", n_two, len(timed))),
             "bytes_per_launch": gemm_bytes, "avg_launch_ms": gemm_ms, "launches_timed": len(pm),
             "timing": f"HIP events around the launch of layer {probe_layer} in every timed verification forward",
