@@ -2386,16 +2386,11 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
   if (live) dense_epilogue<EPI, RT, CG>(d, cb, rt, acc);
 }
 
-template <int EPI, bool HI>
-static hipError_t launch_gemm_dense_e(const DenseArgs& d, hipStream_t s) {
-  constexpr int NB = HI ? 4 : 5;                  // k-tiles of loads in flight per wavefront (measured best of 3..5 with two panels)
+template <int EPI, int NB, int RT, bool HI>
+static hipError_t launch_gemm_dense_rt(const DenseArgs& d, hipStream_t s) {
   constexpr int CG = HI ? 8 : 4;
   const int n_tiles = d.g.n_rows / 16, ncb = (d.n_groups + CG - 1) / CG;
-  // 128-row wavefront tiles (bf16 activations only: 128 x 128 accumulators fill the accumulation registers) where they
-  // still give every compute unit a workgroup; narrower row blocks when 64-row tiles would not
-  const bool wide8 = HI && (n_tiles % 8) == 0 && (long long)((n_tiles + 31) / 32) * ncb >= 256;
-  const bool wide = (long long)((n_tiles + 15) / 16) * ncb >= 256;
-  const int nrb = wide8 ? (n_tiles + 31) / 32 : (wide ? (n_tiles + 15) / 16 : (n_tiles + 7) / 8);
+  const int nrb = (n_tiles + 4 * RT - 1) / (4 * RT);
   DenseArgs a = d;
   // about 64 workgroups run on an XCD at once: 8 x 8 for long prompts, 16 x 4 measured better at 8 token blocks
   a.tile_t = ncb >= 16 ? 8 : (ncb < 4 ? ncb : 4);
@@ -2403,13 +2398,42 @@ static hipError_t launch_gemm_dense_e(const DenseArgs& d, hipStream_t s) {
   a.tile_r = 64 / a.tile_t < nrbl ? 64 / a.tile_t : nrbl;
   const long long blocks = 8LL * ((nrbl + a.tile_r - 1) / a.tile_r) * ((ncb + a.tile_t - 1) / a.tile_t) * a.tile_r * a.tile_t;
   if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)blocks);
-  if constexpr (HI) {
-    if (wide8) { hipLaunchKernelGGL((k_gemm_dense<EPI, 3, 8, true>), grid, dim3(256), 0, s, a); return hipGetLastError(); }
-  }
-  if (wide) hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 4, HI>), grid, dim3(256), 0, s, a);
-  else hipLaunchKernelGGL((k_gemm_dense<EPI, NB, 2, HI>), grid, dim3(256), 0, s, a);
+  hipLaunchKernelGGL((k_gemm_dense<EPI, NB, RT, HI>), dim3((unsigned)blocks), dim3(256), 0, s, a);
   return hipGetLastError();
+}
+
+// Row tiles per wavefront (a workgroup covers 4 x RT tiles x CG token groups).  Larger tiles fetch every operand less
+// often, but the grid should fill the 256 compute units in its last round too: 5120 rows x 2048 tokens are 320
+// workgroups at RT = 4 (the last 64 run alone) and exactly 256 at RT = 5.  A tile count is taken only if it fills the
+// chip clearly better than the next larger one.  Two-tile epilogues need an even count; 128-row tiles need the bf16-activation
+// form (their accumulators fill the accumulation registers).
+template <int EPI, bool HI>
+static hipError_t launch_gemm_dense_e(const DenseArgs& d, hipStream_t s) {
+  constexpr bool PAIR = EpiTraits<EPI>::pair;
+  constexpr int CG = HI ? 8 : 4;
+  constexpr int NB = HI ? 4 : 5;                  // k-tiles of loads in flight per wavefront (measured best of 3..5 with two panels)
+  const int n_tiles = d.g.n_rows / 16, ncb = (d.n_groups + CG - 1) / CG;
+  auto wgs_of = [&](int rt) { return (long)((n_tiles + 4 * rt - 1) / (4 * rt)) * ncb; };
+  // 64-row wavefront tiles unless they would leave compute units without a workgroup; 128-row tiles for the wide
+  // projections with bf16 activations
+  int best = wgs_of(4) >= 256 ? 4 : 2;
+  if (HI && (n_tiles % 8) == 0 && wgs_of(8) >= 256) best = 8;
+  if (wgs_of(best) <= 2 * 256 && cu_fill(wgs_of(best)) < 0.9) {        // at most two rounds: the idle share of the last one counts
+    const int cand[] = {6, 5, 4, 3, 2};            // largest first
+    for (int rt : cand) {
+      if ((PAIR && (rt & 1)) || n_tiles % rt) continue;
+      if (wgs_of(rt) >= 256 && cu_fill(wgs_of(rt)) >= 0.95) { best = rt; break; }
+    }
+  }
+  switch (best) {
+    case 8: if constexpr (HI) return launch_gemm_dense_rt<EPI, 3, 8, true>(d, s); else break;
+    case 6: return launch_gemm_dense_rt<EPI, HI ? 4 : 3, 6, HI>(d, s);   // fewer tiles in flight: 6 x NB weight tiles must fit the registers
+    case 5: if constexpr (!PAIR) return launch_gemm_dense_rt<EPI, 4, 5, HI>(d, s); else break;
+    case 4: return launch_gemm_dense_rt<EPI, NB, 4, HI>(d, s);
+    case 3: if constexpr (!PAIR) return launch_gemm_dense_rt<EPI, NB, 3, HI>(d, s); else break;
+    default: break;
+  }
+  return launch_gemm_dense_rt<EPI, NB, 2, HI>(d, s);
 }
 
 template <int EPI>
