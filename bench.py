@@ -163,7 +163,9 @@ def micro(B, W, dev, reps):
         nbytes = weight_bytes(ds) + ds.n_layers * 2 * ctx * ds.d_kv * 2 + ds.vocab * 4
         out["draft_step"].append({"ctx": ctx, "us_per_step": 1e6 * t, "us_per_step_median_events": 1e6 * t_med,
                                   "us_single_step_warm_cache": 1e6 * t_warm1, "us_single_step_cold_cache": 1e6 * t_cold1,
-                                  "bytes": nbytes, "gbs": nbytes / t / 1e9, "frac": nbytes / t / 1e9 / HBM_PEAK_GBS})
+                                  "bytes": nbytes, "gbs": nbytes / t / 1e9, "frac": nbytes / t / 1e9 / HBM_PEAK_GBS,
+                                  "gbs_cold_cache": nbytes / t_cold1 / 1e9,
+                                  "frac_cold_cache": nbytes / t_cold1 / 1e9 / HBM_PEAK_GBS})
         log(f"[bench] draft step ctx {ctx}: {1e6 * t:.1f} us ({1e6 * t_med:.1f} median by events; single step warm "
             f"{1e6 * t_warm1:.1f}, cold {1e6 * t_cold1:.1f}), {nbytes / t / 1e9:.0f} GB/s")
     del gd, evict
