@@ -91,6 +91,22 @@ int main() {
   disco_loop_opts opts{};
   opts.ppl_threshold = 2.f;
   EXPECT(disco_draft_loop_ex(m, kv, &clf, tok, 1, 4, 0, 1.f, .5f, &opts, logits, co, lo, nullptr, FAKE, wsb, nullptr) == DISCO_EINVAL);
+  disco_loop_opts cont{};
+  cont.block_offset = 9;
+  EXPECT(disco_draft_loop_ex(m, kv, &clf, tok, 1, 8, 0, 1.f, .5f, &cont, logits, co, lo, nullptr, FAKE, wsb, nullptr) == DISCO_ECAP);
+  // the iteration driver: everything below is refused before the first launch
+  disco_iter_buffers ib{tok, logits, co, lo, lo, tok, ao, ao};
+  disco_iter_result ir{};
+  const int32_t pending[3] = {1, 2, 3};
+  EXPECT(disco_iterate(nullptr, kv, FAKE, wsb, m, kv, FAKE, wsb, &clf, pending, 1, 4, 0, 0, 1.f, .5f, nullptr, &ib, &ir, nullptr) == DISCO_EINVAL);
+  EXPECT(disco_iterate(m, kv, FAKE, wsb, m, kv, FAKE, wsb, &clf, pending, 3, 4, 0, 0, 1.f, .5f, nullptr, &ib, &ir, nullptr) == DISCO_EINVAL);
+  EXPECT(disco_iterate(m, kv, FAKE, wsb, m, kv, FAKE, wsb, &clf, pending, 1, 16, 0, 0, 1.f, .5f, nullptr, &ib, &ir, nullptr) == DISCO_ECAP);
+  EXPECT(disco_iterate(m, kv, FAKE, wsb, m, kv, FAKE, wsb, &clf, pending, 1, 4, 0, -2, 1.f, .5f, nullptr, &ib, &ir, nullptr) == DISCO_EINVAL);
+  EXPECT(disco_iterate(m, kv, FAKE, wsb, m, kv, FAKE, wsb, &clf, pending, 1, 4, 0, 0, 1.f, .5f, &cont, &ib, &ir, nullptr) == DISCO_EINVAL);
+  disco_iter_buffers ib_bad = ib;
+  ib_bad.host_accept_out = nullptr;
+  EXPECT(disco_iterate(m, kv, FAKE, wsb, m, kv, FAKE, wsb, &clf, pending, 1, 4, 0, 0, 1.f, .5f, nullptr, &ib_bad, &ir, nullptr) == DISCO_EINVAL);
+  EXPECT(disco_prefill_ex(m, kv, tok, 16, nullptr, 8u, FAKE, wsb, nullptr) == DISCO_EINVAL);
   EXPECT(disco_sample(logits, 1, 1001, 1001, 1.f, logits, nullptr, tok, nullptr) == DISCO_EINVAL);
   EXPECT(disco_sample(logits, 1, 1000, 1000, 0.f, logits, nullptr, tok, nullptr) == DISCO_EINVAL);
   EXPECT(disco_accept_sample(tok, 2, nullptr, nullptr, logits, 1000, 1.f, nullptr, logits, ao, nullptr, nullptr) == DISCO_EINVAL);

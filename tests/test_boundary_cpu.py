@@ -173,6 +173,51 @@ def test_sampling_and_loop_options_reject_bad_arguments_before_any_launch():
     lib.disco_model_destroy(m)
 
 
+def test_iteration_driver_and_block_continuation_reject_bad_arguments_before_any_launch():
+    rc, m = _model()
+    lib = B.lib()
+    rc, kv, _ = _kv(m)
+    rc, kv2, _ = _kv(m)
+    ws = lib.disco_workspace_bytes(m, 16, 48)
+    bufs = B.IterBuffers(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)
+    res = B.IterResult()
+    pend = (C.c_int32 * 3)(1, 2, 3)
+
+    def it(target=m, kv_t=kv, draft=m, kv_d=kv2, n_pending=1, cap=4, static_sl=0, chunk=0, opts=None, buffers=bufs, result=res):
+        return lib.disco_iterate(target, kv_t, FAKE, ws, draft, kv_d, FAKE, ws, None, pend, n_pending, cap, static_sl, chunk,
+                                 1.0, 0.5, C.byref(opts) if opts is not None else None,
+                                 C.byref(buffers) if buffers is not None else None,
+                                 C.byref(result) if result is not None else None, None)
+
+    assert it(target=None) == B.EINVAL
+    assert it(buffers=None) == B.EINVAL and it(result=None) == B.EINVAL
+    assert it(n_pending=0) == B.EINVAL and it(n_pending=3) == B.EINVAL
+    assert it(cap=-1) == B.ECAP and it(cap=16) == B.ECAP
+    assert it(chunk=-1) == B.EINVAL
+    assert it(buffers=B.IterBuffers(FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE)) == B.EINVAL      # no loop record
+    assert it(buffers=B.IterBuffers(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, None)) == B.EINVAL      # no pinned accept record
+    assert it(buffers=B.IterBuffers(None, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE)) == B.EINVAL      # drafting needs the token slots
+    assert it(kv_d=None) == B.EINVAL
+    # sampling and continuation are not options of an iteration
+    assert it(opts=B.LoopOpts(None, None, 1.0, FAKE, FAKE, 0.0, 0, 0)) == B.EINVAL
+    assert it(opts=B.LoopOpts(None, None, 0.0, None, None, 0.0, 2, 0)) == B.EINVAL
+    assert it(opts=B.LoopOpts(None, None, 0.0, None, None, 0.0, 0, 1)) == B.EINVAL
+    # continued blocks: offset + cap must fit a block, one token in, no sampling
+    args_tail = (FAKE, FAKE, FAKE, None, FAKE, ws, None)
+    o = B.LoopOpts(None, None, 0.0, None, None, 0.0, -1, 0)
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.ECAP
+    o = B.LoopOpts(None, None, 0.0, None, None, 0.0, 8, 0)
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 8, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.ECAP
+    o = B.LoopOpts(None, None, 0.0, None, None, 0.0, 2, 0)
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 2, 4, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.EINVAL
+    o = B.LoopOpts(None, None, 1.0, FAKE, FAKE, 0.0, 2, 0)
+    assert lib.disco_draft_loop_ex(m, kv, None, FAKE, 1, 4, 0, 1.0, 0.5, C.byref(o), *args_tail) == B.EINVAL
+    assert lib.disco_kv_len(kv) == 0 and lib.disco_kv_len(kv2) == 0
+    lib.disco_kv_destroy(kv)
+    lib.disco_kv_destroy(kv2)
+    lib.disco_model_destroy(m)
+
+
 def test_kv_capacity_is_enforced_on_the_host():
     rc, m = _model(family=0)
     lib = B.lib()
