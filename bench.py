@@ -590,6 +590,24 @@ def main():
         for k, v in res["sl_hist"].items():
             hist[k] = hist.get(k, 0) + v
     B.disco_probe_enable(-1)
+    # The paper's reference point (Table 1, row "Target"): the target model decoding on its own, one token per forward, on
+    # the last prompt of the run.  Same library path (disco_iterate without a draft model), 8 warm-up + 48 timed tokens.
+    target_only = None
+    if args.temperature <= 0 and not args.layers:
+        eng.reset()
+        eng.prefill(prompt[:-1])
+        torch.cuda.synchronize()
+        t_stamps = [time.perf_counter()]
+
+        def on_target_token(it):
+            torch.cuda.synchronize()
+            t_stamps.append(time.perf_counter())
+
+        eng.generate(prompt, 56, {"mode": "static", "gamma": 0}, do_prefill=False, on_iteration=on_target_token)
+        dt = (t_stamps[-1] - t_stamps[8]) / (len(t_stamps) - 9)
+        target_only = {"tokens_per_s": 1.0 / dt, "ms_per_token": 1e3 * dt, "tokens_timed": len(t_stamps) - 9,
+                       "kv_context": args.prompt_len + 8 + (len(t_stamps) - 9) // 2}
+        log(f"[bench] target alone: {1e3 * dt:.3f} ms per token")
     if run_to_end or (multi and args.steps == 0):   # every prompt to its end
         n_iter = len(its)
         args.steps = n_iter - args.warmup
@@ -663,6 +681,9 @@ def main():
             "timing": f"HIP events around the launch of layer {probe_layer} in every timed verification forward",
         },
     }
+    if target_only is not None:
+        out["target_only"] = target_only
+        out["speedup_vs_target_only"] = value / target_only["tokens_per_s"]
     if not args.no_cpu_baseline:
         g = max(1, round(drafted / args.steps))
         out["cpu_baseline"] = cpu_baseline(target_shape, draft_shape, tw_host, dw, clf, g, emitted / args.steps,
