@@ -78,6 +78,10 @@ struct Ws {
   float* h; float* q; bf16_t* xn; bf16_t* xattn; bf16_t* xact; float* part; float* gpart; float* logits;
   float* ssq; int* gemm_counters; int* attn_counters; int n_counters; float* clf_scratch;
   uint32_t* gate; int32_t* sl_count; int32_t* tok_next;
+  // LayerNorm family: per-tile sums beside ssq, and the correction vectors of the deferred norms (W . g, W . b) of
+  // every matrix that reads a normalised row: per layer [wg | wb] of the QKV matrix (2 d_qkv floats) and of the MLP
+  // input matrix (2 d_ff), then the LM head's (2 vocab); written by disco_workspace_init
+  float* sum; float* ln_vec; size_t ln_layer_stride;
   // persistent forward: panel versions (a fresh address per phase and step), the layer table, barrier words
   bf16_t* xn_v; bf16_t* xattn_v; bf16_t* xact_v; float* q_v; size_t xn_stride, xattn_stride, xact_stride;
   FwdLayer* fwd_layers; unsigned* bar;
@@ -111,6 +115,11 @@ Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
   w.gpart = static_cast<float*>(take(sizeof(float) * GEMM_MAX_SPLIT * 256 * (size_t)max_tiles));
   w.logits = static_cast<float*>(take(sizeof(float) * 16 * (size_t)d.vocab));
   w.ssq = static_cast<float*>(take(sizeof(float) * 16 * (size_t)(d.d_model / 16)));
+  w.sum = nullptr; w.ln_vec = nullptr; w.ln_layer_stride = 2 * ((size_t)m->d_qkv + d.d_ff);
+  if (d.family == DISCO_FAMILY_A) {
+    w.sum = static_cast<float*>(take(sizeof(float) * 16 * (size_t)(d.d_model / 16)));
+    w.ln_vec = static_cast<float*>(take(sizeof(float) * (w.ln_layer_stride * d.n_layers + 2 * (size_t)d.vocab)));
+  }
   w.n_counters = max_tiles + d.n_heads;
   w.gemm_counters = static_cast<int*>(take(sizeof(int) * (size_t)w.n_counters));
   w.attn_counters = w.gemm_counters ? w.gemm_counters + max_tiles : nullptr;
@@ -204,19 +213,23 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   NormArgs na{};
   na.h = ws.h; na.d = d.d_model; na.M = n; na.layernorm = fam_a; na.eps = d.norm_eps;
   na.Xout = ws.xn; na.gate = gate; na.pos0 = pos0; na.vocab = d.vocab; na.max_pos = d.max_pos;
-  if (!fam_a) { na.ssq_out = ws.ssq; na.n_ssq_out = n_tiles; }   // RMSNorm is deferred to the consumer GEMM
+  na.ssq_out = ws.ssq; na.n_ssq_out = n_tiles;                   // every norm is deferred to the consumer GEMM
+  if (fam_a) na.sum_out = ws.sum;
 
-  // Family B: every GEMM that reads a normalised row reads gain * h panels and rescales by 1 / rms
-  // in its epilogue; the residual-update GEMMs write those panels.  Family A keeps LayerNorm kernels.
-  auto normed_input = [&](GemmArgs& g) {
+  // Every GEMM that reads a normalised row reads gain * h panels and applies the norm in its epilogue: 1 / rms
+  // (family B), or rstd * (y - mean * W.g) + W.b with the vectors that disco_workspace_init left (family A);
+  // the residual-update GEMMs write those panels and the per-tile sums.
+  auto normed_input = [&](GemmArgs& g, const float* ln_vec, int n_rows) {
     g.X = ws.xn; g.KT = d.d_model / 32;
-    if (!fam_a) { g.ssq = ws.ssq; g.n_ssq = n_tiles; g.d_in = d.d_model; g.eps = d.norm_eps; }
+    g.ssq = ws.ssq; g.n_ssq = n_tiles; g.d_in = d.d_model; g.eps = d.norm_eps;
+    if (fam_a) { g.sum = ws.sum; g.wg = ln_vec; g.wb = ln_vec + n_rows; }
   };
   auto residual_update = [&](GemmArgs& g, const void* w, const bf16_t* x, int k, int split, const float* next_gain) {
     g.M = n; g.gate = gate; g.W = static_cast<const bf16_t*>(w); g.X = x; g.KT = k / 32;
     g.n_rows = d.d_model; g.h = ws.h; g.ld_out = d.d_model; g.only_row = -1;
     g.n_split = split; g.planes = ws.gpart; g.counters = ws.gemm_counters;
-    if (!fam_a) { g.Xout = ws.xn; g.KT_out = d.d_model / 32; g.gain = next_gain; g.ssq_out = ws.ssq; g.n_ssq_out = n_tiles; }
+    g.Xout = ws.xn; g.KT_out = d.d_model / 32; g.gain = next_gain; g.ssq_out = ws.ssq; g.n_ssq_out = n_tiles;
+    if (fam_a) g.sum_out = ws.sum;
   };
 
   {
@@ -230,12 +243,12 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     const disco_layer_weights& L = m->layers[l];
     const bool last = (l + 1 == d.n_layers);
     const float* next_g = last ? m->w.normf_g : m->layers[l + 1].norm1_g;
-    const float* next_b = last ? m->w.normf_b : m->layers[l + 1].norm1_b;
 
     GemmArgs g{};
     g.M = n; g.gate = gate; g.planes = ws.gpart; g.counters = ws.gemm_counters;
     // QKV projection, rotary, KV append
-    g.W = static_cast<const bf16_t*>(L.wqkv); normed_input(g); g.n_rows = m->d_qkv;
+    const float* ln_l = fam_a ? ws.ln_vec + ws.ln_layer_stride * l : nullptr;
+    g.W = static_cast<const bf16_t*>(L.wqkv); normed_input(g, ln_l, m->d_qkv); g.n_rows = m->d_qkv;
     g.grp = d.d_head / 32; g.q = ws.q; g.ldq = m->d_q; g.nq = d.n_heads; g.nkv = d.n_kv_heads; g.dh = d.d_head;
     g.pos0 = pos0; g.rope_tab = kv->dev_rope;
     g.kv_layer = kv->pages + (size_t)l * kv->layer_stride; g.page_table = kv->dev_page_table;
@@ -254,15 +267,9 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     residual_update(o, L.wo, ws.xattn, m->d_q, split_o, L.norm2_g);
     HIP_TRY(launch_gemm(o, EPI_PARTIAL, s), "o-proj launch");
 
-    if (fam_a) {
-      NormArgs n2 = na;
-      n2.g = L.norm2_g; n2.b = L.norm2_b;
-      HIP_TRY(launch_norm(n2, s), "norm launch");
-    }
-
     GemmArgs u{};
     u.M = n; u.gate = gate; u.planes = ws.gpart; u.counters = ws.gemm_counters;
-    u.W = static_cast<const bf16_t*>(L.w_in); normed_input(u);
+    u.W = static_cast<const bf16_t*>(L.w_in); normed_input(u, fam_a ? ln_l + 2 * (size_t)m->d_qkv : nullptr, d.d_ff);
     u.n_rows = fam_a ? d.d_ff : 2 * d.d_ff; u.grp = 1; u.Xout = ws.xact; u.KT_out = d.d_ff / 32;
     HIP_TRY(probe_record(l, 0, s), "probe event");
     HIP_TRY(launch_gemm(u, fam_a ? EPI_GELU : EPI_SWIGLU, s), "mlp-in launch");
@@ -272,15 +279,10 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     residual_update(dn, L.w_out, ws.xact, d.d_ff, split_dn, next_g);
     HIP_TRY(launch_gemm(dn, EPI_PARTIAL, s), "mlp-out launch");
 
-    if (fam_a) {
-      NormArgs n3 = na;
-      n3.g = next_g; n3.b = next_b;
-      HIP_TRY(launch_norm(n3, s), "norm launch");
-    }
   }
   GemmArgs lm{};
   lm.M = n; lm.gate = gate; lm.planes = ws.gpart; lm.counters = ws.gemm_counters;
-  lm.W = static_cast<const bf16_t*>(m->w.wlm); normed_input(lm);
+  lm.W = static_cast<const bf16_t*>(m->w.wlm); normed_input(lm, fam_a ? ws.ln_vec + ws.ln_layer_stride * d.n_layers : nullptr, d.vocab);
   lm.n_rows = d.vocab; lm.out = logits_out; lm.ld_out = d.vocab; lm.only_row = only_last ? n - 1 : -1;
   HIP_TRY(launch_gemm(lm, EPI_STORE, s), "lm-head launch");
   kv->len = pos0 + n;
@@ -592,6 +594,32 @@ int disco_workspace_init(const disco_model* m, void* dev_ws, size_t ws_bytes, in
   const Ws ws = carve(m, max_block, max_ctx, dev_ws);
   HIP_TRY(launch_zero(ws.gemm_counters, ws.n_counters, static_cast<hipStream_t>(s)), "workspace init launch");
   HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.clf_scratch), 64, static_cast<hipStream_t>(s)), "workspace init launch");
+  if (ws.ln_vec != nullptr) {
+    // correction vectors of the deferred LayerNorms: one-token GEMVs of every consumer matrix with the gain vector
+    // and with the bias vector of the norm in front of it (a missing bias gives zeros)
+    const disco_model_desc& d = m->d;
+    hipStream_t st = static_cast<hipStream_t>(s);
+    auto gemv = [&](const void* W, int n_rows, const float* vec, float* out) -> int {
+      HIP_TRY(launch_vec_panel(vec, d.d_model, ws.xn, st), "norm vector panel launch");
+      GemmArgs g{};
+      g.M = 1; g.W = static_cast<const bf16_t*>(W); g.X = ws.xn; g.KT = d.d_model / 32; g.n_rows = n_rows; g.grp = 1;
+      g.n_split = 1; g.out = out; g.ld_out = n_rows; g.only_row = 0;
+      HIP_TRY(launch_gemm(g, EPI_STORE, st), "norm vector launch");
+      return DISCO_OK;
+    };
+    for (int l = 0; l < d.n_layers; ++l) {
+      const disco_layer_weights& L = m->layers[l];
+      float* v = ws.ln_vec + ws.ln_layer_stride * l;
+      int rc = gemv(L.wqkv, m->d_qkv, L.norm1_g, v); if (rc) return rc;
+      rc = gemv(L.wqkv, m->d_qkv, L.norm1_b, v + m->d_qkv); if (rc) return rc;
+      v += 2 * (size_t)m->d_qkv;
+      rc = gemv(L.w_in, d.d_ff, L.norm2_g, v); if (rc) return rc;
+      rc = gemv(L.w_in, d.d_ff, L.norm2_b, v + d.d_ff); if (rc) return rc;
+    }
+    float* v = ws.ln_vec + ws.ln_layer_stride * d.n_layers;
+    int rc = gemv(m->w.wlm, d.vocab, m->w.normf_g, v); if (rc) return rc;
+    rc = gemv(m->w.wlm, d.vocab, m->w.normf_b, v + d.vocab); if (rc) return rc;
+  }
   if (ws.fwd_layers != nullptr) {
     HIP_TRY(hipMemcpyAsync(ws.fwd_layers, m->fwd_layers.data(), sizeof(FwdLayer) * m->fwd_layers.size(), hipMemcpyHostToDevice,
                            static_cast<hipStream_t>(s)), "layer table upload");

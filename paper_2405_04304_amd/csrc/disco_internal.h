@@ -31,9 +31,14 @@ struct GemmArgs {
   float* planes;        // partial tiles of row groups whose K range is shared by several workgroups:
                         // [row group][GEMM_MAX_SPLIT][tile of the group][64 lanes][4] fp32
   const float* ssq; int n_ssq; int d_in; float eps;   // deferred RMSNorm of the input (ssq == nullptr: none)
+  // deferred LayerNorm of the input (sum != nullptr; needs ssq too): per-tile sums of the row beside the sums of
+  // squares, and two vectors over the output rows, wg[n] = sum_k W[n][k] g[k] and wb[n] = sum_k W[n][k] b[k]:
+  // W . LN(h) = rstd * (W . (g * h) - mean * wg) + wb
+  const float* sum; const float* wg; const float* wb;
   int* counters;        // one zeroed ticket counter per row group (used when a K range is shared)
   float* h;             // PARTIAL: residual stream updated in place, row stride ld_out
   const float* gain; float* ssq_out; int n_ssq_out;   // PARTIAL with Xout: next norm's gain, sums of squares
+  float* sum_out;                                     // PARTIAL with Xout, next norm a LayerNorm: per-tile sums too
   float* out;           // STORE target, row stride ld_out
   int64_t ld_out;
   int only_row;         // STORE: write only this token's row to out[0..N) (-1: all rows)
@@ -63,6 +68,7 @@ struct NormArgs {
   const float* g; const float* b;
   bf16_t* Xout;                      // packed panels, K = d
   float* ssq_out; int n_ssq_out;     // deferred RMSNorm: write gain * h panels and the row's sum of squares
+  float* sum_out;                    // deferred LayerNorm (with ssq_out): the row's sum as well
   // embedding mode (tokens != nullptr): h = tok_emb[token] (+ pos_emb[pos0 + m]) first
   const int32_t* tokens; const bf16_t* tok_emb; int64_t tok_stride; const bf16_t* pos_emb;
   int pos0; int vocab; int max_pos;
@@ -157,6 +163,8 @@ hipError_t launch_pack(const bf16_t* src, int64_t n, int64_t k, bf16_t* dst, int
 hipError_t launch_gemm(const GemmArgs& a, int epi, hipStream_t s);
 int gemm_split_for(int n_rows, int KT, int M);   // K ranges the PARTIAL epilogue should be launched with
 hipError_t launch_norm(const NormArgs& a, hipStream_t s);
+// one-token activation panel (hi + lo) of an fp32 vector of d elements (d % 32 == 0), or of zeros if v == nullptr
+hipError_t launch_vec_panel(const float* v, int d, bf16_t* Xout, hipStream_t s);
 bool forward_shape_ok(int d, int d_q, int d_qkv, int d_ff, int dh, int vocab, bool big);
 hipError_t launch_forward(const FwdArgs& f, bool big, bool loop, hipStream_t s);
 constexpr int FWD_BAR_WORDS = (2 * 16 + 2) * 64;   // group counters, top counter, release words, abort word: 256 bytes apart

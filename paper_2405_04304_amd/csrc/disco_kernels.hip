@@ -335,10 +335,11 @@ template <int EPI> struct EpiTraits { static constexpr bool pair = (EPI == EPI_Q
 constexpr int gemm_buffers(int rt, int panels) { return rt >= 8 ? (panels >= 2 ? 2 : 3) : 4; }
 
 // LDS of one GEMM work unit.
-template <int RT, int NW>
+template <int RT, int NW, bool LN = false>
 struct GemmSmem {
   f32x4 red[NW][RT][64];
   float red_ssq[NW][64];
+  float red_sum[LN ? NW : 1][64];                 // per-tile sums of a deferred LayerNorm
   int s_last;
 };
 
@@ -368,9 +369,11 @@ __device__ __forceinline__ void gemm_unit_tiles(const GemmArgs& a, const int b, 
 // barrier that ends the phase before, so the weight stream is in flight while that phase drains.
 struct NoHook { __device__ __forceinline__ void operator()() const {} };
 
-template <int P, int RT, int EPI, int NW, int U, bool COH = false, typename Hook = NoHook>
+// LN: the input's norm is a LayerNorm (deferred like the RMSNorm: the panels hold g * h, the producer left per-tile
+// sums and sums of squares, and the epilogue applies rstd * (y - mean * wg) + wb).
+template <int P, int RT, int EPI, int NW, int U, bool COH = false, typename Hook = NoHook, bool LN = false>
 __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const int kt_begin, const int kt_end,
-                                          const int seg, const int n_seg, GemmSmem<RT, NW>& sm, const Hook hook = Hook()) {
+                                          const int seg, const int n_seg, GemmSmem<RT, NW, LN>& sm, const Hook hook = Hook()) {
   constexpr bool PAIR = EpiTraits<EPI>::pair;
   constexpr int UNITS = PAIR ? RT / 2 : RT;       // output units handled by one wavefront each
   static_assert(!PAIR || RT % 2 == 0, "pair epilogues need an even tile count");
@@ -417,10 +420,15 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
   // epilogue adds them up in a fixed order to get 1 / rms.
   constexpr bool NORMED = (EPI != EPI_PARTIAL);
   constexpr int MAXS = NORMED ? 128 / NW : 1;
-  float sv[MAXS];
+  static_assert(!LN || NORMED, "only epilogues that read a normalised input defer a LayerNorm");
+  float sv[MAXS], su[LN ? MAXS : 1];
   if (NORMED) {
 #pragma unroll
     for (int k = 0; k < MAXS; ++k) sv[k] = 0.f;
+    if (LN) {
+#pragma unroll
+      for (int k = 0; k < MAXS; ++k) su[k] = 0.f;
+    }
     // rounds of 4 NW slots; the rounds past n_ssq are skipped by a uniform branch (a 768-wide model
     // needs 2 of the 16 rounds: per-lane tests of all 16 cost more than the loads)
     const int rounds = a.ssq != nullptr ? (a.n_ssq + 4 * NW - 1) / (4 * NW) : 0;
@@ -429,6 +437,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
       if (k < rounds) {
         const int idx = (lane >> 4) * NW + w + 4 * NW * k;
         sv[k] = idx < a.n_ssq ? a.ssq[idx * 16 + (lane & 15)] : 0.f;   // [slot][token]; plain loads: see k_forward
+        if (LN) su[k] = idx < a.n_ssq ? a.sum[idx * 16 + (lane & 15)] : 0.f;
       }
     }
     asm volatile("" ::: "memory");     // keep these loads ahead of the rest of the stream
@@ -472,6 +481,15 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
       part += sv[k];
     }
     sm.red_ssq[w][lane] = part;
+    if (LN) {
+      float ps = 0.f;
+#pragma unroll
+      for (int k = 0; k < MAXS; ++k) {
+        asm volatile("" : "+v"(su[k]));
+        ps += su[k];
+      }
+      sm.red_sum[w][lane] = ps;
+    }
   }
   __syncthreads();
   constexpr int TPU = PAIR ? 2 : 1;               // tiles per unit
@@ -540,9 +558,27 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
     for (int ww = 0; ww < NW; ++ww)
 #pragma unroll
       for (int gg = 0; gg < 4; ++gg) ss += sm.red_ssq[ww][gg * 16 + m];
-    const float rstd = 1.0f / sqrtf(ss / (float)a.d_in + a.eps);
+    if (LN) {
+      float sx = 0.f;
 #pragma unroll
-    for (int i = 0; i < TPU; ++i) y[i] *= rstd;
+      for (int ww = 0; ww < NW; ++ww)
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) sx += sm.red_sum[ww][gg * 16 + m];
+      const float mean = sx / (float)a.d_in;
+      const float var = fmaxf(ss / (float)a.d_in - mean * mean, 0.f);
+      const float rstd = 1.0f / sqrtf(var + a.eps);
+#pragma unroll
+      for (int i = 0; i < TPU; ++i) {
+        const int row = urt[i] * 16 + 4 * g;
+        const float4 cg = *reinterpret_cast<const float4*>(a.wg + row), cb = *reinterpret_cast<const float4*>(a.wb + row);
+        y[i][0] = rstd * (y[i][0] - mean * cg.x) + cb.x; y[i][1] = rstd * (y[i][1] - mean * cg.y) + cb.y;
+        y[i][2] = rstd * (y[i][2] - mean * cg.z) + cb.z; y[i][3] = rstd * (y[i][3] - mean * cg.w) + cb.w;
+      }
+    } else {
+      const float rstd = 1.0f / sqrtf(ss / (float)a.d_in + a.eps);
+#pragma unroll
+      for (int i = 0; i < TPU; ++i) y[i] *= rstd;
+    }
   }
 
   if (EPI == EPI_PARTIAL) {
@@ -557,6 +593,10 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
       xpack_store4<COH>(a.Xout, a.KT_out, a.M, m, col, o);
       const float sq = row4_sum((h.x * h.x + h.y * h.y) + (h.z * h.z + h.w * h.w));
       if (g == 0) st_f1<COH>(a.ssq_out + urt[0] * 16 + m, sq);              // [slot][token]
+      if (a.sum_out != nullptr) {
+        const float sx = row4_sum((h.x + h.y) + (h.z + h.w));
+        if (g == 0) st_f1<COH>(a.sum_out + urt[0] * 16 + m, sx);
+      }
     }
     return;
   }
@@ -589,18 +629,24 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
   }
 }
 
-template <int P, int RT, int EPI, int NW, int U>
+template <int P, int RT, int EPI, int NW, int U, bool LN = false>
 __global__ __launch_bounds__(NW * 64) void k_gemm(GemmArgs a) {
-  __shared__ GemmSmem<RT, NW> sm;
+  __shared__ GemmSmem<RT, NW, LN> sm;
   const int split = blockIdx.y;
   const int kt_begin = (int)((int64_t)a.KT * split / a.n_split), kt_end = (int)((int64_t)a.KT * (split + 1) / a.n_split);
-  gemm_unit<P, RT, EPI, NW, U>(a, blockIdx.x, kt_begin, kt_end, split, a.n_split, sm);
+  gemm_unit<P, RT, EPI, NW, U, false, NoHook, LN>(a, blockIdx.x, kt_begin, kt_end, split, a.n_split, sm);
 }
 
 template <int P, int RT, int EPI, int NW, int U>
 static hipError_t launch_gemm_cfg(const GemmArgs& a, hipStream_t s) {
   constexpr int rows = RT * 16;
   if (a.n_rows % rows) return hipErrorInvalidValue;
+  if constexpr (EPI == EPI_QKV || EPI == EPI_GELU || EPI == EPI_STORE) {
+    if (a.sum != nullptr) {                       // deferred LayerNorm
+      hipLaunchKernelGGL((k_gemm<P, RT, EPI, NW, U, true>), dim3(a.n_rows / rows, a.n_split), dim3(NW * 64), 0, s, a);
+      return hipGetLastError();
+    }
+  }
   hipLaunchKernelGGL((k_gemm<P, RT, EPI, NW, U>), dim3(a.n_rows / rows, a.n_split), dim3(NW * 64), 0, s, a);
   return hipGetLastError();
 }
@@ -741,6 +787,14 @@ __device__ __forceinline__ void norm_row(const NormArgs& a, const int row, const
     ss = block_sum<NT>(ss, red);
     float* sq = a.ssq_out + (size_t)grp * a.n_ssq_out * 16;
     for (int i = t; i < a.n_ssq_out; i += NT) st_f1<COH>(sq + i * 16 + m, (i == 0) ? ss : 0.f);   // [slot][token]
+    if (a.sum_out != nullptr) {                   // the consumer's norm is a LayerNorm: the row's sum as well
+      float sx = 0.f;
+#pragma unroll
+      for (int i = 0; i < VPT; ++i) sx += (v[i].x + v[i].y) + (v[i].z + v[i].w);   // zero beyond d
+      sx = block_sum<NT>(sx, red);
+      float* su = a.sum_out + (size_t)grp * a.n_ssq_out * 16;
+      for (int i = t; i < a.n_ssq_out; i += NT) st_f1<COH>(su + i * 16 + m, (i == 0) ? sx : 0.f);
+    }
     const int KT = d >> 5;
 #pragma unroll
     for (int i = 0; i < VPT; ++i) {
@@ -790,6 +844,22 @@ template <int NT>
 __global__ __launch_bounds__(NT) void k_norm(NormArgs a) {
   __shared__ float red[NT / 64 + 1];
   norm_row<NT>(a, blockIdx.x, -1, red, gate_request(a.gate));
+}
+
+// One-token activation panel of an fp32 vector (the operand of the GEMVs that give the correction vectors of a
+// deferred LayerNorm, W . g and W . b).
+__global__ __launch_bounds__(256) void k_vec_panel(const float* __restrict__ v, int d, bf16_t* __restrict__ Xout) {
+  const int k = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (k >= d) return;
+  float o[4] = {0.f, 0.f, 0.f, 0.f};
+  if (v != nullptr) { const float4 x = *reinterpret_cast<const float4*>(v + k); o[0] = x.x; o[1] = x.y; o[2] = x.z; o[3] = x.w; }
+  xpack_store4(Xout, d >> 5, 1, 0, k, o);
+}
+
+hipError_t launch_vec_panel(const float* v, int d, bf16_t* Xout, hipStream_t s) {
+  if (d < 32 || (d & 31) || Xout == nullptr) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_vec_panel, dim3((d / 4 + 255) / 256), dim3(256), 0, s, v, d, Xout);
+  return hipGetLastError();
 }
 
 hipError_t launch_norm(const NormArgs& a, hipStream_t s) {
