@@ -212,6 +212,29 @@ def test_draft_step_small_models(shape, ctx, page, permute):
         assert gkv.len == okv.len
 
 
+@pytest.mark.parametrize("offset", [0.1, 0.5])
+def test_layernorm_rows_with_a_mean(offset):
+    """The LayerNorm of a forward is applied inside the consumer GEMM from per-tile sums: variance as E[h^2] - mean^2
+    and the mean's share of the product removed afterwards, which lose digits as a row's mean grows against its
+    spread.  Embedding rows with a common offset (mean / spread = 2 and 10 at sigma 0.05) must stay inside the
+    regression bar; the stated bar holds far beyond."""
+    shape = SMALL_A_MQA
+    w = W.make_weights(shape, 7, "bf16", sigma=0.05, gain_jitter=0.2)
+    w["tok_emb"] = (w["tok_emb"].float() + offset).to(torch.bfloat16)
+    om, gm, okv, gkv, ws = setup_pair(shape, 7, kv_ctx=60, page_tokens=16, capacity=120, weights=w)
+    d = dev()
+    toks = W.make_tokens(9, 20, shape.vocab).tolist()
+    am = torch.zeros(16, dtype=torch.int32, device=d)
+    i = 0
+    for M in (1, 5, 11):
+        lg = torch.empty(M, shape.vocab, dtype=torch.float32, device=d)
+        B.disco_verify(gm, gkv, torch.tensor(toks[i:i + M], dtype=torch.int32, device=d), M, am, lg, ws)
+        torch.cuda.synchronize()
+        ref = om.forward(toks[i:i + M], okv)
+        check_logits(lg, ref, f"LayerNorm rows with mean offset {offset}, M {M}")
+        i += M
+
+
 @pytest.mark.parametrize("ctx", [512, 1024, 2048])
 def test_draft_step_68m_shape(ctx):
     shape = W.CFG1_DRAFT
