@@ -672,10 +672,10 @@ def main():
                                "profiles/gemm_gateup_13b_hbm_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch, "
                                "scaled by a plain copy)"),
             # template arguments: panels, row tiles per workgroup (24576 rows run 96-row workgroups, 27648 rows 128-row
-            # ones), epilogue, wavefronts, register buffers
-            "kernel": ("k_gemm<%d, %d, %d, 8, %d> (target %s; %d of the %d timed blocks had more than 8 tokens and ran the "
+            # ones), epilogue, wavefronts, register buffers, deferred LayerNorm
+            "kernel": ("k_gemm<%d, %d, %d, 8, %d, %s> (target %s; %d of the %d timed blocks had more than 8 tokens and ran the "
                        "two-panel form)" % (panels, 6 if cfg3 else 8, 4 if cfg3 else 3,
-                                            4 if cfg3 else (2 if panels == 2 else 3),
+                                            4 if cfg3 else (2 if panels == 2 else 3), "true" if cfg3 else "false",
                                             "W1 GEMM + GELU" if cfg3 else "gate/up GEMM + SwiGLU", n_two, len(timed))),
             "bytes_per_launch": gemm_bytes, "avg_launch_ms": gemm_ms, "launches_timed": len(pm),
             "timing": f"HIP events around the launch of layer {probe_layer} in every timed verification forward",

@@ -892,7 +892,8 @@ int disco_iterate(const disco_model* target, disco_kv* kv_t, void* dev_ws_t, siz
     }
     if (sl > DISCO_MAX_BLOCK - 1) return fail(DISCO_ESTATE, "draft loop reported %d tokens", sl);
     // with a reference the step whose token left it ran too
-    ran = sl + ((o.dev_ref_tokens && sl < cap) ? 1 : 0);
+    ran = sl + ((o.dev_ref_tokens && sl < total) ? 1 : 0);
+    if (ran > enq) ran = enq;
     const int rc = disco_kv_rollback(kv_d, len_d0 + n_pending + ran - 1);
     if (rc) return rc;
   } else {
