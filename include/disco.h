@@ -146,8 +146,12 @@ int disco_kv_fill(disco_kv* kv, const void* dev_src, int ctx, disco_stream s);
 size_t disco_workspace_bytes(const disco_model* m, int max_block, int max_ctx);
 /* Must run once on a fresh workspace before its first use (and again if a launch that used it was
  * aborted): zeroes the small ticket counters with which the workgroups of a split reduction find
- * out which of them finishes last.  Kernels leave the counters at zero.  A workspace serves one
- * stream at a time.                                                                               */
+ * out which of them finishes last (kernels leave the counters at zero), and, for a LayerNorm model,
+ * computes the two correction vectors of every matrix that reads a normalised row (W . gain and
+ * W . bias of the norm in front of it: 4 one-token products per layer and 2 for the LM head, a few
+ * ms for a 15B-class model) into the workspace: the forwards apply LayerNorm inside those matrices'
+ * kernels.  The model's weights must therefore be in place when this runs, and it must run again if
+ * they change.  A workspace belongs to the model it was initialised for and serves one stream at a time. */
 int disco_workspace_init(const disco_model* m, void* dev_ws, size_t ws_bytes, int max_block, int max_ctx,
                          disco_stream s);
 
