@@ -899,19 +899,24 @@ struct AttnWave {
   // raw operands of one step: K rows of two 16-position tiles, V^T tiles of the same positions
   struct Raw { u32x4 k[2][KS]; uint2 v[2][CT]; };
   const AttnArgs& a;
+  const float* qb;
   int j, g, kvh, total, s1, pt, pshift, qpos;
   size_t kv_head_elems, page_elems;
   bf16x8 qh[KS], ql[KS];
   f32x4 O[CT];
   float m_run, l_run;
 
-  __device__ __forceinline__ AttnWave(const AttnArgs& a_, int head, int s1_) : a(a_) {
+  // pos0_ / q_: first position and query rows of this object's token group when they are not the launch's (prompt pass:
+  // one workgroup serves two groups of 16 tokens); s1_ < 0: the range ends with the group's own tokens
+  __device__ __forceinline__ AttnWave(const AttnArgs& a_, int head, int s1_, int pos0_ = -1, const float* q_ = nullptr) : a(a_) {
     const int lane = threadIdx.x & 63;
     j = lane & 15; g = lane >> 4;
     kvh = head / (a.nq / a.nkv);
-    total = a.pos0 + a.M; s1 = s1_; pt = a.page_tokens;
+    const int pos0 = pos0_ < 0 ? a.pos0 : pos0_;
+    qb = q_ != nullptr ? q_ : a.q;
+    total = pos0 + a.M; s1 = s1_ < 0 ? total : s1_; pt = a.page_tokens;
     pshift = (pt & (pt - 1)) == 0 ? __builtin_ctz(pt) : -1;     // power-of-two pages: shifts instead of divisions
-    qpos = a.pos0 + j;                                            // last position query j may see
+    qpos = pos0 + j;                                              // last position query j may see
     kv_head_elems = (size_t)pt * DH;                              // one head's K (or V) block in a page
     page_elems = 2 * (size_t)a.nkv * kv_head_elems;
 #pragma unroll
@@ -956,7 +961,7 @@ struct AttnWave {
 
   // query operand: column j holds query min(j, M-1) (surplus columns are never stored)
   __device__ __forceinline__ void load_q(int head) {
-    const float* qp = a.q + (size_t)min(j, a.M - 1) * a.ldq + head * DH + 8 * g;
+    const float* qp = qb + (size_t)min(j, a.M - 1) * a.ldq + head * DH + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       const float4 x0 = ld_f4<QCOH>(qp + ks * 32), x1 = ld_f4<QCOH>(qp + ks * 32 + 4);
@@ -1201,17 +1206,67 @@ __global__ __launch_bounds__(512) void k_attn_head(AttnArgs a) {
   attn_whole_head<DH>(a, blockIdx.x, gate_request(a.gate));
 }
 
-// Prompt pass: workgroup = (query head, group of 16 prompt tokens).  Group r sits at positions
-// pos0 + 16 r .. and sees everything up to its own tokens, so every group runs the whole-head routine
-// on its own range; the longest ranges are scheduled first.
+// Prompt pass: workgroup = (query head, two consecutive groups of 16 prompt tokens).  Group r sits at positions
+// pos0 + 16 r .. and sees everything up to its own tokens.  The eight wavefronts share the cached positions (32 per
+// wavefront and step); every K and V tile a wavefront fetches serves the queries of both groups (half the cache reads
+// and half the workgroups of one group per workgroup: the kernel waits on those reads), each group with its own
+// running soft-max.  The groups are merged across the wavefronts one after the other through one LDS buffer.  The
+// longest ranges are scheduled first.
+constexpr int ATTN_MG = 2;
 template <int DH>
 __global__ __launch_bounds__(512) void k_attn_groups(AttnArgs a, int n_groups, size_t x_stride) {
-  const int r = n_groups - 1 - (int)blockIdx.y;
-  AttnArgs b = a;
-  b.pos0 = a.pos0 + 16 * r;
-  b.q = a.q + (size_t)r * 16 * a.ldq;
-  b.Xout = a.Xout + (size_t)r * x_stride;
-  attn_whole_head<DH>(b, blockIdx.x);
+  constexpr int CT = DH / 16, NWV = 8, WKEYS = 32, STEP = NWV * WKEYS, NG = ATTN_MG;
+  __shared__ f32x4 o_s[NWV][CT][64];
+  __shared__ float m_s[NWV][16], l_s[NWV][16];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int head = blockIdx.x;
+  const int nb = (n_groups + NG - 1) / NG;
+  const int r0g = (nb - 1 - (int)blockIdx.y) * NG;                // first group of this workgroup
+  const int ng = min(NG, n_groups - r0g);
+  auto grp = [&](int i) { return r0g + min(i, ng - 1); };          // a surplus slot repeats the last group and stores nothing
+  auto wave_of = [&](int i) { return AttnWave<DH>(a, head, -1, a.pos0 + 16 * grp(i), a.q + (size_t)grp(i) * 16 * a.ldq); };
+  AttnWave<DH> aw[NG] = {wave_of(0), wave_of(1)};
+  static_assert(NG == 2, "the initialiser above lists two groups");
+  const int total = aw[NG - 1].total;                              // the longest range: its object issues the loads
+  // one set of raw operands per wavefront (two would not fit beside the state of two groups); the other wavefront of
+  // the SIMD covers the wait (re-issuing the K loads between the two halves of a step measured slower)
+  typename AttnWave<DH>::Raw ra;
+  int base = w * WKEYS;
+  if (base < total) aw[NG - 1].issue(ra, base);
+#pragma unroll
+  for (int i = 0; i < NG; ++i) aw[i].load_q(head);
+  while (base < total) {
+#pragma unroll
+    for (int i = 0; i < NG; ++i)
+      if (base < aw[i].total) aw[i].step(ra, base);
+    base += STEP;
+    if (base < total) aw[NG - 1].issue(ra, base);
+  }
+#pragma unroll
+  for (int i = 0; i < NG; ++i) {
+    if (i > 0) __syncthreads();                                    // the merge of the group before has read the buffer
+#pragma unroll
+    for (int c = 0; c < CT; ++c) o_s[w][c][lane] = aw[i].O[c];
+    if (g == 0) { m_s[w][j] = aw[i].m_run; l_s[w][j] = aw[i].l_run; }
+    __syncthreads();
+    if (i < ng && w < CT) {                                        // wavefront w finishes channel tile w
+      float mm = m_s[0][j];
+#pragma unroll
+      for (int ww = 1; ww < NWV; ++ww) mm = fmaxf(mm, m_s[ww][j]);
+      float ll = 0.f;
+      f32x4 o = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ww = 0; ww < NWV; ++ww) {                           // fixed order: deterministic
+        const float f = expf(m_s[ww][j] - mm);
+        ll += l_s[ww][j] * f;
+        o += o_s[ww][w][lane] * f;
+      }
+      const float inv = 1.0f / ll;
+      const float out4[4] = {o[0] * inv, o[1] * inv, o[2] * inv, o[3] * inv};
+      xpack_store4(a.Xout + (size_t)(r0g + i) * x_stride, (a.nq * DH) >> 5, a.M, j, head * DH + w * 16 + 4 * g, out4);
+    }
+  }
 }
 
 constexpr int ATTN_HEAD_MAX_CTX = 256;    // positions up to which the whole-head kernel is used (one step per wavefront);
@@ -1244,7 +1299,7 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t s) {
 
 hipError_t launch_attn_groups(const AttnArgs& a, int n_groups, size_t x_stride, hipStream_t s) {
   if (a.M != 16 || n_groups < 1 || n_groups > 65535) return hipErrorInvalidValue;
-  const dim3 g1(a.nq, n_groups);
+  const dim3 g1(a.nq, (n_groups + ATTN_MG - 1) / ATTN_MG);
   if (a.dh == 128) hipLaunchKernelGGL(k_attn_groups<128>, g1, dim3(512), 0, s, a, n_groups, x_stride);
   else if (a.dh == 64) hipLaunchKernelGGL(k_attn_groups<64>, g1, dim3(512), 0, s, a, n_groups, x_stride);
   else return hipErrorInvalidValue;
