@@ -2418,7 +2418,7 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
   constexpr int CG = HI ? 8 : 4, NWV = 4, NS = NB + 1;
   constexpr bool PAIR = EpiTraits<EPI>::pair;
   constexpr int UNITS = PAIR ? RT / 2 : RT;
-  __shared__ u32x4 bs[2][8][64];
+  __shared__ u32x4 bs[HI ? 3 : 2][8][64];
   const GemmArgs& a = d.g;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int n_tiles = a.n_rows >> 4;
@@ -2465,37 +2465,69 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
   u32x4 A[NS][RT], Bw[NS][2];
   auto gload = [&](u32x4 (&Ad)[RT], u32x4 (&Bd)[2], const int kt) {
     const size_t t = (size_t)(kt < KT ? kt : KT - 1) * 64;
+    if (HI) { Bd[0] = Xw[t]; Bd[1] = Xw1[t]; }    // first: the pipelined form needs them one k-tile earlier than the weights
 #pragma unroll
     for (int r = 0; r < RT; ++r) Ad[r] = Wp[r][t];
-    Bd[0] = Xw[t]; Bd[1] = Xw1[t];
+    if (!HI) { Bd[0] = Xw[t]; Bd[1] = Xw1[t]; }
   };
-  static_assert(NB >= 2, "the slot refilled in an iteration must not be the one it hands to LDS");
 #pragma unroll
   for (int i = 0; i < NB; ++i) gload(A[i], Bw[i], i);
-  bs[0][2 * w][lane] = Bw[0][0]; bs[0][2 * w + 1][lane] = Bw[0][1];
-  __syncthreads();
-  // Iteration kt: request k-tile kt + NB from memory, read the fragments of k-tile kt from LDS stage
-  // kt % 2, put this wavefront's share of k-tile kt + 1 into the other stage (its readers passed the
-  // barrier of the iteration before), run the matrix instructions of k-tile kt, barrier.
-  for (int kt0 = 0; kt0 < KT; kt0 += NS) {
+  if constexpr (HI) {
+    // Three LDS stages, fragments read one k-tile ahead (with half the matrix work per k-tile the LDS round trip at the
+    // head of an iteration shows; with hi + lo panels it hides behind twice the matrix instructions, and this form,
+    // which asks for the activation tiles a k-tile earlier, measured slower there).  Iteration kt: request k-tile
+    // kt + NB from memory, read the fragments of k-tile kt + 1 from stage (kt + 1) % 3 (written an iteration ago,
+    // barrier passed) while the matrix instructions of k-tile kt run on the fragments read an iteration ago, put this
+    // wavefront's share of k-tile kt + 2 into stage (kt + 2) % 3 (its last readers passed two barriers ago), barrier.
+    static_assert(!HI || NB >= 3, "the activation tiles of k-tile kt + 2 go to LDS in iteration kt: they must have been requested before it");
+    bs[0][2 * w][lane] = Bw[0][0]; bs[0][2 * w + 1][lane] = Bw[0][1];
+    bs[1][2 * w][lane] = Bw[1][0]; bs[1][2 * w + 1][lane] = Bw[1][1];
+    __syncthreads();
+    u32x4 Bf[8], Bn[8];
 #pragma unroll
-    for (int i = 0; i < NS; ++i) {
-      const int kt = kt0 + i;
-      if (kt < KT) {                              // uniform over the workgroup
-        gload(A[(i + NB) % NS], Bw[(i + NB) % NS], kt + NB);
-        u32x4 Bf[8];
+    for (int t = 0; t < 8; ++t) Bf[t] = bs[0][t][lane];
+    int st1 = 1, st2 = 2;                         // (kt + 1) % 3, (kt + 2) % 3
+    for (int kt0 = 0; kt0 < KT; kt0 += NS) {
 #pragma unroll
-        for (int t = 0; t < 8; ++t) Bf[t] = bs[kt & 1][t][lane];
-        bs[(kt + 1) & 1][2 * w][lane] = Bw[(i + 1) % NS][0];
-        bs[(kt + 1) & 1][2 * w + 1][lane] = Bw[(i + 1) % NS][1];
-        // hi panels of all accumulators, then lo panels: no instruction reads the result of the one before it
-        if constexpr (HI) {
+      for (int i = 0; i < NS; ++i) {
+        const int kt = kt0 + i;
+        if (kt < KT) {                            // uniform over the workgroup
+          gload(A[(i + NB) % NS], Bw[(i + NB) % NS], kt + NB);
+#pragma unroll
+          for (int t = 0; t < 8; ++t) Bn[t] = bs[st1][t][lane];
+          bs[st2][2 * w][lane] = Bw[(i + 2) % NS][0];
+          bs[st2][2 * w + 1][lane] = Bw[(i + 2) % NS][1];
 #pragma unroll
           for (int r = 0; r < RT; ++r)
 #pragma unroll
             for (int c = 0; c < 8; ++c)
               acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(Bf[c]), acc[r][c], 0, 0, 0);
-        } else {
+#pragma unroll
+          for (int t = 0; t < 8; ++t) Bf[t] = Bn[t];
+          st1 = st2; st2 = st2 == 2 ? 0 : st2 + 1;
+          __syncthreads();
+        }
+      }
+    }
+  } else {
+    static_assert(NB >= 2, "the slot refilled in an iteration must not be the one it hands to LDS");
+    bs[0][2 * w][lane] = Bw[0][0]; bs[0][2 * w + 1][lane] = Bw[0][1];
+    __syncthreads();
+    // Iteration kt: request k-tile kt + NB from memory, read the fragments of k-tile kt from LDS stage
+    // kt % 2, put this wavefront's share of k-tile kt + 1 into the other stage (its readers passed the
+    // barrier of the iteration before), run the matrix instructions of k-tile kt, barrier.
+    for (int kt0 = 0; kt0 < KT; kt0 += NS) {
+#pragma unroll
+      for (int i = 0; i < NS; ++i) {
+        const int kt = kt0 + i;
+        if (kt < KT) {                            // uniform over the workgroup
+          gload(A[(i + NB) % NS], Bw[(i + NB) % NS], kt + NB);
+          u32x4 Bf[8];
+#pragma unroll
+          for (int t = 0; t < 8; ++t) Bf[t] = bs[kt & 1][t][lane];
+          bs[(kt + 1) & 1][2 * w][lane] = Bw[(i + 1) % NS][0];
+          bs[(kt + 1) & 1][2 * w + 1][lane] = Bw[(i + 1) % NS][1];
+          // hi panels of all accumulators, then lo panels: no instruction reads the result of the one before it
 #pragma unroll
           for (int p = 0; p < 2; ++p)
 #pragma unroll
@@ -2503,8 +2535,8 @@ __global__ __launch_bounds__(256) void k_gemm_dense(DenseArgs d) {
 #pragma unroll
               for (int c = 0; c < CG; ++c)
                 acc[r][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(A[i][r]), as_bf16x8(Bf[2 * c + p]), acc[r][c], 0, 0, 0);
+          __syncthreads();
         }
-        __syncthreads();
       }
     }
   }
