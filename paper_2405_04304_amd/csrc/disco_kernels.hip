@@ -330,9 +330,10 @@ __device__ __forceinline__ void qkv_store(const GemmArgs& a, float* q, const int
 
 template <int EPI> struct EpiTraits { static constexpr bool pair = (EPI == EPI_QKV || EPI == EPI_SWIGLU); };
 
-// Register buffers (k-tiles in flight per wavefront) by row tiles per unit: as many as the register file of a
-// workgroup of eight wavefronts holds next to the accumulators.
-constexpr int gemm_buffers(int rt, int panels) { return rt >= 8 ? (panels >= 2 ? 2 : 3) : 4; }
+// Register buffers (k-tiles in flight per wavefront) by row tiles per unit and activation panels: as many as the
+// register file of a workgroup of eight wavefronts holds next to the accumulators; with two panels two buffers
+// measured best at every tile count (a same-box sweep over 2 / 3 / 4 at the 13B shapes).
+constexpr int gemm_buffers(int rt, int panels) { return panels >= 2 ? 2 : (rt >= 8 ? 3 : 4); }
 
 // LDS of one GEMM work unit.
 template <int RT, int NW, bool LN = false>
