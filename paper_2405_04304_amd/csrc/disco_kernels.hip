@@ -666,11 +666,13 @@ int gemm_split_for(int n_rows, int KT, int M) {
   if (n_rows % 64 == 0 && n_rows >= 2048) {
     // about 480 workgroups for a short K, about 240 for a long one (fewer, longer streams), but never a count that
     // leaves a large part of the chip idle in the last round (288 workgroups keep 56 % of the units busy, 480 keep 94 %)
+    // and not more than two rounds (96 row groups: 480 workgroups measured 1 - 1.5 % better than 768)
     const int groups = n_rows / 64, target = KT > 256 ? 240 : 480;
     double best = -1.0;
     s = 1;
     for (int c = 1; c <= GEMM_MAX_SPLIT && c <= KT / 16; ++c) {
       const long wgs = (long)groups * c;
+      if (c > 1 && wgs > 512) break;
       const double dist = (double)(wgs > target ? wgs - target : target - wgs) / target;
       const double score = cu_fill(wgs) - 0.05 * dist;
       if (score > best + 1e-9) { best = score; s = c; }
