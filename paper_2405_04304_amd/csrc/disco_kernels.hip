@@ -696,7 +696,11 @@ static hipError_t launch_gemm_p(const GemmArgs& a, hipStream_t s) {
     // 96-row workgroups where they fill the compute units clearly better than 64 rows (24576 rows: 256 workgroups against 384)
     if (EPI != EPI_QKV && a.KT >= 64 && n % 96 == 0 && n / 96 >= 200 && cu_fill(n / 96) > cu_fill(n / 64) + 0.1)
       return launch_gemm_cfg<P, 6, EPI, 8, gemm_buffers(6, P)>(a, s);
-    if (n % 64 == 0 && n / 64 >= 200) return launch_gemm_cfg<P, 4, EPI, 8, gemm_buffers(4, P)>(a, s);
+    if (n % 64 == 0 && n / 64 >= 200) {
+      // a short K (a wavefront sees at most four k-tiles: the 68M-class LM head) is served best by two buffers
+      if constexpr (EPI == EPI_STORE) { if (a.KT <= 32) return launch_gemm_cfg<P, 4, EPI, 8, 2>(a, s); }
+      return launch_gemm_cfg<P, 4, EPI, 8, gemm_buffers(4, P)>(a, s);
+    }
     if constexpr (PAIR) {
       return launch_gemm_cfg<P, 2, EPI, 8, gemm_buffers(2, P)>(a, s);
     } else {
