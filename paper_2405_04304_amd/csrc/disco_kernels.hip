@@ -1327,7 +1327,9 @@ constexpr int FEAT_NT = 1024;
 // loads).  Arg-max, soft-max sums and entropy are DPP wave reductions merged across the 16
 // wavefronts in a fixed order.  Top-10: every wavefront finds the ten largest of the values its
 // lanes hold by ten cross-lane arg-max rounds, and one wavefront picks the ten largest of those 160.
-constexpr int CM_NT = 512;     // threads per slice of the many-workgroup form: 2048 logits (the persistent draft loop uses the same slicing)
+constexpr int CM_NT = 512;     // threads per slice inside the persistent draft loop (its workgroups have 512 threads): 2048 logits
+constexpr int CM_MULTI_NT = 256;   // threads per slice of the many-workgroup launch: 1024 logits (32 workgroups at vocab 32000, 64
+                                   // records at most: measured 2 us per draft step better than slices of 2048)
 constexpr int CM_REC = 16;     // floats per record
 
 // Order-preserving map float -> uint32 (larger float <=> larger key; -inf maps above key 0, which marks
@@ -1676,11 +1678,11 @@ __device__ __forceinline__ int classify_merge_finish(const ClassifyArgs& a, cons
   return gbest.i;
 }
 
-// The same computation spread over ceil(V / 2048) workgroups (used when the caller gives scratch
-// memory).  Each workgroup reduces 2048 logits to a record {max, arg-max, S, T relative to its own
+// The same computation spread over ceil(V / (4 NT)) workgroups (used when the caller gives scratch
+// memory).  Each workgroup reduces its slice of the logits (4 per thread) to a record {max, arg-max, S, T relative to its own
 // max, its ten largest values}; the last workgroup to finish (ticket, no waiting) merges the
 // records in index order: S = sum S_b e^(m_b - M), T = sum e^(m_b - M) (T_b + (m_b - M) S_b), the ten
-// largest of the <= 320 candidates, then features, classifier and halt decision.  Forcing a token
+// largest of the records' candidates (ten per record), then features, classifier and halt decision.  Forcing a token
 // to max + 4 is applied to the merged sums in closed form.
 // b = index of this workgroup's slice of NT * 4 logits, nb = number of slices.  Returns the arg-max token in
 // every thread of the workgroup that finished the computation (the last to arrive), -1 in all others.
@@ -1758,14 +1760,14 @@ __device__ __forceinline__ int classify_unit(const ClassifyArgs& a, const int b,
   return classify_merge_finish<NT, CPT>(a, a.scratch + 64, nb, force, xf, k, sv, si, wtop, top_s, feat_s);
 }
 
-__global__ __launch_bounds__(CM_NT) void k_classify_multi(ClassifyArgs a) {
-  classify_unit<CM_NT>(a, blockIdx.x, gridDim.x, gate_request(const_cast<const uint32_t*>(a.gate)));
+__global__ __launch_bounds__(CM_MULTI_NT) void k_classify_multi(ClassifyArgs a) {
+  classify_unit<CM_MULTI_NT>(a, blockIdx.x, gridDim.x, gate_request(const_cast<const uint32_t*>(a.gate)));
 }
 
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s) {
   if (a.vocab < 1 || a.vocab > 65536) return hipErrorInvalidValue;
   if (a.scratch != nullptr && a.vocab >= 4096) {
-    hipLaunchKernelGGL(k_classify_multi, dim3((a.vocab + 4 * CM_NT - 1) / (4 * CM_NT)), dim3(CM_NT), 0, s, a);
+    hipLaunchKernelGGL(k_classify_multi, dim3((a.vocab + 4 * CM_MULTI_NT - 1) / (4 * CM_MULTI_NT)), dim3(CM_MULTI_NT), 0, s, a);
     return hipGetLastError();
   }
   if (a.vocab <= 8192) hipLaunchKernelGGL(k_classify<2>, dim3(1), dim3(FEAT_NT), 0, s, a);
