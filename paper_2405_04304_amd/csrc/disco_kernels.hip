@@ -2793,8 +2793,11 @@ __device__ __forceinline__ void fwd_gemm_phase(const FwdCtx& c, const GemmArgs& 
     for (; u < n_units; u += gridDim.x) {
       const int b = u % groups, seg = u / groups;
       const int kt_begin = (int)((int64_t)ga.KT * seg / ga.n_split), kt_end = (int)((int64_t)ga.KT * (seg + 1) / ga.n_split);
-      if (first) gemm_unit<P, RT, EPI, 8, gemm_buffers(RT, P), true, FwdWaitHook>(ga, b, kt_begin, kt_end, seg, ga.n_split, sm, hook);
-      else gemm_unit<P, RT, EPI, 8, gemm_buffers(RT, P), true, FwdWaitHook>(ga, b, kt_begin, kt_end, seg, ga.n_split, sm, FwdWaitHook{nullptr, 0u});
+      // (inside one launch the buffers filled before the barrier are the only prefetch across it: deeper buffers than the
+      //  per-phase launches take with two panels)
+      constexpr int U = RT >= 8 ? (P >= 2 ? 2 : 3) : 4;
+      if (first) gemm_unit<P, RT, EPI, 8, U, true, FwdWaitHook>(ga, b, kt_begin, kt_end, seg, ga.n_split, sm, hook);
+      else gemm_unit<P, RT, EPI, 8, U, true, FwdWaitHook>(ga, b, kt_begin, kt_end, seg, ga.n_split, sm, FwdWaitHook{nullptr, 0u});
       first = false;
     }
   }
