@@ -100,3 +100,57 @@ def test_mode1_draft_loop_equals_mode0():
             assert abs(s0[j].score - s1[j].score) < 1e-5
         for j in range(lo0.sl, cap):
             assert s1[j].executed == 0                      # the kernel left at the halting step
+
+
+def test_mode1_iteration_driver_with_chunks_equals_mode0():
+    """disco_iterate under launch mode 1: every chunk of draft steps is one cooperative launch that continues the block
+    of the launch before (block_offset / open_end inside the kernel's own loop), the verification forward another.  The
+    run must be the run of launch mode 0: same tokens, same blocks and acceptance counts, iteration by iteration."""
+    from paper_2405_04304_amd.engine import SpecEngine
+    d = dev()
+    st = W.scaled_shape(W.CFG1_DRAFT, vocab=4096, n_layers=3)
+    sd = W.scaled_shape(W.CFG1_DRAFT, vocab=4096)
+    tw, dw = W.make_weights(st, 3, "bf16"), W.make_weights(sd, 13, "bf16")
+    ot = O.Model(st, tw, kv_bf16=True)
+    clf = W.make_classifier(100)
+    prompt = W.make_prompt(2, 24, st.vocab).tolist()
+    n_new = 40
+    ref, _ = O.greedy_target(ot, prompt, n_new)
+    force = {"mask": W.make_force_mask(5, n_new, 0.6), "tokens": ref}
+    eng = SpecEngine(B.DiscoModel(st, tw, d), B.DiscoModel(sd, dw, d), B.DiscoClf(clf, d), max_ctx=96, page_tokens=16)
+    runs = {}
+    TAU = 0.52          # the seeded classifier's score grows with the position: short blocks first, then blocks up to the cap
+    for mode in (0, 1):
+        prev = B.disco_set_launch_mode(mode)
+        try:
+            for chunk in (2, 100):
+                runs[(mode, chunk)] = eng.generate(prompt, n_new, {"mode": "disco", "tau": TAU, "sl_max": 7, "pos_mode": "absolute",
+                                                                   "chunk": chunk}, force=force, trace=True)
+        finally:
+            B.disco_set_launch_mode(prev)
+    base = runs[(0, 100)]
+    print("[launch mode] lookahead histogram of the run:", base["sl_hist"], flush=True)
+    assert any(it["sl"] >= 3 for it in base["iterations"])                           # blocks that span several chunks occur
+    for key, r in runs.items():
+        if key[0] == 0:
+            assert r["tokens"] == base["tokens"]
+            assert [(a["sl"], a["n"], a["block"]) for a in r["iterations"]] == [(b["sl"], b["n"], b["block"]) for b in base["iterations"]]
+    # mode 1 against mode 0: equal unless the differing decision sits at a flagged margin (the two modes add in different
+    # orders): a draft token whose two largest probabilities are within 2e-2 in logit units, or a score within 1e-3 of tau
+    import math
+    from loop_compare import first_difference
+    assert runs[(1, 2)]["tokens"] == runs[(1, 100)]["tokens"]
+    for chunk in (2, 100):
+        a, b = runs[(1, chunk)], runs[(0, chunk)]
+        for ai, bi in zip(a["iterations"], b["iterations"]):
+            diff = first_difference(ai, bi)
+            if diff is None:
+                continue
+            kind, j = diff
+            assert kind in ("draft_token", "halt"), (chunk, diff)
+            rec = bi["steps"][j - 1]
+            if kind == "draft_token":
+                assert math.log(rec.feats[0] / rec.feats[1]) < MARGIN, (chunk, diff)
+            else:
+                assert abs(rec.score - TAU) < 1e-3, (chunk, diff)
+            break
