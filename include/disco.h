@@ -432,10 +432,11 @@ int disco_prefill(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
                   float* dev_logits_last, void* dev_ws, size_t ws_bytes, disco_stream s);
 
 /* The prompt pass with options.  flags = 0 is disco_prefill.
- * DISCO_PREFILL_BF16_ACTIVATIONS: the GEMM inputs of the pass (normalised residual rows, attention output,
- * MLP activations) are rounded to bf16, the usual mixed-precision arithmetic of bf16 inference, instead of
- * being carried as a bf16 hi + lo pair (fp32 grade).  Half the matrix-unit work and each weight tile fetched
- * for twice as many tokens; accumulation, residual stream, norms, soft-max and the KV entries are unchanged.
+ * DISCO_PREFILL_BF16_ACTIVATIONS: the matrix-unit inputs of the pass (normalised residual rows, attention output,
+ * MLP activations, and inside the attention the queries and the soft-max probabilities) are rounded to bf16,
+ * the usual mixed-precision arithmetic of bf16 inference, instead of being carried as a bf16 hi + lo pair
+ * (fp32 grade).  Half the matrix-unit work and each weight tile fetched for twice as many tokens;
+ * accumulation, residual stream, norms, soft-max statistics and the KV entries are unchanged.
  * Each GEMM then carries a relative input rounding error of up to 2^-9 per element (the weights already carry
  * one of that size), so logits and KV entries differ from those of the fp32-grade pass by a few 1e-3 of their
  * row's scale per layer pair: a pass for throughput, outside the parity statement of the decode path.       */

@@ -403,7 +403,7 @@ int disco_prefill_ex(const disco_model* m, disco_kv* kv, const int32_t* dev_toke
     at.q = ws.q; at.ldq = m->d_q; at.kv_layer = kv_layer; at.page_table = kv->dev_page_table;
     at.page_tokens = kv->page_tokens; at.nq = d.n_heads; at.nkv = d.n_kv_heads; at.dh = d.d_head; at.M = 16;
     at.pos0 = pos0; at.scale = 1.0f / sqrtf((float)d.d_head); at.Xout = ws.xattn;
-    HIP_TRY(launch_attn_groups(at, G, xs_q, st), "attention launch");
+    HIP_TRY(launch_attn_groups(at, G, xs_q, hi_only != 0, st), "attention launch");
 
     DenseArgs oa = dense(L.wo, ws.xattn, xs_q, m->d_q, d.d_model);
     residual_update(oa, L.norm2_g);

@@ -173,7 +173,7 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
 // dense prompt pass (groups of 16 tokens; every group holds 16 rows, surplus rows are padding)
 hipError_t launch_gemm_dense(const DenseArgs& a, int epi, hipStream_t s);
 hipError_t launch_rstd_groups(const float* ssq, int n_ssq, int d, float eps, float* rstd, int n_groups, hipStream_t s);
-hipError_t launch_attn_groups(const AttnArgs& a, int n_groups, size_t x_stride, hipStream_t s);
+hipError_t launch_attn_groups(const AttnArgs& a, int n_groups, size_t x_stride, bool bf16_operands, hipStream_t s);
 hipError_t launch_classify(const ClassifyArgs& a, hipStream_t s);
 // device address of the current GPU's file-scope classify scratch (CLASSIFY_SCRATCH_BYTES; no allocation)
 hipError_t classify_static_scratch(float** out);

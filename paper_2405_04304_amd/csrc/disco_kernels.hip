@@ -900,7 +900,9 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 // QCOH: the queries were written by other workgroups of this launch (hand-off loads); VCOH: so were entries of
 // the transposed V blocks, in 128-byte lines that an earlier step of the same launch may have read (a draft loop
 // inside one launch), so V tiles are fetched with L2-bypassing loads.
-template <int DH, bool QCOH = false, bool VCOH = false>
+// LO: q and P enter the matrix unit as bf16 hi + lo (fp32 grade); without it as bf16 only (the prompt pass with bf16
+// activations: half the matrix instructions).
+template <int DH, bool QCOH = false, bool VCOH = false, bool LO = true>
 struct AttnWave {
   static constexpr int KS = DH / 32, CT = DH / 16;
   // raw operands of one step: K rows of two 16-position tiles, V^T tiles of the same positions
@@ -975,7 +977,7 @@ struct AttnWave {
       const float xv[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
       union { bf16_t u[8]; bf16x8 v; } h, l;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { h.u[i] = f32_to_bf16(xv[i]); l.u[i] = f32_to_bf16(xv[i] - bf16_to_f32(h.u[i])); }
+      for (int i = 0; i < 8; ++i) { h.u[i] = f32_to_bf16(xv[i]); l.u[i] = LO ? f32_to_bf16(xv[i] - bf16_to_f32(h.u[i])) : (bf16_t)0; }
       qh[ks] = h.v; ql[ks] = l.v;
     }
   }
@@ -993,7 +995,7 @@ struct AttnWave {
         for (int ks = 0; ks < KS; ++ks) {
           const bf16x8 kk = as_bf16x8(r.k[t][ks]);
           acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[ks], acc, 0, 0, 0);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[ks], acc, 0, 0, 0);
+          if (LO) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[ks], acc, 0, 0, 0);
         }
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -1026,7 +1028,7 @@ struct AttnWave {
       if (kb < s1) {
         union { bf16_t u[4]; s16x4 v; } ph, pl;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) { ph.u[v] = f32_to_bf16(S[t][v]); pl.u[v] = f32_to_bf16(S[t][v] - bf16_to_f32(ph.u[v])); }
+        for (int v = 0; v < 4; ++v) { ph.u[v] = f32_to_bf16(S[t][v]); pl.u[v] = LO ? f32_to_bf16(S[t][v] - bf16_to_f32(ph.u[v])) : (bf16_t)0; }
         // positions at or beyond `total` hold stale bytes: zero them (0 * NaN would poison the sum)
         const int p0 = kb + 4 * g;
         uint2 keep;
@@ -1038,7 +1040,7 @@ struct AttnWave {
           raw.x &= keep.x; raw.y &= keep.y;
           union { uint2 u; s16x4 v; } vv; vv.u = raw;
           O[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vv.v, ph.v, O[c], 0, 0, 0);
-          O[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vv.v, pl.v, O[c], 0, 0, 0);
+          if (LO) O[c] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(vv.v, pl.v, O[c], 0, 0, 0);
         }
       }
     }
@@ -1220,7 +1222,7 @@ __global__ __launch_bounds__(512) void k_attn_head(AttnArgs a) {
 // running soft-max.  The groups are merged across the wavefronts one after the other through one LDS buffer.  The
 // longest ranges are scheduled first.
 constexpr int ATTN_MG = 2;
-template <int DH>
+template <int DH, bool LO>
 __global__ __launch_bounds__(512) void k_attn_groups(AttnArgs a, int n_groups, size_t x_stride) {
   constexpr int CT = DH / 16, NWV = 8, WKEYS = 32, STEP = NWV * WKEYS, NG = ATTN_MG;
   __shared__ f32x4 o_s[NWV][CT][64];
@@ -1232,13 +1234,13 @@ __global__ __launch_bounds__(512) void k_attn_groups(AttnArgs a, int n_groups, s
   const int r0g = (nb - 1 - (int)blockIdx.y) * NG;                // first group of this workgroup
   const int ng = min(NG, n_groups - r0g);
   auto grp = [&](int i) { return r0g + min(i, ng - 1); };          // a surplus slot repeats the last group and stores nothing
-  auto wave_of = [&](int i) { return AttnWave<DH>(a, head, -1, a.pos0 + 16 * grp(i), a.q + (size_t)grp(i) * 16 * a.ldq); };
-  AttnWave<DH> aw[NG] = {wave_of(0), wave_of(1)};
+  auto wave_of = [&](int i) { return AttnWave<DH, false, false, LO>(a, head, -1, a.pos0 + 16 * grp(i), a.q + (size_t)grp(i) * 16 * a.ldq); };
+  AttnWave<DH, false, false, LO> aw[NG] = {wave_of(0), wave_of(1)};
   static_assert(NG == 2, "the initialiser above lists two groups");
   const int total = aw[NG - 1].total;                              // the longest range: its object issues the loads
   // one set of raw operands per wavefront (two would not fit beside the state of two groups); the other wavefront of
   // the SIMD covers the wait (re-issuing the K loads between the two halves of a step measured slower)
-  typename AttnWave<DH>::Raw ra;
+  typename AttnWave<DH, false, false, LO>::Raw ra;
   int base = w * WKEYS;
   if (base < total) aw[NG - 1].issue(ra, base);
 #pragma unroll
@@ -1304,12 +1306,16 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_attn_groups(const AttnArgs& a, int n_groups, size_t x_stride, hipStream_t s) {
+hipError_t launch_attn_groups(const AttnArgs& a, int n_groups, size_t x_stride, bool bf16_operands, hipStream_t s) {
   if (a.M != 16 || n_groups < 1 || n_groups > 65535) return hipErrorInvalidValue;
   const dim3 g1(a.nq, (n_groups + ATTN_MG - 1) / ATTN_MG);
-  if (a.dh == 128) hipLaunchKernelGGL(k_attn_groups<128>, g1, dim3(512), 0, s, a, n_groups, x_stride);
-  else if (a.dh == 64) hipLaunchKernelGGL(k_attn_groups<64>, g1, dim3(512), 0, s, a, n_groups, x_stride);
-  else return hipErrorInvalidValue;
+  if (a.dh == 128) {
+    if (bf16_operands) hipLaunchKernelGGL((k_attn_groups<128, false>), g1, dim3(512), 0, s, a, n_groups, x_stride);
+    else hipLaunchKernelGGL((k_attn_groups<128, true>), g1, dim3(512), 0, s, a, n_groups, x_stride);
+  } else if (a.dh == 64) {
+    if (bf16_operands) hipLaunchKernelGGL((k_attn_groups<64, false>), g1, dim3(512), 0, s, a, n_groups, x_stride);
+    else hipLaunchKernelGGL((k_attn_groups<64, true>), g1, dim3(512), 0, s, a, n_groups, x_stride);
+  } else return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
