@@ -631,6 +631,8 @@ def main():
     # which form of the dominant kernel the timed blocks ran: one activation panel (blocks of <= 8 tokens) or two
     n_two = sum(1 for it in timed if it["sl"] + 1 > 8)
     panels = 2 if n_two * 2 > len(timed) else 1
+    # measured HBM traffic of that kernel: from the counter summary under profiles/ (13B shape only; none was taken for cfg3)
+    traffic = gateup_traffic_bytes(panels) if not (args.layers or cfg3) else None
     out = {
         "metric": ("accepted tokens/s at the 15B multi-query code-model pair, bf16 (verify+draft achieved HBM GB/s in roofline)" if cfg3 else
                    "accepted tokens/s at 13B/68M bf16 (verify+draft achieved HBM GB/s in roofline)"),
@@ -667,8 +669,8 @@ def main():
         "iteration_hbm_frac": iter_bytes / (t_timed / args.steps) / 1e9 / HBM_PEAK_GBS,
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": gateup_traffic_bytes(panels) if not (args.layers or cfg3) else None,
-            "traffic_source": (None if (args.layers or cfg3) else
+            "traffic": traffic,
+            "traffic_source": (None if traffic is None else
                                "profiles/gemm_gateup_13b_hbm_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch, "
                                "scaled by a plain copy)"),
             # template arguments: panels, row tiles per workgroup (24576 rows run 96-row workgroups, 27648 rows 128-row
