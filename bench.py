@@ -28,15 +28,17 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-TRAFFIC_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "gemm_gateup_13b_hbm_traffic.txt")
+TRAFFIC_FILES = {"cfg4": "gemm_gateup_13b_hbm_traffic.txt", "cfg3": "gemm_w1_15b_mqa_hbm_traffic.txt"}
 
 
-def gateup_traffic_bytes(panels: int):
-    """HBM bytes per launch of the dominant kernel (target gate/up GEMM) from the rocprofv3 FETCH_SIZE +
-    WRITE_SIZE counter summary under profiles/ (counters cannot be read from inside this process): the line
-    'traffic_bytes_per_launch panels=<1|2> <bytes>'.  None if the summary is missing or has no such line."""
+def gateup_traffic_bytes(panels: int, config: str = "cfg4"):
+    """HBM bytes per launch of the dominant kernel (the target's MLP-input GEMM) from the rocprofv3 FETCH_SIZE +
+    WRITE_SIZE counter summary of that configuration under profiles/ (counters cannot be read from inside this
+    process): the line 'traffic_bytes_per_launch panels=<1|2> <bytes>'.  None if the summary is missing or has
+    no such line."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", TRAFFIC_FILES[config])
     try:
-        for ln in open(TRAFFIC_FILE):
+        for ln in open(path):
             w = ln.split()
             if len(w) == 3 and w[0] == "traffic_bytes_per_launch" and w[1] == f"panels={panels}":
                 return int(w[2])
@@ -631,8 +633,8 @@ def main():
     # which form of the dominant kernel the timed blocks ran: one activation panel (blocks of <= 8 tokens) or two
     n_two = sum(1 for it in timed if it["sl"] + 1 > 8)
     panels = 2 if n_two * 2 > len(timed) else 1
-    # measured HBM traffic of that kernel: from the counter summary under profiles/ (13B shape only; none was taken for cfg3)
-    traffic = gateup_traffic_bytes(panels) if not (args.layers or cfg3) else None
+    # measured HBM traffic of that kernel: from the counter summary of the configuration under profiles/
+    traffic = gateup_traffic_bytes(panels, args.config) if not args.layers else None
     out = {
         "metric": ("accepted tokens/s at the 15B multi-query code-model pair, bf16 (verify+draft achieved HBM GB/s in roofline)" if cfg3 else
                    "accepted tokens/s at 13B/68M bf16 (verify+draft achieved HBM GB/s in roofline)"),
@@ -671,7 +673,7 @@ def main():
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": traffic,
             "traffic_source": (None if traffic is None else
-                               "profiles/gemm_gateup_13b_hbm_traffic.txt (rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch, "
+                               "profiles/" + TRAFFIC_FILES[args.config] + " (rocprofv3 FETCH_SIZE + WRITE_SIZE per dispatch, "
                                "scaled by a plain copy)"),
             # template arguments: panels, row tiles per workgroup (24576 rows run 96-row workgroups, 27648 rows 128-row
             # ones), epilogue, wavefronts, register buffers, deferred LayerNorm
