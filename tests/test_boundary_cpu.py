@@ -283,3 +283,21 @@ def test_heuristic_lookahead_rule_by_hand():
     lib = B.lib()
     assert lib.disco_clf_examples(None, 4, FAKE, FAKE, FAKE, None, None) == B.EINVAL
     assert lib.disco_clf_examples(FAKE, 0, FAKE, FAKE, FAKE, None, None) == B.EINVAL
+
+
+def test_bench_reads_the_measured_traffic_of_both_configurations_from_profiles():
+    """bench.py takes `roofline.traffic` from the counter summaries under profiles/ (never from a literal): the
+    summaries must be there, carry the line it parses, and sit within a few per cent above the algorithmic bytes."""
+    import importlib.util
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    spec = importlib.util.spec_from_file_location("bench_module", os.path.join(root, "bench.py"))
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    gate_up = 2 * 13824 * 5120 * 2              # 13B-class gate + up, bf16
+    w1 = 24576 * 6144 * 2                       # 15B-class W1, bf16
+    for cfg, panels, algorithmic in (("cfg4", 1, gate_up), ("cfg4", 2, gate_up), ("cfg3", 1, w1)):
+        t = bench.gateup_traffic_bytes(panels, cfg)
+        assert t is not None and algorithmic <= t <= 1.05 * algorithmic, (cfg, panels, t)
+    with open(os.path.join(root, ".gpurunignore")) as f:
+        assert "profiles" not in f.read()       # the summaries must travel to the GPU box with bench.py
