@@ -452,7 +452,8 @@ int disco_prefill_ex(const disco_model* m, disco_kv* kv, const int32_t* dev_toke
  * next token's embedding, the kernel leaving at the first halting step) instead of one launch per phase.
  * mode 0 (default): one launch per phase.  mode 1: one launch per forward where the model's shapes allow
  * it (else mode 0 is used silently); results agree with mode 0 to fp32 summation order.  On MI355X mode 0
- * is the faster one: see the measurements in the design notes.  Process-wide; returns the previous mode,
+ * is the faster one (a 13B-class verification block: 5.0 ms against 5.8 ms; a 68M-class draft step: 78 us against
+ * 139 us): a phase boundary inside the launch costs more than a kernel boundary there.  Process-wide; returns the previous mode,
  * or DISCO_EINVAL.  Not to be changed while calls are in flight on other threads.                      */
 int disco_set_launch_mode(int mode);
 

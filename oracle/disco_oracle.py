@@ -27,7 +27,7 @@ Written from the paper (arXiv 2405.04304):
 The two transformer families are not the paper's subject (it uses published checkpoints as black
 boxes); their definitions below are the standard pre-norm decoder equations.
 
-Readings of points the paper leaves open (all listed with reasons in the design notes):
+Readings of points the paper leaves open:
   the two rule-based baselines are named but not specified in the paper: the dynamic heuristic is
   taken as "lookahead + 2 after a fully accepted block, otherwise - 1 (not below 1), starting at 5";
   the perplexity rule as "stop when exp(-mean ln p) of the block's draft tokens exceeds a threshold";

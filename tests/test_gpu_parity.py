@@ -403,7 +403,7 @@ def test_loop_cfg0_matches_oracle_and_greedy():
 
 def test_cfg0_fp32_statement_against_bf16_storage():
     """The tiny pair is stated with fp32 weights; the library stores matrices and KV entries as bf16 (the
-    reading recorded in the design notes).  The oracle on the fp32 weights with an fp32 cache, against the
+    reading: bf16 storage is part of the design and applies to the tiny pair too).  The oracle on the fp32 weights with an fp32 cache, against the
     GPU on the bf16-rounded weights with a bf16 cache, teacher-forced along the oracle's own greedy text:
     every row of logits within the stated 2e-2 relative, every arg-max equal except where the oracle flags a
     top-2 margin below 2e-2."""
