@@ -514,8 +514,24 @@ def main():
                          "ms_per_iteration_median": 1e3 * sorted(
                              stamps[i + 1] - stamps[i] for i in range(args.warmup, n_iter))[len(its) // 2]})
             log(f"[bench] sweep {rows[-1]['policy']}: {rows[-1]['tokens_per_s']:.1f} tokens/s, {rows[-1]['iterations_per_s']:.1f} it/s")
-        print(json.dumps({"sweep": rows, "steps": args.steps, "warmup": args.warmup, "alpha": args.alpha,
-                          "prompt_len": args.prompt_len, "n_gpus": 1, "data": "synthetic", "dtype": "bf16"}), flush=True)
+        # the reference point of the paper's speed-ups (Table 1, row "Target"): the target decoding alone on the same prompt
+        eng.reset()
+        eng.prefill(prompt[:-1])
+        torch.cuda.synchronize()
+        t_stamps = [time.perf_counter()]
+
+        def tick_target(it):
+            torch.cuda.synchronize()
+            t_stamps.append(time.perf_counter())
+
+        eng.generate(prompt, 8 + min(args.steps, 64), {"mode": "static", "gamma": 0}, do_prefill=False, on_iteration=tick_target)
+        target_tps = (len(t_stamps) - 9) / (t_stamps[-1] - t_stamps[8])
+        for r in rows:
+            r["speedup_vs_target_only"] = r["tokens_per_s"] / target_tps
+        log(f"[bench] target alone: {target_tps:.1f} tokens/s")
+        print(json.dumps({"sweep": rows, "target_only_tokens_per_s": target_tps, "steps": args.steps, "warmup": args.warmup,
+                          "alpha": args.alpha, "prompt_len": args.prompt_len, "n_gpus": 1, "data": "synthetic", "dtype": "bf16"}),
+              flush=True)
         return
 
     # DISCO's classifier is TRAINED before the clock starts (Sec. 4 "SL classifier training", App. D.1): labelling
