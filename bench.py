@@ -336,8 +336,9 @@ def main():
                          "12-layer draft that reuses the target's embedding table), one prompt of 2048 tokens, 128 new tokens")
     ap.add_argument("--chunk", type=int, default=0,
                     help="draft steps enqueued between two looks at the halt flag (0 = library default, >= sl-max: whole loop at once)")
-    ap.add_argument("--launch-mode", type=int, default=0, choices=[0, 1],
-                    help="0: one launch per phase (default); 1: one cooperative launch per forward / draft loop (disco_set_launch_mode)")
+    ap.add_argument("--launch-mode", type=int, default=0, choices=[0, 1, 2],
+                    help="0: one launch per phase, QKV projection + attention of a layer in one launch (default); 1: one cooperative "
+                         "launch per forward / draft loop; 2: one launch per phase, nothing fused (disco_set_launch_mode)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run plain device copies of known size and exit (reference for HBM byte counters)")
     args = ap.parse_args()

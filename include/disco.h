@@ -446,15 +446,25 @@ int disco_prefill_ex(const disco_model* m, disco_kv* kv, const int32_t* dev_toke
 
 /* ---- launch structure ------------------------------------------------------------------------------ */
 
-/* A forward (and a whole draft loop) of the RMSNorm / rotary / SwiGLU family can run as ONE cooperative
- * launch of persistent workgroups with a grid barrier between the phases (QKV projection, attention,
- * O-projection, gate/up, down per layer; LM head; in a draft loop also the features / classifier and the
- * next token's embedding, the kernel leaving at the first halting step) instead of one launch per phase.
- * mode 0 (default): one launch per phase.  mode 1: one launch per forward where the model's shapes allow
- * it (else mode 0 is used silently); results agree with mode 0 to fp32 summation order.  On MI355X mode 0
- * is the faster one (a 13B-class verification block: 5.0 ms against 5.8 ms; a 68M-class draft step: 78 us against
- * 139 us): a phase boundary inside the launch costs more than a kernel boundary there.  Process-wide; returns the previous mode,
- * or DISCO_EINVAL.  Not to be changed while calls are in flight on other threads.                      */
+/* How a forward is cut into launches.  Process-wide; returns the previous mode, or DISCO_EINVAL.  Not to be
+ * changed while calls are in flight on other threads.
+ * mode 0 (default): one launch per phase (QKV projection, attention, O-projection, MLP input, MLP output per
+ *   layer; LM head), except that the QKV projection and the attention of a layer share ONE launch in models of
+ *   the RMSNorm / rotary / SwiGLU family whose query heads all have their own K / V head: the attention of a head
+ *   needs only that head's rows of the projection, so its workgroups wait for those alone (a counter per head)
+ *   instead of for the whole grid.  Every such wait is bounded; if one ever runs out (about a second; it needs the
+ *   launch's workgroups not to be resident together for that long) the launch still ends, the workspace is
+ *   marked, and every later result of that workspace says so -- NaN logits, -1 in disco_verify's arg-max and in
+ *   disco_loop_out.sl, DISCO_EHIP from disco_iterate -- until disco_workspace_init is called again.
+ * mode 1: a forward (and a whole draft loop) of that family as ONE cooperative launch of persistent workgroups
+ *   with a grid barrier between the phases (in a draft loop also the features / classifier and the next token's
+ *   embedding, the kernel leaving at the first halting step), where the model's shapes allow it (else mode 0 is
+ *   used silently); results agree with mode 0 to fp32 summation order.
+ * mode 2: one launch per phase, nothing shared; results agree with mode 0 to fp32 summation order (the context
+ *   is dealt to the attention's workgroups differently).
+ * On MI355X mode 0 is the fastest (a 13B-class verification block: 4.97 ms, against 5.03 ms in mode 2 and
+ * 5.8 ms in mode 1; a 68M-class draft step: 76 us against 78 us and 139 us): a phase boundary inside a
+ * launch costs more than a kernel boundary there, a per-head hand-off a little less.                     */
 int disco_set_launch_mode(int mode);
 
 #ifdef __cplusplus

@@ -18,6 +18,14 @@ extern "C" {
 int disco_probe_enable(int layer);
 float disco_probe_read_ms(void);
 
+/* Testing aid for the failure path of launches that wait inside (the QKV projection + attention launch of launch
+ * mode 0): polls before such a wait gives up, sets the workspace's abort word and lets the launch finish with
+ * unusable data (default 2^20, about a second).  A negative value makes every such wait give up at once, so the
+ * failure path (NaN logits, -1 from the arg-max and loop-finish kernels, DISCO_EHIP from disco_iterate) can be
+ * exercised with kernels that still run to their end.  After a failure the workspace has to be initialised again
+ * (disco_workspace_init).  Returns the previous value.  Process-wide.                                     */
+int disco_set_wait_limit(int polls);
+
 #ifdef __cplusplus
 }
 #endif

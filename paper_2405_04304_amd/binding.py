@@ -136,6 +136,7 @@ _SIGNATURES = {
     "disco_heuristic_next": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int]),
     "disco_probe_enable": (C.c_int, [C.c_int]),
     "disco_probe_read_ms": (C.c_float, []),
+    "disco_set_wait_limit": (C.c_int, [C.c_int]),
 }
 EXPORTS = sorted(_SIGNATURES)
 
@@ -336,6 +337,10 @@ def disco_set_launch_mode(mode: int) -> int:
     if prev < 0:
         raise DiscoError(prev, last_error())
     return prev
+
+
+def disco_set_wait_limit(polls: int) -> int:
+    return int(lib().disco_set_wait_limit(polls))
 
 
 def disco_probe_enable(layer: int) -> None:

@@ -78,6 +78,7 @@ struct Ws {
   float* h; float* q; bf16_t* xn; bf16_t* xattn; bf16_t* xact; float* part; float* gpart; float* logits;
   float* ssq; int* gemm_counters; int* attn_counters; int n_counters; float* clf_scratch;
   uint32_t* gate; int32_t* sl_count; int32_t* tok_next;
+  int* head_ready; unsigned* abort_word;     // fused QKV + attention launch: per-head counters, sticky failure flag
   // LayerNorm family: per-tile sums beside ssq, and the correction vectors of the deferred norms (W . g, W . b) of
   // every matrix that reads a normalised row: per layer [wg | wb] of the QKV matrix (2 d_qkv floats) and of the MLP
   // input matrix (2 d_ff), then the LM head's (2 vocab); written by disco_workspace_init
@@ -88,10 +89,12 @@ struct Ws {
   size_t total;
 };
 
-// Launch structure (disco_set_launch_mode): 0 = one launch per phase (default), 1 = one cooperative launch per
-// forward / draft loop.  DISCO_PERSISTENT=1 in the environment selects 1 at load time.
+// Launch structure (disco_set_launch_mode): 0 = one launch per phase, the QKV projection and the attention of a layer
+// in one launch where the model allows it (default), 1 = one cooperative launch per forward / draft loop, 2 = one
+// launch per phase, nothing fused.  DISCO_PERSISTENT=1 in the environment selects 1 at load time.
 int g_launch_mode = [] { const char* e = getenv("DISCO_PERSISTENT"); return (e && e[0] == '1') ? 1 : 0; }();
 bool persistent_enabled() { return g_launch_mode == 1; }
+int g_wait_limit = 1 << 20;     // polls before a wait inside a launch gives up (disco_set_wait_limit)
 
 // Carve the workspace; with base == nullptr only the total is meaningful.
 Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
@@ -127,6 +130,8 @@ Ws carve(const disco_model* m, int max_block, int max_ctx, void* base) {
   w.gate = static_cast<uint32_t*>(take(256));
   w.sl_count = reinterpret_cast<int32_t*>(w.gate ? w.gate + 16 : nullptr);
   w.tok_next = reinterpret_cast<int32_t*>(w.gate ? w.gate + 32 : nullptr);
+  w.abort_word = w.gate ? w.gate + 48 : nullptr;
+  w.head_ready = static_cast<int*>(take(sizeof(int) * QKV_ATTN_READY_SLOT * (size_t)d.n_heads));
   w.xn_stride = (size_t)2 * 16 * d.d_model + 2 * (size_t)d.d_model;      // two panels + d floats of sums of squares
   w.xattn_stride = (size_t)2 * 16 * m->d_q; w.xact_stride = (size_t)2 * 16 * d.d_ff;
   w.xn_v = w.xattn_v = w.xact_v = nullptr; w.q_v = nullptr; w.fwd_layers = nullptr; w.bar = nullptr;
@@ -253,15 +258,21 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
     g.pos0 = pos0; g.rope_tab = kv->dev_rope;
     g.kv_layer = kv->pages + (size_t)l * kv->layer_stride; g.page_table = kv->dev_page_table;
     g.page_tokens = kv->page_tokens;
-    HIP_TRY(launch_gemm(g, EPI_QKV, s), "qkv launch");
-
     AttnArgs at{};
     at.q = ws.q; at.ldq = m->d_q; at.kv_layer = g.kv_layer; at.page_table = kv->dev_page_table;
     at.page_tokens = kv->page_tokens; at.nq = d.n_heads; at.nkv = d.n_kv_heads; at.dh = d.d_head; at.M = n;
     at.pos0 = pos0; at.scale = 1.0f / sqrtf((float)d.d_head); at.part = ws.part;
     at.split_len = attn_split_len(pos0 + n); at.n_splits = (pos0 + n + at.split_len - 1) / at.split_len;
     at.Xout = ws.xattn; at.counters = ws.attn_counters; at.gate = gate;
-    HIP_TRY(launch_attn(at, s), "attention launch");
+    bool fused = false;
+    // (a bounded wait inside the fused launch that runs out sets the workspace's abort word: the LM head then stores
+    // NaN logits, the arg-max and loop-finish kernels report -1)
+    if (g_launch_mode != 2)
+      HIP_TRY(launch_qkv_attn(g, at, ws.head_ready, ws.abort_word, g_wait_limit, &fused, s), "qkv + attention launch");
+    if (!fused) {
+      HIP_TRY(launch_gemm(g, EPI_QKV, s), "qkv launch");
+      HIP_TRY(launch_attn(at, s), "attention launch");
+    }
 
     GemmArgs o{};
     residual_update(o, L.wo, ws.xattn, m->d_q, split_o, L.norm2_g);
@@ -284,6 +295,7 @@ int forward_block(const disco_model* m, disco_kv* kv, const int32_t* dev_tokens,
   lm.M = n; lm.gate = gate; lm.planes = ws.gpart; lm.counters = ws.gemm_counters;
   lm.W = static_cast<const bf16_t*>(m->w.wlm); normed_input(lm, fam_a ? ws.ln_vec + ws.ln_layer_stride * d.n_layers : nullptr, d.vocab);
   lm.n_rows = d.vocab; lm.out = logits_out; lm.ld_out = d.vocab; lm.only_row = only_last ? n - 1 : -1;
+  lm.abort_word = ws.abort_word;
   HIP_TRY(launch_gemm(lm, EPI_STORE, s), "lm-head launch");
   kv->len = pos0 + n;
   return DISCO_OK;
@@ -592,8 +604,11 @@ int disco_workspace_init(const disco_model* m, void* dev_ws, size_t ws_bytes, in
   const size_t need = disco_workspace_bytes(m, max_block, max_ctx);
   if (need == 0 || ws_bytes < need) return fail(DISCO_EINVAL, "workspace of %zu bytes, %zu needed", ws_bytes, need);
   const Ws ws = carve(m, max_block, max_ctx, dev_ws);
+  const disco_model_desc& d0 = m->d;
   HIP_TRY(launch_zero(ws.gemm_counters, ws.n_counters, static_cast<hipStream_t>(s)), "workspace init launch");
   HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.clf_scratch), 64, static_cast<hipStream_t>(s)), "workspace init launch");
+  HIP_TRY(launch_zero(ws.head_ready, QKV_ATTN_READY_SLOT * d0.n_heads, static_cast<hipStream_t>(s)), "workspace init launch");
+  HIP_TRY(launch_zero(reinterpret_cast<int*>(ws.gate), 64, static_cast<hipStream_t>(s)), "workspace init launch");
   if (ws.ln_vec != nullptr) {
     // correction vectors of the deferred LayerNorms: one-token GEMVs of every consumer matrix with the gain vector
     // and with the bias vector of the norm in front of it (a missing bias gives zeros)
@@ -699,7 +714,8 @@ int disco_verify(const disco_model* target, disco_kv* kv, const int32_t* dev_blo
   hipStream_t st = static_cast<hipStream_t>(s);
   rc = forward_block(target, kv, dev_block, n_block, logits, false, ws, nullptr, st);
   if (rc) return rc;
-  HIP_TRY(launch_argmax_rows(logits, n_block, target->d.vocab, dev_argmax, ws.bar ? ws.bar + FWD_BAR_ABORT_WORD : nullptr, st), "argmax launch");
+  const bool persistent = target->persist_ok && ws.bar != nullptr && persistent_enabled();
+  HIP_TRY(launch_argmax_rows(logits, n_block, target->d.vocab, dev_argmax, persistent ? ws.bar + FWD_BAR_ABORT_WORD : ws.abort_word, st), "argmax launch");
   return DISCO_OK;
 }
 
@@ -813,7 +829,7 @@ static int draft_loop_impl(const disco_model* draft, disco_kv* kv, const disco_c
     a.scratch = ws.clf_scratch;
     { const hipError_t e = launch_classify(a, st); if (e != hipSuccess) { kv->len = len_entry; return hip_fail(e, "classify launch"); } }
   }
-  HIP_TRY(launch_loop_finish(ws.sl_count, ws.gate, dev_out, host_out, nullptr, st), "loop finish launch");
+  HIP_TRY(launch_loop_finish(ws.sl_count, ws.gate, dev_out, host_out, ws.abort_word, st), "loop finish launch");
   return DISCO_OK;
 }
 
@@ -1004,9 +1020,16 @@ int disco_heuristic_next(int lookahead, int drafted, int accepted, int up, int d
 }
 
 int disco_set_launch_mode(int mode) {
-  if (mode != 0 && mode != 1) return fail(DISCO_EINVAL, "launch mode %d: 0 (one launch per phase) or 1 (one launch per forward)", mode);
+  if (mode < 0 || mode > 2)
+    return fail(DISCO_EINVAL, "launch mode %d: 0 (one launch per phase, QKV + attention in one), 1 (one launch per forward) or 2 (one launch per phase)", mode);
   const int prev = g_launch_mode;
   g_launch_mode = mode;
+  return prev;
+}
+
+int disco_set_wait_limit(int polls) {
+  const int prev = g_wait_limit;
+  g_wait_limit = polls > (1 << 24) ? (1 << 24) : polls;
   return prev;
 }
 

@@ -42,6 +42,7 @@ struct GemmArgs {
   float* out;           // STORE target, row stride ld_out
   int64_t ld_out;
   int only_row;         // STORE: write only this token's row to out[0..N) (-1: all rows)
+  const unsigned* abort_word;   // STORE, optional: when the word is set (a bounded wait of an earlier launch ran out) NaN is stored
   // QKV epilogue
   float* q; int ldq; int nq, nkv, dh; int pos0;
   const float* rope_tab;  // rotary table [position][d_head / 2][cos, sin], or nullptr for no rotation
@@ -170,6 +171,14 @@ hipError_t launch_forward(const FwdArgs& f, bool big, bool loop, hipStream_t s);
 constexpr int FWD_BAR_WORDS = (2 * 16 + 2) * 64;   // group counters, top counter, release words, abort word: 256 bytes apart
 constexpr int FWD_BAR_ABORT_WORD = (2 * 16 + 1) * 64;
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
+// QKV projection (EPI_QKV arguments) and attention of one layer in one launch, where the shape allows it (every query
+// head with its own K / V head, RMSNorm family): sets *launched; when it stays false nothing was enqueued and the caller
+// launches the two kernels.  head_ready: one zeroed counter per query head, QKV_ATTN_READY_SLOT ints apart; abort_word:
+// set when a bounded wait inside the launch ran out (results unusable).
+constexpr int QKV_ATTN_READY_SLOT = 64;
+// wait_limit: polls before a wait gives up (negative: at once).
+hipError_t launch_qkv_attn(const GemmArgs& g, const AttnArgs& a, int* head_ready, unsigned* abort_word, int wait_limit, bool* launched,
+                           hipStream_t s);
 // dense prompt pass (groups of 16 tokens; every group holds 16 rows, surplus rows are padding)
 hipError_t launch_gemm_dense(const DenseArgs& a, int epi, hipStream_t s);
 hipError_t launch_rstd_groups(const float* ssq, int n_ssq, int d, float eps, float* rstd, int n_groups, hipStream_t s);

@@ -381,6 +381,8 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
   static_assert(UNITS <= NW, "one epilogue wavefront per unit");
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const uint32_t halted = gate_request(a.gate);
+  uint32_t aborted = 0u;                          // requested here, used by the last store
+  if (EPI == EPI_STORE) aborted = a.abort_word != nullptr ? __builtin_nontemporal_load(a.abort_word) : 0u;
   int rt[RT];
   gemm_unit_tiles<RT, EPI>(a, b, rt);
 
@@ -605,6 +607,7 @@ __device__ __forceinline__ void gemm_unit(const GemmArgs& a, const int b, const 
   if (EPI == EPI_STORE) {
     if (a.only_row >= 0 && m != a.only_row) return;
     const size_t row_off = a.only_row >= 0 ? 0 : (size_t)m * a.ld_out;
+    if (aborted != 0u) y[0] = f32x4{NAN, NAN, NAN, NAN};   // the forward's data is unusable: say so in its result
     st_f4<COH>(a.out + row_off + urt[0] * 16 + 4 * g, y[0][0], y[0][1], y[0][2], y[0][3]);
   } else if (EPI == EPI_QKV) {
     // two tiles: features c .. c+3 and their rotary partners c + dh/2 .. of one head
@@ -1057,21 +1060,29 @@ struct AttnSmem {
 
 // Work unit (query head, range `split` of split_len cached positions) run by NWV wavefronts; the last range of
 // a head to finish merges all of the head's records and writes the O-projection panels.
-template <int DH, int NWV, bool COH = false, bool VCOH = false>
+// `hook` runs once before anything that other workgroups of the launch may still be writing is touched (the queries,
+// cache entries at or beyond `safe_end`): a wavefront whose first 32 positions lie below safe_end requests them
+// before the hook, so those loads are in flight while the hook waits.  The workgroup that merges the head also
+// zeroes `reset_word` (the counter the hook waited on), if given.
+template <int DH, int NWV, bool COH = false, bool VCOH = false, bool QCOH = false, typename Hook = NoHook>
 __device__ __forceinline__ void attn_range(const AttnArgs& a, const int head, const int split, AttnSmem<DH, NWV>& sm,
-                                           const uint32_t halted) {
+                                           const uint32_t halted, const Hook hook = Hook(), const int safe_end = 0x7fffff00,
+                                           int* reset_word = nullptr) {
   constexpr int CT = DH / 16, WKEYS = 32;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int j = lane & 15, g = lane >> 4;
   const int total = a.pos0 + a.M;
   const int s0 = split * a.split_len, s1 = min(s0 + a.split_len, total);
-  AttnWave<DH, false, VCOH> aw(a, head, s1);     // (a persistent kernel gives the queries a fresh address per layer)
-  typename AttnWave<DH, false, VCOH>::Raw r0, r1;
+  AttnWave<DH, QCOH, VCOH> aw(a, head, s1);      // (a persistent kernel gives the queries a fresh address per layer)
+  typename AttnWave<DH, QCOH, VCOH>::Raw r0, r1;
   // the first step's cache loads go out ahead of the q loads; later steps' loads are in flight during
   // the arithmetic of the step before
   constexpr int STEP = NWV * WKEYS;
   int base = s0 + w * WKEYS;
-  if (base < s1) aw.issue(r0, base);
+  const bool early = base + WKEYS <= safe_end;
+  if (base < s1 && early) aw.issue(r0, base);
+  hook();
+  if (base < s1 && !early) aw.issue(r0, base);
   aw.load_q(head);
   if (halted != 0u) return;                       // uniform over the launch; nothing has been written yet
   while (base < s1) {
@@ -1115,6 +1126,7 @@ __device__ __forceinline__ void attn_range(const AttnArgs& a, const int head, co
   // the last range of this head to finish merges all ranges (in range order) into the panels that
   // feed the O-projection
   if (!last_arrival(a.counters + head, a.n_splits, &sm.s_last)) return;
+  if (reset_word != nullptr && threadIdx.x == 0) __hip_atomic_store(reset_word, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   // 8 channels per thread: DH / 8 threads per query, so that all 16 queries of a block are merged in one
   // pass (a second pass would put a second round trip to the records behind the first)
   constexpr int TPQ = DH / 8;
@@ -2672,6 +2684,115 @@ hipError_t launch_rstd_groups(const float* ssq, int n_ssq, int d, float eps, flo
   return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// QKV projection and attention of one layer in ONE launch (models whose heads all have their own K / V)
+// ---------------------------------------------------------------------------------------------
+//
+// The attention of head h needs only the 3 d_head rows of the QKV projection that belong to h, so the dependency
+// between the two phases is per head, not grid-wide.  The launch has the QKV projection's workgroups, dealt so that
+// the G = 3 d_head / (16 RT) workgroups holding the q, K and V rows of one head are neighbours.  Each finishes its
+// rows (rotary, query rows, cache entries: write-through stores), adds 1 to the head's counter, and then acts as
+// range `j` of the head's attention: it waits until the counter shows G (bounded: after `limit` polls it sets the
+// abort word and goes on with unusable data; the LM head then stores NaN logits and the arg-max and loop-finish
+// kernels turn a set abort word into -1 outputs), with its first cache loads already in flight where they cannot touch a 128-byte line that the
+// head's other workgroups are still writing.  The head's ranges are merged by the last one to finish, as in the
+// stand-alone attention kernel; that workgroup also zeroes the head's counter for the next launch.  Nobody waits
+// before it has signalled, so the launch completes whenever all its workgroups are resident at once; the launcher
+// checks that they fit.  The counters are 256 bytes apart.
+constexpr int QA_READY_SLOT = QKV_ATTN_READY_SLOT;   // ints between two heads' counters
+
+struct HeadWaitHook {
+  int* ready; int n; unsigned* abort_word; int limit;   // limit: polls (each a memory round trip, about 1 us) before giving up
+  __device__ __forceinline__ void operator()() const {
+    if (threadIdx.x == 0) {
+      int spins = 0;
+      if (limit < 0) __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      while (limit >= 0 && __hip_atomic_load(ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < n) {
+        if (++spins > limit) {
+          __hip_atomic_store(abort_word, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+      }
+    }
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+  }
+};
+
+template <int P, int RT, int U, int DH>
+__global__ __launch_bounds__(512) void k_qkv_attn(GemmArgs g, AttnArgs a, int* ready, unsigned* abort_word, int safe_end, int limit) {
+  constexpr int UH = DH / (16 * RT), G = 3 * UH;   // workgroups per q / K / V part of a head, per head
+  static_assert(UH >= 1 && UH * 16 * RT == DH, "a head part is a whole number of workgroups");
+  union Smem { GemmSmem<RT, 8> gemm; AttnSmem<DH, 8> attn; };
+  __shared__ Smem sm;
+  const int head = blockIdx.x / G, j = blockIdx.x % G;
+  const int part = j / UH, sub = j % UH;
+  const int hu = part == 0 ? head : (part == 1 ? g.nq + head : g.nq + g.nkv + head);
+  const uint32_t halted = gate_request(g.gate);
+  gemm_unit<P, RT, EPI_QKV, 8, U, true>(g, hu * UH + sub, 0, g.KT, 0, 1, sm.gemm);
+  if (halted != 0u) return;                       // uniform over the launch; nothing has been written
+  __atomic_signal_fence(__ATOMIC_SEQ_CST);
+  __builtin_amdgcn_s_waitcnt(0);                  // this wavefront's write-through stores have completed
+  __syncthreads();                                // ... and those of the whole workgroup
+  int* rdy = ready + head * QA_READY_SLOT;
+  if (threadIdx.x == 0) __hip_atomic_fetch_add(rdy, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (j >= a.n_splits) return;
+  attn_range<DH, 8, false, false, true, HeadWaitHook>(a, head, j, sm.attn, 0u, HeadWaitHook{rdy, G, abort_word, limit}, safe_end, rdy);
+}
+
+// Workgroups of `kernel` (512 threads, static LDS only) that the device holds at once.
+static long resident_capacity(const void* kernel) {
+  int per_cu = 0, dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, 512, 0) != hipSuccess || per_cu < 1) return 0;
+  return (long)per_cu * prop.multiProcessorCount;
+}
+
+template <int P, int RT, int DH>
+static hipError_t launch_qkv_attn_cfg(const GemmArgs& g, const AttnArgs& a, int* ready, unsigned* abort_word, int safe_end, int limit,
+                                      bool* launched, hipStream_t s) {
+  constexpr int U = gemm_buffers(RT, P);
+  static const long capacity = resident_capacity(reinterpret_cast<const void*>(k_qkv_attn<P, RT, U, DH>));
+  const int wgs = g.n_rows / (16 * RT);
+  if (wgs > capacity) return hipSuccess;          // not all resident at once: the caller launches the two kernels
+  hipLaunchKernelGGL((k_qkv_attn<P, RT, U, DH>), dim3(wgs), dim3(512), 0, s, g, a, ready, abort_word, safe_end, limit);
+  *launched = true;
+  return hipGetLastError();
+}
+
+// Sets *launched and enqueues the fused launch when the shape allows it; otherwise leaves *launched false and does
+// nothing (the caller then launches the QKV projection and the attention separately).  a.split_len / a.n_splits are
+// chosen here.
+hipError_t launch_qkv_attn(const GemmArgs& g0, const AttnArgs& a0, int* ready, unsigned* abort_word, int limit, bool* launched, hipStream_t s) {
+  *launched = false;
+  if (ready == nullptr || abort_word == nullptr) return hipSuccess;
+  if (g0.sum != nullptr || g0.nq != g0.nkv || (g0.dh != 64 && g0.dh != 128)) return hipSuccess;
+  if (g0.M < 1 || g0.M > 16 || g0.KT < 1 || g0.n_rows != 3 * g0.nq * g0.dh || g0.grp != g0.dh / 32) return hipSuccess;
+  if (g0.ssq != nullptr && (g0.n_ssq < 1 || g0.n_ssq > 512)) return hipErrorInvalidValue;
+  if (a0.M != g0.M || a0.nq != g0.nq || a0.nkv != g0.nkv || a0.dh != g0.dh || a0.pos0 != g0.pos0 || a0.counters == nullptr) return hipErrorInvalidValue;
+  GemmArgs g = g0;
+  g.n_split = 1;
+  AttnArgs a = a0;
+  const int n = g.n_rows, total = a.pos0 + a.M, pt = a.page_tokens;
+  const int rt = (n % 64 == 0 && n / 64 >= 200) ? 4 : 2;                 // the row tiles of the stand-alone QKV launch
+  const int G = 3 * g.dh / (16 * rt);
+  int len = ((total + G - 1) / G + 31) / 32 * 32;
+  if (len < ATTN_SPLIT_LEN) len = ATTN_SPLIT_LEN;                        // (the records are sized for ranges of at least this)
+  a.split_len = len; a.n_splits = (total + len - 1) / len;
+  // positions below safe_end share no 128-byte line with the block's own positions: K rows are 128 bytes or more per
+  // position; a V^T row holds the positions of one page, 64 to a line
+  const int safe_end = (pt % 64 == 0) ? (a.pos0 & ~63) : (a.pos0 / pt) * pt;
+  const bool p1 = g.M <= 8;
+  if (g.dh == 128) {
+    if (rt == 4) return p1 ? launch_qkv_attn_cfg<1, 4, 128>(g, a, ready, abort_word, safe_end, limit, launched, s) : launch_qkv_attn_cfg<2, 4, 128>(g, a, ready, abort_word, safe_end, limit, launched, s);
+    return p1 ? launch_qkv_attn_cfg<1, 2, 128>(g, a, ready, abort_word, safe_end, limit, launched, s) : launch_qkv_attn_cfg<2, 2, 128>(g, a, ready, abort_word, safe_end, limit, launched, s);
+  }
+  if (rt == 4) return p1 ? launch_qkv_attn_cfg<1, 4, 64>(g, a, ready, abort_word, safe_end, limit, launched, s) : launch_qkv_attn_cfg<2, 4, 64>(g, a, ready, abort_word, safe_end, limit, launched, s);
+  return p1 ? launch_qkv_attn_cfg<1, 2, 64>(g, a, ready, abort_word, safe_end, limit, launched, s) : launch_qkv_attn_cfg<2, 2, 64>(g, a, ready, abort_word, safe_end, limit, launched, s);
+}
 
 
 // ---------------------------------------------------------------------------------------------

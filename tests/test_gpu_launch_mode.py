@@ -25,8 +25,11 @@ def mode1():
 def test_launch_mode_argument():
     prev = B.disco_set_launch_mode(0)
     assert B.disco_set_launch_mode(prev) == 0
-    with pytest.raises(B.DiscoError):
-        B.disco_set_launch_mode(2)
+    assert B.disco_set_launch_mode(2) == prev            # 2: one launch per phase, nothing fused
+    assert B.disco_set_launch_mode(prev) == 2
+    for bad in (-1, 3):
+        with pytest.raises(B.DiscoError):
+            B.disco_set_launch_mode(bad)
 
 
 def test_mode1_draft_step_and_verify_match_oracle(mode1):
