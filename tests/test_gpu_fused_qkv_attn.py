@@ -168,3 +168,28 @@ def test_a_wait_that_gives_up_is_reported_and_reinitialising_the_workspace_recov
     lg, am = _verify(gm, gkv, ws, blk, 0)
     assert am == want_am
     assert float((lg - want).abs().max()) <= 2e-4 * float(want.abs().max())
+
+
+def test_fused_launch_at_page_and_line_boundaries():
+    """Which cache loads may go out before the per-head wait depends on where the block starts inside its page and inside
+    a 128-byte line of the transposed V rows; sweep block starts around those boundaries, for page sizes below, at and
+    above a line, against the separate launches (held to the oracle by the parity tests)."""
+    d = dev()
+    shape = W.ModelShape("B", 2, 128, 2, 64, 2, 256, 512)
+    gm = B.DiscoModel(shape, W.make_weights(shape, 21, "bf16", sigma=0.08), d)
+    cap = 560
+    full = W.make_kv_fill(shape, 520, 5).to(d)
+    for page_tokens in (4, 16, 64, 128):
+        gkv = B.DiscoKV(gm, cap, page_tokens)
+        ws = gm.workspace(16, cap)
+        for ctx in (1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 192, 255, 256, 257, 300, 383, 384, 511, 512, 520):
+            fill = full[:, :, :ctx].contiguous()
+            for M in (1, 16):
+                blk = W.make_tokens(ctx + M, M, shape.vocab).tolist()
+                out = []
+                for mode in (0, 2):
+                    gkv.fill(fill)
+                    out.append(_verify(gm, gkv, ws, blk, mode))
+                (lg0, am0), (lg2, am2) = out
+                scale = float(lg2.abs().max())
+                assert bool(torch.isfinite(lg0).all()) and float((lg0 - lg2).abs().max()) <= 2e-4 * scale, (page_tokens, ctx, M)
