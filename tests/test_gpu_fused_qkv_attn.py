@@ -193,3 +193,38 @@ def test_fused_launch_at_page_and_line_boundaries():
                 (lg0, am0), (lg2, am2) = out
                 scale = float(lg2.abs().max())
                 assert bool(torch.isfinite(lg0).all()) and float((lg0 - lg2).abs().max()) <= 2e-4 * scale, (page_tokens, ctx, M)
+
+
+def test_fused_launch_over_other_head_layouts():
+    """Head counts and widths that give 3, 6 and 12 workgroups per head, d_q different from d_model, odd head counts,
+    pages of every size, permuted page order: the shared launch against the separate launches."""
+    import random
+    rng = random.Random(7)
+    shapes = (W.ModelShape("B", 1, 256, 80, 64, 80, 256, 512),      # 15360 projection rows of 64-wide heads: 64-row workgroups, 3 per head
+              W.ModelShape("B", 2, 128, 3, 64, 3, 128, 320),        # 6 per head, three heads, d_q 192 against d_model 128
+              W.ModelShape("B", 2, 192, 5, 128, 5, 256, 320),       # 12 per head, five heads, d_q 640 against d_model 192
+              W.ModelShape("B", 1, 64, 1, 128, 1, 64, 256))         # one head
+    for si, shape in enumerate(shapes):
+        gm = B.DiscoModel(shape, W.make_weights(shape, 30 + si, "bf16", sigma=0.08), dev())
+        for _ in range(6):
+            page_tokens = rng.choice((4, 8, 16, 32, 64, 128))
+            ctx = rng.choice((0, 1, 17, 100, 129, 333, 640, 1500))
+            M = rng.choice((1, 2, 3, 7, 8, 9, 16))
+            cap = ctx + 32
+            n_pages = (cap + page_tokens - 1) // page_tokens
+            order = list(range(n_pages))
+            rng.shuffle(order)
+            gkv = B.DiscoKV(gm, cap, page_tokens, order)
+            ws = gm.workspace(16, cap)
+            fill = W.make_kv_fill(shape, ctx, 40 + si).to(dev()) if ctx else None
+            blk = W.make_tokens(ctx + M, M, shape.vocab).tolist()
+            out = []
+            for mode in (0, 2):
+                if fill is not None:
+                    gkv.fill(fill)
+                else:
+                    B.disco_kv_rollback(gkv, 0)
+                out.append(_verify(gm, gkv, ws, blk, mode))
+            (lg0, am0), (lg2, am2) = out
+            scale = float(lg2.abs().max())
+            assert bool(torch.isfinite(lg0).all()) and float((lg0 - lg2).abs().max()) <= 2e-4 * scale, (si, page_tokens, ctx, M)
